@@ -1,0 +1,204 @@
+"""ctypes front end of the CPU oracle (``cpoconv_oracle.c``).  TEST INFRASTRUCTURE ONLY.
+
+Only tests, the smoke check and the benchmark's ``cpu_baseline`` leg may import this
+package.  It shares nothing with the HIP library and never imports it.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+import subprocess
+from dataclasses import dataclass
+from typing import Tuple
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_SRC = os.path.join(_HERE, "cpoconv_oracle.c")
+_LIB = os.path.join(_HERE, "liboracle.so")
+
+NPF = -2
+NPC = -3
+ALGO_CPO = 0
+ALGO_CPS = 1
+
+
+def build(force: bool = False) -> str:
+    """Compile the oracle with gcc (plain -O2, no vectoriser flags, no OpenMP)."""
+    if force or not os.path.exists(_LIB) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC):
+        subprocess.check_call(["gcc", "-O2", "-std=c11", "-fPIC", "-shared", "-Wall", "-Wextra",
+                               "-o", _LIB, _SRC])
+    return _LIB
+
+
+class _Shape(ctypes.Structure):
+    _fields_ = [(n, ctypes.c_int32) for n in ("C", "H", "W", "K", "kh", "kw", "stride", "pad")]
+
+
+_lib = None
+
+
+def _load():
+    global _lib
+    if _lib is None:
+        _lib = ctypes.CDLL(build())
+        _lib.orc_max_ptr.restype = ctypes.c_int64
+    return _lib
+
+
+def _p(a: np.ndarray):
+    return a.ctypes.data_as(ctypes.c_void_p)
+
+
+def _shape(shape) -> _Shape:
+    return _Shape(*[int(v) for v in shape])
+
+
+def _check(rc: int, what: str) -> None:
+    if rc != 0:
+        raise ValueError(f"oracle {what} failed with code {rc}")
+
+
+@dataclass
+class Geometry:
+    Ih: int
+    Iw: int
+    Oh: int
+    Ow: int
+    nop3: bool
+    top: int
+    cls: np.ndarray
+    p0: np.ndarray
+    what: np.ndarray
+    real: np.ndarray
+    present: np.ndarray
+
+
+def geometry(shape) -> Geometry:
+    sh = _shape(shape)
+    Iw = sh.W + 2 * sh.pad
+    info = np.zeros(6, np.int32)
+    cls, p0, what, real = (np.zeros(max(Iw, 1), np.int32) for _ in range(4))
+    present = np.zeros(max(sh.kw, 1), np.int32)
+    _check(_load().orc_geometry(ctypes.byref(sh), _p(info), _p(cls), _p(p0), _p(what), _p(real),
+                                _p(present)), "geometry")
+    return Geometry(int(info[0]), int(info[1]), int(info[2]), int(info[3]), bool(info[4]),
+                    int(info[5]), cls, p0, what, real, present)
+
+
+@dataclass
+class EncodedMap:
+    """The three streams of the paper plus the per-channel side band."""
+    algo: int
+    shape: Tuple[int, ...]
+    ptr: np.ndarray       # int32
+    da: np.ndarray        # float32
+    ind: np.ndarray       # int32 ("IN")
+    chan_off: np.ndarray  # int32, 3 x (C+1): ptr / DA / IN offsets
+
+    @property
+    def elements(self) -> int:
+        """|ptr| + |DA| + |IN| (SI: total size of the CPO/CPS structure)."""
+        return int(self.ptr.size + self.da.size + self.ind.size)
+
+
+def encode(act: np.ndarray, shape, algo: int) -> EncodedMap:
+    sh = _shape(shape)
+    act = np.ascontiguousarray(act, dtype=np.float32)
+    assert act.shape == (sh.C, sh.H, sh.W), (act.shape, tuple(shape))
+    lib = _load()
+    ptr_cap = int(lib.orc_max_ptr(ctypes.byref(sh)))
+    if ptr_cap < 0:
+        raise ValueError("oracle: bad shape")
+    da_cap = (sh.C + 1) * (sh.H + 2 * sh.pad) * (sh.W + 2 * sh.pad)
+    ptr = np.zeros(ptr_cap, np.int32)
+    da = np.zeros(da_cap, np.float32)
+    ind = np.zeros(da_cap, np.int32)
+    chan_off = np.zeros(3 * (sh.C + 1), np.int32)
+    lens = np.zeros(3, np.int64)
+    _check(lib.orc_encode(_p(act), ctypes.byref(sh), int(algo), _p(ptr), ctypes.c_int64(ptr_cap),
+                          _p(da), _p(ind), ctypes.c_int64(da_cap), _p(chan_off), _p(lens)), "encode")
+    return EncodedMap(int(algo), tuple(int(v) for v in shape), ptr[:lens[0]].copy(),
+                      da[:lens[1]].copy(), ind[:lens[2]].copy(), chan_off.reshape(3, sh.C + 1).copy())
+
+
+def cpo_encode(act, shape) -> EncodedMap:
+    return encode(act, shape, ALGO_CPO)
+
+
+def cps_encode(act, shape) -> EncodedMap:
+    return encode(act, shape, ALGO_CPS)
+
+
+def _out_shape(sh: _Shape) -> Tuple[int, int, int]:
+    Oh = (sh.H + 2 * sh.pad - sh.kh) // sh.stride + 1
+    Ow = (sh.W + 2 * sh.pad - sh.kw) // sh.stride + 1
+    return sh.K, Oh, Ow
+
+
+def sparse_conv(m: EncodedMap, weights: np.ndarray) -> np.ndarray:
+    """Algorithm 2 / Algorithm 4 on an encoded map; returns K x Oh x Ow."""
+    sh = _shape(m.shape)
+    weights = np.ascontiguousarray(weights, dtype=np.float32)
+    assert weights.shape == (sh.K, sh.C, sh.kh, sh.kw)
+    out = np.zeros(_out_shape(sh), np.float32)
+    ptr = np.ascontiguousarray(m.ptr); da = np.ascontiguousarray(m.da); ind = np.ascontiguousarray(m.ind)
+    _check(_load().orc_sparse_conv(_p(ptr), _p(da), _p(ind), ctypes.byref(sh), int(m.algo),
+                                   _p(weights), _p(out)), "sparse_conv")
+    return out
+
+
+def decode(m: EncodedMap) -> np.ndarray:
+    sh = _shape(m.shape)
+    act = np.zeros((sh.C, sh.H, sh.W), np.float32)
+    ptr = np.ascontiguousarray(m.ptr); da = np.ascontiguousarray(m.da); ind = np.ascontiguousarray(m.ind)
+    _check(_load().orc_decode(_p(ptr), _p(da), _p(ind), ctypes.byref(sh), int(m.algo), _p(act)),
+           "decode")
+    return act
+
+
+def conv_direct(act: np.ndarray, weights: np.ndarray, shape) -> np.ndarray:
+    """Eq. 1: the dense definition, K x Oh x Ow."""
+    sh = _shape(shape)
+    act = np.ascontiguousarray(act, dtype=np.float32)
+    weights = np.ascontiguousarray(weights, dtype=np.float32)
+    assert act.shape == (sh.C, sh.H, sh.W) and weights.shape == (sh.K, sh.C, sh.kh, sh.kw)
+    out = np.zeros(_out_shape(sh), np.float32)
+    _check(_load().orc_conv_direct(_p(act), ctypes.byref(sh), _p(weights), _p(out)), "conv_direct")
+    return out
+
+
+def im2col_lower(act: np.ndarray, shape) -> np.ndarray:
+    sh = _shape(shape)
+    act = np.ascontiguousarray(act, dtype=np.float32)
+    _, Oh, Ow = _out_shape(sh)
+    low = np.zeros((sh.C * sh.kh * sh.kw, Oh * Ow), np.float32)
+    _check(_load().orc_im2col_lower(_p(act), ctypes.byref(sh), _p(low)), "im2col_lower")
+    return low
+
+
+def gemm(a: np.ndarray, b: np.ndarray) -> np.ndarray:
+    a = np.ascontiguousarray(a, dtype=np.float32)
+    b = np.ascontiguousarray(b, dtype=np.float32)
+    M, Kd = a.shape
+    Kd2, N = b.shape
+    assert Kd == Kd2
+    out = np.zeros((M, N), np.float32)
+    _check(_load().orc_gemm(_p(a), _p(b), ctypes.c_int64(M), ctypes.c_int64(N), ctypes.c_int64(Kd),
+                            _p(out)), "gemm")
+    return out
+
+
+def im2col_conv(act: np.ndarray, weights: np.ndarray, shape) -> np.ndarray:
+    sh = _shape(shape)
+    low = im2col_lower(act, shape)
+    wmat = np.ascontiguousarray(weights, dtype=np.float32).reshape(sh.K, -1)
+    return gemm(wmat, low).reshape(_out_shape(sh))
+
+
+def select_layer_algo(t_im2col, t_cpo, t_cps, mode: int) -> int:
+    a = np.ascontiguousarray(t_im2col, dtype=np.float64)
+    b = np.ascontiguousarray(t_cpo, dtype=np.float64)
+    c = np.ascontiguousarray(t_cps, dtype=np.float64)
+    assert a.size == b.size == c.size
+    return int(_load().orc_select(_p(a), _p(b), _p(c), int(a.size), int(mode)))
