@@ -1,0 +1,187 @@
+/*
+ * cpoconv — convolution of sparse post-ReLU activation maps with Compressed Pattern Overlap
+ * (CPO) and Compressed Pattern Sets (CPS) on AMD MI355X (gfx950), after arXiv 2104.08314
+ * ("High Performance Convolution Using Sparsity and Patterns for Inference in Deep CNNs").
+ *
+ * C ABI.  Conventions shared by every call unless a call says otherwise:
+ *   - Tensors are DEVICE pointers owned by the caller; the library never allocates or frees
+ *     device memory and never synchronises unless stated.  Work is queued on `stream`
+ *     (a hipStream_t passed as void*, NULL = the default stream) of the current device.
+ *   - Batch 1, fp32, square stride and padding.  act is C x H x W row-major; weights are
+ *     K x C x kh x kw row-major; out is K x Oh x Ow row-major with
+ *     Oh = (H + 2 pad - kh) / stride + 1, Ow = (W + 2 pad - kw) / stride + 1 (floor).
+ *   - Every call returns CPOCONV_OK (0) or a negative CPOCONV_ERR_* code.  Arguments are
+ *     validated on the host before anything is queued: a call that returns an error other
+ *     than CPOCONV_ERR_HIP has launched nothing.
+ *   - Limits: 1 <= kh, kw <= CPOCONV_MAX_K; H + 2 pad, W + 2 pad <= CPOCONV_MAX_I;
+ *     C * H * W < 2^31.
+ */
+#ifndef CPOCONV_H
+#define CPOCONV_H
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define CPOCONV_MAX_K 11
+#define CPOCONV_MAX_I 256
+
+/* Skip flags stored in ptr (Section 3.3 names them; the numeric values are this library's). */
+#define CPOCONV_NPF (-2) /* No Ptr Flag: an overlap type of a live channel holds no NZE */
+#define CPOCONV_NPC (-3) /* No Ptr Channel: the whole channel holds no NZE              */
+
+#define CPOCONV_OK 0
+#define CPOCONV_ERR_NULL (-1)        /* a required pointer is NULL                         */
+#define CPOCONV_ERR_SHAPE (-2)       /* shape outside the limits above or inconsistent     */
+#define CPOCONV_ERR_SMALL (-3)       /* a caller buffer is smaller than required           */
+#define CPOCONV_ERR_HIP (-4)         /* a HIP call failed: see cpoconv_last_hip_error()    */
+#define CPOCONV_ERR_ALGO (-5)        /* unknown algorithm / precision / mode value         */
+
+#define CPOCONV_ALGO_IM2COL 0
+#define CPOCONV_ALGO_CPO 1
+#define CPOCONV_ALGO_CPS 2
+
+typedef struct {
+    int32_t C, H, W;     /* input channels, unpadded map height and width */
+    int32_t K;           /* output kernels                                */
+    int32_t kh, kw;      /* kernel height and width                       */
+    int32_t stride, pad; /* both directions                               */
+} cpoconv_shape;
+
+/*
+ * An encoded activation map: the three streams of Section 3.3 in caller-allocated device
+ * buffers, plus a small side band.
+ *   ptr, da, in  ptr (int32), DA (fp32 NZE values), IN (int32 indices) as Algorithms 1 and 3
+ *                define them, for channels in order; inside a channel for the overlap types
+ *                present in the layer, ascending (NOP, overlap2, .., overlap-kw); inside a
+ *                type for partitions, then columns, then rows ascending.
+ *                ptr per channel: CPOCONV_NPC if the channel has no NZE, else per type
+ *                CPOCONV_NPF if the type has no NZE, else [pType, e_0 .. e_{Ow-1}] with e_p
+ *                the cumulative NZE count of the type after partition p or -1 if partition
+ *                p shows no new column of the type; with pad = 0 and stride 1 the NOP type
+ *                is [0, n_first_column, n_first_column + n_last_column] instead.
+ *                IN: index = column inside the first partition holding the cell +
+ *                padded row * kw.  CPS differs in the overlap-kw type only: per column and
+ *                group of four padded rows, 3-4 NZEs -> {index of the first, 4-bit row
+ *                pattern}, 2 -> both indices negated, 1 -> the index negated (Section 3.4).
+ *   *_cap        capacities in elements; required: ptr_cap >= cpoconv_sizes().ptr_cap,
+ *                da_cap and in_cap >= C*H*W.
+ *   chan_off     3*(C+1) int32: offset of every channel in ptr, then in da, then in in, each
+ *                list closed by the total.  Side band for parallel readers (Algorithm 2
+ *                leaves "indexing relative to each channel" out).
+ *   hdr          8 int32: |ptr|, |DA|, |IN|, algorithm (CPOCONV_ALGO_CPO / _CPS), C, Ow, 0, 0.
+ */
+typedef struct {
+    int32_t *ptr;
+    int64_t ptr_cap;
+    float *da;
+    int64_t da_cap;
+    int32_t *in;
+    int64_t in_cap;
+    int32_t *chan_off;
+    int32_t *hdr;
+} cpoconv_map;
+
+/* Buffer sizes for one layer shape (elements unless named bytes). */
+typedef struct {
+    int64_t ptr_cap;       /* largest possible |ptr|                                      */
+    int64_t da_cap;        /* C*H*W                                                        */
+    int64_t in_cap;        /* C*H*W                                                        */
+    int64_t chan_off_len;  /* 3*(C+1)                                                      */
+    int64_t wt_len;        /* prepared weights: C*kh*kw*round_up(K,64) floats              */
+    int64_t out_len;       /* K*Oh*Ow                                                      */
+    int64_t lowered_bytes; /* im2col lowered matrix, fp32: 4*C*kh*kw*Oh*Ow                 */
+    int64_t scratch_bytes; /* scratch for encode and conv calls                            */
+    int32_t Oh, Ow;
+} cpoconv_sizes_t;
+
+/* Host only.  Fills *sizes for the shape.  Errors: NULL, SHAPE. */
+int cpoconv_sizes(const cpoconv_shape *shape, cpoconv_sizes_t *sizes);
+
+/*
+ * CPO encoding of one activation map (Algorithm 1; partition / overlap-type geometry of
+ * Sections 3.1-3.2).  Reads act, writes every stream of *map, chan_off and hdr.  scratch:
+ * device memory of at least sizes.scratch_bytes bytes, contents irrelevant on entry,
+ * clobbered.  Streams, counts and indices are bit-exact functions of act and shape.
+ * Errors: NULL, SHAPE, SMALL (a capacity or scratch_bytes below the requirement), HIP.
+ */
+int cpo_encode(const float *act, const cpoconv_shape *shape, const cpoconv_map *map,
+               void *scratch, int64_t scratch_bytes, void *stream);
+
+/* CPS encoding (Algorithm 3): as cpo_encode, with the overlap-kw indices packed in set4
+ * patterns. */
+int cps_encode(const float *act, const cpoconv_shape *shape, const cpoconv_map *map,
+               void *scratch, int64_t scratch_bytes, void *stream);
+
+/*
+ * Re-lays weights K x C x kh x kw as C x kh x kw x round_up(K,64) (kernel index fastest,
+ * zero filled) for cpo_conv / cps_conv: "the kernel is transformed to a row-major vector"
+ * (Section 3.3), here once per layer for all kernels.  wt: sizes.wt_len floats.
+ * Errors: NULL, SHAPE, HIP.
+ */
+int cpoconv_prepare_weights(const float *weights, const cpoconv_shape *shape, float *wt,
+                            void *stream);
+
+/*
+ * Convolution as sparse matrix-vector products over a CPO map (Algorithm 2): every NZE
+ * meets kh * (pType+1) kernel cells, for all K kernels.  map must come from cpo_encode with
+ * the same shape and stream order must place that call before this one.  out is overwritten
+ * (no accumulation into previous contents).  fp32 multiply-add, fp32 accumulation; the order
+ * of additions is fixed, so results are bitwise repeatable.  scratch as in cpo_encode.
+ * Errors: NULL, SHAPE, SMALL, HIP.
+ */
+int cpo_conv(const cpoconv_map *map, const cpoconv_shape *shape, const float *wt, float *out,
+             void *scratch, int64_t scratch_bytes, void *stream);
+
+/* Convolution over a CPS map (Algorithm 4): indices of the overlap-kw type are rebuilt
+ * from singletons and {first index, pattern} pairs, then as cpo_conv. */
+int cps_conv(const cpoconv_map *map, const cpoconv_shape *shape, const float *wt, float *out,
+             void *scratch, int64_t scratch_bytes, void *stream);
+
+/*
+ * The comparator of Section 3.1: im2col lowering (lowered matrix C*kh*kw x Oh*Ow, row
+ * (c*kh + l)*kw + w, column y*Ow + x, holds the padded input at (c, y*stride + l,
+ * x*stride + w)) followed by a dense matrix product with the K x C*kh*kw kernel matrix on
+ * the matrix cores.  precision 0: fp32 operands; 1: operands rounded to bf16 (nearest even),
+ * fp32 accumulation.  lowered: scratch of sizes.lowered_bytes bytes (the bf16 variant uses
+ * half).  weights in the K x C x kh x kw layout.
+ * Errors: NULL, SHAPE, ALGO (precision), HIP.
+ */
+int im2col_conv(const float *act, const cpoconv_shape *shape, const float *weights,
+                void *lowered, float *out, int precision, void *stream);
+
+/*
+ * Offline per-layer selection (Section 3.5).  Host only.  t_*: times of the three methods on
+ * the same m_inputs offline inputs, any common unit.  mode 0 "favour time": the smaller total
+ * of im2col and CPO; mode 1 "favour space": the smaller total of im2col and CPS; im2col keeps
+ * a tie.  *algo_out receives CPOCONV_ALGO_*.  The array of the method not compared may be NULL.
+ * Errors: NULL, SHAPE (m_inputs < 1), ALGO (mode).
+ */
+int select_layer_algo(const double *t_im2col, const double *t_cpo, const double *t_cps,
+                      int m_inputs, int mode, int *algo_out);
+
+/* Copies map->hdr to the host and waits for the stream: the only synchronising call.
+ * Errors: NULL, HIP. */
+int cpoconv_map_header_to_host(const cpoconv_map *map, int32_t hdr_host[8], void *stream);
+
+/* Host only: partition / overlap-type table of a layer, as the encoders use it.
+ * info: 8 int32 = Ih, Iw, Oh, Ow, number of encoded columns, number of present types,
+ * nop3 (NOP uses the three-entry segment), top (the type CPS packs, or -1).
+ * col_j / col_type / col_p0 / col_what: CPOCONV_MAX_I int32 each, one entry per encoded
+ * column in stream order: padded column, overlap type (0 = NOP), first partition holding the
+ * column, column inside that partition.  Errors: NULL, SHAPE. */
+int cpoconv_geometry(const cpoconv_shape *shape, int32_t info[8], int32_t *col_j,
+                     int32_t *col_type, int32_t *col_p0, int32_t *col_what);
+
+/* Text for an error code (static storage). */
+const char *cpoconv_strerror(int code);
+
+/* hipError_t value of the last failed HIP call made by this library in this thread (0 if none). */
+int cpoconv_last_hip_error(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* CPOCONV_H */

@@ -1,0 +1,266 @@
+// C ABI of libcpoconv: argument validation, layer geometry, host-only calls.  Every device
+// step is queued by the launch_* functions next to the kernels.
+#include <string.h>
+
+#include "common.hpp"
+
+namespace cpoconv {
+
+static thread_local int g_last_hip_error = 0;
+
+void set_hip_error(hipError_t e) { g_last_hip_error = static_cast<int>(e); }
+
+int check_shape(const cpoconv_shape *s)
+{
+    if (s->C < 1 || s->H < 1 || s->W < 1 || s->K < 1) return CPOCONV_ERR_SHAPE;
+    if (s->kh < 1 || s->kw < 1 || s->kh > CPOCONV_MAX_K || s->kw > CPOCONV_MAX_K)
+        return CPOCONV_ERR_SHAPE;
+    if (s->stride < 1 || s->pad < 0 || s->pad > CPOCONV_MAX_I) return CPOCONV_ERR_SHAPE;
+    if (s->H > CPOCONV_MAX_I || s->W > CPOCONV_MAX_I) return CPOCONV_ERR_SHAPE;
+    const int Ih = s->H + 2 * s->pad, Iw = s->W + 2 * s->pad;
+    if (Ih > CPOCONV_MAX_I || Iw > CPOCONV_MAX_I) return CPOCONV_ERR_SHAPE;
+    if (Ih < s->kh || Iw < s->kw) return CPOCONV_ERR_SHAPE;
+    if (static_cast<int64_t>(s->C) * s->H * s->W >= (int64_t{1} << 31)) return CPOCONV_ERR_SHAPE;
+    if (static_cast<int64_t>(s->K) * s->C * s->kh * s->kw >= (int64_t{1} << 31))
+        return CPOCONV_ERR_SHAPE;
+    return CPOCONV_OK;
+}
+
+// A padded column j lies in partitions p with p*stride <= j <= p*stride + kw - 1, 0 <= p < Ow
+// (Section 3.1: Ow partitions of width kw separated by the stride).  Its overlap type is the
+// number of such partitions minus one; the first of them indexes the column (Section 3.2).
+int build_geometry(const cpoconv_shape *s, Geometry *g)
+{
+    const int rc = check_shape(s);
+    if (rc != CPOCONV_OK) return rc;
+    memset(g, 0, sizeof(*g));
+    g->C = s->C; g->H = s->H; g->W = s->W; g->K = s->K;
+    g->kh = s->kh; g->kw = s->kw; g->stride = s->stride; g->pad = s->pad;
+    g->Ih = s->H + 2 * s->pad;
+    g->Iw = s->W + 2 * s->pad;
+    g->Oh = (g->Ih - s->kh) / s->stride + 1;
+    g->Ow = (g->Iw - s->kw) / s->stride + 1;
+    g->Kpad = (s->K + 63) / 64 * 64;
+
+    int type_of[kMaxCols], p0_of[kMaxCols];
+    int count[kMaxTypes] = {0};
+    for (int j = 0; j < g->Iw; ++j) {
+        type_of[j] = -1;
+        const int lo_num = j - s->kw + 1;
+        const int p_lo = lo_num <= 0 ? 0 : (lo_num + s->stride - 1) / s->stride;
+        int p_hi = j / s->stride;
+        if (p_hi > g->Ow - 1) p_hi = g->Ow - 1;
+        const int m = p_hi - p_lo + 1;
+        const bool real = j >= s->pad && j < s->pad + s->W;
+        if (m < 1 || !real) continue;
+        type_of[j] = m - 1;
+        p0_of[j] = p_lo;
+        ++count[m - 1];
+    }
+    int n = 0;
+    for (int t = 0; t < s->kw; ++t) {
+        if (count[t] == 0) continue;
+        g->type_id[g->n_types] = static_cast<uint8_t>(t);
+        g->type_begin[g->n_types] = static_cast<uint16_t>(n);
+        for (int j = 0; j < g->Iw; ++j) {
+            if (type_of[j] != t) continue;
+            g->col_j[n] = static_cast<uint8_t>(j);
+            g->col_p0[n] = static_cast<uint8_t>(p0_of[j]);
+            g->col_what[n] = static_cast<uint8_t>(j - p0_of[j] * s->stride);
+            ++n;
+        }
+        ++g->n_types;
+    }
+    g->type_begin[g->n_types] = static_cast<uint16_t>(n);
+    g->n_cols = n;
+    g->nop3 = (s->stride == 1 && s->pad == 0 && s->kw >= 2 && g->Ow >= 2) ? 1 : 0;
+    g->top = -1;
+    g->top_slot = -1;
+    const int top = (s->kw + s->stride - 1) / s->stride - 1;
+    if (top >= 1) {
+        for (int i = 0; i < g->n_types; ++i)
+            if (g->type_id[i] == top) { g->top = top; g->top_slot = i; }
+    }
+    return CPOCONV_OK;
+}
+
+int64_t max_ptr_len(const Geometry &g)
+{
+    int64_t per_channel = 0;
+    for (int i = 0; i < g.n_types; ++i)
+        per_channel += (g.nop3 && g.type_id[i] == 0) ? 3 : 1 + g.Ow;
+    if (per_channel < 1) per_channel = 1;
+    return per_channel * g.C;
+}
+
+// Scratch layout: [0, 16*(C+1)) per-channel stream lengths of the encoder's first pass,
+// rounded up to 256 bytes; then C*H*W int32 for the indices cps_conv rebuilds.
+int64_t scratch_bytes_for(const Geometry &g)
+{
+    const int64_t counts = (16 * static_cast<int64_t>(g.C + 1) + 255) / 256 * 256;
+    return counts + 4 * static_cast<int64_t>(g.C) * g.H * g.W;
+}
+
+}  // namespace cpoconv
+
+using namespace cpoconv;
+
+extern "C" {
+
+int cpoconv_sizes(const cpoconv_shape *shape, cpoconv_sizes_t *sizes)
+{
+    if (!shape || !sizes) return CPOCONV_ERR_NULL;
+    Geometry g;
+    const int rc = build_geometry(shape, &g);
+    if (rc != CPOCONV_OK) return rc;
+    const int64_t chw = static_cast<int64_t>(g.C) * g.H * g.W;
+    sizes->ptr_cap = max_ptr_len(g);
+    sizes->da_cap = chw;
+    sizes->in_cap = chw;
+    sizes->chan_off_len = 3 * static_cast<int64_t>(g.C + 1);
+    sizes->wt_len = static_cast<int64_t>(g.C) * g.kh * g.kw * g.Kpad;
+    sizes->out_len = static_cast<int64_t>(g.K) * g.Oh * g.Ow;
+    sizes->lowered_bytes = 4 * static_cast<int64_t>(g.C) * g.kh * g.kw * g.Oh * g.Ow;
+    sizes->scratch_bytes = scratch_bytes_for(g);
+    sizes->Oh = g.Oh;
+    sizes->Ow = g.Ow;
+    return CPOCONV_OK;
+}
+
+static int encode_common(const float *act, const cpoconv_shape *shape, const cpoconv_map *map,
+                         void *scratch, int64_t scratch_bytes, void *stream, int algo)
+{
+    if (!act || !shape || !map || !scratch) return CPOCONV_ERR_NULL;
+    if (!map->ptr || !map->da || !map->in || !map->chan_off || !map->hdr) return CPOCONV_ERR_NULL;
+    Geometry g;
+    const int rc = build_geometry(shape, &g);
+    if (rc != CPOCONV_OK) return rc;
+    const int64_t chw = static_cast<int64_t>(g.C) * g.H * g.W;
+    if (map->ptr_cap < max_ptr_len(g) || map->da_cap < chw || map->in_cap < chw)
+        return CPOCONV_ERR_SMALL;
+    if (scratch_bytes < scratch_bytes_for(g)) return CPOCONV_ERR_SMALL;
+    return launch_encode(act, g, *map, algo, scratch, static_cast<hipStream_t>(stream));
+}
+
+int cpo_encode(const float *act, const cpoconv_shape *shape, const cpoconv_map *map,
+               void *scratch, int64_t scratch_bytes, void *stream)
+{
+    return encode_common(act, shape, map, scratch, scratch_bytes, stream, CPOCONV_ALGO_CPO);
+}
+
+int cps_encode(const float *act, const cpoconv_shape *shape, const cpoconv_map *map,
+               void *scratch, int64_t scratch_bytes, void *stream)
+{
+    return encode_common(act, shape, map, scratch, scratch_bytes, stream, CPOCONV_ALGO_CPS);
+}
+
+int cpoconv_prepare_weights(const float *weights, const cpoconv_shape *shape, float *wt,
+                            void *stream)
+{
+    if (!weights || !shape || !wt) return CPOCONV_ERR_NULL;
+    Geometry g;
+    const int rc = build_geometry(shape, &g);
+    if (rc != CPOCONV_OK) return rc;
+    return launch_prepare_weights(weights, g, wt, static_cast<hipStream_t>(stream));
+}
+
+static int conv_common(const cpoconv_map *map, const cpoconv_shape *shape, const float *wt,
+                       float *out, void *scratch, int64_t scratch_bytes, void *stream, int algo)
+{
+    if (!map || !shape || !wt || !out || !scratch) return CPOCONV_ERR_NULL;
+    if (!map->ptr || !map->da || !map->in || !map->chan_off || !map->hdr) return CPOCONV_ERR_NULL;
+    Geometry g;
+    const int rc = build_geometry(shape, &g);
+    if (rc != CPOCONV_OK) return rc;
+    if (scratch_bytes < scratch_bytes_for(g)) return CPOCONV_ERR_SMALL;
+    return launch_sparse_conv(*map, g, algo, wt, out, scratch, static_cast<hipStream_t>(stream));
+}
+
+int cpo_conv(const cpoconv_map *map, const cpoconv_shape *shape, const float *wt, float *out,
+             void *scratch, int64_t scratch_bytes, void *stream)
+{
+    return conv_common(map, shape, wt, out, scratch, scratch_bytes, stream, CPOCONV_ALGO_CPO);
+}
+
+int cps_conv(const cpoconv_map *map, const cpoconv_shape *shape, const float *wt, float *out,
+             void *scratch, int64_t scratch_bytes, void *stream)
+{
+    return conv_common(map, shape, wt, out, scratch, scratch_bytes, stream, CPOCONV_ALGO_CPS);
+}
+
+int im2col_conv(const float *act, const cpoconv_shape *shape, const float *weights, void *lowered,
+                float *out, int precision, void *stream)
+{
+    if (!act || !shape || !weights || !lowered || !out) return CPOCONV_ERR_NULL;
+    Geometry g;
+    const int rc = build_geometry(shape, &g);
+    if (rc != CPOCONV_OK) return rc;
+    if (precision != 0 && precision != 1) return CPOCONV_ERR_ALGO;
+    return launch_im2col_conv(act, g, weights, lowered, out, precision,
+                              static_cast<hipStream_t>(stream));
+}
+
+int select_layer_algo(const double *t_im2col, const double *t_cpo, const double *t_cps,
+                      int m_inputs, int mode, int *algo_out)
+{
+    if (!algo_out || !t_im2col) return CPOCONV_ERR_NULL;
+    if (mode != 0 && mode != 1) return CPOCONV_ERR_ALGO;
+    const double *t_sparse = mode == 0 ? t_cpo : t_cps;
+    if (!t_sparse) return CPOCONV_ERR_NULL;
+    if (m_inputs < 1) return CPOCONV_ERR_SHAPE;
+    double total_dense = 0.0, total_sparse = 0.0;
+    for (int i = 0; i < m_inputs; ++i) {
+        total_dense += t_im2col[i];
+        total_sparse += t_sparse[i];
+    }
+    if (total_sparse < total_dense)
+        *algo_out = mode == 0 ? CPOCONV_ALGO_CPO : CPOCONV_ALGO_CPS;
+    else
+        *algo_out = CPOCONV_ALGO_IM2COL;
+    return CPOCONV_OK;
+}
+
+int cpoconv_map_header_to_host(const cpoconv_map *map, int32_t hdr_host[8], void *stream)
+{
+    if (!map || !map->hdr || !hdr_host) return CPOCONV_ERR_NULL;
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    CPOCONV_HIP_TRY(hipMemcpyAsync(hdr_host, map->hdr, 8 * sizeof(int32_t), hipMemcpyDeviceToHost, st));
+    CPOCONV_HIP_TRY(hipStreamSynchronize(st));
+    return CPOCONV_OK;
+}
+
+int cpoconv_geometry(const cpoconv_shape *shape, int32_t info[8], int32_t *col_j,
+                     int32_t *col_type, int32_t *col_p0, int32_t *col_what)
+{
+    if (!shape || !info || !col_j || !col_type || !col_p0 || !col_what) return CPOCONV_ERR_NULL;
+    Geometry g;
+    const int rc = build_geometry(shape, &g);
+    if (rc != CPOCONV_OK) return rc;
+    info[0] = g.Ih; info[1] = g.Iw; info[2] = g.Oh; info[3] = g.Ow;
+    info[4] = g.n_cols; info[5] = g.n_types; info[6] = g.nop3; info[7] = g.top;
+    for (int i = 0; i < g.n_types; ++i)
+        for (int n = g.type_begin[i]; n < g.type_begin[i + 1]; ++n) {
+            col_j[n] = g.col_j[n];
+            col_type[n] = g.type_id[i];
+            col_p0[n] = g.col_p0[n];
+            col_what[n] = g.col_what[n];
+        }
+    return CPOCONV_OK;
+}
+
+const char *cpoconv_strerror(int code)
+{
+    switch (code) {
+    case CPOCONV_OK: return "ok";
+    case CPOCONV_ERR_NULL: return "a required pointer is NULL";
+    case CPOCONV_ERR_SHAPE: return "shape outside the supported limits or inconsistent";
+    case CPOCONV_ERR_SMALL: return "a caller buffer is smaller than required";
+    case CPOCONV_ERR_HIP: return "a HIP call failed (see cpoconv_last_hip_error)";
+    case CPOCONV_ERR_ALGO: return "unknown algorithm, precision or mode value";
+    default: return "unknown error code";
+    }
+}
+
+int cpoconv_last_hip_error(void) { return g_last_hip_error; }
+
+}  // extern "C"

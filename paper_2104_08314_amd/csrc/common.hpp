@@ -1,0 +1,60 @@
+// Internal declarations shared by the translation units of libcpoconv.
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "cpoconv.h"
+
+namespace cpoconv {
+
+constexpr int kMaxTypes = CPOCONV_MAX_K;   // overlap types 0 .. kw-1
+constexpr int kMaxCols = CPOCONV_MAX_I;    // padded columns
+constexpr int kLanes = 64;                 // wavefront width on CDNA
+
+// Partition / overlap-type table of a layer (Sections 3.1-3.2), built on the host once per
+// call and passed to kernels by value.  "Columns" are the encoded ones (covered by a
+// partition and part of the unpadded map) in stream order: overlap type ascending, then
+// padded column ascending (which is also first-partition ascending).
+struct Geometry {
+    int32_t C, H, W, K, kh, kw, stride, pad;
+    int32_t Ih, Iw, Oh, Ow;
+    int32_t n_cols;                  // encoded columns
+    int32_t n_types;                 // present overlap types
+    int32_t nop3;                    // NOP type is the 3-entry segment (pad 0, stride 1)
+    int32_t top;                     // overlap type CPS packs, -1 if none
+    int32_t top_slot;                // its slot in type_id, -1 if none
+    int32_t Kpad;                    // K rounded up to a multiple of 64
+    uint8_t type_id[kMaxTypes];      // present types, ascending
+    uint16_t type_begin[kMaxTypes + 1];  // column range of each present type
+    uint8_t col_j[kMaxCols];         // padded column
+    uint8_t col_p0[kMaxCols];        // first partition holding it
+    uint8_t col_what[kMaxCols];      // column inside that partition
+};
+
+int check_shape(const cpoconv_shape *s);           // CPOCONV_OK or CPOCONV_ERR_SHAPE
+int build_geometry(const cpoconv_shape *s, Geometry *g);
+int64_t max_ptr_len(const Geometry &g);
+int64_t scratch_bytes_for(const Geometry &g);
+
+void set_hip_error(hipError_t e);
+
+#define CPOCONV_HIP_TRY(expr)                         \
+    do {                                              \
+        hipError_t e__ = (expr);                      \
+        if (e__ != hipSuccess) {                      \
+            ::cpoconv::set_hip_error(e__);            \
+            return CPOCONV_ERR_HIP;                   \
+        }                                             \
+    } while (0)
+
+// launchers (defined next to their kernels)
+int launch_encode(const float *act, const Geometry &g, const cpoconv_map &map, int algo,
+                  void *scratch, hipStream_t stream);
+int launch_prepare_weights(const float *w, const Geometry &g, float *wt, hipStream_t stream);
+int launch_sparse_conv(const cpoconv_map &map, const Geometry &g, int algo, const float *wt,
+                       float *out, void *scratch, hipStream_t stream);
+int launch_im2col_conv(const float *act, const Geometry &g, const float *w, void *lowered,
+                       float *out, int precision, hipStream_t stream);
+
+}  // namespace cpoconv

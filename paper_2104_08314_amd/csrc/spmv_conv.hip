@@ -1,0 +1,275 @@
+// Convolution as sparse matrix-vector products over a CPO / CPS map (Algorithms 2 and 4).
+//
+// Mapping to the GPU: the 64 lanes of a wavefront are 64 output kernels k, so one NZE
+// (value, index) is wavefront-uniform and skipping zeros costs no divergence; the
+// kh * (pType+1) multiply-adds of convSpMv become that many 64-wide FMAs against weights
+// laid out kernel-index-fastest.  A workgroup owns a tile of output rows x columns (and 64
+// kernels); ptr's per-partition cumulative counts give exactly the DA / IN ranges of the
+// partitions that reach the tile's columns, and since a column's NZEs are sorted by row, the
+// rows that reach a wavefront's output rows form one contiguous lane range found by a
+// ballot.  No two wavefronts add to the same output and every output adds its terms in
+// stream order, so results are bitwise repeatable.
+#include "common.hpp"
+
+namespace cpoconv {
+
+namespace {
+
+__device__ __forceinline__ int lane_id() { return threadIdx.x & (kLanes - 1); }
+
+__device__ __forceinline__ int wave_inclusive_max(int v)
+{
+#pragma unroll
+    for (int d = 1; d < kLanes; d <<= 1) {
+        const int n = __shfl_up(v, d, kLanes);
+        if (lane_id() >= d) v = max(v, n);
+    }
+    return v;
+}
+
+__device__ __forceinline__ int wave_inclusive_sum(int v)
+{
+#pragma unroll
+    for (int d = 1; d < kLanes; d <<= 1) {
+        const int n = __shfl_up(v, d, kLanes);
+        if (lane_id() >= d) v += n;
+    }
+    return v;
+}
+
+__device__ __forceinline__ int bcast_i(int v, int src) { return __builtin_amdgcn_readlane(v, src); }
+__device__ __forceinline__ float bcast_f(float v, int src)
+{
+    return __int_as_float(__builtin_amdgcn_readlane(__float_as_int(v), src));
+}
+
+// ---------------------------------------------------------------------------------------
+// Index reconstruction of Algorithm 4 for a whole map: IN_cps -> one index per NZE, laid out
+// like DA.  One workgroup per channel.  In the overlap-kw type an entry < 0 is a singleton; a
+// run of entries >= 0 alternates {first index, pattern}, so an entry's role is the parity of
+// its distance to the last negative entry before it.
+// ---------------------------------------------------------------------------------------
+constexpr int kExpThreads = 256;
+
+__global__ __launch_bounds__(kExpThreads) void cps_expand_kernel(const Geometry g, const int32_t *__restrict__ ptr,
+                                                               const int32_t *__restrict__ in,
+                                                               const int32_t *__restrict__ chan_off,
+                                                               int32_t *__restrict__ in_full)
+{
+    __shared__ int32_t wave_a[kExpThreads / kLanes], wave_b[kExpThreads / kLanes];
+    __shared__ int32_t s_top_count;
+    const int c = blockIdx.x, tid = threadIdx.x, lane = lane_id(), wave = tid / kLanes;
+    const int da0 = chan_off[(g.C + 1) + c], da1 = chan_off[(g.C + 1) + c + 1];
+    const int in0 = chan_off[2 * (g.C + 1) + c], in1 = chan_off[2 * (g.C + 1) + c + 1];
+    const int nnz = da1 - da0;
+    if (nnz == 0) return;
+    // NZEs of the overlap-kw type.  It is the highest type, so its segment closes the channel's
+    // ptr: a single NPF, or 1+Ow entries whose last non-negative one is the type's NZE count.
+    int top_count = 0;
+    if (g.top_slot >= 0) {
+        if (tid == 0) {
+            const int seg_end = chan_off[c + 1];
+            int n = 0;
+            if (ptr[seg_end - 1] != CPOCONV_NPF)
+                for (int p = g.Ow - 1; p >= 0; --p) {
+                    const int e = ptr[seg_end - g.Ow + p];
+                    if (e >= 0) { n = e; break; }
+                }
+            s_top_count = n;
+        }
+        __syncthreads();
+        top_count = s_top_count;
+    }
+    const int lower = nnz - top_count;  // NZEs of the other types: their IN entries are plain
+    for (int i = tid; i < lower; i += kExpThreads) in_full[da0 + i] = in[in0 + i];
+    if (top_count == 0) return;
+
+    const int e0 = in0 + lower, n_entries = in1 - e0;
+    int carry_neg = -1;   // position (relative to e0) of the last negative entry seen so far
+    int carry_out = 0;    // NZEs emitted so far
+    for (int base = 0; base < n_entries; base += kExpThreads) {
+        const int e = base + tid;
+        const bool valid = e < n_entries;
+        const int entry = valid ? in[e0 + e] : -1;
+        // inclusive max scan of "position if negative"
+        int m = wave_inclusive_max(entry < 0 ? e : -1);
+        if (lane == kLanes - 1) wave_a[wave] = m;
+        __syncthreads();
+        int prev = carry_neg;
+        for (int w = 0; w < wave; ++w) prev = max(prev, wave_a[w]);
+        const int last_neg = max(m, prev);
+        const bool is_index = valid && entry >= 0 && (((e - last_neg - 1) & 1) == 0);
+        const int pattern = (is_index && e + 1 < n_entries) ? in[e0 + e + 1] : 0;
+        const int emits = !valid ? 0 : (entry < 0 ? 1 : (is_index ? __popc(pattern) : 0));
+        int s = wave_inclusive_sum(emits);
+        if (lane == kLanes - 1) wave_b[wave] = s;
+        __syncthreads();
+        int before = carry_out;
+        for (int w = 0; w < wave; ++w) before += wave_b[w];
+        const int at = da0 + lower + before + s - emits;
+        if (valid && entry < 0) {
+            in_full[at] = -entry;
+        } else if (is_index) {
+            // NZEs of the set: first index, then + kw per row after the first set bit
+            const int first = __ffs(pattern) - 1;
+            int k = 0;
+            for (int b = first; b < 4; ++b)
+                if (pattern & (1 << b)) in_full[at + k++] = entry + g.kw * (b - first);
+        }
+        int tot_neg = carry_neg, tot_out = carry_out;
+        for (int w = 0; w < kExpThreads / kLanes; ++w) { tot_neg = max(tot_neg, wave_a[w]); tot_out += wave_b[w]; }
+        __syncthreads();
+        carry_neg = tot_neg;
+        carry_out = tot_out;
+    }
+}
+
+// ---------------------------------------------------------------------------------------
+// General SpMV convolution (any kh, kw, stride): accumulators of a TY x TX output tile for 64
+// kernels live in LDS, [row][col][k] with k fastest (conflict-free).  Wavefront w of the
+// workgroup owns the tile rows w*RW .. w*RW+RW-1.
+// ---------------------------------------------------------------------------------------
+constexpr int kConvThreads = 256;
+constexpr int kConvWaves = kConvThreads / kLanes;
+constexpr int kTY = 8, kTX = 8;
+constexpr int kRW = kTY / kConvWaves;              // output rows per wavefront
+constexpr int kMspan = kTX + kMaxTypes + 1;        // partitions a tile can reach, plus one
+
+__global__ __launch_bounds__(kConvThreads) void spmv_conv_lds_kernel(const Geometry g, const int32_t *__restrict__ ptr,
+                                                                    const float *__restrict__ da,
+                                                                    const int32_t *__restrict__ in,
+                                                                    const int32_t *__restrict__ chan_off,
+                                                                    const float *__restrict__ wt,
+                                                                    float *__restrict__ out)
+{
+    extern __shared__ float smem[];
+    float *acc = smem;                               // kTY*kTX*64
+    float *wl = smem + kTY * kTX * kLanes;           // kh*kw*64: weights of the current channel
+    __shared__ int32_t Mtab[kMaxTypes][kMspan];      // running NZE count at the tile's partitions
+    __shared__ int32_t type_da0[kMaxTypes];          // DA start of each type inside the channel
+
+    const int tid = threadIdx.x, lane = lane_id(), wave = tid / kLanes;
+    const int x0 = blockIdx.x * kTX, y0 = blockIdx.y * kTY, k0 = blockIdx.z * kLanes;
+    const int ylo = y0 + wave * kRW;                       // this wavefront's output rows
+    const int yhi = min(min(ylo + kRW, y0 + kTY), g.Oh);
+    const int taps = g.kh * g.kw;
+    const int s = g.stride;
+
+    for (int i = tid; i < kTY * kTX * kLanes; i += kConvThreads) acc[i] = 0.0f;
+    __syncthreads();
+
+    for (int c = 0; c < g.C; ++c) {
+        const int pbase = chan_off[c];
+        if (ptr[pbase] == CPOCONV_NPC) continue;       // skip channel (uniform)
+        __syncthreads();                                 // previous channel done with wl / Mtab
+        for (int i = tid; i < taps * kLanes; i += kConvThreads)
+            wl[i] = wt[(static_cast<int64_t>(c) * taps + i / kLanes) * g.Kpad + k0 + (i & (kLanes - 1))];
+        if (wave == 0) {
+            // walk the channel's ptr: one segment per present type
+            int seg = pbase, da_run = chan_off[(g.C + 1) + c];
+            for (int i = 0; i < g.n_types; ++i) {
+                const int t = g.type_id[i];
+                const int p_lo = max(0, x0 - t), p_hi = min(g.Ow - 1, x0 + kTX - 1);
+                const int span = p_hi - p_lo + 2;          // entries M[p_lo-1 .. p_hi]
+                int count = 0;
+                if (g.nop3 && t == 0) {
+                    const int n_first = ptr[seg + 1], n_both = ptr[seg + 2];
+                    // running count after partition p: n_first for p < Ow-1, n_both for the last
+                    if (lane < span) {
+                        const int p = p_lo - 1 + lane;
+                        Mtab[i][lane] = p < 0 ? 0 : (p < g.Ow - 1 ? n_first : n_both);
+                    }
+                    count = n_both;
+                    seg += 3;
+                } else if (ptr[seg] == CPOCONV_NPF) {
+                    if (lane < span) Mtab[i][lane] = 0;
+                    seg += 1;
+                } else {
+                    // running maximum of the cumulative entries = count after each partition,
+                    // the "-1 takes the previous entry" rule of Algorithm 2 without writing ptr
+                    int carry = 0;
+                    for (int b = 0; b < g.Ow; b += kLanes) {
+                        const int p = b + lane;
+                        const int e = p < g.Ow ? ptr[seg + 1 + p] : -1;
+                        const int m = max(wave_inclusive_max(e), carry);
+                        if (p < g.Ow && p >= p_lo - 1 && p <= p_hi) Mtab[i][p - (p_lo - 1)] = m;
+                        carry = bcast_i(m, kLanes - 1);
+                    }
+                    if (p_lo == 0 && lane == 0) Mtab[i][0] = 0;
+                    count = carry;
+                    seg += 1 + g.Ow;
+                }
+                if (lane == 0) type_da0[i] = da_run;
+                da_run += count;
+            }
+        }
+        __syncthreads();
+
+        for (int i = 0; i < g.n_types; ++i) {
+            const int t = g.type_id[i];
+            const int p_lo = max(0, x0 - t), p_hi = min(g.Ow - 1, x0 + kTX - 1);
+            const int base = type_da0[i];
+            for (int p = p_lo; p <= p_hi; ++p) {
+                const int beg = Mtab[i][p - p_lo], end = Mtab[i][p - p_lo + 1];
+                for (int n0 = beg; n0 < end; n0 += kLanes) {
+                    const int n = n0 + lane;
+                    const bool valid = n < end;
+                    const int idx = valid ? in[base + n] : 0;
+                    const float v = valid ? da[base + n] : 0.0f;
+                    const int h = idx / g.kw, wh = idx - h * g.kw;   // padded row, column in partition
+                    const int qh = h / s, rh = h - qh * s;
+                    // rows of the map that reach output rows [ylo, yhi)
+                    const bool hit = valid && h >= ylo * s && h <= (yhi - 1) * s + g.kh - 1;
+                    unsigned long long bits = __ballot(hit);
+                    while (bits) {
+                        const int src = __ffsll(static_cast<long long>(bits)) - 1;
+                        bits &= bits - 1;
+                        const float sv = bcast_f(v, src);
+                        const int swh = bcast_i(wh, src), sqh = bcast_i(qh, src), srh = bcast_i(rh, src);
+                        // kernel rows l = rh, rh+s, ..: output row (h-l)/s = qh, qh-1, ..
+                        for (int l = srh, y = sqh; l < g.kh; l += s, --y) {
+                            if (y < ylo) break;
+                            if (y >= yhi) continue;
+                            for (int ii = 0; ii <= t; ++ii) {
+                                const int x = p + ii - x0;
+                                if (x < 0 || x >= kTX) continue;
+                                const int wcol = swh - ii * s;
+                                acc[((y - y0) * kTX + x) * kLanes + lane] += sv * wl[(l * g.kw + wcol) * kLanes + lane];
+                            }
+                        }
+                    }
+                }
+            }
+        }
+    }
+    // each wavefront stores its own rows
+    const int k = k0 + lane;
+    if (k < g.K)
+        for (int y = ylo; y < yhi; ++y)
+            for (int x = 0; x < kTX && x0 + x < g.Ow; ++x)
+                out[(static_cast<int64_t>(k) * g.Oh + y) * g.Ow + x0 + x] = acc[((y - y0) * kTX + x) * kLanes + lane];
+}
+
+}  // namespace
+
+int launch_sparse_conv(const cpoconv_map &map, const Geometry &g, int algo, const float *wt, float *out,
+                       void *scratch, hipStream_t stream)
+{
+    const int32_t *indices = map.in;
+    if (algo == CPOCONV_ALGO_CPS && g.top_slot >= 0) {
+        const int64_t counts_bytes = (16 * static_cast<int64_t>(g.C + 1) + 255) / 256 * 256;
+        int32_t *in_full = reinterpret_cast<int32_t *>(static_cast<char *>(scratch) + counts_bytes);
+        hipLaunchKernelGGL(cps_expand_kernel, dim3(g.C), dim3(kExpThreads), 0, stream, g, map.ptr, map.in,
+                           map.chan_off, in_full);
+        CPOCONV_HIP_TRY(hipGetLastError());
+        indices = in_full;
+    }
+    const dim3 grid((g.Ow + kTX - 1) / kTX, (g.Oh + kTY - 1) / kTY, g.Kpad / kLanes);
+    const size_t lds = (static_cast<size_t>(kTY) * kTX + static_cast<size_t>(g.kh) * g.kw) * kLanes * sizeof(float);
+    hipLaunchKernelGGL(spmv_conv_lds_kernel, grid, dim3(kConvThreads), lds, stream, g, map.ptr, map.da, indices,
+                       map.chan_off, wt, out);
+    CPOCONV_HIP_TRY(hipGetLastError());
+    return CPOCONV_OK;
+}
+
+}  // namespace cpoconv

@@ -1,0 +1,115 @@
+"""Host-side checks of the C-ABI library that need no GPU: it loads, exports every symbol the
+header declares, rejects bad arguments before touching the device, and its host-only calls
+(sizes, geometry table, selection) agree with the oracle."""
+import ctypes
+import os
+import re
+
+import numpy as np
+import pytest
+
+import oracle
+from paper_2104_08314_amd import api, workloads
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def _declared_functions():
+    text = open(os.path.join(ROOT, "include", "cpoconv.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(?:int|const char \*)\s*(\w+)\s*\(", text)))
+
+
+def test_library_exports_every_declared_symbol():
+    lib = api.lib()
+    names = _declared_functions()
+    assert len(names) >= 12
+    for n in names:
+        assert hasattr(lib, n), n
+    assert sorted(api.EXPORTS) == names
+
+
+SHAPES = [s.shape_tuple for s in workloads.all_layers()] + [
+    (2, 8, 8, 2, 4, 4, 1, 1), (2, 9, 10, 2, 5, 5, 1, 2), (2, 11, 8, 2, 3, 2, 3, 0),
+    (4, 6, 5, 2, 1, 3, 1, 0), (2, 5, 6, 2, 3, 1, 1, 0), (2, 6, 3, 2, 3, 3, 1, 0),
+    (2, 6, 4, 2, 3, 3, 1, 0), (3, 13, 9, 2, 3, 5, 2, 2), (2, 9, 9, 2, 3, 3, 1, 2),
+    (1, 1, 1, 1, 3, 3, 5, 3),
+]
+
+
+@pytest.mark.parametrize("shape", SHAPES)
+def test_geometry_table_matches_oracle(shape):
+    info, cols = api.cpoconv_geometry(shape)
+    g = oracle.geometry(shape)
+    assert (info["Ih"], info["Iw"], info["Oh"], info["Ow"]) == (g.Ih, g.Iw, g.Oh, g.Ow)
+    assert bool(info["nop3"]) == g.nop3 and info["top"] == g.top
+    enc = [j for j in range(g.Iw) if g.real[j] and g.cls[j] >= 0]
+    order = sorted(enc, key=lambda j: (g.cls[j], j))
+    assert cols["j"].tolist() == order
+    assert cols["type"].tolist() == [int(g.cls[j]) for j in order]
+    assert cols["p0"].tolist() == [int(g.p0[j]) for j in order]
+    assert cols["what"].tolist() == [int(g.what[j]) for j in order]
+    assert info["n_types"] == int(g.present.sum())
+
+
+@pytest.mark.parametrize("shape", SHAPES)
+def test_sizes(shape):
+    C, H, W, K, kh, kw, s, p = shape
+    sz = api.cpoconv_sizes(shape)
+    g = oracle.geometry(shape)
+    assert (sz.Oh, sz.Ow) == (g.Oh, g.Ow)
+    assert sz.da_cap == sz.in_cap == C * H * W
+    assert sz.out_len == K * g.Oh * g.Ow
+    assert sz.lowered_bytes == 4 * C * kh * kw * g.Oh * g.Ow
+    assert sz.wt_len == C * kh * kw * ((K + 63) // 64 * 64)
+    # the ptr capacity covers the oracle's ptr for a dense map (no skip flags)
+    act = np.ones((C, H, W), np.float32)
+    assert sz.ptr_cap >= oracle.cpo_encode(act, shape).ptr.size
+    assert sz.ptr_cap >= C
+
+
+def test_bad_arguments_are_rejected_on_the_host():
+    lib = api.lib()
+    good = api.Shape(4, 8, 8, 4, 3, 3, 1, 1)
+    sz = api.Sizes()
+    assert lib.cpoconv_sizes(None, ctypes.byref(sz)) == api.ERR_NULL
+    assert lib.cpoconv_sizes(ctypes.byref(good), None) == api.ERR_NULL
+    for bad in [(0, 8, 8, 4, 3, 3, 1, 1), (4, 8, 8, 4, 3, 3, 0, 1), (4, 8, 8, 4, 3, 3, 1, -1),
+                (4, 2, 8, 4, 5, 3, 1, 1), (4, 8, 8, 4, 12, 3, 1, 1), (4, 300, 8, 4, 3, 3, 1, 1),
+                (4, 8, 255, 4, 3, 3, 1, 1), (4, 8, 8, 0, 3, 3, 1, 1)]:
+        sh = api.Shape(*bad)
+        assert lib.cpoconv_sizes(ctypes.byref(sh), ctypes.byref(sz)) == api.ERR_SHAPE, bad
+    # encode / conv / im2col: NULL pointers, short buffers, unknown precision -> no launch
+    m = api._Map()
+    one = ctypes.c_void_p(256)   # never dereferenced: validation fails first
+    assert lib.cpo_encode(None, ctypes.byref(good), ctypes.byref(m), one, ctypes.c_int64(1 << 30), None) == api.ERR_NULL
+    assert lib.cpo_encode(one, ctypes.byref(good), ctypes.byref(m), one, ctypes.c_int64(1 << 30), None) == api.ERR_NULL
+    full = api._Map(256, 10, 256, 10, 256, 10, 256, 256)
+    assert lib.cpo_encode(one, ctypes.byref(good), ctypes.byref(full), one, ctypes.c_int64(1 << 30), None) == api.ERR_SMALL
+    assert lib.cps_encode(one, ctypes.byref(good), ctypes.byref(full), one, ctypes.c_int64(1 << 30), None) == api.ERR_SMALL
+    big = api._Map(256, 1 << 20, 256, 1 << 20, 256, 1 << 20, 256, 256)
+    assert lib.cpo_encode(one, ctypes.byref(good), ctypes.byref(big), one, ctypes.c_int64(8), None) == api.ERR_SMALL
+    assert lib.cpo_conv(ctypes.byref(big), ctypes.byref(good), None, one, one, ctypes.c_int64(1 << 30), None) == api.ERR_NULL
+    assert lib.cps_conv(ctypes.byref(big), ctypes.byref(good), one, one, one, ctypes.c_int64(8), None) == api.ERR_SMALL
+    assert lib.im2col_conv(one, ctypes.byref(good), one, one, one, 7, None) == api.ERR_ALGO
+    assert lib.im2col_conv(one, ctypes.byref(good), one, None, one, 0, None) == api.ERR_NULL
+    assert lib.cpoconv_prepare_weights(one, ctypes.byref(good), None, None) == api.ERR_NULL
+    assert lib.cpoconv_map_header_to_host(None, None, None) == api.ERR_NULL
+    assert api.cpoconv_strerror(api.ERR_SMALL) != api.cpoconv_strerror(api.ERR_SHAPE)
+    assert "unknown" in api.cpoconv_strerror(-99)
+
+
+def test_select_layer_algo_matches_oracle_and_rules():
+    rng = np.random.default_rng(1)
+    for _ in range(200):
+        m = int(rng.integers(1, 7))
+        t = rng.integers(1, 6, size=(3, m)).astype(float)      # small integers: ties happen
+        for mode in (0, 1):
+            assert api.select_layer_algo(t[0], t[1], t[2], mode) == oracle.select_layer_algo(t[0], t[1], t[2], mode)
+    assert api.select_layer_algo([2.0], [1.0], None, 0) == api.ALGO_CPO
+    assert api.select_layer_algo([2.0], None, [1.0], 1) == api.ALGO_CPS
+    assert api.select_layer_algo([1.0], [1.0], [1.0], 0) == api.ALGO_IM2COL
+    with pytest.raises(api.CpoconvError):
+        api.select_layer_algo([1.0], [1.0], [1.0], 2)
+    with pytest.raises(api.CpoconvError):
+        api.select_layer_algo([1.0], None, [1.0], 0)
