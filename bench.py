@@ -1,0 +1,307 @@
+#!/usr/bin/env python3
+"""Benchmark of the CPO / CPS convolution hot path on one MI355X.
+
+A step is one pass of the whole path over one layer: CPO encode + SpMV conv, CPS encode +
+SpMV conv, im2col lowering + MFMA GEMM (fp32), and the per-layer selection.  Inputs are
+resident in HBM before the timed region.  Prints ONE JSON line.
+
+  python bench.py [--gpus 1] [--steps K] [--warmup W] [--config 2] [--all-layers]
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0
+FP32_VECTOR_PEAK_TFLOPS = 157.3
+FP32_MFMA_PEAK_TFLOPS = 157.3
+BF16_MFMA_PEAK_TFLOPS = 2500.0
+
+
+def _events(torch):
+    return torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+
+
+def _time_us(torch, fn, reps):
+    """Average duration in microseconds of `fn` over `reps` back-to-back calls (HIP events on
+    the current stream, which is the stream the library launches on)."""
+    e0, e1 = _events(torch)
+    torch.cuda.synchronize()
+    e0.record()
+    for _ in range(reps):
+        fn()
+    e1.record()
+    torch.cuda.synchronize()
+    return e0.elapsed_time(e1) * 1000.0 / reps
+
+
+class LayerRun:
+    """One layer resident on the device with every stage as a callable."""
+
+    def __init__(self, api, torch, workloads, spec, m=0):
+        self.api, self.spec, self.shape = api, spec, spec.shape_tuple
+        act_np, w_np = workloads.make_layer(spec, m)
+        self.act_np, self.w_np = act_np, w_np
+        self.buf = api.LayerBuffers(self.shape)
+        self.act = torch.from_numpy(act_np).cuda()
+        self.w = torch.from_numpy(w_np).cuda()
+        api.cpoconv_prepare_weights(self.w, self.shape, self.buf.wt)   # once per layer, untimed
+        torch.cuda.synchronize()
+        b = self.buf
+        self.stages = {
+            "cpo_encode": lambda: api.cpo_encode(self.act, self.shape, b.cpo, b.scratch),
+            "cpo_conv": lambda: api.cpo_conv(b.cpo, self.shape, b.wt, b.out, b.scratch),
+            "cps_encode": lambda: api.cps_encode(self.act, self.shape, b.cps, b.scratch),
+            "cps_conv": lambda: api.cps_conv(b.cps, self.shape, b.wt, b.out, b.scratch),
+            "im2col_f32": lambda: api.im2col_conv(self.act, self.shape, self.w, b.lowered, b.out, 0),
+            "im2col_bf16": lambda: api.im2col_conv(self.act, self.shape, self.w, b.lowered, b.out, 1),
+        }
+
+    def set_input(self, torch, act_np):
+        self.act.copy_(torch.from_numpy(act_np))
+
+    def lengths(self):
+        for k in ("cpo_encode", "cps_encode"):
+            self.stages[k]()
+        h_cpo, h_cps = self.buf.cpo.header(), self.buf.cps.header()
+        return {"ptr": h_cpo[0], "nnz": h_cpo[1], "in_cpo": h_cpo[2], "in_cps": h_cps[2]}
+
+
+def algorithmic_figures(spec, lens):
+    """Bytes and flops the method itself must move / compute for one layer (4-byte elements)."""
+    C, H, W, K, kh, kw, s, p = spec.shape_tuple
+    nnz, ptr = lens["nnz"], lens["ptr"]
+    out_elems = K * spec.Oh * spec.Ow
+    wbytes = 4 * K * C * kh * kw
+    S = spec.s_im2col
+    return {
+        "cpo_encode_bytes": 4 * C * H * W + 8 * nnz + 4 * ptr,
+        "cps_encode_bytes": 4 * C * H * W + 4 * nnz + 4 * lens["in_cps"] + 4 * ptr,
+        "cpo_conv_bytes": 8 * nnz + 4 * ptr + wbytes + 4 * out_elems,
+        "cps_conv_bytes": 4 * nnz + 4 * lens["in_cps"] + 4 * ptr + wbytes + 4 * out_elems,
+        # every NZE meets kh*kw/stride^2 kernel cells on average, for K kernels
+        "sparse_flops": 2.0 * nnz * kh * kw * K / (s * s),
+        "im2col_f32_bytes": 4 * C * H * W + 2 * 4 * S + wbytes + 4 * out_elems,
+        "im2col_bf16_bytes": 4 * C * H * W + 2 * 2 * S + wbytes + 4 * out_elems,
+        "dense_flops": float(spec.dense_flops),
+        "s_im2col": S,
+        "cr_cpo": S / float(ptr + 2 * nnz),
+        "cr_cps": S / float(ptr + nnz + lens["in_cps"]),
+        "cr_cpo_with_side_band": S / float(ptr + 2 * nnz + 3 * (C + 1)),
+        "cr_cps_with_side_band": S / float(ptr + nnz + lens["in_cps"] + 3 * (C + 1)),
+    }
+
+
+def stage_roofline(name, us, fig):
+    """Roofline entry of one stage: the bound that binds and the achieved fraction of it."""
+    t = us * 1e-6
+    if name.endswith("encode"):
+        a = fig[name + "_bytes"] / t / 1e9
+        return {"bound": "hbm", "achieved": a, "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": a / HBM_PEAK_GBS}
+    if name.endswith("conv") and name[:3] in ("cpo", "cps"):
+        gbs = fig[name + "_bytes"] / t / 1e9
+        tf = fig["sparse_flops"] / t / 1e12
+        # the binding roof is the one that takes longer at peak
+        if fig["sparse_flops"] / (FP32_VECTOR_PEAK_TFLOPS * 1e12) >= fig[name + "_bytes"] / (HBM_PEAK_GBS * 1e9):
+            return {"bound": "alu", "achieved": tf, "peak": FP32_VECTOR_PEAK_TFLOPS, "unit": "TFLOP/s",
+                    "frac": tf / FP32_VECTOR_PEAK_TFLOPS, "hbm_gbs": gbs}
+        return {"bound": "hbm", "achieved": gbs, "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": gbs / HBM_PEAK_GBS,
+                "alu_tflops": tf}
+    peak = FP32_MFMA_PEAK_TFLOPS if name == "im2col_f32" else BF16_MFMA_PEAK_TFLOPS
+    tf = fig["dense_flops"] / t / 1e12
+    return {"bound": "mfma", "achieved": tf, "peak": peak, "unit": "TFLOP/s", "frac": tf / peak,
+            "hbm_gbs": fig[name + "_bytes"] / t / 1e9}
+
+
+def measure_layer(api, torch, workloads, spec, reps, warm):
+    run = LayerRun(api, torch, workloads, spec)
+    lens = run.lengths()
+    fig = algorithmic_figures(spec, lens)
+    times = {}
+    for name, fn in run.stages.items():
+        for _ in range(warm):
+            fn()
+        times[name] = _time_us(torch, fn, reps)
+    row = {
+        "layer": spec.name, "shape": list(spec.shape_tuple), "nnz": lens["nnz"],
+        "density": lens["nnz"] / float(spec.C * spec.H * spec.W),
+        "us": {k: round(v, 2) for k, v in times.items()},
+        "cpo_total_us": round(times["cpo_encode"] + times["cpo_conv"], 2),
+        "cps_total_us": round(times["cps_encode"] + times["cps_conv"], 2),
+        "speedup_cpo_vs_im2col_f32": times["im2col_f32"] / (times["cpo_encode"] + times["cpo_conv"]),
+        "speedup_cps_vs_im2col_f32": times["im2col_f32"] / (times["cps_encode"] + times["cps_conv"]),
+        "cr_cpo": fig["cr_cpo"], "cr_cps": fig["cr_cps"],
+        "cr_cpo_with_side_band": fig["cr_cpo_with_side_band"],
+        "cr_cps_with_side_band": fig["cr_cps_with_side_band"],
+        "roofline": {k: stage_roofline(k, v, fig) for k, v in times.items()},
+    }
+    return run, row, times, fig
+
+
+def offline_selection(api, torch, workloads, run, spec, reps, m_inputs=5):
+    """Section 3.5: total time of each method over M offline inputs, then the two modes."""
+    t = {"im2col": [], "cpo": [], "cps": []}
+    for m in range(m_inputs):
+        run.set_input(torch, workloads.make_activation(spec, m))
+        st = run.stages
+        t["im2col"].append(_time_us(torch, st["im2col_f32"], reps))
+        t["cpo"].append(_time_us(torch, lambda: (st["cpo_encode"](), st["cpo_conv"]()), reps))
+        t["cps"].append(_time_us(torch, lambda: (st["cps_encode"](), st["cps_conv"]()), reps))
+    run.set_input(torch, run.act_np)
+    names = {api.ALGO_IM2COL: "im2col", api.ALGO_CPO: "cpo", api.ALGO_CPS: "cps"}
+    return t, {"favour_time": names[api.select_layer_algo(t["im2col"], t["cpo"], t["cps"], 0)],
+               "favour_space": names[api.select_layer_algo(t["im2col"], t["cpo"], t["cps"], 1)]}
+
+
+def cpu_baseline(spec, act_np, w_np):
+    """The CPU oracle as it stands, one thread, on the same layer: CPO encode + Algorithm 2."""
+    import oracle
+
+    shape = spec.shape_tuple
+    oracle.cpo_encode(act_np, shape)                      # builds / loads the library
+    t0 = time.perf_counter()
+    m = oracle.cpo_encode(act_np, shape)
+    t1 = time.perf_counter()
+    oracle.sparse_conv(m, w_np)
+    t2 = time.perf_counter()
+    oracle.conv_direct(act_np, w_np, shape)
+    t3 = time.perf_counter()
+    return {"value": (t2 - t0) * 1e6, "unit": "us", "cores": 1, "kind": "oracle",
+            "sample": "the whole layer once: oracle CPO encode (%.0f us) + sequential Algorithm 2 convolution "
+                      "(%.0f us), double accumulation, gcc -O2, one thread; dense 7-loop definition of the same "
+                      "layer: %.0f us" % ((t1 - t0) * 1e6, (t2 - t1) * 1e6, (t3 - t2) * 1e6)}
+
+
+def traffic_from_profiles(kernel_key):
+    """HBM bytes per launch measured with rocprofv3 --pmc (FETCH_SIZE / WRITE_SIZE runs), if a
+    summary under profiles/ records them as a line `traffic_bytes_per_launch[<key>]: <n>`."""
+    pdir = os.path.join(ROOT, "profiles")
+    if not os.path.isdir(pdir):
+        return None
+    tag = f"traffic_bytes_per_launch[{kernel_key}]:"
+    for fn in sorted(os.listdir(pdir)):
+        if not fn.endswith((".txt", ".md")):
+            continue
+        with open(os.path.join(pdir, fn)) as f:
+            for line in f:
+                if line.strip().startswith(tag):
+                    try:
+                        return float(line.split(":", 1)[1].split()[0])
+                    except ValueError:
+                        return None
+    return None
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=200)
+    ap.add_argument("--warmup", type=int, default=20)
+    ap.add_argument("--config", type=int, default=2, help="workload whose first layer is timed")
+    ap.add_argument("--all-layers", action="store_true",
+                    help="also measure every layer of the five workloads (per-layer report on stderr and "
+                         "in gpurun_out/layers.json)")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        sys.exit("bench.py: this build runs on one GPU only (the path is a single-GPU kernel pipeline); "
+                 "use --gpus 1")
+
+    import torch
+
+    from paper_2104_08314_amd import api, workloads
+
+    api.lib()
+    if not torch.cuda.is_available():
+        sys.exit("bench.py: no GPU visible")
+    torch.cuda.set_device(0)
+
+    spec = workloads.layers(args.config)[0]
+    run, row, times, fig = measure_layer(api, torch, workloads, spec, reps=max(args.steps, 20), warm=max(args.warmup, 5))
+    sel_times, selection = offline_selection(api, torch, workloads, run, spec, reps=20)
+
+    st = run.stages
+
+    def step():
+        st["cpo_encode"](); st["cpo_conv"]()
+        st["cps_encode"](); st["cps_conv"]()
+        st["im2col_f32"]()
+        api.select_layer_algo(sel_times["im2col"], sel_times["cpo"], sel_times["cps"], 0)
+        api.select_layer_algo(sel_times["im2col"], sel_times["cpo"], sel_times["cps"], 1)
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        step()
+    torch.cuda.synchronize()
+    ms_per_step = (time.perf_counter() - t0) * 1e3 / args.steps
+
+    # dominant kernel of the step: the longest single-kernel stage
+    single_kernel = {"cpo_conv": times["cpo_conv"], "cpo_encode": times["cpo_encode"] / 2.0,
+                     "im2col_f32": times["im2col_f32"]}
+    dominant = max(single_kernel, key=single_kernel.get)
+    roof = dict(row["roofline"][dominant])
+    roof["kernel"] = {"cpo_conv": "spmv_conv (CPO map)", "cpo_encode": "encode (two launches)",
+                      "im2col_f32": "im2col lowering + MFMA GEMM fp32"}[dominant]
+    roof["avg_launch_us"] = times[dominant]
+    roof["traffic"] = traffic_from_profiles(dominant)
+
+    result = {
+        "metric": "per-layer CPO/CPS conv time (us) + HBM GB/s, speedup and CR vs im2col",
+        "value": round(times["cpo_encode"] + times["cpo_conv"], 3),
+        "unit": "us per layer (CPO encode + SpMV conv)",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": round(ms_per_step, 5),
+        "higher_is_better": False, "scaling": "weak", "vs_baseline": None,
+        "dtype": "f32", "data": "synthetic",
+        "config": {"workload": f"configs[{args.config - 1}]: {spec.name} 3x3 s{spec.stride} p{spec.pad}, "
+                               f"C={spec.C} H=W={spec.H} K={spec.K}, batch 1, "
+                               f"{100 * (1 - row['density']):.1f}% zeros",
+                   "step": "cpo_encode+cpo_conv+cps_encode+cps_conv+im2col_conv(fp32)+select_layer_algo(2 modes)"},
+        "layer": row,
+        "selection": selection,
+        "selection_times_us": {k: [round(x, 2) for x in v] for k, v in sel_times.items()},
+        "roofline": roof,
+    }
+    if not args.no_cpu_baseline:
+        result["cpu_baseline"] = cpu_baseline(spec, run.act_np, run.w_np)
+
+    if args.all_layers:
+        rows = []
+        for s in workloads.all_layers():
+            r, lrow, _, _ = measure_layer(api, torch, workloads, s, reps=50, warm=5)
+            _, sel = offline_selection(api, torch, workloads, r, s, reps=10)
+            lrow["selection"] = sel
+            rows.append(lrow)
+            print(f"{s.name:24s} nnz={lrow['nnz']:7d} enc {lrow['us']['cpo_encode']:8.1f} conv {lrow['us']['cpo_conv']:9.1f} "
+                  f"cps {lrow['cps_total_us']:9.1f} im2col {lrow['us']['im2col_f32']:8.1f} bf16 {lrow['us']['im2col_bf16']:8.1f} "
+                  f"CR {lrow['cr_cpo']:5.1f}/{lrow['cr_cps']:5.1f} pick {sel['favour_time']}/{sel['favour_space']}",
+                  file=sys.stderr, flush=True)
+            del r
+            torch.cuda.empty_cache()
+        os.makedirs(os.path.join(ROOT, "gpurun_out"), exist_ok=True)
+        with open(os.path.join(ROOT, "gpurun_out", "layers.json"), "w") as f:
+            json.dump(rows, f, indent=1)
+        cfg5 = [r for r in rows if r["layer"].startswith("cfg5")]
+        result["config5_end_to_end_us"] = {
+            "all_im2col_f32": round(sum(r["us"]["im2col_f32"] for r in cfg5), 1),
+            "hybrid_favour_time": round(sum(r["cpo_total_us"] if r["selection"]["favour_time"] == "cpo"
+                                            else r["us"]["im2col_f32"] for r in cfg5), 1),
+            "hybrid_favour_space": round(sum(r["cps_total_us"] if r["selection"]["favour_space"] == "cps"
+                                             else r["us"]["im2col_f32"] for r in cfg5), 1),
+            "layers_cpo_selected": sum(r["selection"]["favour_time"] == "cpo" for r in cfg5),
+            "layers_cps_selected": sum(r["selection"]["favour_space"] == "cps" for r in cfg5),
+        }
+    print(json.dumps(result))
+
+
+if __name__ == "__main__":
+    main()

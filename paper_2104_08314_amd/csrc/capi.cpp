@@ -93,12 +93,21 @@ int64_t max_ptr_len(const Geometry &g)
     return per_channel * g.C;
 }
 
-// Scratch layout: [0, 16*(C+1)) per-channel stream lengths of the encoder's first pass,
-// rounded up to 256 bytes; then C*H*W int32 for the indices cps_conv rebuilds.
+// Scratch layout: per-channel stream lengths of the encoder's first pass | one int32 per NZE
+// for the indices cps_conv rebuilds | partial sums of the register-tile convolution.
+int64_t scratch_counts_bytes(const Geometry &g)
+{
+    return (16 * static_cast<int64_t>(g.C + 1) + 255) / 256 * 256;
+}
+
+int64_t scratch_indices_bytes(const Geometry &g)
+{
+    return (4 * static_cast<int64_t>(g.C) * g.H * g.W + 255) / 256 * 256;
+}
+
 int64_t scratch_bytes_for(const Geometry &g)
 {
-    const int64_t counts = (16 * static_cast<int64_t>(g.C + 1) + 255) / 256 * 256;
-    return counts + 4 * static_cast<int64_t>(g.C) * g.H * g.W;
+    return scratch_counts_bytes(g) + scratch_indices_bytes(g) + tile_kernel_partial_bytes(g);
 }
 
 }  // namespace cpoconv

@@ -255,14 +255,18 @@ __global__ __launch_bounds__(kConvThreads) void spmv_conv_lds_kernel(const Geome
 int launch_sparse_conv(const cpoconv_map &map, const Geometry &g, int algo, const float *wt, float *out,
                        void *scratch, hipStream_t stream)
 {
+    char *base = static_cast<char *>(scratch);
     const int32_t *indices = map.in;
     if (algo == CPOCONV_ALGO_CPS && g.top_slot >= 0) {
-        const int64_t counts_bytes = (16 * static_cast<int64_t>(g.C + 1) + 255) / 256 * 256;
-        int32_t *in_full = reinterpret_cast<int32_t *>(static_cast<char *>(scratch) + counts_bytes);
+        int32_t *in_full = reinterpret_cast<int32_t *>(base + scratch_counts_bytes(g));
         hipLaunchKernelGGL(cps_expand_kernel, dim3(g.C), dim3(kExpThreads), 0, stream, g, map.ptr, map.in,
                            map.chan_off, in_full);
         CPOCONV_HIP_TRY(hipGetLastError());
         indices = in_full;
+    }
+    if (tile_kernel_supports(g)) {
+        float *partial = reinterpret_cast<float *>(base + scratch_counts_bytes(g) + scratch_indices_bytes(g));
+        return launch_sparse_conv_tile(map, indices, g, wt, out, partial, stream);
     }
     const dim3 grid((g.Ow + kTX - 1) / kTX, (g.Oh + kTY - 1) / kTY, g.Kpad / kLanes);
     const size_t lds = (static_cast<size_t>(kTY) * kTX + static_cast<size_t>(g.kh) * g.kw) * kLanes * sizeof(float);
