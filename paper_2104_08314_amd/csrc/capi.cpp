@@ -93,8 +93,9 @@ int64_t max_ptr_len(const Geometry &g)
     return per_channel * g.C;
 }
 
-// Scratch layout: per-channel stream lengths of the encoder's first pass | one int32 per NZE
-// for the indices cps_conv rebuilds | partial sums of the register-tile convolution.
+// Scratch layout: per-channel stream lengths of the encoder's first pass | the convolution's
+// table of resolved ptr offsets | one int32 per NZE for the indices cps_conv rebuilds | partial
+// sums of the register-tile convolution.
 int64_t scratch_counts_bytes(const Geometry &g)
 {
     return (16 * static_cast<int64_t>(g.C + 1) + 255) / 256 * 256;
@@ -105,9 +106,15 @@ int64_t scratch_indices_bytes(const Geometry &g)
     return (4 * static_cast<int64_t>(g.C) * g.H * g.W + 255) / 256 * 256;
 }
 
+int64_t scratch_mtab_bytes(const Geometry &g)
+{
+    const int types = g.n_types > 0 ? g.n_types : 1;
+    return (4 * static_cast<int64_t>(g.C) * types * (g.Ow + 1) + 255) / 256 * 256;
+}
+
 int64_t scratch_bytes_for(const Geometry &g)
 {
-    return scratch_counts_bytes(g) + scratch_indices_bytes(g) + tile_kernel_partial_bytes(g);
+    return scratch_counts_bytes(g) + scratch_mtab_bytes(g) + scratch_indices_bytes(g) + tile_kernel_partial_bytes(g);
 }
 
 }  // namespace cpoconv

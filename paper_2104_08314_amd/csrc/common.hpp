@@ -57,11 +57,12 @@ int launch_sparse_conv(const cpoconv_map &map, const Geometry &g, int algo, cons
 // register-tile SpMV kernel (spmv_conv_tile.hip)
 bool tile_kernel_supports(const Geometry &g);
 int64_t tile_kernel_partial_bytes(const Geometry &g);
-int launch_sparse_conv_tile(const cpoconv_map &map, const int32_t *indices, const Geometry &g, const float *wt,
+int launch_sparse_conv_tile(const cpoconv_map &map, const int32_t *indices, const int32_t *mtab, const Geometry &g, const float *wt,
                             float *out, float *partial, hipStream_t stream);
 // byte offsets of the regions of the caller's scratch buffer
 int64_t scratch_counts_bytes(const Geometry &g);
 int64_t scratch_indices_bytes(const Geometry &g);
+int64_t scratch_mtab_bytes(const Geometry &g);
 int launch_im2col_conv(const float *act, const Geometry &g, const float *w, void *lowered,
                        float *out, int precision, hipStream_t stream);
 

@@ -44,42 +44,65 @@ __device__ __forceinline__ float bcast_f(float v, int src)
 }
 
 // ---------------------------------------------------------------------------------------
-// Index reconstruction of Algorithm 4 for a whole map: IN_cps -> one index per NZE, laid out
-// like DA.  One workgroup per channel.  In the overlap-kw type an entry < 0 is a singleton; a
-// run of entries >= 0 alternates {first index, pattern}, so an entry's role is the parity of
-// its distance to the last negative entry before it.
+// Prologue of every convolution call, one workgroup per channel.
+//  (1) ptr -> table of absolute DA offsets: mtab[c][type][0] = first NZE of the type in DA,
+//      mtab[c][type][1+p] = one past the last NZE of partitions 0..p.  This is Algorithm 2's
+//      "an entry of -1 takes the previous entry" applied once for all readers (a running
+//      maximum, since live entries are cumulative counts), with NPC / NPF resolved to empty
+//      ranges.
+//  (2) CPS only - index reconstruction of Algorithm 4: IN_cps -> one index per NZE, laid out
+//      like DA.  In the overlap-kw type an entry < 0 is a singleton; a run of entries >= 0
+//      alternates {first index, pattern}, so an entry's role is the parity of its distance to
+//      the last negative entry before it.
 // ---------------------------------------------------------------------------------------
 constexpr int kExpThreads = 256;
 
-__global__ __launch_bounds__(kExpThreads) void cps_expand_kernel(const Geometry g, const int32_t *__restrict__ ptr,
-                                                               const int32_t *__restrict__ in,
-                                                               const int32_t *__restrict__ chan_off,
-                                                               int32_t *__restrict__ in_full)
+__global__ __launch_bounds__(kExpThreads) void conv_prologue_kernel(const Geometry g, const int32_t *__restrict__ ptr,
+                                                                  const int32_t *__restrict__ in,
+                                                                  const int32_t *__restrict__ chan_off,
+                                                                  int32_t *__restrict__ mtab,
+                                                                  int32_t *__restrict__ in_full)
 {
     __shared__ int32_t wave_a[kExpThreads / kLanes], wave_b[kExpThreads / kLanes];
-    __shared__ int32_t s_top_count;
     const int c = blockIdx.x, tid = threadIdx.x, lane = lane_id(), wave = tid / kLanes;
     const int da0 = chan_off[(g.C + 1) + c], da1 = chan_off[(g.C + 1) + c + 1];
     const int in0 = chan_off[2 * (g.C + 1) + c], in1 = chan_off[2 * (g.C + 1) + c + 1];
+
+    // Segments of the channel: NPC = none; per present type NPF (1 entry), the 3-entry NOP form,
+    // or [pType, e_0 .. e_{Ow-1}].  Every thread walks them (uniform loads); a type's NZE count is
+    // the running maximum of its entries.
+    int seg = chan_off[c], base = da0, top_base = da1;
+    const bool npc = ptr[seg] == CPOCONV_NPC;
+    for (int i = 0; i < g.n_types; ++i) {
+        int32_t *row = mtab + (static_cast<int64_t>(c) * g.n_types + i) * (g.Ow + 1);
+        int live = 0;
+        if (!npc) live = (g.nop3 && g.type_id[i] == 0) ? 2 : (ptr[seg] == CPOCONV_NPF ? 0 : 1);
+        int e = -1;   // Ow <= 256 = workgroup size: one entry per thread
+        if (tid < g.Ow) {
+            if (live == 1) e = ptr[seg + 1 + tid];
+            else if (live == 2) e = tid < g.Ow - 1 ? ptr[seg + 1] : ptr[seg + 2];
+        }
+        int m = wave_inclusive_max(e);
+        if (lane == kLanes - 1) wave_a[wave] = m;
+        __syncthreads();
+        int total = 0;
+        for (int w = 0; w < kExpThreads / kLanes; ++w) {
+            total = max(total, wave_a[w]);
+            if (w < wave) m = max(m, wave_a[w]);
+        }
+        if (tid < g.Ow) row[1 + tid] = base + max(m, 0);
+        if (tid == 0) row[0] = base;
+        if (i == g.top_slot) top_base = base;
+        base += total;
+        seg += npc ? 0 : (live == 2 ? 3 : (live == 1 ? 1 + g.Ow : 1));
+        __syncthreads();
+    }
+    if (in_full == nullptr) return;
+
     const int nnz = da1 - da0;
     if (nnz == 0) return;
-    // NZEs of the overlap-kw type.  It is the highest type, so its segment closes the channel's
-    // ptr: a single NPF, or 1+Ow entries whose last non-negative one is the type's NZE count.
-    int top_count = 0;
-    if (g.top_slot >= 0) {
-        if (tid == 0) {
-            const int seg_end = chan_off[c + 1];
-            int n = 0;
-            if (ptr[seg_end - 1] != CPOCONV_NPF)
-                for (int p = g.Ow - 1; p >= 0; --p) {
-                    const int e = ptr[seg_end - g.Ow + p];
-                    if (e >= 0) { n = e; break; }
-                }
-            s_top_count = n;
-        }
-        __syncthreads();
-        top_count = s_top_count;
-    }
+    // NZEs of the overlap-kw type: it is the highest type, so it closes the channel
+    const int top_count = da1 - top_base;
     const int lower = nnz - top_count;  // NZEs of the other types: their IN entries are plain
     for (int i = tid; i < lower; i += kExpThreads) in_full[da0 + i] = in[in0 + i];
     if (top_count == 0) return;
@@ -256,17 +279,23 @@ int launch_sparse_conv(const cpoconv_map &map, const Geometry &g, int algo, cons
                        void *scratch, hipStream_t stream)
 {
     char *base = static_cast<char *>(scratch);
+    int32_t *mtab = reinterpret_cast<int32_t *>(base + scratch_counts_bytes(g));
+    int32_t *in_full = nullptr;
     const int32_t *indices = map.in;
     if (algo == CPOCONV_ALGO_CPS && g.top_slot >= 0) {
-        int32_t *in_full = reinterpret_cast<int32_t *>(base + scratch_counts_bytes(g));
-        hipLaunchKernelGGL(cps_expand_kernel, dim3(g.C), dim3(kExpThreads), 0, stream, g, map.ptr, map.in,
-                           map.chan_off, in_full);
-        CPOCONV_HIP_TRY(hipGetLastError());
+        in_full = reinterpret_cast<int32_t *>(base + scratch_counts_bytes(g) + scratch_mtab_bytes(g));
         indices = in_full;
     }
-    if (tile_kernel_supports(g)) {
-        float *partial = reinterpret_cast<float *>(base + scratch_counts_bytes(g) + scratch_indices_bytes(g));
-        return launch_sparse_conv_tile(map, indices, g, wt, out, partial, stream);
+    const bool tile = tile_kernel_supports(g);
+    if (tile || in_full != nullptr) {
+        hipLaunchKernelGGL(conv_prologue_kernel, dim3(g.C), dim3(kExpThreads), 0, stream, g, map.ptr, map.in,
+                           map.chan_off, mtab, in_full);
+        CPOCONV_HIP_TRY(hipGetLastError());
+    }
+    if (tile) {
+        float *partial = reinterpret_cast<float *>(base + scratch_counts_bytes(g) + scratch_mtab_bytes(g) +
+                                                   scratch_indices_bytes(g));
+        return launch_sparse_conv_tile(map, indices, mtab, g, wt, out, partial, stream);
     }
     const dim3 grid((g.Ow + kTX - 1) / kTX, (g.Oh + kTY - 1) / kTY, g.Kpad / kLanes);
     const size_t lds = (static_cast<size_t>(kTY) * kTX + static_cast<size_t>(g.kh) * g.kw) * kLanes * sizeof(float);

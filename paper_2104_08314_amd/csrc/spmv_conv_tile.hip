@@ -18,45 +18,64 @@
 //      FMAs of convSpMv that land inside the tile, all with compile-time register indices.
 // The tile's partial sums go to a [slice][y][x][k] buffer (k fastest: coalesced); a second
 // kernel adds the slices in order and transposes to the K x Oh x Ow output.
+#include <stdlib.h>
+
 #include "common.hpp"
 
 namespace cpoconv {
 
 namespace {
 
-constexpr int kWavesPerWg = 4;
 constexpr int kTabBytes = 8 * 1024;  // LDS budget of the per-channel range table
+constexpr int kGroup = 4;
+constexpr int kChunksAhead = 4;
 
 __device__ __forceinline__ int lane_id() { return threadIdx.x & (kLanes - 1); }
+#ifdef CPOCONV_PHASE_TIMING
+// development aid: wall-clock stamps (100 MHz) of wavefront 0 of every workgroup
+#define CPOCONV_STAMP(slot)                                                                                   \
+    do {                                                                                                      \
+        if (threadIdx.x == 0) {                                                                               \
+            const int wg = (blockIdx.z * gridDim.y + blockIdx.y) * gridDim.x + blockIdx.x;                    \
+            if (wg < 64 && (slot) < 32) a.dbg[wg * 32 + (slot)] = wall_clock64();                             \
+        }                                                                                                     \
+    } while (0)
+#else
+#define CPOCONV_STAMP(slot) do {} while (0)
+#endif
 __device__ __forceinline__ int uni(int v) { return __builtin_amdgcn_readfirstlane(v); }
 
 struct TileArgs {
-    const int32_t *ptr;
     const float *da;
     const int32_t *in;        // one index per NZE, laid out like DA
-    const int32_t *chan_off;  // 3*(C+1)
+    const int32_t *mtab;      // [C][n_types][Ow+1] absolute DA offsets (prologue kernel)
     const float *wt;          // [C][kh*kw][Kpad]
     float *partial;           // [slices][Ypad][Xpad][Kpad]
+    float *out;               // K x Oh x Ow, written directly when there is one slice
+    long long *dbg;           // phase stamps (development builds only)
     int32_t slices;           // channel slices across workgroups
     int32_t Ypad, Xpad;
     int32_t batch;            // channels per table refill
+    int32_t red_slots;        // accumulator-sized LDS buffers available to the reduction
 };
 
-template <int KH, int KW, int S, int TY, int TX, int KPL>
-__global__ __launch_bounds__(kWavesPerWg *kLanes) void spmv_conv_tile_kernel(const Geometry g, const TileArgs a)
+template <int KH, int KW, int S, int TY, int TX, int KPL, int NW>
+__global__ __launch_bounds__(NW *kLanes) void spmv_conv_tile_kernel(const Geometry g, const TileArgs a)
 {
+    constexpr int kWavesPerWg = NW;
     constexpr int RH = (TY - 1) * S + KH;      // rows of the input patch behind the tile
     constexpr int RW = (TX - 1) * S + KW;      // columns of it
     constexpr int NCELL = RH * RW;
     constexpr int NDREG = (NCELL + kLanes - 1) / kLanes;
     constexpr int TAPS = KH * KW;
     constexpr int SPAN_MAX = TX + KW + 1;      // table entries per (channel, type): M[p_lo-1 .. p_hi]
+    constexpr int G = kGroup;                  // channels whose loads are in flight together
+    constexpr int MAXC = kChunksAhead;         // 64-NZE chunks of a channel loaded ahead
 
     extern __shared__ int32_t smem[];
-    // layout: lastp[n_types][SPAN_MAX] | tab[batch][n_types][SPAN_MAX] | patch[4][NCELL] ; the
-    // reduction buffer (TY*TX*KPL*64 floats) overlays all of it after the channel loop
-    int32_t *lastp = smem;
-    int32_t *tab = lastp + g.n_types * SPAN_MAX;
+    // layout: tab[batch][n_types][SPAN_MAX] | patch[NW][G][NCELL] ; the reduction buffers
+    // overlay all of it after the channel loop
+    int32_t *tab = smem;
     float *patch_all = reinterpret_cast<float *>(tab + a.batch * g.n_types * SPAN_MAX);
 
     const int tid = threadIdx.x, lane = lane_id(), wave = tid / kLanes;
@@ -64,12 +83,13 @@ __global__ __launch_bounds__(kWavesPerWg *kLanes) void spmv_conv_tile_kernel(con
     const int ngroups = g.Kpad / (kLanes * KPL);
     const int kg = blockIdx.z % ngroups, slice = blockIdx.z / ngroups;
     const int kbase = kg * kLanes * KPL;
-    float *patch = patch_all + wave * NCELL;
+    float *patch = patch_all + wave * (G * NCELL);   // G private patches per wavefront
 
     // channel range of this workgroup
     const int per_slice = (g.C + a.slices - 1) / a.slices;
     const int c_begin = slice * per_slice, c_end = min(g.C, c_begin + per_slice);
 
+    CPOCONV_STAMP(0);
     float acc[TY][TX][KPL];
 #pragma unroll
     for (int y = 0; y < TY; ++y)
@@ -78,263 +98,379 @@ __global__ __launch_bounds__(kWavesPerWg *kLanes) void spmv_conv_tile_kernel(con
 #pragma unroll
             for (int k = 0; k < KPL; ++k) acc[y][x][k] = 0.0f;
 
-    for (int i = lane; i < NCELL; i += kLanes) patch[i] = 0.0f;
-
-    // ---- geometry only: for every type and table slot, the last partition <= p that shows a
-    // column of the type (binary search in the type's ascending first-partition list) ----------
-    for (int idx = tid; idx < g.n_types * SPAN_MAX; idx += blockDim.x) {
-        const int i = idx / SPAN_MAX, e = idx - i * SPAN_MAX;
-        const int t = g.type_id[i];
-        const int p = max(0, x0 - t) - 1 + e;                 // slot e holds partition p_lo - 1 + e
-        int lo = g.type_begin[i], hi = g.type_begin[i + 1];   // columns [lo, hi)
-        const int first = lo;
-        while (lo < hi) {                                     // first column with p0 > p
-            const int mid = (lo + hi) >> 1;
-            if (static_cast<int>(g.col_p0[mid]) <= p) lo = mid + 1; else hi = mid;
-        }
-        // slot of ptr's segment to read: column index inside the type for the 3-entry NOP
-        // segment, else the partition number; -1: nothing of this type up to p
-        int v = -1;
-        if (lo > first) v = (g.nop3 && t == 0) ? (lo - first - 1) : static_cast<int>(g.col_p0[lo - 1]);
-        lastp[idx] = v;
-    }
+    for (int i = lane; i < G * NCELL; i += kLanes) patch[i] = 0.0f;
 
     for (int cb = c_begin; cb < c_end; cb += a.batch) {
         const int nb = min(a.batch, c_end - cb);
-        __syncthreads();   // lastp ready / previous batch's table no longer in use
-        // ---- table: absolute DA offset after partition p, for the partitions that reach the tile
+        __syncthreads();   // previous batch's table no longer in use
+        // ---- table: DA offset after partition p for the partitions that reach the tile; slot e
+        // of (channel, type) holds partition p_lo - 1 + e (clamped: later slots repeat the end)
         for (int idx = tid; idx < nb * g.n_types * SPAN_MAX; idx += blockDim.x) {
             const int e = idx % SPAN_MAX;
             const int i = (idx / SPAN_MAX) % g.n_types;
             const int c = cb + idx / (SPAN_MAX * g.n_types);
-            int seg = a.chan_off[c];
-            int off = a.chan_off[(g.C + 1) + c];
-            int val = off;
-            if (a.ptr[seg] != CPOCONV_NPC) {
-                // walk the segments of the types before i: NPF = 1 entry, else 1+Ow (3 for NOP3);
-                // a live type's NZE count is its last cumulative entry
-                for (int ii = 0; ii < i; ++ii) {
-                    const bool three = g.nop3 && g.type_id[ii] == 0;
-                    if (three) { off += a.ptr[seg + 2]; seg += 3; }
-                    else if (a.ptr[seg] == CPOCONV_NPF) seg += 1;
-                    else {
-                        const int last_col = g.type_begin[ii + 1] - 1;
-                        off += a.ptr[seg + 1 + g.col_p0[last_col]];
-                        seg += 1 + g.Ow;
-                    }
-                }
-                const bool three = g.nop3 && g.type_id[i] == 0;
-                const int lp = lastp[i * SPAN_MAX + e];
-                val = off;
-                if (lp >= 0 && (three || a.ptr[seg] != CPOCONV_NPF)) val = off + a.ptr[seg + 1 + lp];
-            }
-            tab[idx] = val;
+            const int p = min(max(0, x0 - static_cast<int>(g.type_id[i])) - 1 + e, g.Ow - 1);
+            tab[idx] = a.mtab[(static_cast<int64_t>(c) * g.n_types + i) * (g.Ow + 1) + p + 1];
         }
         __syncthreads();
+        CPOCONV_STAMP(1);
 
-        // ---- this wavefront's channels of the batch: wave, wave+4, ... ---------------------
-        for (int cl = wave; cl < nb; cl += kWavesPerWg) {
-            const int c = cb + cl;
-            // weights of channel c for this lane's kernels
-            float w[TAPS][KPL];
-            const float *wc = a.wt + static_cast<int64_t>(c) * TAPS * g.Kpad + kbase + lane;
+        // ---- this wavefront's channels of the batch (wave, wave+NW, ..), G at a time ----------
+        // The DA / IN loads of G channels are issued back to back before any of them is used,
+        // so their latency is paid once per group and not once per partition.
+        const int main_slot = g.n_types - 1;   // the highest overlap type holds most NZEs
+        int gctr = 0; (void)gctr;
+        for (int j0 = wave; j0 < nb; j0 += kWavesPerWg * G) {
+            int idxr[G][MAXC];
+            float valr[G][MAXC];
+            int first[G], last[G];
+            {
+                const int t = g.type_id[main_slot];
+                const int span = min(g.Ow - 1, x0 + TX - 1) - max(0, x0 - t) + 1;
 #pragma unroll
-            for (int tp = 0; tp < TAPS; ++tp)
-#pragma unroll
-                for (int k = 0; k < KPL; ++k) w[tp][k] = wc[tp * g.Kpad + k * kLanes];
-
-            bool any = false;
-            for (int i = 0; i < g.n_types; ++i) {
-                const int t = g.type_id[i];
-                const int p_lo = max(0, x0 - t), p_hi = min(g.Ow - 1, x0 + TX - 1);
-                const int32_t *row = tab + (cl * g.n_types + i) * SPAN_MAX;
-                const int first = uni(row[0]), last = uni(row[p_hi - p_lo + 1]);
-                if (last == first) continue;                       // nothing of this type reaches the tile
-                for (int p = p_lo; p <= p_hi; ++p) {
-                    const int beg = uni(row[p - p_lo]), end = uni(row[p - p_lo + 1]);
-                    for (int n0 = beg; n0 < end; n0 += kLanes) {
-                        const int n = n0 + lane;
-                        if (n < end) {
-                            const int idx = a.in[n];
-                            const float v = a.da[n];
-                            const int h = idx / KW, wh = idx - h * KW;
-                            const int r = h - y0 * S;                 // row inside the patch
-                            const int q = (p - x0) * S + wh;          // column inside the patch
-                            if (r >= 0 && r < RH && q >= 0 && q < RW) patch[q * RH + r] = v;
-                        }
+                for (int gi = 0; gi < G; ++gi) {
+                    const int cl = j0 + gi * kWavesPerWg;
+                    first[gi] = 0;
+                    last[gi] = 0;
+                    if (cl < nb) {
+                        const int32_t *row = tab + (cl * g.n_types + main_slot) * SPAN_MAX;
+                        first[gi] = uni(row[0]);
+                        last[gi] = uni(row[span]);
                     }
-                    any = true;
+#pragma unroll
+                    for (int ch = 0; ch < MAXC; ++ch) {
+                        const int n = first[gi] + ch * kLanes + lane;
+                        const bool ok = n < last[gi];
+                        idxr[gi][ch] = ok ? a.in[n] : -1;
+                        valr[gi][ch] = ok ? a.da[n] : 0.0f;
+                    }
                 }
             }
-            if (!any) continue;
-
-            // ---- patch -> lanes, bitmap of non-zero cells, clear the patch ------------------
-            float cell[NDREG];
-            unsigned long long bits[NDREG];
+            CPOCONV_STAMP(8 + 3 * gctr);
+            // weights of the group's first channel
+            float w[TAPS][KPL];
+            {
+                const float *wc = a.wt + static_cast<int64_t>(cb + j0) * TAPS * g.Kpad + kbase + lane;
 #pragma unroll
-            for (int d = 0; d < NDREG; ++d) {
-                const int i = d * kLanes + lane;
-                cell[d] = i < NCELL ? patch[i] : 0.0f;
-                bits[d] = __ballot((__float_as_uint(cell[d]) & 0x7fffffffu) != 0u);
-            }
+                for (int tp = 0; tp < TAPS; ++tp)
 #pragma unroll
-            for (int d = 0; d < NDREG; ++d) {
-                const int i = d * kLanes + lane;
-                if (i < NCELL) patch[i] = 0.0f;
+                    for (int k = 0; k < KPL; ++k) w[tp][k] = wc[tp * g.Kpad + k * kLanes];
             }
 
-            // ---- convSpMv over the patch: compile-time cells, registers and weights ---------
+            // one NZE -> its cell of the patch.  n is its position in DA; the partition is the
+            // number of table boundaries at or below n (ptr used as in CSR).
+            auto scatter = [&](int idx, float v, int n, const int (&bound)[SPAN_MAX], int p_lo, float *pt) {
+                int prel = 0;
 #pragma unroll
-            for (int q = 0; q < RW; ++q) {
+                for (int e = 1; e < SPAN_MAX; ++e) prel += (n >= bound[e]) ? 1 : 0;
+                const int h = idx / KW, wh = idx - h * KW;   // padded row, column inside the partition
+                const int r = h - y0 * S;
+                const int q = (p_lo + prel - x0) * S + wh;
+                if (idx >= 0 && r >= 0 && r < RH && q >= 0 && q < RW) pt[q * RH + r] = v;
+            };
+
 #pragma unroll
-                for (int r = 0; r < RH; ++r) {
-                    const int cellno = q * RH + r;
-                    if (bits[cellno / kLanes] & (1ull << (cellno % kLanes))) {
-                        const float v = __int_as_float(
-                            __builtin_amdgcn_readlane(__float_as_int(cell[cellno / kLanes]), cellno % kLanes));
+            for (int gi = 0; gi < G; ++gi) {
+                const int cl = j0 + gi * kWavesPerWg;
+                if (cl >= nb) continue;
+                float *pt = patch + gi * NCELL;
+                {
+                    const int t = g.type_id[main_slot];
+                    const int p_lo = max(0, x0 - t);
+                    const int32_t *row = tab + (cl * g.n_types + main_slot) * SPAN_MAX;
+                    int bound[SPAN_MAX];
 #pragma unroll
-                        for (int l = 0; l < KH; ++l) {
-                            if ((r - l) < 0 || (r - l) % S != 0 || (r - l) / S >= TY) continue;
+                    for (int e = 0; e < SPAN_MAX; ++e) bound[e] = uni(row[e]);
 #pragma unroll
-                            for (int ww = 0; ww < KW; ++ww) {
-                                if ((q - ww) < 0 || (q - ww) % S != 0 || (q - ww) / S >= TX) continue;
+                    for (int ch = 0; ch < MAXC; ++ch)
+                        if (first[gi] + ch * kLanes < last[gi])
+                            scatter(idxr[gi][ch], valr[gi][ch], first[gi] + ch * kLanes + lane, bound, p_lo, pt);
+                    // columns with more NZEs than the prefetched chunks hold
+                    for (int n0 = first[gi] + MAXC * kLanes; n0 < last[gi]; n0 += kLanes) {
+                        const int n = n0 + lane;
+                        const bool ok = n < last[gi];
+                        scatter(ok ? a.in[n] : -1, ok ? a.da[n] : 0.0f, n, bound, p_lo, pt);
+                    }
+                }
+                // the lower overlap types (edge columns): few NZEs, loaded on demand
+                for (int i = 0; i < main_slot; ++i) {
+                    const int t = g.type_id[i];
+                    const int p_lo = max(0, x0 - t), p_hi = min(g.Ow - 1, x0 + TX - 1);
+                    const int32_t *row = tab + (cl * g.n_types + i) * SPAN_MAX;
+                    const int f = uni(row[0]), l = uni(row[p_hi - p_lo + 1]);
+                    if (l == f) continue;
+                    int bound[SPAN_MAX];
 #pragma unroll
-                                for (int k = 0; k < KPL; ++k)
-                                    acc[(r - l) / S][(q - ww) / S][k] =
-                                        fmaf(v, w[l * KW + ww][k], acc[(r - l) / S][(q - ww) / S][k]);
+                    for (int e = 0; e < SPAN_MAX; ++e) bound[e] = uni(row[e]);
+                    for (int n0 = f; n0 < l; n0 += kLanes) {
+                        const int n = n0 + lane;
+                        const bool ok = n < l;
+                        scatter(ok ? a.in[n] : -1, ok ? a.da[n] : 0.0f, n, bound, p_lo, pt);
+                    }
+                }
+            }
+
+            CPOCONV_STAMP(9 + 3 * gctr);
+#pragma unroll 1
+            for (int gi = 0; gi < G; ++gi) {
+                const int cl = j0 + gi * kWavesPerWg;
+                if (cl >= nb) break;
+                float *pt = patch + gi * NCELL;
+                // weights of the next channel of the group, in flight during this channel's FMAs
+                float wn[TAPS][KPL];
+                {
+                    const int cn = min(cb + cl + kWavesPerWg, g.C - 1);
+                    const float *wc = a.wt + static_cast<int64_t>(cn) * TAPS * g.Kpad + kbase + lane;
+#pragma unroll
+                    for (int tp = 0; tp < TAPS; ++tp)
+#pragma unroll
+                        for (int k = 0; k < KPL; ++k) wn[tp][k] = wc[tp * g.Kpad + k * kLanes];
+                }
+                // ---- patch -> lanes, bitmap of non-zero cells, clear the patch ------------------
+                float cell[NDREG];
+                unsigned long long bits[NDREG];
+#pragma unroll
+                for (int d = 0; d < NDREG; ++d) {
+                    const int i = d * kLanes + lane;
+                    cell[d] = i < NCELL ? pt[i] : 0.0f;
+                    bits[d] = __ballot((__float_as_uint(cell[d]) & 0x7fffffffu) != 0u);
+                }
+#pragma unroll
+                for (int d = 0; d < NDREG; ++d) {
+                    const int i = d * kLanes + lane;
+                    if (i < NCELL) pt[i] = 0.0f;
+                }
+                // ---- convSpMv over the patch: compile-time cells, registers and weights ---------
+#pragma unroll
+                for (int q = 0; q < RW; ++q) {
+#pragma unroll
+                    for (int r = 0; r < RH; ++r) {
+                        const int cellno = q * RH + r;
+                        if (bits[cellno / kLanes] & (1ull << (cellno % kLanes))) {
+                            const float v = __int_as_float(
+                                __builtin_amdgcn_readlane(__float_as_int(cell[cellno / kLanes]), cellno % kLanes));
+#pragma unroll
+                            for (int l = 0; l < KH; ++l) {
+                                if ((r - l) < 0 || (r - l) % S != 0 || (r - l) / S >= TY) continue;
+#pragma unroll
+                                for (int ww = 0; ww < KW; ++ww) {
+                                    if ((q - ww) < 0 || (q - ww) % S != 0 || (q - ww) / S >= TX) continue;
+#pragma unroll
+                                    for (int k = 0; k < KPL; ++k)
+                                        acc[(r - l) / S][(q - ww) / S][k] =
+                                            fmaf(v, w[l * KW + ww][k], acc[(r - l) / S][(q - ww) / S][k]);
+                                }
                             }
                         }
                     }
                 }
+#pragma unroll
+                for (int tp = 0; tp < TAPS; ++tp)
+#pragma unroll
+                    for (int k = 0; k < KPL; ++k) w[tp][k] = wn[tp][k];
+            }
+            CPOCONV_STAMP(10 + 3 * gctr);
+            ++gctr;
+        }
+    }
+    CPOCONV_STAMP(5);
+
+    // ---- add the wavefronts' accumulators: fixed binary tree (w += w + stride), so the order
+    // of additions never changes.  Senders park their registers in LDS, 16 bytes per lane.
+    constexpr int KW64 = KPL * kLanes;
+    constexpr int A = TY * TX * KPL;           // accumulators per lane
+    static_assert(A % 4 == 0, "tile accumulators must pack into float4");
+    float4 *red4 = reinterpret_cast<float4 *>(smem);
+    auto acc_at = [&](int n) -> float & { return acc[n / (TX * KPL)][(n / KPL) % TX][n % KPL]; };
+    for (int stride = 1; stride < kWavesPerWg; stride *= 2) {
+        const int npairs = (kWavesPerWg - stride + 2 * stride - 1) / (2 * stride);   // receivers w with w + stride < NW
+        const bool sender = (wave % (2 * stride)) == stride;
+        const bool receiver = (wave % (2 * stride)) == 0 && wave + stride < kWavesPerWg;
+        const int pair = wave / (2 * stride);
+        for (int first = 0; first < npairs; first += a.red_slots) {
+            __syncthreads();
+            if (sender && pair >= first && pair < first + a.red_slots) {
+                float4 *dst = red4 + (pair - first) * (A / 4) * kLanes + lane;
+#pragma unroll
+                for (int j = 0; j < A / 4; ++j)
+                    dst[j * kLanes] = make_float4(acc_at(4 * j), acc_at(4 * j + 1), acc_at(4 * j + 2), acc_at(4 * j + 3));
+            }
+            __syncthreads();
+            if (receiver && pair >= first && pair < first + a.red_slots) {
+                const float4 *src = red4 + (pair - first) * (A / 4) * kLanes + lane;
+#pragma unroll
+                for (int j = 0; j < A / 4; ++j) {
+                    const float4 v = src[j * kLanes];
+                    acc_at(4 * j) += v.x; acc_at(4 * j + 1) += v.y; acc_at(4 * j + 2) += v.z; acc_at(4 * j + 3) += v.w;
+                }
             }
         }
     }
-
-    // ---- add the four wavefronts' accumulators in a fixed order: 3 -> 2 -> 1 -> 0 -----------
-    float *red = reinterpret_cast<float *>(smem);   // TY*TX*KPL*64 floats, overlays the tables
-    for (int src = kWavesPerWg - 1; src >= 1; --src) {
-        __syncthreads();
-        if (wave == src) {
+    float *red = reinterpret_cast<float *>(smem);
+    CPOCONV_STAMP(6);
+    if (a.slices > 1) {
+        // partial sums of this channel slice, kernel index fastest
+        if (wave == 0) {
+            float *dst = a.partial + ((static_cast<int64_t>(slice) * a.Ypad + y0) * a.Xpad + x0) * g.Kpad + kbase + lane;
 #pragma unroll
             for (int y = 0; y < TY; ++y)
 #pragma unroll
                 for (int x = 0; x < TX; ++x)
 #pragma unroll
-                    for (int k = 0; k < KPL; ++k) red[((y * TX + x) * KPL + k) * kLanes + lane] = acc[y][x][k];
+                    for (int k = 0; k < KPL; ++k)
+                        dst[(static_cast<int64_t>(y) * a.Xpad + x) * g.Kpad + k * kLanes] = acc[y][x][k];
         }
-        __syncthreads();
-        if (wave == src - 1) {
-#pragma unroll
-            for (int y = 0; y < TY; ++y)
-#pragma unroll
-                for (int x = 0; x < TX; ++x)
-#pragma unroll
-                    for (int k = 0; k < KPL; ++k) acc[y][x][k] += red[((y * TX + x) * KPL + k) * kLanes + lane];
-        }
+        return;
     }
+    // one slice: transpose through LDS (row stride KW64+1 against bank conflicts) and store the
+    // K x Oh x Ow output directly, TX consecutive x per kernel and row
+    constexpr int LDT = KW64 + 1;
+    __syncthreads();
     if (wave == 0) {
-        float *dst = a.partial + ((static_cast<int64_t>(slice) * a.Ypad + y0) * a.Xpad + x0) * g.Kpad + kbase + lane;
 #pragma unroll
         for (int y = 0; y < TY; ++y)
 #pragma unroll
             for (int x = 0; x < TX; ++x)
 #pragma unroll
-                for (int k = 0; k < KPL; ++k)
-                    dst[(static_cast<int64_t>(y) * a.Xpad + x) * g.Kpad + k * kLanes] = acc[y][x][k];
+                for (int k = 0; k < KPL; ++k) red[(y * TX + x) * LDT + k * kLanes + lane] = acc[y][x][k];
     }
+    __syncthreads();
+    for (int i = tid; i < TY * TX * KW64; i += kWavesPerWg * kLanes) {
+        const int x = i % TX, k = (i / TX) % KW64, y = i / (TX * KW64);
+        if (kbase + k < g.K && y0 + y < g.Oh && x0 + x < g.Ow)
+            a.out[(static_cast<int64_t>(kbase + k) * g.Oh + y0 + y) * g.Ow + x0 + x] = red[(y * TX + x) * LDT + k];
+    }
+    CPOCONV_STAMP(7);
 }
 
 // out[k][y][x] = sum over slices (ascending) of partial[slice][y][x][k]; one workgroup per
-// (output row, 64 kernels): reads coalesced along k, writes coalesced along x via an LDS tile.
+// (output row, 64 kernels, 16 columns): reads coalesced along k, writes runs along x via LDS.
+constexpr int kEpiCols = 16;
+
 __global__ __launch_bounds__(256) void reduce_transpose_kernel(const Geometry g, const float *__restrict__ partial,
                                                               int slices, int Ypad, int Xpad, float *__restrict__ out)
 {
-    extern __shared__ float t[];            // 64 x (Ow + 1)
-    const int y = blockIdx.x, kb = blockIdx.y * kLanes;
+    __shared__ float t[kLanes][kEpiCols + 1];
+    const int y = blockIdx.x, kb = blockIdx.y * kLanes, xb = blockIdx.z * kEpiCols;
     const int tid = threadIdx.x, lane = tid & (kLanes - 1), wave = tid / kLanes;
-    const int ld = g.Ow + 1;
     const int64_t slice_stride = static_cast<int64_t>(Ypad) * Xpad * g.Kpad;
-    for (int x = wave; x < g.Ow; x += 4) {
-        const float *src = partial + (static_cast<int64_t>(y) * Xpad + x) * g.Kpad + kb + lane;
-        float s = src[0];
-        for (int sl = 1; sl < slices; ++sl) s += src[sl * slice_stride];
-        t[lane * ld + x] = s;
+    float s[kEpiCols / 4];
+#pragma unroll
+    for (int u = 0; u < kEpiCols / 4; ++u) {
+        const int x = xb + wave * (kEpiCols / 4) + u;   // x < Xpad always: the buffer is padded
+        const float *src = partial + (static_cast<int64_t>(y) * Xpad + min(x, Xpad - 1)) * g.Kpad + kb + lane;
+        float v = src[0];
+#pragma unroll 4
+        for (int sl = 1; sl < slices; ++sl) v += src[sl * slice_stride];
+        s[u] = v;
     }
+#pragma unroll
+    for (int u = 0; u < kEpiCols / 4; ++u) t[lane][wave * (kEpiCols / 4) + u] = s[u];
     __syncthreads();
-    for (int i = tid; i < kLanes * g.Ow; i += 256) {
-        const int k = i / g.Ow, x = i - k * g.Ow;
-        if (kb + k < g.K) out[(static_cast<int64_t>(kb + k) * g.Oh + y) * g.Ow + x] = t[k * ld + x];
+    for (int i = tid; i < kLanes * kEpiCols; i += 256) {
+        const int k = i / kEpiCols, x = i % kEpiCols;
+        if (kb + k < g.K && xb + x < g.Ow) out[(static_cast<int64_t>(kb + k) * g.Oh + y) * g.Ow + xb + x] = t[k][x];
     }
 }
 
-template <int KH, int KW, int S, int TY, int TX, int KPL>
-int launch_tile(const cpoconv_map &map, const int32_t *indices, const Geometry &g, const float *wt, float *out,
-                float *partial, int slices, hipStream_t stream)
+// Launch shape of the register kernel for a layer.
+struct TilePlan {
+    int ty, tx, kpl, nw, slices;
+};
+
+TilePlan plan_for(const Geometry &g)
+{
+    TilePlan p;
+    p.ty = 8; p.tx = 8;
+    p.kpl = (g.Kpad % 128 == 0 && g.kh * g.kw <= 9) ? 2 : 1;
+    p.nw = 8;
+    const int ntiles = ((g.Ow + p.tx - 1) / p.tx) * ((g.Oh + p.ty - 1) / p.ty);
+    const int wgs = ntiles * (g.Kpad / (kLanes * p.kpl));
+    int s = (512 + wgs - 1) / wgs;
+    const int cap = (g.C + 7) / 8;
+    if (s > cap) s = cap;
+    if (s > 16) s = 16;
+    if (s < 1) s = 1;
+    p.slices = s;
+    // tuning overrides (development only)
+    if (const char *e = getenv("CPOCONV_TILE_KPL")) p.kpl = atoi(e);
+    if (const char *e = getenv("CPOCONV_TILE_NW")) p.nw = atoi(e);
+    if (const char *e = getenv("CPOCONV_TILE_TY")) p.ty = atoi(e);
+    if (const char *e = getenv("CPOCONV_TILE_SLICES")) p.slices = atoi(e);
+    if (g.Kpad % (kLanes * p.kpl) != 0) p.kpl = 1;
+    if (p.slices > 16) p.slices = 16;
+    if (p.slices < 1) p.slices = 1;
+    return p;
+}
+
+template <int KH, int KW, int S, int TY, int TX, int KPL, int NW>
+int launch_tile(const cpoconv_map &map, const int32_t *indices, const int32_t *mtab, const Geometry &g,
+                const float *wt, float *out, float *partial, int slices, hipStream_t stream)
 {
     constexpr int RH = (TY - 1) * S + KH, RW = (TX - 1) * S + KW, NCELL = RH * RW;
     constexpr int SPAN_MAX = TX + KW + 1;
     const int ntx = (g.Ow + TX - 1) / TX, nty = (g.Oh + TY - 1) / TY;
     const int ngroups = g.Kpad / (kLanes * KPL);
     int batch = kTabBytes / (g.n_types * SPAN_MAX * 4);
-    if (batch > 64) batch = 64;
-    if (batch < kWavesPerWg) batch = kWavesPerWg;
+    if (batch > 128) batch = 128;
+    if (batch < NW) batch = NW;
     TileArgs a;
-    a.ptr = map.ptr; a.da = map.da; a.in = indices; a.chan_off = map.chan_off; a.wt = wt;
-    a.partial = partial; a.slices = slices; a.Ypad = nty * TY; a.Xpad = ntx * TX; a.batch = batch;
-    const size_t work = (static_cast<size_t>(g.n_types) * SPAN_MAX * (1 + batch) + kWavesPerWg * NCELL) * 4;
-    const size_t red = static_cast<size_t>(TY) * TX * KPL * kLanes * 4;
-    const size_t lds = work > red ? work : red;
-    hipLaunchKernelGGL((spmv_conv_tile_kernel<KH, KW, S, TY, TX, KPL>), dim3(ntx, nty, ngroups * slices),
-                       dim3(kWavesPerWg * kLanes), lds, stream, g, a);
+    a.da = map.da; a.in = indices; a.mtab = mtab; a.wt = wt;
+    a.partial = partial; a.out = out; a.dbg = nullptr; a.slices = slices; a.Ypad = nty * TY; a.Xpad = ntx * TX; a.batch = batch;
+    const size_t work = (static_cast<size_t>(g.n_types) * SPAN_MAX * batch + NW * kGroup * NCELL) * 4;
+    const size_t acc_bytes = static_cast<size_t>(TY) * TX * KPL * kLanes * 4;
+    const size_t transpose = static_cast<size_t>(TY) * TX * (KPL * kLanes + 1) * 4;
+    int red_slots = static_cast<int>((48 * 1024) / acc_bytes);
+    if (red_slots > NW / 2) red_slots = NW / 2;
+    if (red_slots < 1) red_slots = 1;
+    a.red_slots = red_slots;
+    size_t lds = work;
+    if (red_slots * acc_bytes > lds) lds = red_slots * acc_bytes;
+    if (transpose > lds) lds = transpose;
+    hipLaunchKernelGGL((spmv_conv_tile_kernel<KH, KW, S, TY, TX, KPL, NW>), dim3(ntx, nty, ngroups * slices),
+                       dim3(NW * kLanes), lds, stream, g, a);
     CPOCONV_HIP_TRY(hipGetLastError());
-    hipLaunchKernelGGL(reduce_transpose_kernel, dim3(g.Oh, g.Kpad / kLanes), dim3(256),
-                       static_cast<size_t>(kLanes) * (g.Ow + 1) * 4, stream, g, partial, slices, a.Ypad, a.Xpad, out);
-    CPOCONV_HIP_TRY(hipGetLastError());
+    if (slices > 1) {
+        hipLaunchKernelGGL(reduce_transpose_kernel, dim3(g.Oh, g.Kpad / kLanes, (g.Ow + kEpiCols - 1) / kEpiCols),
+                           dim3(256), 0, stream, g, partial, slices, a.Ypad, a.Xpad, out);
+        CPOCONV_HIP_TRY(hipGetLastError());
+    }
     return CPOCONV_OK;
 }
 
 }  // namespace
 
-// Tile geometry of the register kernel, shared with the scratch-size computation.
-constexpr int kTileY = 8, kTileX = 8;
-
 bool tile_kernel_supports(const Geometry &g)
 {
-    const bool shape = (g.kh == 3 && g.kw == 3 && (g.stride == 1 || g.stride == 2)) ||
-                       (g.kh == 5 && g.kw == 5 && g.stride == 1) || (g.kh == 7 && g.kw == 7 && g.stride == 2);
-    return shape;
-}
-
-int tile_kernel_slices(const Geometry &g)
-{
-    // enough workgroups to fill the chip (about 2 per CU), each keeping >= 8 channels
-    const int ntiles = ((g.Ow + kTileX - 1) / kTileX) * ((g.Oh + kTileY - 1) / kTileY);
-    const int kpl = (g.Kpad % 128 == 0 && g.kh * g.kw <= 9) ? 2 : 1;
-    const int wgs = ntiles * (g.Kpad / (kLanes * kpl));
-    int s = (512 + wgs - 1) / wgs;
-    const int cap = (g.C + 7) / 8;
-    if (s > cap) s = cap;
-    if (s > 16) s = 16;
-    if (s < 1) s = 1;
-    return s;
+    if (g.n_types < 1) return false;
+    return (g.kh == 3 && g.kw == 3 && (g.stride == 1 || g.stride == 2)) ||
+           (g.kh == 5 && g.kw == 5 && g.stride == 1) || (g.kh == 7 && g.kw == 7 && g.stride == 2);
 }
 
 int64_t tile_kernel_partial_bytes(const Geometry &g)
 {
     if (!tile_kernel_supports(g)) return 0;
-    const int64_t Ypad = (g.Oh + kTileY - 1) / kTileY * kTileY, Xpad = (g.Ow + kTileX - 1) / kTileX * kTileX;
-    return 4 * Ypad * Xpad * g.Kpad * tile_kernel_slices(g);
+    // room for the largest slice count and the smallest tile height the planner may choose
+    const int64_t Ypad = (g.Oh + 55) / 56 * 56, Xpad = (g.Ow + 7) / 8 * 8;
+    return 4 * Ypad * Xpad * g.Kpad * 16;
 }
 
-int launch_sparse_conv_tile(const cpoconv_map &map, const int32_t *indices, const Geometry &g, const float *wt,
-                            float *out, float *partial, hipStream_t stream)
+int launch_sparse_conv_tile(const cpoconv_map &map, const int32_t *indices, const int32_t *mtab, const Geometry &g,
+                            const float *wt, float *out, float *partial, hipStream_t stream)
 {
-    const int slices = tile_kernel_slices(g);
-    const bool kpl2 = (g.Kpad % 128 == 0 && g.kh * g.kw <= 9);
-#define CPOCONV_TILE(KH, KW, S)                                                                         \
-    if (g.kh == KH && g.kw == KW && g.stride == S) {                                                    \
-        if (kpl2) return launch_tile<KH, KW, S, kTileY, kTileX, 2>(map, indices, g, wt, out, partial, slices, stream); \
-        return launch_tile<KH, KW, S, kTileY, kTileX, 1>(map, indices, g, wt, out, partial, slices, stream);           \
+    const TilePlan p = plan_for(g);
+#define CPOCONV_TILE(KH, KW, S)                                                                                 \
+    if (g.kh == KH && g.kw == KW && g.stride == S) {                                                            \
+        if (p.ty == 8 && p.kpl == 2) return launch_tile<KH, KW, S, 8, 8, 2, 8>(map, indices, mtab, g, wt, out, partial, p.slices, stream); \
+        if (p.ty == 8 && p.kpl == 1) return launch_tile<KH, KW, S, 8, 8, 1, 8>(map, indices, mtab, g, wt, out, partial, p.slices, stream); \
+        if (p.ty == 4 && p.kpl == 2) return launch_tile<KH, KW, S, 4, 8, 2, 8>(map, indices, mtab, g, wt, out, partial, p.slices, stream); \
+        if (p.ty == 4 && p.kpl == 1) return launch_tile<KH, KW, S, 4, 8, 1, 8>(map, indices, mtab, g, wt, out, partial, p.slices, stream); \
+    }
+    if (g.kh == 3 && g.kw == 3 && g.stride == 1) {
+        if (p.ty == 56) return launch_tile<3, 3, 1, 56, 2, 1, 8>(map, indices, mtab, g, wt, out, partial, p.slices, stream);
+        if (p.ty == 28) return launch_tile<3, 3, 1, 28, 4, 1, 8>(map, indices, mtab, g, wt, out, partial, p.slices, stream);
+        if (p.ty == 14) return launch_tile<3, 3, 1, 14, 8, 1, 8>(map, indices, mtab, g, wt, out, partial, p.slices, stream);
+        if (p.ty == 16) return launch_tile<3, 3, 1, 16, 4, 1, 8>(map, indices, mtab, g, wt, out, partial, p.slices, stream);
     }
     CPOCONV_TILE(3, 3, 1)
     CPOCONV_TILE(3, 3, 2)
