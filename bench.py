@@ -119,6 +119,54 @@ def stage_roofline(name, us, fig):
             "hbm_gbs": fig[name + "_bytes"] / t / 1e9}
 
 
+def kernel_times(api, torch, run, reps):
+    """Average duration of every kernel of every stage, from HIP events recorded by the library
+    around each launch on the launch stream (cpoconv_kernel_timing)."""
+    out = {}
+    for stage, fn in run.stages.items():
+        torch.cuda.synchronize()
+        api.cpoconv_kernel_timing(True)
+        for _ in range(reps):
+            fn()
+        torch.cuda.synchronize()
+        out[stage] = {k: {"avg_us": round(v[0], 3), "launches": v[1]} for k, v in api.cpoconv_kernel_timing_read().items()}
+        api.cpoconv_kernel_timing(False)
+    return out
+
+
+def kernel_roofline(stage, kernel, us, fig, spec, lens):
+    """Roofline entry of one kernel launch: algorithmic bytes or flops of the launch / duration."""
+    t = us * 1e-6
+    C, H, W, K, kh, kw, s, p = spec.shape_tuple
+    out_bytes = 4 * K * spec.Oh * spec.Ow
+    hbm = lambda b: {"bound": "hbm", "achieved": b / t / 1e9, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                     "frac": b / t / 1e9 / HBM_PEAK_GBS, "algorithmic_bytes": b}
+    if kernel == "encode_count":
+        return hbm(4 * C * H * W)
+    if kernel == "encode_write":
+        return hbm(fig[stage + "_bytes"])
+    if kernel == "conv_prologue":
+        b = 4 * lens["ptr"] + 4 * C * 2 * (spec.Ow + 1)
+        if stage == "cps_conv":
+            b += 4 * lens["in_cps"] + 4 * lens["nnz"]
+        return hbm(b)
+    if kernel in ("spmv_conv_tile", "spmv_conv_lds"):
+        r = stage_roofline(stage, us, fig)
+        r["algorithmic_flops"] = fig["sparse_flops"]
+        r["algorithmic_bytes"] = fig[stage + "_bytes"]
+        return r
+    if kernel == "reduce_transpose":
+        return hbm(2 * out_bytes)
+    if kernel.startswith("im2col_lower"):
+        return hbm(4 * C * H * W + (4 if kernel.endswith("f32") else 2) * fig["s_im2col"])
+    if kernel.startswith("gemm"):
+        peak = FP32_MFMA_PEAK_TFLOPS if kernel == "gemm_f32" else BF16_MFMA_PEAK_TFLOPS
+        tf = fig["dense_flops"] / t / 1e12
+        return {"bound": "mfma", "achieved": tf, "peak": peak, "unit": "TFLOP/s", "frac": tf / peak,
+                "algorithmic_flops": fig["dense_flops"]}
+    return None
+
+
 def measure_layer(api, torch, workloads, spec, reps, warm):
     run = LayerRun(api, torch, workloads, spec)
     lens = run.lengths()
@@ -244,15 +292,25 @@ def main():
     torch.cuda.synchronize()
     ms_per_step = (time.perf_counter() - t0) * 1e3 / args.steps
 
-    # dominant kernel of the step: the longest single-kernel stage
-    single_kernel = {"cpo_conv": times["cpo_conv"], "cpo_encode": times["cpo_encode"] / 2.0,
-                     "im2col_f32": times["im2col_f32"]}
-    dominant = max(single_kernel, key=single_kernel.get)
-    roof = dict(row["roofline"][dominant])
-    roof["kernel"] = {"cpo_conv": "spmv_conv (CPO map)", "cpo_encode": "encode (two launches)",
-                      "im2col_f32": "im2col lowering + MFMA GEMM fp32"}[dominant]
-    roof["avg_launch_us"] = times[dominant]
-    roof["traffic"] = traffic_from_profiles(dominant)
+    # per-kernel durations (HIP events around every launch) and the dominant kernel of the step
+    lens = run.lengths()
+    ktimes = kernel_times(api, torch, run, reps=max(20, min(args.steps, 100)))
+    kernels = []
+    for stage in ("cpo_encode", "cpo_conv", "cps_encode", "cps_conv", "im2col_f32"):
+        for kname, rec in ktimes[stage].items():
+            entry = {"stage": stage, "kernel": kname, "avg_us": rec["avg_us"], "launches": rec["launches"]}
+            r = kernel_roofline(stage, kname, rec["avg_us"], fig, spec, lens)
+            if r:
+                entry.update(r)
+            kernels.append(entry)
+    dom = max(kernels, key=lambda e: e["avg_us"])
+    roof = {k: dom[k] for k in ("bound", "achieved", "peak", "unit", "frac") if k in dom}
+    roof["kernel"] = dom["kernel"] + " (" + dom["stage"] + ")"
+    roof["avg_launch_us"] = dom["avg_us"]
+    for k in ("algorithmic_bytes", "algorithmic_flops"):
+        if k in dom:
+            roof[k] = dom[k]
+    roof["traffic"] = traffic_from_profiles(dom["kernel"])
 
     result = {
         "metric": "per-layer CPO/CPS conv time (us) + HBM GB/s, speedup and CR vs im2col",
@@ -270,6 +328,7 @@ def main():
         "selection": selection,
         "selection_times_us": {k: [round(x, 2) for x in v] for k, v in sel_times.items()},
         "roofline": roof,
+        "kernels": kernels,
     }
     if not args.no_cpu_baseline:
         result["cpu_baseline"] = cpu_baseline(spec, run.act_np, run.w_np)

@@ -175,6 +175,18 @@ int cpoconv_map_header_to_host(const cpoconv_map *map, int32_t hdr_host[8], void
 int cpoconv_geometry(const cpoconv_shape *shape, int32_t info[8], int32_t *col_j,
                      int32_t *col_type, int32_t *col_p0, int32_t *col_what);
 
+/*
+ * Measurement aid (not part of the method).  cpoconv_kernel_timing(1) clears earlier records
+ * and makes every later kernel launch of the library bracket itself with two HIP events on the
+ * stream it runs on; cpoconv_kernel_timing(0) stops that.  cpoconv_kernel_timing_read returns
+ * record `index` (0, 1, .. until it returns CPOCONV_ERR_SHAPE): kernel name (NUL-terminated,
+ * at most name_cap bytes), average duration in microseconds and number of launches; it waits
+ * for the recorded launches to finish.  Host-side events only: no device memory is allocated.
+ * Errors: NULL, SHAPE (index out of range), HIP.
+ */
+int cpoconv_kernel_timing(int enable);
+int cpoconv_kernel_timing_read(int index, char *name_out, int name_cap, double *avg_us, int *calls);
+
 /* Text for an error code (static storage). */
 const char *cpoconv_strerror(int code);
 

@@ -74,12 +74,33 @@ def lib() -> ctypes.CDLL:
 EXPORTS = (
     "cpoconv_sizes", "cpo_encode", "cps_encode", "cpoconv_prepare_weights", "cpo_conv", "cps_conv",
     "im2col_conv", "select_layer_algo", "cpoconv_map_header_to_host", "cpoconv_geometry",
-    "cpoconv_strerror", "cpoconv_last_hip_error",
+    "cpoconv_strerror", "cpoconv_last_hip_error", "cpoconv_kernel_timing", "cpoconv_kernel_timing_read",
 )
 
 
 def cpoconv_strerror(code: int) -> str:
     return lib().cpoconv_strerror(int(code)).decode()
+
+
+def cpoconv_kernel_timing(enable: bool) -> None:
+    """Measurement aid: bracket every kernel launch of the library with HIP events."""
+    _check(lib().cpoconv_kernel_timing(1 if enable else 0))
+
+
+def cpoconv_kernel_timing_read():
+    """{kernel name: (average microseconds, launches)} recorded since timing was enabled."""
+    out = {}
+    name = ctypes.create_string_buffer(64)
+    avg, calls = ctypes.c_double(0.0), ctypes.c_int(0)
+    i = 0
+    while True:
+        rc = lib().cpoconv_kernel_timing_read(i, name, 64, ctypes.byref(avg), ctypes.byref(calls))
+        if rc == ERR_SHAPE:
+            break
+        _check(rc)
+        out[name.value.decode()] = (float(avg.value), int(calls.value))
+        i += 1
+    return out
 
 
 def _check(rc: int) -> None:

@@ -2,6 +2,11 @@
 // step is queued by the launch_* functions next to the kernels.
 #include <string.h>
 
+#include <mutex>
+#include <string>
+#include <utility>
+#include <vector>
+
 #include "common.hpp"
 
 namespace cpoconv {
@@ -9,6 +14,50 @@ namespace cpoconv {
 static thread_local int g_last_hip_error = 0;
 
 void set_hip_error(hipError_t e) { g_last_hip_error = static_cast<int>(e); }
+
+namespace {
+struct TimingRecord {
+    std::string name;
+    std::vector<std::pair<hipEvent_t, hipEvent_t>> events;
+};
+std::mutex g_timing_mutex;
+bool g_timing_enabled = false;
+std::vector<TimingRecord> g_timing;
+
+void timing_clear()
+{
+    for (auto &rec : g_timing)
+        for (auto &ev : rec.events) {
+            hipEventDestroy(ev.first);
+            hipEventDestroy(ev.second);
+        }
+    g_timing.clear();
+}
+}  // namespace
+
+KernelTimer::KernelTimer(const char *name, hipStream_t stream) : stream_(stream), stop_(nullptr)
+{
+    if (!g_timing_enabled) return;
+    std::lock_guard<std::mutex> lock(g_timing_mutex);
+    hipEvent_t start, stop;
+    if (hipEventCreate(&start) != hipSuccess) return;
+    if (hipEventCreate(&stop) != hipSuccess) { hipEventDestroy(start); return; }
+    TimingRecord *rec = nullptr;
+    for (auto &r : g_timing)
+        if (r.name == name) rec = &r;
+    if (!rec) {
+        g_timing.push_back(TimingRecord{name, {}});
+        rec = &g_timing.back();
+    }
+    rec->events.emplace_back(start, stop);
+    hipEventRecord(start, stream_);
+    stop_ = stop;
+}
+
+KernelTimer::~KernelTimer()
+{
+    if (stop_) hipEventRecord(static_cast<hipEvent_t>(stop_), stream_);
+}
 
 int check_shape(const cpoconv_shape *s)
 {
@@ -261,6 +310,34 @@ int cpoconv_geometry(const cpoconv_shape *shape, int32_t info[8], int32_t *col_j
             col_p0[n] = g.col_p0[n];
             col_what[n] = g.col_what[n];
         }
+    return CPOCONV_OK;
+}
+
+int cpoconv_kernel_timing(int enable)
+{
+    std::lock_guard<std::mutex> lock(g_timing_mutex);
+    if (enable) timing_clear();
+    g_timing_enabled = enable != 0;
+    return CPOCONV_OK;
+}
+
+int cpoconv_kernel_timing_read(int index, char *name_out, int name_cap, double *avg_us, int *calls)
+{
+    if (!name_out || !avg_us || !calls) return CPOCONV_ERR_NULL;
+    std::lock_guard<std::mutex> lock(g_timing_mutex);
+    if (index < 0 || index >= static_cast<int>(g_timing.size()) || name_cap < 1) return CPOCONV_ERR_SHAPE;
+    const TimingRecord &rec = g_timing[index];
+    double total_ms = 0.0;
+    for (const auto &ev : rec.events) {
+        CPOCONV_HIP_TRY(hipEventSynchronize(ev.second));
+        float ms = 0.0f;
+        CPOCONV_HIP_TRY(hipEventElapsedTime(&ms, ev.first, ev.second));
+        total_ms += ms;
+    }
+    strncpy(name_out, rec.name.c_str(), static_cast<size_t>(name_cap) - 1);
+    name_out[name_cap - 1] = '\0';
+    *calls = static_cast<int>(rec.events.size());
+    *avg_us = rec.events.empty() ? 0.0 : total_ms * 1000.0 / rec.events.size();
     return CPOCONV_OK;
 }
 

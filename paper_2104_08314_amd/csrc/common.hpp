@@ -48,6 +48,20 @@ void set_hip_error(hipError_t e);
         }                                             \
     } while (0)
 
+// Measurement aid: while kernel timing is enabled (cpoconv_kernel_timing), every kernel launch is
+// bracketed by two HIP events on its own stream.
+class KernelTimer {
+public:
+    KernelTimer(const char *name, hipStream_t stream);
+    ~KernelTimer();
+    KernelTimer(const KernelTimer &) = delete;
+    KernelTimer &operator=(const KernelTimer &) = delete;
+
+private:
+    hipStream_t stream_;
+    void *stop_;
+};
+
 // launchers (defined next to their kernels)
 int launch_encode(const float *act, const Geometry &g, const cpoconv_map &map, int algo,
                   void *scratch, hipStream_t stream);

@@ -172,15 +172,23 @@ int launch_im2col_conv(const float *act, const Geometry &g, const float *w, void
     const dim3 lgrid(static_cast<unsigned>(Kd) * chunks);
     const dim3 ggrid((N + kBN - 1) / kBN, (M + kBM - 1) / kBM);
     if (precision == 0) {
-        hipLaunchKernelGGL(im2col_lower_kernel<float>, lgrid, dim3(kLowThreads), 0, stream, g, act,
-                           static_cast<float *>(lowered));
+        {
+            KernelTimer timer("im2col_lower_f32", stream);
+            hipLaunchKernelGGL(im2col_lower_kernel<float>, lgrid, dim3(kLowThreads), 0, stream, g, act,
+                               static_cast<float *>(lowered));
+        }
         CPOCONV_HIP_TRY(hipGetLastError());
+        KernelTimer timer("gemm_f32", stream);
         hipLaunchKernelGGL(gemm_f32_kernel, ggrid, dim3(kGemmThreads), 0, stream, w,
                            static_cast<const float *>(lowered), out, M, N, Kd);
     } else {
-        hipLaunchKernelGGL(im2col_lower_kernel<uint16_t>, lgrid, dim3(kLowThreads), 0, stream, g, act,
-                           static_cast<uint16_t *>(lowered));
+        {
+            KernelTimer timer("im2col_lower_bf16", stream);
+            hipLaunchKernelGGL(im2col_lower_kernel<uint16_t>, lgrid, dim3(kLowThreads), 0, stream, g, act,
+                               static_cast<uint16_t *>(lowered));
+        }
         CPOCONV_HIP_TRY(hipGetLastError());
+        KernelTimer timer("gemm_bf16", stream);
         hipLaunchKernelGGL(gemm_bf16_kernel, ggrid, dim3(kGemmThreads), 0, stream, w,
                            static_cast<const uint16_t *>(lowered), out, M, N, Kd);
     }

@@ -288,6 +288,7 @@ int launch_sparse_conv(const cpoconv_map &map, const Geometry &g, int algo, cons
     }
     const bool tile = tile_kernel_supports(g);
     if (tile || in_full != nullptr) {
+        KernelTimer timer("conv_prologue", stream);
         hipLaunchKernelGGL(conv_prologue_kernel, dim3(g.C), dim3(kExpThreads), 0, stream, g, map.ptr, map.in,
                            map.chan_off, mtab, in_full);
         CPOCONV_HIP_TRY(hipGetLastError());
@@ -299,8 +300,11 @@ int launch_sparse_conv(const cpoconv_map &map, const Geometry &g, int algo, cons
     }
     const dim3 grid((g.Ow + kTX - 1) / kTX, (g.Oh + kTY - 1) / kTY, g.Kpad / kLanes);
     const size_t lds = (static_cast<size_t>(kTY) * kTX + static_cast<size_t>(g.kh) * g.kw) * kLanes * sizeof(float);
-    hipLaunchKernelGGL(spmv_conv_lds_kernel, grid, dim3(kConvThreads), lds, stream, g, map.ptr, map.da, indices,
-                       map.chan_off, wt, out);
+    {
+        KernelTimer timer("spmv_conv_lds", stream);
+        hipLaunchKernelGGL(spmv_conv_lds_kernel, grid, dim3(kConvThreads), lds, stream, g, map.ptr, map.da, indices,
+                           map.chan_off, wt, out);
+    }
     CPOCONV_HIP_TRY(hipGetLastError());
     return CPOCONV_OK;
 }

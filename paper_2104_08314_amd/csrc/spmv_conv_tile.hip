@@ -18,8 +18,6 @@
 //      FMAs of convSpMv that land inside the tile, all with compile-time register indices.
 // The tile's partial sums go to a [slice][y][x][k] buffer (k fastest: coalesced); a second
 // kernel adds the slices in order and transposes to the K x Oh x Ow output.
-#include <stdlib.h>
-
 #include "common.hpp"
 
 namespace cpoconv {
@@ -29,20 +27,9 @@ namespace {
 constexpr int kTabBytes = 8 * 1024;  // LDS budget of the per-channel range table
 constexpr int kGroup = 4;
 constexpr int kChunksAhead = 4;
+constexpr int kMaxSlices = 16;
 
 __device__ __forceinline__ int lane_id() { return threadIdx.x & (kLanes - 1); }
-#ifdef CPOCONV_PHASE_TIMING
-// development aid: wall-clock stamps (100 MHz) of wavefront 0 of every workgroup
-#define CPOCONV_STAMP(slot)                                                                                   \
-    do {                                                                                                      \
-        if (threadIdx.x == 0) {                                                                               \
-            const int wg = (blockIdx.z * gridDim.y + blockIdx.y) * gridDim.x + blockIdx.x;                    \
-            if (wg < 64 && (slot) < 32) a.dbg[wg * 32 + (slot)] = wall_clock64();                             \
-        }                                                                                                     \
-    } while (0)
-#else
-#define CPOCONV_STAMP(slot) do {} while (0)
-#endif
 __device__ __forceinline__ int uni(int v) { return __builtin_amdgcn_readfirstlane(v); }
 
 struct TileArgs {
@@ -52,7 +39,6 @@ struct TileArgs {
     const float *wt;          // [C][kh*kw][Kpad]
     float *partial;           // [slices][Ypad][Xpad][Kpad]
     float *out;               // K x Oh x Ow, written directly when there is one slice
-    long long *dbg;           // phase stamps (development builds only)
     int32_t slices;           // channel slices across workgroups
     int32_t Ypad, Xpad;
     int32_t batch;            // channels per table refill
@@ -88,8 +74,6 @@ __global__ __launch_bounds__(NW *kLanes) void spmv_conv_tile_kernel(const Geomet
     // channel range of this workgroup
     const int per_slice = (g.C + a.slices - 1) / a.slices;
     const int c_begin = slice * per_slice, c_end = min(g.C, c_begin + per_slice);
-
-    CPOCONV_STAMP(0);
     float acc[TY][TX][KPL];
 #pragma unroll
     for (int y = 0; y < TY; ++y)
@@ -113,13 +97,11 @@ __global__ __launch_bounds__(NW *kLanes) void spmv_conv_tile_kernel(const Geomet
             tab[idx] = a.mtab[(static_cast<int64_t>(c) * g.n_types + i) * (g.Ow + 1) + p + 1];
         }
         __syncthreads();
-        CPOCONV_STAMP(1);
 
         // ---- this wavefront's channels of the batch (wave, wave+NW, ..), G at a time ----------
         // The DA / IN loads of G channels are issued back to back before any of them is used,
         // so their latency is paid once per group and not once per partition.
         const int main_slot = g.n_types - 1;   // the highest overlap type holds most NZEs
-        int gctr = 0; (void)gctr;
         for (int j0 = wave; j0 < nb; j0 += kWavesPerWg * G) {
             int idxr[G][MAXC];
             float valr[G][MAXC];
@@ -146,7 +128,6 @@ __global__ __launch_bounds__(NW *kLanes) void spmv_conv_tile_kernel(const Geomet
                     }
                 }
             }
-            CPOCONV_STAMP(8 + 3 * gctr);
             // weights of the group's first channel
             float w[TAPS][KPL];
             {
@@ -209,8 +190,6 @@ __global__ __launch_bounds__(NW *kLanes) void spmv_conv_tile_kernel(const Geomet
                     }
                 }
             }
-
-            CPOCONV_STAMP(9 + 3 * gctr);
 #pragma unroll 1
             for (int gi = 0; gi < G; ++gi) {
                 const int cl = j0 + gi * kWavesPerWg;
@@ -269,11 +248,8 @@ __global__ __launch_bounds__(NW *kLanes) void spmv_conv_tile_kernel(const Geomet
 #pragma unroll
                     for (int k = 0; k < KPL; ++k) w[tp][k] = wn[tp][k];
             }
-            CPOCONV_STAMP(10 + 3 * gctr);
-            ++gctr;
         }
     }
-    CPOCONV_STAMP(5);
 
     // ---- add the wavefronts' accumulators: fixed binary tree (w += w + stride), so the order
     // of additions never changes.  Senders park their registers in LDS, 16 bytes per lane.
@@ -307,7 +283,6 @@ __global__ __launch_bounds__(NW *kLanes) void spmv_conv_tile_kernel(const Geomet
         }
     }
     float *red = reinterpret_cast<float *>(smem);
-    CPOCONV_STAMP(6);
     if (a.slices > 1) {
         // partial sums of this channel slice, kernel index fastest
         if (wave == 0) {
@@ -340,7 +315,6 @@ __global__ __launch_bounds__(NW *kLanes) void spmv_conv_tile_kernel(const Geomet
         if (kbase + k < g.K && y0 + y < g.Oh && x0 + x < g.Ow)
             a.out[(static_cast<int64_t>(kbase + k) * g.Oh + y0 + y) * g.Ow + x0 + x] = red[(y * TX + x) * LDT + k];
     }
-    CPOCONV_STAMP(7);
 }
 
 // out[k][y][x] = sum over slices (ascending) of partial[slice][y][x][k]; one workgroup per
@@ -380,26 +354,19 @@ struct TilePlan {
 
 TilePlan plan_for(const Geometry &g)
 {
+    // Measured on MI355X over the workload layers: 4 x 8 tiles with 64 kernels per wavefront and
+    // eight wavefronts per workgroup win or tie everywhere; the channel slices are chosen so that
+    // about 1.5 workgroups per compute unit exist while each wavefront keeps a channel or more.
     TilePlan p;
-    p.ty = 8; p.tx = 8;
-    p.kpl = (g.Kpad % 128 == 0 && g.kh * g.kw <= 9) ? 2 : 1;
-    p.nw = 8;
+    p.ty = 4; p.tx = 8; p.kpl = 1; p.nw = 8;
     const int ntiles = ((g.Ow + p.tx - 1) / p.tx) * ((g.Oh + p.ty - 1) / p.ty);
     const int wgs = ntiles * (g.Kpad / (kLanes * p.kpl));
-    int s = (512 + wgs - 1) / wgs;
+    int s = (384 + wgs / 2) / wgs;
     const int cap = (g.C + 7) / 8;
     if (s > cap) s = cap;
-    if (s > 16) s = 16;
+    if (s > kMaxSlices) s = kMaxSlices;
     if (s < 1) s = 1;
     p.slices = s;
-    // tuning overrides (development only)
-    if (const char *e = getenv("CPOCONV_TILE_KPL")) p.kpl = atoi(e);
-    if (const char *e = getenv("CPOCONV_TILE_NW")) p.nw = atoi(e);
-    if (const char *e = getenv("CPOCONV_TILE_TY")) p.ty = atoi(e);
-    if (const char *e = getenv("CPOCONV_TILE_SLICES")) p.slices = atoi(e);
-    if (g.Kpad % (kLanes * p.kpl) != 0) p.kpl = 1;
-    if (p.slices > 16) p.slices = 16;
-    if (p.slices < 1) p.slices = 1;
     return p;
 }
 
@@ -416,7 +383,7 @@ int launch_tile(const cpoconv_map &map, const int32_t *indices, const int32_t *m
     if (batch < NW) batch = NW;
     TileArgs a;
     a.da = map.da; a.in = indices; a.mtab = mtab; a.wt = wt;
-    a.partial = partial; a.out = out; a.dbg = nullptr; a.slices = slices; a.Ypad = nty * TY; a.Xpad = ntx * TX; a.batch = batch;
+    a.partial = partial; a.out = out; a.slices = slices; a.Ypad = nty * TY; a.Xpad = ntx * TX; a.batch = batch;
     const size_t work = (static_cast<size_t>(g.n_types) * SPAN_MAX * batch + NW * kGroup * NCELL) * 4;
     const size_t acc_bytes = static_cast<size_t>(TY) * TX * KPL * kLanes * 4;
     const size_t transpose = static_cast<size_t>(TY) * TX * (KPL * kLanes + 1) * 4;
@@ -427,10 +394,14 @@ int launch_tile(const cpoconv_map &map, const int32_t *indices, const int32_t *m
     size_t lds = work;
     if (red_slots * acc_bytes > lds) lds = red_slots * acc_bytes;
     if (transpose > lds) lds = transpose;
-    hipLaunchKernelGGL((spmv_conv_tile_kernel<KH, KW, S, TY, TX, KPL, NW>), dim3(ntx, nty, ngroups * slices),
-                       dim3(NW * kLanes), lds, stream, g, a);
+    {
+        KernelTimer timer("spmv_conv_tile", stream);
+        hipLaunchKernelGGL((spmv_conv_tile_kernel<KH, KW, S, TY, TX, KPL, NW>), dim3(ntx, nty, ngroups * slices),
+                           dim3(NW * kLanes), lds, stream, g, a);
+    }
     CPOCONV_HIP_TRY(hipGetLastError());
     if (slices > 1) {
+        KernelTimer timer("reduce_transpose", stream);
         hipLaunchKernelGGL(reduce_transpose_kernel, dim3(g.Oh, g.Kpad / kLanes, (g.Ow + kEpiCols - 1) / kEpiCols),
                            dim3(256), 0, stream, g, partial, slices, a.Ypad, a.Xpad, out);
         CPOCONV_HIP_TRY(hipGetLastError());
@@ -451,27 +422,17 @@ int64_t tile_kernel_partial_bytes(const Geometry &g)
 {
     if (!tile_kernel_supports(g)) return 0;
     // room for the largest slice count and the smallest tile height the planner may choose
-    const int64_t Ypad = (g.Oh + 55) / 56 * 56, Xpad = (g.Ow + 7) / 8 * 8;
-    return 4 * Ypad * Xpad * g.Kpad * 16;
+    const int64_t Ypad = (g.Oh + 3) / 4 * 4, Xpad = (g.Ow + 7) / 8 * 8;
+    return 4 * Ypad * Xpad * g.Kpad * kMaxSlices;
 }
 
 int launch_sparse_conv_tile(const cpoconv_map &map, const int32_t *indices, const int32_t *mtab, const Geometry &g,
                             const float *wt, float *out, float *partial, hipStream_t stream)
 {
     const TilePlan p = plan_for(g);
-#define CPOCONV_TILE(KH, KW, S)                                                                                 \
-    if (g.kh == KH && g.kw == KW && g.stride == S) {                                                            \
-        if (p.ty == 8 && p.kpl == 2) return launch_tile<KH, KW, S, 8, 8, 2, 8>(map, indices, mtab, g, wt, out, partial, p.slices, stream); \
-        if (p.ty == 8 && p.kpl == 1) return launch_tile<KH, KW, S, 8, 8, 1, 8>(map, indices, mtab, g, wt, out, partial, p.slices, stream); \
-        if (p.ty == 4 && p.kpl == 2) return launch_tile<KH, KW, S, 4, 8, 2, 8>(map, indices, mtab, g, wt, out, partial, p.slices, stream); \
-        if (p.ty == 4 && p.kpl == 1) return launch_tile<KH, KW, S, 4, 8, 1, 8>(map, indices, mtab, g, wt, out, partial, p.slices, stream); \
-    }
-    if (g.kh == 3 && g.kw == 3 && g.stride == 1) {
-        if (p.ty == 56) return launch_tile<3, 3, 1, 56, 2, 1, 8>(map, indices, mtab, g, wt, out, partial, p.slices, stream);
-        if (p.ty == 28) return launch_tile<3, 3, 1, 28, 4, 1, 8>(map, indices, mtab, g, wt, out, partial, p.slices, stream);
-        if (p.ty == 14) return launch_tile<3, 3, 1, 14, 8, 1, 8>(map, indices, mtab, g, wt, out, partial, p.slices, stream);
-        if (p.ty == 16) return launch_tile<3, 3, 1, 16, 4, 1, 8>(map, indices, mtab, g, wt, out, partial, p.slices, stream);
-    }
+#define CPOCONV_TILE(KH, KW, S)                    \
+    if (g.kh == KH && g.kw == KW && g.stride == S) \
+        return launch_tile<KH, KW, S, 4, 8, 1, 8>(map, indices, mtab, g, wt, out, partial, p.slices, stream);
     CPOCONV_TILE(3, 3, 1)
     CPOCONV_TILE(3, 3, 2)
     CPOCONV_TILE(5, 5, 1)

@@ -23,7 +23,7 @@ def _declared_functions():
 def test_library_exports_every_declared_symbol():
     lib = api.lib()
     names = _declared_functions()
-    assert len(names) >= 12
+    assert len(names) >= 14
     for n in names:
         assert hasattr(lib, n), n
     assert sorted(api.EXPORTS) == names
@@ -97,6 +97,11 @@ def test_bad_arguments_are_rejected_on_the_host():
     assert lib.cpoconv_map_header_to_host(None, None, None) == api.ERR_NULL
     assert api.cpoconv_strerror(api.ERR_SMALL) != api.cpoconv_strerror(api.ERR_SHAPE)
     assert "unknown" in api.cpoconv_strerror(-99)
+    # the timing aid records nothing when no kernel was launched
+    api.cpoconv_kernel_timing(True)
+    assert api.cpoconv_kernel_timing_read() == {}
+    api.cpoconv_kernel_timing(False)
+    assert lib.cpoconv_kernel_timing_read(0, None, 0, None, None) == api.ERR_NULL
 
 
 def test_select_layer_algo_matches_oracle_and_rules():
