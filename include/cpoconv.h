@@ -92,7 +92,8 @@ typedef struct {
     int64_t chan_off_len;  /* 3*(C+1)                                                      */
     int64_t wt_len;        /* prepared weights: C*kh*kw*round_up(K,64) floats              */
     int64_t out_len;       /* K*Oh*Ow                                                      */
-    int64_t lowered_bytes; /* im2col lowered matrix, fp32: 4*C*kh*kw*Oh*Ow                 */
+    int64_t lowered_bytes; /* im2col scratch: lowered matrix (rows padded to 4 columns) +  */
+                           /* split-K partial sums of the matrix product                   */
     int64_t scratch_bytes; /* scratch for encode and conv calls                            */
     int32_t Oh, Ow;
 } cpoconv_sizes_t;
@@ -145,9 +146,11 @@ int cps_conv(const cpoconv_map *map, const cpoconv_shape *shape, const float *wt
  * (c*kh + l)*kw + w, column y*Ow + x, holds the padded input at (c, y*stride + l,
  * x*stride + w)) followed by a dense matrix product with the K x C*kh*kw kernel matrix on
  * the matrix cores.  precision 0: fp32 operands; 1: operands rounded to bf16 (nearest even),
- * fp32 accumulation.  lowered: scratch of sizes.lowered_bytes bytes (the bf16 variant uses
- * half).  weights in the K x C x kh x kw layout.
- * Errors: NULL, SHAPE, ALGO (precision), HIP.
+ * fp32 accumulation.  lowered: scratch of sizes.lowered_bytes bytes (lowered matrix, then the
+ * partial sums of the product when the contraction is split over workgroups; slices are added
+ * in a fixed order).  weights in the K x C x kh x kw layout.
+ * lowered must be 16-byte aligned.
+ * Errors: NULL, SHAPE (also a misaligned lowered), ALGO (precision), HIP.
  */
 int im2col_conv(const float *act, const cpoconv_shape *shape, const float *weights,
                 void *lowered, float *out, int precision, void *stream);

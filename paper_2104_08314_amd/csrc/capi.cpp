@@ -185,7 +185,7 @@ int cpoconv_sizes(const cpoconv_shape *shape, cpoconv_sizes_t *sizes)
     sizes->chan_off_len = 3 * static_cast<int64_t>(g.C + 1);
     sizes->wt_len = static_cast<int64_t>(g.C) * g.kh * g.kw * g.Kpad;
     sizes->out_len = static_cast<int64_t>(g.K) * g.Oh * g.Ow;
-    sizes->lowered_bytes = 4 * static_cast<int64_t>(g.C) * g.kh * g.kw * g.Oh * g.Ow;
+    sizes->lowered_bytes = im2col_scratch_bytes(g);
     sizes->scratch_bytes = scratch_bytes_for(g);
     sizes->Oh = g.Oh;
     sizes->Ow = g.Ow;
@@ -261,6 +261,7 @@ int im2col_conv(const float *act, const cpoconv_shape *shape, const float *weigh
     const int rc = build_geometry(shape, &g);
     if (rc != CPOCONV_OK) return rc;
     if (precision != 0 && precision != 1) return CPOCONV_ERR_ALGO;
+    if (reinterpret_cast<uintptr_t>(lowered) % 16 != 0) return CPOCONV_ERR_SHAPE;   // vector accesses
     return launch_im2col_conv(act, g, weights, lowered, out, precision,
                               static_cast<hipStream_t>(stream));
 }

@@ -77,6 +77,7 @@ int launch_sparse_conv_tile(const cpoconv_map &map, const int32_t *indices, cons
 int64_t scratch_counts_bytes(const Geometry &g);
 int64_t scratch_indices_bytes(const Geometry &g);
 int64_t scratch_mtab_bytes(const Geometry &g);
+int64_t im2col_scratch_bytes(const Geometry &g);
 int launch_im2col_conv(const float *act, const Geometry &g, const float *w, void *lowered,
                        float *out, int precision, hipStream_t stream);
 

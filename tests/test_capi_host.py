@@ -60,7 +60,7 @@ def test_sizes(shape):
     assert (sz.Oh, sz.Ow) == (g.Oh, g.Ow)
     assert sz.da_cap == sz.in_cap == C * H * W
     assert sz.out_len == K * g.Oh * g.Ow
-    assert sz.lowered_bytes == 4 * C * kh * kw * g.Oh * g.Ow
+    assert sz.lowered_bytes >= 4 * C * kh * kw * g.Oh * g.Ow            # S_im2col elements at least
     assert sz.wt_len == C * kh * kw * ((K + 63) // 64 * 64)
     # the ptr capacity covers the oracle's ptr for a dense map (no skip flags)
     act = np.ones((C, H, W), np.float32)
@@ -92,6 +92,7 @@ def test_bad_arguments_are_rejected_on_the_host():
     assert lib.cpo_conv(ctypes.byref(big), ctypes.byref(good), None, one, one, ctypes.c_int64(1 << 30), None) == api.ERR_NULL
     assert lib.cps_conv(ctypes.byref(big), ctypes.byref(good), one, one, one, ctypes.c_int64(8), None) == api.ERR_SMALL
     assert lib.im2col_conv(one, ctypes.byref(good), one, one, one, 7, None) == api.ERR_ALGO
+    assert lib.im2col_conv(one, ctypes.byref(good), one, ctypes.c_void_p(260), one, 0, None) == api.ERR_SHAPE
     assert lib.im2col_conv(one, ctypes.byref(good), one, None, one, 0, None) == api.ERR_NULL
     assert lib.cpoconv_prepare_weights(one, ctypes.byref(good), None, None) == api.ERR_NULL
     assert lib.cpoconv_map_header_to_host(None, None, None) == api.ERR_NULL
