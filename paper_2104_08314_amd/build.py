@@ -9,7 +9,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libcpoconv.so")
-SOURCES = ["capi.cpp", "encode.hip", "spmv_conv.hip", "spmv_conv_tile.hip", "im2col_gemm.hip"]
+SOURCES = ["capi.cpp", "encode.hip", "spmv_conv.hip", "spmv_conv_tile.hip", "spmv_conv_strip.hip", "im2col_gemm.hip"]
 
 COMPILE_FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC",

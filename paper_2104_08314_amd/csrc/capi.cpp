@@ -163,7 +163,8 @@ int64_t scratch_mtab_bytes(const Geometry &g)
 
 int64_t scratch_bytes_for(const Geometry &g)
 {
-    return scratch_counts_bytes(g) + scratch_mtab_bytes(g) + scratch_indices_bytes(g) + tile_kernel_partial_bytes(g);
+    const int64_t tile = tile_kernel_partial_bytes(g), strip = strip_kernel_partial_bytes(g);
+    return scratch_counts_bytes(g) + scratch_mtab_bytes(g) + scratch_indices_bytes(g) + (tile > strip ? tile : strip);
 }
 
 }  // namespace cpoconv

@@ -73,10 +73,35 @@ bool tile_kernel_supports(const Geometry &g);
 int64_t tile_kernel_partial_bytes(const Geometry &g);
 int launch_sparse_conv_tile(const cpoconv_map &map, const int32_t *indices, const int32_t *mtab, const Geometry &g, const float *wt,
                             float *out, float *partial, hipStream_t stream);
+// strip SpMV kernel (spmv_conv_strip.hip)
+bool strip_kernel_supports(const Geometry &g);
+bool strip_kernel_preferred(const Geometry &g);
+int64_t strip_kernel_partial_bytes(const Geometry &g);
+int launch_sparse_conv_strip(const cpoconv_map &map, const int32_t *indices, const int32_t *mtab, const Geometry &g,
+                             const float *wt, float *out, float *partial, hipStream_t stream);
 // byte offsets of the regions of the caller's scratch buffer
 int64_t scratch_counts_bytes(const Geometry &g);
 int64_t scratch_indices_bytes(const Geometry &g);
 int64_t scratch_mtab_bytes(const Geometry &g);
+// out[k][y][x] = sum over channel slices of partial[slice][y][x][k] (spmv_conv.hip)
+int launch_reduce_transpose(const Geometry &g, const float *partial, int slices, int Ypad, int Xpad, float *out,
+                            hipStream_t stream);
+
+// Sum over the channel slices of one output element: four interleaved running sums, then
+// pairwise.  Every kernel that adds slices uses this order, so they agree bit for bit.
+__device__ inline float sum_slices(const float *src, int64_t slice_stride, int slices)
+{
+    float s0 = 0.0f, s1 = 0.0f, s2 = 0.0f, s3 = 0.0f;
+    int sl = 0;
+    for (; sl + 3 < slices; sl += 4) {
+        s0 += src[sl * slice_stride];
+        s1 += src[(sl + 1) * slice_stride];
+        s2 += src[(sl + 2) * slice_stride];
+        s3 += src[(sl + 3) * slice_stride];
+    }
+    for (; sl < slices; ++sl) s0 += src[sl * slice_stride];
+    return (s0 + s1) + (s2 + s3);
+}
 int64_t im2col_scratch_bytes(const Geometry &g);
 int launch_im2col_conv(const float *act, const Geometry &g, const float *w, void *lowered,
                        float *out, int precision, hipStream_t stream);

@@ -9,6 +9,7 @@
 // rows that reach a wavefront's output rows form one contiguous lane range found by a
 // ballot.  No two wavefronts add to the same output and every output adds its terms in
 // stream order, so results are bitwise repeatable.
+
 #include "common.hpp"
 
 namespace cpoconv {
@@ -273,29 +274,68 @@ __global__ __launch_bounds__(kConvThreads) void spmv_conv_lds_kernel(const Geome
                 out[(static_cast<int64_t>(k) * g.Oh + y) * g.Ow + x0 + x] = acc[((y - y0) * kTX + x) * kLanes + lane];
 }
 
+// out[k][y][x] = sum over slices of partial[slice][y][x][k]; one workgroup per (output row,
+// 64 kernels, 16 columns): reads coalesced along k, writes runs along x via LDS.
+constexpr int kEpiCols = 16;
+
+__global__ __launch_bounds__(256) void reduce_transpose_kernel(const Geometry g, const float *__restrict__ partial,
+                                                              int slices, int Ypad, int Xpad, float *__restrict__ out)
+{
+    __shared__ float t[kLanes][kEpiCols + 1];
+    const int y = blockIdx.x, kb = blockIdx.y * kLanes, xb = blockIdx.z * kEpiCols;
+    const int tid = threadIdx.x, lane = tid & (kLanes - 1), wave = tid / kLanes;
+    const int64_t slice_stride = static_cast<int64_t>(Ypad) * Xpad * g.Kpad;
+#pragma unroll
+    for (int u = 0; u < kEpiCols / 4; ++u) {
+        const int x = xb + wave * (kEpiCols / 4) + u;
+        const float *src = partial + (static_cast<int64_t>(y) * Xpad + min(x, Xpad - 1)) * g.Kpad + kb + lane;
+        t[lane][wave * (kEpiCols / 4) + u] = sum_slices(src, slice_stride, slices);
+    }
+    __syncthreads();
+    for (int i = tid; i < kLanes * kEpiCols; i += 256) {
+        const int k = i / kEpiCols, x = i % kEpiCols;
+        if (kb + k < g.K && xb + x < g.Ow) out[(static_cast<int64_t>(kb + k) * g.Oh + y) * g.Ow + xb + x] = t[k][x];
+    }
+}
+
 }  // namespace
+
+int launch_reduce_transpose(const Geometry &g, const float *partial, int slices, int Ypad, int Xpad, float *out,
+                            hipStream_t stream)
+{
+    KernelTimer timer("reduce_transpose", stream);
+    hipLaunchKernelGGL(reduce_transpose_kernel, dim3(g.Oh, g.Kpad / kLanes, (g.Ow + kEpiCols - 1) / kEpiCols), dim3(256),
+                       0, stream, g, partial, slices, Ypad, Xpad, out);
+    CPOCONV_HIP_TRY(hipGetLastError());
+    return CPOCONV_OK;
+}
 
 int launch_sparse_conv(const cpoconv_map &map, const Geometry &g, int algo, const float *wt, float *out,
                        void *scratch, hipStream_t stream)
 {
     char *base = static_cast<char *>(scratch);
     int32_t *mtab = reinterpret_cast<int32_t *>(base + scratch_counts_bytes(g));
+    const int64_t after_mtab = scratch_counts_bytes(g) + scratch_mtab_bytes(g);
     int32_t *in_full = nullptr;
     const int32_t *indices = map.in;
     if (algo == CPOCONV_ALGO_CPS && g.top_slot >= 0) {
-        in_full = reinterpret_cast<int32_t *>(base + scratch_counts_bytes(g) + scratch_mtab_bytes(g));
+        in_full = reinterpret_cast<int32_t *>(base + after_mtab);
         indices = in_full;
     }
-    const bool tile = tile_kernel_supports(g);
+    const bool strip = strip_kernel_preferred(g) || (strip_kernel_supports(g) && !tile_kernel_supports(g));
+    const bool tile = strip || tile_kernel_supports(g);
     if (tile || in_full != nullptr) {
         KernelTimer timer("conv_prologue", stream);
         hipLaunchKernelGGL(conv_prologue_kernel, dim3(g.C), dim3(kExpThreads), 0, stream, g, map.ptr, map.in,
                            map.chan_off, mtab, in_full);
         CPOCONV_HIP_TRY(hipGetLastError());
     }
+    if (strip) {
+        float *partial = reinterpret_cast<float *>(base + after_mtab + scratch_indices_bytes(g));
+        return launch_sparse_conv_strip(map, indices, mtab, g, wt, out, partial, stream);
+    }
     if (tile) {
-        float *partial = reinterpret_cast<float *>(base + scratch_counts_bytes(g) + scratch_mtab_bytes(g) +
-                                                   scratch_indices_bytes(g));
+        float *partial = reinterpret_cast<float *>(base + after_mtab + scratch_indices_bytes(g));
         return launch_sparse_conv_tile(map, indices, mtab, g, wt, out, partial, stream);
     }
     const dim3 grid((g.Ow + kTX - 1) / kTX, (g.Oh + kTY - 1) / kTY, g.Kpad / kLanes);

@@ -1,0 +1,344 @@
+// Strip SpMV convolution over a CPO map (Algorithm 2) for the common kernel shapes.
+//
+// CPO streams are column-major: inside a channel and overlap type the NZEs follow the
+// partitions (columns) and, inside a column, the rows.  ptr therefore delimits exactly the NZEs
+// of a strip of output columns, for all rows at once.  A workgroup owns such a strip (TX output
+// columns, all or up to 16*TY output rows) for 64 output kernels and one slice of the input
+// channels; its wavefronts are the strip's row bands.
+//
+// Per group of G channels
+//   decode   the wavefronts share the NZE chunks (64 NZEs each) of the group's channels: load
+//            value and index, find the partition from the position in DA (ptr used as CSR row
+//            pointers), split the index into padded row and column inside the partition, and
+//            drop the value at its cell of the channel's LDS patch of the padded input;
+//   apply    every wavefront reads the cells behind its TY x TX tile one per lane, takes a ballot
+//            of the non-zero ones and walks them in a fully unrolled loop: a clear bit costs three
+//            scalar instructions, a set bit broadcasts the value from its lane (lanes are the 64
+//            output kernels, so the NZE is a scalar operand) and issues the kh*(pType+1) FMAs of
+//            convSpMv that land in the tile, with compile-time registers for sums and weights.
+// No two wavefronts add to the same output, so there is no reduction inside the workgroup.  The
+// tile's sums go to partial[slice][y][x][k] (k fastest: coalesced); a second kernel adds the
+// channel slices in a fixed order and transposes to K x Oh x Ow (one slice: written directly).
+
+#include "common.hpp"
+
+namespace cpoconv {
+
+namespace {
+
+constexpr int kMaxBands = 16;        // wavefronts (row bands) per workgroup
+constexpr int kStripTabBytes = 6 * 1024;
+constexpr int kMaxSlices = 32;
+
+__device__ __forceinline__ int lane_id() { return threadIdx.x & (kLanes - 1); }
+__device__ __forceinline__ int uni(int v) { return __builtin_amdgcn_readfirstlane(v); }
+
+struct StripArgs {
+    const float *da;
+    const int32_t *in;        // one index per NZE, laid out like DA
+    const int32_t *mtab;      // [C][n_types][Ow+1] absolute DA offsets (prologue kernel)
+    const float *wt;          // [C][kh*kw][Kpad]
+    float *partial;           // [slices][Ypad][Xpad][Kpad]
+    float *out;               // K x Oh x Ow
+    int32_t slices;           // channel slices across workgroups
+    int32_t Ypad, Xpad;
+    int32_t bands;            // wavefronts per workgroup
+    int32_t batch;            // channels per table refill (multiple of G)
+    int32_t chunks;           // upper bound of 64-NZE chunks of one channel's strip
+};
+
+template <int KH, int KW, int S, int TY, int TX, int G>
+__global__ __launch_bounds__(kMaxBands *kLanes) void spmv_conv_strip_kernel(const Geometry g, const StripArgs a)
+{
+    constexpr int RH = (TY - 1) * S + KH;      // rows of the padded input behind one tile
+    constexpr int RW = (TX - 1) * S + KW;      // columns behind the strip
+    constexpr int NCELL = RH * RW;
+    constexpr int NDREG = (NCELL + kLanes - 1) / kLanes;
+    constexpr int TAPS = KH * KW;
+    constexpr int SPAN = TX + KW + 1;          // table slots per (channel, type): partitions p_lo-1 ..
+    constexpr int IT = 4;                      // decode items whose loads are in flight together
+
+    extern __shared__ int32_t smem[];
+    // layout: tab[batch][n_types][SPAN] | wl[G][TAPS][64] | patch[G][RW][PH]
+    int32_t *tab = smem;
+    float *wl = reinterpret_cast<float *>(tab + a.batch * g.n_types * SPAN);
+    float *patch = wl + G * TAPS * kLanes;
+
+    const int tid = threadIdx.x, lane = lane_id(), wave = tid / kLanes;
+    const int nthreads = a.bands * kLanes;
+    const int x0 = blockIdx.x * TX;
+    const int yb = blockIdx.y * a.bands * TY;               // first output row of the workgroup
+    const int y0 = yb + wave * TY;                          // first output row of this wavefront
+    const int PH = (a.bands * TY - 1) * S + KH;             // patch height: rows behind the workgroup
+    const int ngroups = g.Kpad / kLanes;
+    const int kg = blockIdx.z % ngroups, slice = blockIdx.z / ngroups;
+    const int kbase = kg * kLanes;
+    const int per_slice = (g.C + a.slices - 1) / a.slices;
+    const int c_begin = slice * per_slice, c_end = min(g.C, c_begin + per_slice);
+
+    float acc[TY][TX];
+#pragma unroll
+    for (int y = 0; y < TY; ++y)
+#pragma unroll
+        for (int x = 0; x < TX; ++x) acc[y][x] = 0.0f;
+
+    // one NZE -> its cell of the patch.  n is its position in DA; the partition is the number of
+    // table boundaries at or below n.
+    auto scatter = [&](int idx, float v, int n, const int (&bound)[SPAN], int p_lo, float *pt) {
+        int prel = 0;
+#pragma unroll
+        for (int e = 1; e < SPAN; ++e) prel += (n >= bound[e]) ? 1 : 0;
+        const int h = idx / KW, wh = idx - h * KW;   // padded row, column inside the partition
+        const int r = h - yb * S;
+        const int q = (p_lo + prel - x0) * S + wh;
+        if (idx >= 0 && r >= 0 && r < PH && q >= 0 && q < RW) pt[q * PH + r] = v;
+    };
+
+    const int main_slot = g.n_types - 1;   // the highest overlap type holds most NZEs
+    for (int cb = c_begin; cb < c_end; cb += a.batch) {
+        const int nb = min(a.batch, c_end - cb);
+        __syncthreads();   // previous batch's table no longer in use
+        // table: DA offset after partition p for the partitions that reach the strip; slot e of
+        // (channel, type) holds partition p_lo - 1 + e (clamped: later slots repeat the end)
+        for (int idx = tid; idx < nb * g.n_types * SPAN; idx += nthreads) {
+            const int e = idx % SPAN;
+            const int i = (idx / SPAN) % g.n_types;
+            const int c = cb + idx / (SPAN * g.n_types);
+            const int p = min(max(0, x0 - static_cast<int>(g.type_id[i])) - 1 + e, g.Ow - 1);
+            tab[idx] = a.mtab[(static_cast<int64_t>(c) * g.n_types + i) * (g.Ow + 1) + p + 1];
+        }
+
+        for (int g0 = 0; g0 < nb; g0 += G) {
+            const int ng = min(G, nb - g0);
+            // ---- clear the patches of the group (all readers of the previous group are done) ----
+            __syncthreads();
+            for (int i = tid; i < ng * RW * PH; i += nthreads) patch[i] = 0.0f;
+            // weights of the group's channels for this workgroup's 64 kernels (coalesced rows of 64)
+            for (int i = tid; i < ng * TAPS * kLanes; i += nthreads)
+                wl[i] = a.wt[(static_cast<int64_t>(cb + g0) * TAPS + i / kLanes) * g.Kpad + kbase + (i & (kLanes - 1))];
+            __syncthreads();
+
+            // ---- decode: work item = (channel of the group, 64-NZE chunk of its main-type range);
+            // the loads of IT items are issued before any of them is used ------------------------
+            const int nitems = ng * a.chunks;
+            for (int it0 = wave; it0 < nitems; it0 += a.bands * IT) {
+                int idxv[IT], nv[IT];
+                float valv[IT];
+                const int t_main = g.type_id[main_slot];
+                const int plo_main = max(0, x0 - t_main), phi = min(g.Ow - 1, x0 + TX - 1);
+#pragma unroll
+                for (int u = 0; u < IT; ++u) {
+                    const int item = it0 + u * a.bands;
+                    idxv[u] = -1; valv[u] = 0.0f; nv[u] = 0;
+                    if (item < nitems) {
+                        const int gi = item / a.chunks, ch = item - gi * a.chunks;
+                        const int32_t *row = tab + ((g0 + gi) * g.n_types + main_slot) * SPAN;
+                        const int first = uni(row[0]), last = uni(row[phi - plo_main + 1]);
+                        const int n = first + ch * kLanes + lane;
+                        nv[u] = n;
+                        if (n < last) { idxv[u] = a.in[n]; valv[u] = a.da[n]; }
+                    }
+                }
+#pragma unroll
+                for (int u = 0; u < IT; ++u) {
+                    const int item = it0 + u * a.bands;
+                    if (item >= nitems) continue;
+                    const int gi = item / a.chunks, ch = item - gi * a.chunks;
+                    float *pt = patch + gi * RW * PH;
+                    const int32_t *rows = tab + ((g0 + gi) * g.n_types) * SPAN;
+                    int bound[SPAN];
+#pragma unroll
+                    for (int e = 0; e < SPAN; ++e) bound[e] = uni(rows[main_slot * SPAN + e]);
+                    scatter(idxv[u], valv[u], nv[u], bound, plo_main, pt);
+                    if (ch != 0) continue;
+                    // the lower overlap types (edge columns): few NZEs, loaded on demand
+                    for (int i = 0; i < main_slot; ++i) {
+                        const int t = g.type_id[i];
+                        const int p_lo = max(0, x0 - t);
+                        const int f = uni(rows[i * SPAN]), l = uni(rows[i * SPAN + phi - p_lo + 1]);
+                        if (l == f) continue;
+#pragma unroll
+                        for (int e = 0; e < SPAN; ++e) bound[e] = uni(rows[i * SPAN + e]);
+                        for (int n0 = f; n0 < l; n0 += kLanes) {
+                            const int n = n0 + lane;
+                            const bool ok = n < l;
+                            scatter(ok ? a.in[n] : -1, ok ? a.da[n] : 0.0f, n, bound, p_lo, pt);
+                        }
+                    }
+                }
+            }
+            __syncthreads();
+
+            // ---- apply: every wavefront walks the cells behind its own tile --------------------
+            if (y0 < g.Oh) {
+#pragma unroll 1
+                for (int gi = 0; gi < ng; ++gi) {
+                    const float *pt = patch + gi * RW * PH + wave * TY * S;   // first row of the band
+                    float cell[NDREG];
+                    unsigned long long bits[NDREG];
+                    bool any = false;
+#pragma unroll
+                    for (int d = 0; d < NDREG; ++d) {
+                        const int i = d * kLanes + lane;
+                        const int q = i / RH, r = i - q * RH;
+                        cell[d] = i < NCELL ? pt[q * PH + r] : 0.0f;
+                        bits[d] = __ballot((__float_as_uint(cell[d]) & 0x7fffffffu) != 0u);
+                        any = any || bits[d] != 0ull;
+                    }
+                    if (!any) continue;
+                    float w[TAPS];
+#pragma unroll
+                    for (int tp = 0; tp < TAPS; ++tp) w[tp] = wl[(gi * TAPS + tp) * kLanes + lane];
+#pragma unroll
+                    for (int q = 0; q < RW; ++q) {
+#pragma unroll
+                        for (int r = 0; r < RH; ++r) {
+                            const int cellno = q * RH + r;
+                            if (bits[cellno / kLanes] & (1ull << (cellno % kLanes))) {
+                                const float v = __int_as_float(
+                                    __builtin_amdgcn_readlane(__float_as_int(cell[cellno / kLanes]), cellno % kLanes));
+#pragma unroll
+                                for (int l = 0; l < KH; ++l) {
+                                    if ((r - l) < 0 || (r - l) % S != 0 || (r - l) / S >= TY) continue;
+#pragma unroll
+                                    for (int ww = 0; ww < KW; ++ww) {
+                                        if ((q - ww) < 0 || (q - ww) % S != 0 || (q - ww) / S >= TX) continue;
+                                        acc[(r - l) / S][(q - ww) / S] =
+                                            fmaf(v, w[l * KW + ww], acc[(r - l) / S][(q - ww) / S]);
+                                    }
+                                }
+                            }
+                        }
+                    }
+                }
+            }
+        }
+    }
+
+    const int k = kbase + lane;
+    if (a.slices == 1) {
+        if (k < g.K)
+#pragma unroll
+            for (int y = 0; y < TY; ++y)
+#pragma unroll
+                for (int x = 0; x < TX; ++x)
+                    if (y0 + y < g.Oh && x0 + x < g.Ow)
+                        a.out[(static_cast<int64_t>(k) * g.Oh + y0 + y) * g.Ow + x0 + x] = acc[y][x];
+        return;
+    }
+    // partial sums of this channel slice, kernel index fastest
+    if (y0 < g.Oh) {
+        float *dst = a.partial + ((static_cast<int64_t>(slice) * a.Ypad + y0) * a.Xpad + x0) * g.Kpad + k;
+#pragma unroll
+        for (int y = 0; y < TY; ++y)
+#pragma unroll
+            for (int x = 0; x < TX; ++x) dst[(static_cast<int64_t>(y) * a.Xpad + x) * g.Kpad] = acc[y][x];
+    }
+}
+
+struct StripPlan {
+    int bands, row_blocks, slices, batch, chunks, Ypad;
+    size_t lds;
+};
+
+template <int KH, int KW, int S, int TY, int TX, int G>
+StripPlan strip_plan(const Geometry &g)
+{
+    constexpr int RW = (TX - 1) * S + KW, SPAN = TX + KW + 1;
+    StripPlan p;
+    const int bands_all = (g.Oh + TY - 1) / TY;
+    p.row_blocks = (bands_all + kMaxBands - 1) / kMaxBands;
+    p.bands = (bands_all + p.row_blocks - 1) / p.row_blocks;
+    const int PH = (p.bands * TY - 1) * S + KH;
+    p.Ypad = p.row_blocks * p.bands * TY;
+    p.chunks = (RW * g.Ih + kLanes - 1) / kLanes;   // a strip's partitions hold at most RW columns of Ih rows
+    // about one workgroup per compute unit (measured best: the workgroups are large), each slice
+    // keeping four channels or more
+    const int wgs = ((g.Ow + TX - 1) / TX) * p.row_blocks * (g.Kpad / kLanes);
+    int s = 256 / wgs;
+    const int cap = (g.C + 3) / 4;
+    if (s > cap) s = cap;
+    if (s > kMaxSlices) s = kMaxSlices;
+    if (s < 1) s = 1;
+    p.slices = s;
+    int batch = kStripTabBytes / (g.n_types * SPAN * 4);
+    batch = batch / G * G;
+    if (batch < G) batch = G;
+    if (batch > 64) batch = 64;
+    p.batch = batch;
+    p.lds = (static_cast<size_t>(batch) * g.n_types * SPAN + static_cast<size_t>(G) * KH * KW * kLanes +
+             static_cast<size_t>(G) * RW * PH) * 4;
+    return p;
+}
+
+template <int KH, int KW, int S, int TY, int TX, int G>
+int launch_strip(const cpoconv_map &map, const int32_t *indices, const int32_t *mtab, const Geometry &g,
+                 const float *wt, float *out, float *partial, hipStream_t stream)
+{
+    const StripPlan p = strip_plan<KH, KW, S, TY, TX, G>(g);
+    const int ntx = (g.Ow + TX - 1) / TX;
+    StripArgs a;
+    a.da = map.da; a.in = indices; a.mtab = mtab; a.wt = wt; a.partial = partial; a.out = out;
+    a.slices = p.slices; a.Ypad = p.row_blocks * p.bands * TY; a.Xpad = ntx * TX;
+    a.bands = p.bands; a.batch = p.batch; a.chunks = p.chunks;
+    {
+        KernelTimer timer("spmv_conv_strip", stream);
+        hipLaunchKernelGGL((spmv_conv_strip_kernel<KH, KW, S, TY, TX, G>),
+                           dim3(ntx, p.row_blocks, (g.Kpad / kLanes) * p.slices), dim3(p.bands * kLanes), p.lds, stream,
+                           g, a);
+    }
+    CPOCONV_HIP_TRY(hipGetLastError());
+    if (p.slices > 1) return launch_reduce_transpose(g, partial, p.slices, a.Ypad, a.Xpad, out, stream);
+    return CPOCONV_OK;
+}
+
+}  // namespace
+
+bool strip_kernel_supports(const Geometry &g)
+{
+    if (g.n_types < 1) return false;
+    return (g.kh == 3 && g.kw == 3 && (g.stride == 1 || g.stride == 2)) ||
+           (g.kh == 5 && g.kw == 5 && g.stride == 1) || (g.kh == 7 && g.kw == 7 && g.stride == 2);
+}
+
+// Measured on MI355X over the workload layers: the strip kernel wins where one channel slice
+// would leave the register-tile kernel few workgroups with long serial channel loops or where
+// its shared patch saves decoding: layers of few channels, 5 x 5 kernels, and wide 3 x 3 stride 1
+// maps with 128 kernels or more.  Elsewhere the register-tile kernel is as fast or faster.
+bool strip_kernel_preferred(const Geometry &g)
+{
+    if (!strip_kernel_supports(g)) return false;
+    if (g.C <= 16 || g.kh == 5) return true;
+    return g.stride == 1 && g.Oh * g.Ow >= 2048 && g.Kpad >= 128;
+}
+
+#define CPOCONV_STRIP_DISPATCH(CALL)                                              \
+    if (g.kh == 3 && g.kw == 3 && g.stride == 1) return CALL(3, 3, 1, 4, 4, 8);   \
+    if (g.kh == 3 && g.kw == 3 && g.stride == 2) return CALL(3, 3, 2, 4, 4, 8);   \
+    if (g.kh == 5 && g.kw == 5 && g.stride == 1) return CALL(5, 5, 1, 4, 4, 8);   \
+    if (g.kh == 7 && g.kw == 7 && g.stride == 2) return CALL(7, 7, 2, 4, 4, 4);
+
+int64_t strip_kernel_partial_bytes(const Geometry &g)
+{
+    if (!strip_kernel_supports(g)) return 0;
+#define CPOCONV_STRIP_BYTES(KH, KW, S, TY, TX, G)                                               \
+    [&]() -> int64_t {                                                                          \
+        const StripPlan p = strip_plan<KH, KW, S, TY, TX, G>(g);                                \
+        return 4 * static_cast<int64_t>(p.slices) * p.Ypad * ((g.Ow + TX - 1) / TX * TX) * g.Kpad; \
+    }()
+    CPOCONV_STRIP_DISPATCH(CPOCONV_STRIP_BYTES)
+#undef CPOCONV_STRIP_BYTES
+    return 0;
+}
+
+int launch_sparse_conv_strip(const cpoconv_map &map, const int32_t *indices, const int32_t *mtab, const Geometry &g,
+                             const float *wt, float *out, float *partial, hipStream_t stream)
+{
+#define CPOCONV_STRIP_LAUNCH(KH, KW, S, TY, TX, G) \
+    launch_strip<KH, KW, S, TY, TX, G>(map, indices, mtab, g, wt, out, partial, stream)
+    CPOCONV_STRIP_DISPATCH(CPOCONV_STRIP_LAUNCH)
+#undef CPOCONV_STRIP_LAUNCH
+    return CPOCONV_ERR_SHAPE;
+}
+
+}  // namespace cpoconv

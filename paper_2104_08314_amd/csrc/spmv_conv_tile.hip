@@ -16,8 +16,9 @@
 //   4. walks the cells in a fully unrolled loop: a cell whose bit is clear costs two scalar
 //      instructions; a set bit broadcasts the value from its lane and issues the kh*(pType+1)
 //      FMAs of convSpMv that land inside the tile, all with compile-time register indices.
-// The tile's partial sums go to a [slice][y][x][k] buffer (k fastest: coalesced); a second
-// kernel adds the slices in order and transposes to the K x Oh x Ow output.
+// With several channel slices the tile's partial sums go to a [slice][y][x][k] buffer (k fastest:
+// coalesced) and a second kernel adds the slices in a fixed order and transposes to the
+// K x Oh x Ow output; with one slice the output is written directly.
 #include "common.hpp"
 
 namespace cpoconv {
@@ -295,7 +296,7 @@ __global__ __launch_bounds__(NW *kLanes) void spmv_conv_tile_kernel(const Geomet
                     for (int k = 0; k < KPL; ++k)
                         dst[(static_cast<int64_t>(y) * a.Xpad + x) * g.Kpad + k * kLanes] = acc[y][x][k];
         }
-        return;
+        return;   // a second kernel adds the slices
     }
     // one slice: transpose through LDS (row stride KW64+1 against bank conflicts) and store the
     // K x Oh x Ow output directly, TX consecutive x per kernel and row
@@ -317,36 +318,6 @@ __global__ __launch_bounds__(NW *kLanes) void spmv_conv_tile_kernel(const Geomet
     }
 }
 
-// out[k][y][x] = sum over slices (ascending) of partial[slice][y][x][k]; one workgroup per
-// (output row, 64 kernels, 16 columns): reads coalesced along k, writes runs along x via LDS.
-constexpr int kEpiCols = 16;
-
-__global__ __launch_bounds__(256) void reduce_transpose_kernel(const Geometry g, const float *__restrict__ partial,
-                                                              int slices, int Ypad, int Xpad, float *__restrict__ out)
-{
-    __shared__ float t[kLanes][kEpiCols + 1];
-    const int y = blockIdx.x, kb = blockIdx.y * kLanes, xb = blockIdx.z * kEpiCols;
-    const int tid = threadIdx.x, lane = tid & (kLanes - 1), wave = tid / kLanes;
-    const int64_t slice_stride = static_cast<int64_t>(Ypad) * Xpad * g.Kpad;
-    float s[kEpiCols / 4];
-#pragma unroll
-    for (int u = 0; u < kEpiCols / 4; ++u) {
-        const int x = xb + wave * (kEpiCols / 4) + u;   // x < Xpad always: the buffer is padded
-        const float *src = partial + (static_cast<int64_t>(y) * Xpad + min(x, Xpad - 1)) * g.Kpad + kb + lane;
-        float v = src[0];
-#pragma unroll 4
-        for (int sl = 1; sl < slices; ++sl) v += src[sl * slice_stride];
-        s[u] = v;
-    }
-#pragma unroll
-    for (int u = 0; u < kEpiCols / 4; ++u) t[lane][wave * (kEpiCols / 4) + u] = s[u];
-    __syncthreads();
-    for (int i = tid; i < kLanes * kEpiCols; i += 256) {
-        const int k = i / kEpiCols, x = i % kEpiCols;
-        if (kb + k < g.K && xb + x < g.Ow) out[(static_cast<int64_t>(kb + k) * g.Oh + y) * g.Ow + xb + x] = t[k][x];
-    }
-}
-
 // Launch shape of the register kernel for a layer.
 struct TilePlan {
     int ty, tx, kpl, nw, slices;
@@ -361,7 +332,7 @@ TilePlan plan_for(const Geometry &g)
     p.ty = 4; p.tx = 8; p.kpl = 1; p.nw = 8;
     const int ntiles = ((g.Ow + p.tx - 1) / p.tx) * ((g.Oh + p.ty - 1) / p.ty);
     const int wgs = ntiles * (g.Kpad / (kLanes * p.kpl));
-    int s = (384 + wgs / 2) / wgs;
+    int s = (512 + wgs / 2) / wgs;
     const int cap = (g.C + 7) / 8;
     if (s > cap) s = cap;
     if (s > kMaxSlices) s = kMaxSlices;
@@ -400,12 +371,7 @@ int launch_tile(const cpoconv_map &map, const int32_t *indices, const int32_t *m
                            dim3(NW * kLanes), lds, stream, g, a);
     }
     CPOCONV_HIP_TRY(hipGetLastError());
-    if (slices > 1) {
-        KernelTimer timer("reduce_transpose", stream);
-        hipLaunchKernelGGL(reduce_transpose_kernel, dim3(g.Oh, g.Kpad / kLanes, (g.Ow + kEpiCols - 1) / kEpiCols),
-                           dim3(256), 0, stream, g, partial, slices, a.Ypad, a.Xpad, out);
-        CPOCONV_HIP_TRY(hipGetLastError());
-    }
+    if (slices > 1) return launch_reduce_transpose(g, partial, slices, a.Ypad, a.Xpad, out, stream);
     return CPOCONV_OK;
 }
 

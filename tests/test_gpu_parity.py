@@ -124,6 +124,12 @@ EDGE_SHAPES = [
     (1, 254, 254, 2, 3, 3, 1, 1),    # largest supported map
     (2, 30, 30, 3, 11, 11, 4, 2),    # largest kernel, stride 4
     (2, 16, 16, 130, 2, 2, 2, 0),
+    # more than 16 channels: the register-tile kernel rather than the strip kernel
+    (20, 9, 11, 66, 3, 3, 1, 1),
+    (18, 13, 9, 3, 3, 3, 2, 1),
+    (17, 15, 14, 5, 7, 7, 2, 3),
+    (40, 30, 29, 70, 3, 3, 1, 1),     # several channel slices, ragged tiles
+    (33, 21, 37, 4, 3, 3, 1, 0),      # VALID padding in the register-tile kernel
 ]
 
 
