@@ -73,7 +73,25 @@ class LayerRun:
         return {"ptr": h_cpo[0], "nnz": h_cpo[1], "in_cpo": h_cpo[2], "in_cps": h_cps[2]}
 
 
-def algorithmic_figures(spec, lens):
+def sparse_flops(spec, act_np):
+    """2 x (kernel cells every NZE meets: rows x partitions holding it) x K, counted exactly."""
+    import numpy as np
+
+    C, H, W, K, kh, kw, s, p = spec.shape_tuple
+
+    def meets(n_in, n_out, k):
+        cnt = np.zeros(n_in, np.int64)
+        for o in range(n_out):
+            cnt[o * s:o * s + k] += 1
+        return cnt
+
+    rows = meets(spec.Ih, spec.Oh, kh)[p:p + H]
+    cols = meets(spec.Iw, spec.Ow, kw)[p:p + W]
+    nz = (act_np.view(np.uint32) & 0x7FFFFFFF) != 0
+    return 2.0 * K * float(np.einsum("chw,h,w->", nz.astype(np.int64), rows, cols))
+
+
+def algorithmic_figures(spec, lens, act_np):
     """Bytes and flops the method itself must move / compute for one layer (4-byte elements)."""
     C, H, W, K, kh, kw, s, p = spec.shape_tuple
     nnz, ptr = lens["nnz"], lens["ptr"]
@@ -85,8 +103,7 @@ def algorithmic_figures(spec, lens):
         "cps_encode_bytes": 4 * C * H * W + 4 * nnz + 4 * lens["in_cps"] + 4 * ptr,
         "cpo_conv_bytes": 8 * nnz + 4 * ptr + wbytes + 4 * out_elems,
         "cps_conv_bytes": 4 * nnz + 4 * lens["in_cps"] + 4 * ptr + wbytes + 4 * out_elems,
-        # every NZE meets kh*kw/stride^2 kernel cells on average, for K kernels
-        "sparse_flops": 2.0 * nnz * kh * kw * K / (s * s),
+        "sparse_flops": sparse_flops(spec, act_np),
         "im2col_f32_bytes": 4 * C * H * W + 2 * 4 * S + wbytes + 4 * out_elems,
         "im2col_bf16_bytes": 4 * C * H * W + 2 * 2 * S + wbytes + 4 * out_elems,
         "dense_flops": float(spec.dense_flops),
@@ -117,6 +134,19 @@ def stage_roofline(name, us, fig):
     tf = fig["dense_flops"] / t / 1e12
     return {"bound": "mfma", "achieved": tf, "peak": peak, "unit": "TFLOP/s", "frac": tf / peak,
             "hbm_gbs": fig[name + "_bytes"] / t / 1e9}
+
+
+def event_pair_overhead_us(torch, pairs=200):
+    """What two HIP events recorded back to back on the launch stream read with nothing between
+    them: the part of an event-bracketed launch that is not the kernel."""
+    ev = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(pairs)]
+    torch.cuda.synchronize()
+    for a, b in ev:
+        a.record()
+        b.record()
+    torch.cuda.synchronize()
+    v = sorted(a.elapsed_time(b) * 1e3 for a, b in ev)
+    return v[len(v) // 2]
 
 
 def kernel_times(api, torch, run, reps):
@@ -150,7 +180,7 @@ def kernel_roofline(stage, kernel, us, fig, spec, lens):
         if stage == "cps_conv":
             b += 4 * lens["in_cps"] + 4 * lens["nnz"]
         return hbm(b)
-    if kernel in ("spmv_conv_tile", "spmv_conv_lds"):
+    if kernel in ("spmv_conv_tile", "spmv_conv_strip", "spmv_conv_lds"):
         r = stage_roofline(stage, us, fig)
         r["algorithmic_flops"] = fig["sparse_flops"]
         r["algorithmic_bytes"] = fig[stage + "_bytes"]
@@ -170,7 +200,7 @@ def kernel_roofline(stage, kernel, us, fig, spec, lens):
 def measure_layer(api, torch, workloads, spec, reps, warm):
     run = LayerRun(api, torch, workloads, spec)
     lens = run.lengths()
-    fig = algorithmic_figures(spec, lens)
+    fig = algorithmic_figures(spec, lens, run.act_np)
     times = {}
     for name, fn in run.stages.items():
         for _ in range(warm):
@@ -256,6 +286,9 @@ def main():
                     help="also measure every layer of the five workloads (per-layer report on stderr and "
                          "in gpurun_out/layers.json)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="also launch a plain elementwise kernel that reads and writes 256 MiB, five times: the "
+                         "known-size kernel that rocprofv3 FETCH_SIZE / WRITE_SIZE readings are scaled by")
     args = ap.parse_args()
     if args.gpus != 1:
         sys.exit("bench.py: this build runs on one GPU only (the path is a single-GPU kernel pipeline); "
@@ -269,6 +302,14 @@ def main():
     if not torch.cuda.is_available():
         sys.exit("bench.py: no GPU visible")
     torch.cuda.set_device(0)
+
+    if args.calibrate_copy:
+        src = torch.ones(64 << 20, dtype=torch.float32, device="cuda")
+        dst = torch.empty_like(src)
+        for _ in range(5):
+            torch.mul(src, 1.0, out=dst)
+        torch.cuda.synchronize()
+        del src, dst
 
     spec = workloads.layers(args.config)[0]
     run, row, times, fig = measure_layer(api, torch, workloads, spec, reps=max(args.steps, 20), warm=max(args.warmup, 5))
@@ -295,11 +336,15 @@ def main():
     # per-kernel durations (HIP events around every launch) and the dominant kernel of the step
     lens = run.lengths()
     ktimes = kernel_times(api, torch, run, reps=max(20, min(args.steps, 100)))
+    overhead = event_pair_overhead_us(torch)
     kernels = []
     for stage in ("cpo_encode", "cpo_conv", "cps_encode", "cps_conv", "im2col_f32"):
         for kname, rec in ktimes[stage].items():
-            entry = {"stage": stage, "kernel": kname, "avg_us": rec["avg_us"], "launches": rec["launches"]}
-            r = kernel_roofline(stage, kname, rec["avg_us"], fig, spec, lens)
+            # launch duration = event-to-event time less what an empty event pair reads
+            net = round(max(rec["avg_us"] - overhead, 0.1), 3)
+            entry = {"stage": stage, "kernel": kname, "avg_us": net, "event_to_event_us": rec["avg_us"],
+                     "launches": rec["launches"]}
+            r = kernel_roofline(stage, kname, net, fig, spec, lens)
             if r:
                 entry.update(r)
             kernels.append(entry)
@@ -307,6 +352,7 @@ def main():
     roof = {k: dom[k] for k in ("bound", "achieved", "peak", "unit", "frac") if k in dom}
     roof["kernel"] = dom["kernel"] + " (" + dom["stage"] + ")"
     roof["avg_launch_us"] = dom["avg_us"]
+    roof["event_pair_overhead_us"] = round(overhead, 3)
     for k in ("algorithmic_bytes", "algorithmic_flops"):
         if k in dom:
             roof[k] = dom[k]
