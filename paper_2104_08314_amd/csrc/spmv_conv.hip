@@ -11,6 +11,7 @@
 // stream order, so results are bitwise repeatable.
 
 #include "common.hpp"
+#include "resolve_ptr.hpp"
 
 namespace cpoconv {
 
@@ -324,7 +325,13 @@ int launch_sparse_conv(const cpoconv_map &map, const Geometry &g, int algo, cons
     }
     const bool strip = strip_kernel_preferred(g) || (strip_kernel_supports(g) && !tile_kernel_supports(g));
     const bool tile = strip || tile_kernel_supports(g);
-    if (tile || in_full != nullptr) {
+    // The strip kernel resolves ptr itself for CPO maps whose segments fit a wavefront (measured:
+    // 1-4 us faster than a prologue launch; in the register-tile kernel, where many more workgroups
+    // would repeat the work, it was slower).  Otherwise, and for the index reconstruction of CPS,
+    // a prologue kernel runs first.
+    const bool in_kernel = strip && in_full == nullptr && resolve_in_kernel_ok(g);
+    if (in_kernel) mtab = nullptr;
+    if ((tile && !in_kernel) || in_full != nullptr) {
         KernelTimer timer("conv_prologue", stream);
         hipLaunchKernelGGL(conv_prologue_kernel, dim3(g.C), dim3(kExpThreads), 0, stream, g, map.ptr, map.in,
                            map.chan_off, mtab, in_full);

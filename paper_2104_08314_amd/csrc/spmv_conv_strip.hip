@@ -21,6 +21,7 @@
 // channel slices in a fixed order and transposes to K x Oh x Ow (one slice: written directly).
 
 #include "common.hpp"
+#include "resolve_ptr.hpp"
 
 namespace cpoconv {
 
@@ -36,7 +37,9 @@ __device__ __forceinline__ int uni(int v) { return __builtin_amdgcn_readfirstlan
 struct StripArgs {
     const float *da;
     const int32_t *in;        // one index per NZE, laid out like DA
-    const int32_t *mtab;      // [C][n_types][Ow+1] absolute DA offsets (prologue kernel)
+    const int32_t *mtab;      // [C][n_types][Ow+1] absolute DA offsets (prologue kernel), or null:
+    const int32_t *ptr;       //   then the kernel resolves ptr itself, with the
+    const int32_t *chan_off;  //   channel offsets of the map's side band
     const float *wt;          // [C][kh*kw][Kpad]
     float *partial;           // [slices][Ypad][Xpad][Kpad]
     float *out;               // K x Oh x Ow
@@ -59,9 +62,10 @@ __global__ __launch_bounds__(kMaxBands *kLanes) void spmv_conv_strip_kernel(cons
     constexpr int IT = 4;                      // decode items whose loads are in flight together
 
     extern __shared__ int32_t smem[];
-    // layout: tab[batch][n_types][SPAN] | wl[G][TAPS][64] | patch[G][RW][PH]
+    // layout: tab[batch][n_types][SPAN] | stage[bands][kStageInts] | wl[G][TAPS][64] | patch[G][RW][PH]
     int32_t *tab = smem;
-    float *wl = reinterpret_cast<float *>(tab + a.batch * g.n_types * SPAN);
+    int32_t *stage = tab + a.batch * g.n_types * SPAN;
+    float *wl = reinterpret_cast<float *>(stage + a.bands * kStageInts);
     float *patch = wl + G * TAPS * kLanes;
 
     const int tid = threadIdx.x, lane = lane_id(), wave = tid / kLanes;
@@ -100,12 +104,16 @@ __global__ __launch_bounds__(kMaxBands *kLanes) void spmv_conv_strip_kernel(cons
         __syncthreads();   // previous batch's table no longer in use
         // table: DA offset after partition p for the partitions that reach the strip; slot e of
         // (channel, type) holds partition p_lo - 1 + e (clamped: later slots repeat the end)
-        for (int idx = tid; idx < nb * g.n_types * SPAN; idx += nthreads) {
-            const int e = idx % SPAN;
-            const int i = (idx / SPAN) % g.n_types;
-            const int c = cb + idx / (SPAN * g.n_types);
-            const int p = min(max(0, x0 - static_cast<int>(g.type_id[i])) - 1 + e, g.Ow - 1);
-            tab[idx] = a.mtab[(static_cast<int64_t>(c) * g.n_types + i) * (g.Ow + 1) + p + 1];
+        if (a.mtab != nullptr) {
+            for (int idx = tid; idx < nb * g.n_types * SPAN; idx += nthreads) {
+                const int e = idx % SPAN;
+                const int i = (idx / SPAN) % g.n_types;
+                const int c = cb + idx / (SPAN * g.n_types);
+                const int p = min(max(0, x0 - static_cast<int>(g.type_id[i])) - 1 + e, g.Ow - 1);
+                tab[idx] = a.mtab[(static_cast<int64_t>(c) * g.n_types + i) * (g.Ow + 1) + p + 1];
+            }
+        } else {
+            resolve_ptr_rows<SPAN>(g, a.ptr, a.chan_off, cb, nb, x0, tab, stage, wave, a.bands, lane);
         }
 
         for (int g0 = 0; g0 < nb; g0 += G) {
@@ -266,7 +274,8 @@ StripPlan strip_plan(const Geometry &g)
     if (batch < G) batch = G;
     if (batch > 64) batch = 64;
     p.batch = batch;
-    p.lds = (static_cast<size_t>(batch) * g.n_types * SPAN + static_cast<size_t>(G) * KH * KW * kLanes +
+    p.lds = (static_cast<size_t>(batch) * g.n_types * SPAN + static_cast<size_t>(p.bands) * kStageInts +
+             static_cast<size_t>(G) * KH * KW * kLanes +
              static_cast<size_t>(G) * RW * PH) * 4;
     return p;
 }
@@ -278,7 +287,8 @@ int launch_strip(const cpoconv_map &map, const int32_t *indices, const int32_t *
     const StripPlan p = strip_plan<KH, KW, S, TY, TX, G>(g);
     const int ntx = (g.Ow + TX - 1) / TX;
     StripArgs a;
-    a.da = map.da; a.in = indices; a.mtab = mtab; a.wt = wt; a.partial = partial; a.out = out;
+    a.da = map.da; a.in = indices; a.mtab = mtab; a.ptr = map.ptr; a.chan_off = map.chan_off; a.wt = wt;
+    a.partial = partial; a.out = out;
     a.slices = p.slices; a.Ypad = p.row_blocks * p.bands * TY; a.Xpad = ntx * TX;
     a.bands = p.bands; a.batch = p.batch; a.chunks = p.chunks;
     {
