@@ -41,6 +41,25 @@ def _time_us(torch, fn, reps):
     return e0.elapsed_time(e1) * 1000.0 / reps
 
 
+def _cold_time_us(torch, fn, reps, sweep):
+    """Median duration of `fn` when every call follows a sweep over a buffer larger than the
+    on-die caches (L2 and the 256 MiB memory-side cache): each call is bracketed by its own event
+    pair, and what an empty pair reads after the same sweep is subtracted."""
+    def one(body):
+        v = []
+        for _ in range(reps):
+            sweep.add_(1.0)
+            e0, e1 = _events(torch)
+            e0.record()
+            body()
+            e1.record()
+            torch.cuda.synchronize()
+            v.append(e0.elapsed_time(e1) * 1000.0)
+        v.sort()
+        return v[len(v) // 2]
+    return max(one(fn) - one(lambda: None), 0.0)
+
+
 class LayerRun:
     """One layer resident on the device with every stage as a callable."""
 
@@ -286,6 +305,7 @@ def main():
                     help="also measure every layer of the five workloads (per-layer report on stderr and "
                          "in gpurun_out/layers.json)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-cold", action="store_true", help="skip the cold-cache timing of the stages")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also launch a plain elementwise kernel that reads and writes 256 MiB, five times: the "
                          "known-size kernel that rocprofv3 FETCH_SIZE / WRITE_SIZE readings are scaled by")
@@ -376,6 +396,14 @@ def main():
         "roofline": roof,
         "kernels": kernels,
     }
+    if not args.no_cold:
+        # cold launches: a 1 GiB sweep between calls evicts inputs, streams and weights
+        sweep = torch.zeros(256 << 20, dtype=torch.float32, device="cuda")
+        cold = {k: round(_cold_time_us(torch, fn, 15, sweep), 2) for k, fn in st.items()}
+        del sweep
+        result["layer"]["cold_us"] = cold
+        result["layer"]["cold_note"] = ("median of 15 single calls, each after a 1 GiB device-memory sweep, less "
+                                        "an empty event pair; 'us' above are warm back-to-back averages")
     if not args.no_cpu_baseline:
         result["cpu_baseline"] = cpu_baseline(spec, run.act_np, run.w_np)
 
