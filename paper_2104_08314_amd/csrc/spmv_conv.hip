@@ -275,6 +275,49 @@ __global__ __launch_bounds__(kConvThreads) void spmv_conv_lds_kernel(const Geome
                 out[(static_cast<int64_t>(k) * g.Oh + y) * g.Ow + x0 + x] = acc[((y - y0) * kTX + x) * kLanes + lane];
 }
 
+// The table of conv_prologue_kernel for layers whose ptr segments of one channel fit a wavefront's
+// stage (resolve_in_kernel_ok): one wavefront per channel, the channel's ptr entries loaded at
+// once, so the chain of dependent loads is side band -> ptr -> table.
+constexpr int kProWaves = 4;
+
+__global__ __launch_bounds__(kProWaves *kLanes) void conv_prologue_wave_kernel(const Geometry g,
+                                                                              const int32_t *__restrict__ ptr,
+                                                                              const int32_t *__restrict__ chan_off,
+                                                                              int32_t *__restrict__ mtab)
+{
+    __shared__ int32_t stage_all[kProWaves * kStageInts];
+    const int lane = lane_id(), wave = threadIdx.x / kLanes;
+    const int c = blockIdx.x * kProWaves + wave;
+    if (c >= g.C) return;   // the whole wavefront leaves; the kernel has no workgroup barrier
+    int32_t *stage = stage_all + wave * kStageInts;
+    const int seg = __builtin_amdgcn_readfirstlane(chan_off[c]);
+    const int len = __builtin_amdgcn_readfirstlane(chan_off[c + 1]) - seg;
+    int at = __builtin_amdgcn_readfirstlane(chan_off[(g.C + 1) + c]);
+#pragma unroll
+    for (int k = 0; k < kStageInts / kLanes; ++k)
+        stage[k * kLanes + lane] = k * kLanes + lane < len ? ptr[seg + k * kLanes + lane] : 0;
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+    const bool npc = stage[0] == CPOCONV_NPC;
+    int pos = 0;
+    for (int i = 0; i < g.n_types; ++i) {
+        int live = 0;   // 0: no NZE, 1: [pType, e_0 .. e_{Ow-1}], 2: the three-entry NOP segment
+        if (!npc) live = (g.nop3 && g.type_id[i] == 0) ? 2 : (stage[pos] == CPOCONV_NPF ? 0 : 1);
+        int e = -1;
+        if (lane < g.Ow) {
+            if (live == 1) e = stage[pos + 1 + lane];
+            else if (live == 2) e = lane < g.Ow - 1 ? stage[pos + 1] : stage[pos + 2];
+        }
+        const int m = max(wave_running_max(e), 0);
+        int32_t *row = mtab + (static_cast<int64_t>(c) * g.n_types + i) * (g.Ow + 1);
+        if (lane < g.Ow) row[1 + lane] = at + m;
+        if (lane == 0) row[0] = at;
+        at += __builtin_amdgcn_readlane(m, kLanes - 1);
+        pos += npc ? 0 : (live == 2 ? 3 : (live == 1 ? 1 + g.Ow : 1));
+    }
+}
+
 // out[k][y][x] = sum over slices of partial[slice][y][x][k]; one workgroup per (output row,
 // 64 kernels, 16 columns): reads coalesced along k, writes runs along x via LDS.
 constexpr int kEpiCols = 16;
@@ -333,8 +376,12 @@ int launch_sparse_conv(const cpoconv_map &map, const Geometry &g, int algo, cons
     if (in_kernel) mtab = nullptr;
     if ((tile && !in_kernel) || in_full != nullptr) {
         KernelTimer timer("conv_prologue", stream);
-        hipLaunchKernelGGL(conv_prologue_kernel, dim3(g.C), dim3(kExpThreads), 0, stream, g, map.ptr, map.in,
-                           map.chan_off, mtab, in_full);
+        if (in_full == nullptr && resolve_in_kernel_ok(g))
+            hipLaunchKernelGGL(conv_prologue_wave_kernel, dim3((g.C + kProWaves - 1) / kProWaves),
+                               dim3(kProWaves * kLanes), 0, stream, g, map.ptr, map.chan_off, mtab);
+        else
+            hipLaunchKernelGGL(conv_prologue_kernel, dim3(g.C), dim3(kExpThreads), 0, stream, g, map.ptr, map.in,
+                               map.chan_off, mtab, in_full);
         CPOCONV_HIP_TRY(hipGetLastError());
     }
     if (strip) {
