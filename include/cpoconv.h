@@ -156,6 +156,35 @@ int im2col_conv(const float *act, const cpoconv_shape *shape, const float *weigh
                 void *lowered, float *out, int precision, void *stream);
 
 /*
+ * Batched variants: n_images activation maps of one shape in one launch (the "I_n" of the
+ * paper's Table 1; Section 3.3 encodes "one input image", so a batch is one independent encoding
+ * per image).  Layouts: act is N x C x H x W, out is N x K x Oh x Ow.  *maps describes image 0;
+ * image n uses the same struct with every buffer advanced by its per-image capacity:
+ * ptr + n * ptr_cap, da + n * da_cap, in + n * in_cap, chan_off + n * 3*(C+1), hdr + n * 8
+ * (so each buffer holds n_images consecutive regions and *_cap are per-image capacities with the
+ * single-image minimum sizes).  Every image's streams, side band and header are exactly what
+ * the single-image call produces for that image.  scratch / lowered: sizes from
+ * cpoconv_batch_sizes.  Errors as the single-image calls, plus SHAPE for n_images < 1 or
+ * n_images > CPOCONV_MAX_BATCH.
+ */
+#define CPOCONV_MAX_BATCH 1024
+
+/* Host only.  As cpoconv_sizes for a batch: ptr_cap, da_cap, in_cap, chan_off_len and wt_len are
+ * per image (unchanged); out_len, lowered_bytes and scratch_bytes cover the whole batch. */
+int cpoconv_batch_sizes(const cpoconv_shape *shape, int n_images, cpoconv_sizes_t *sizes);
+
+int cpo_encode_batch(const float *act, const cpoconv_shape *shape, int n_images, const cpoconv_map *maps,
+                     void *scratch, int64_t scratch_bytes, void *stream);
+int cps_encode_batch(const float *act, const cpoconv_shape *shape, int n_images, const cpoconv_map *maps,
+                     void *scratch, int64_t scratch_bytes, void *stream);
+int cpo_conv_batch(const cpoconv_map *maps, const cpoconv_shape *shape, int n_images, const float *wt,
+                   float *out, void *scratch, int64_t scratch_bytes, void *stream);
+int cps_conv_batch(const cpoconv_map *maps, const cpoconv_shape *shape, int n_images, const float *wt,
+                   float *out, void *scratch, int64_t scratch_bytes, void *stream);
+int im2col_conv_batch(const float *act, const cpoconv_shape *shape, int n_images, const float *weights,
+                      void *lowered, float *out, int precision, void *stream);
+
+/*
  * Offline per-layer selection (Section 3.5).  Host only.  t_*: times of the three methods on
  * the same m_inputs offline inputs, any common unit.  mode 0 "favour time": the smaller total
  * of im2col and CPO; mode 1 "favour space": the smaller total of im2col and CPS; im2col keeps

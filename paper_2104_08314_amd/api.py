@@ -75,6 +75,8 @@ EXPORTS = (
     "cpoconv_sizes", "cpo_encode", "cps_encode", "cpoconv_prepare_weights", "cpo_conv", "cps_conv",
     "im2col_conv", "select_layer_algo", "cpoconv_map_header_to_host", "cpoconv_geometry",
     "cpoconv_strerror", "cpoconv_last_hip_error", "cpoconv_kernel_timing", "cpoconv_kernel_timing_read",
+    "cpoconv_batch_sizes", "cpo_encode_batch", "cps_encode_batch", "cpo_conv_batch", "cps_conv_batch",
+    "im2col_conv_batch",
 )
 
 
@@ -174,36 +176,43 @@ def _dev_ptr(t, dtype=None) -> ctypes.c_void_p:
 
 
 class EncodedMap:
-    """Device buffers of one encoded activation map (cpoconv_map of the C ABI)."""
+    """Device buffers of one encoded activation map (cpoconv_map of the C ABI), or of a batch of
+    n_images maps: then every buffer holds n_images regions of the per-image capacity."""
 
-    def __init__(self, shape, device="cuda:0"):
+    def __init__(self, shape, device="cuda:0", n_images=1):
         import torch
 
         self.shape = make_shape(shape)
+        self.n_images = int(n_images)
         sz = cpoconv_sizes(self.shape)
         self.sizes = sz
-        self.ptr = torch.empty(sz.ptr_cap, dtype=torch.int32, device=device)
-        self.da = torch.empty(sz.da_cap, dtype=torch.float32, device=device)
-        self.ind = torch.empty(sz.in_cap, dtype=torch.int32, device=device)
-        self.chan_off = torch.empty(sz.chan_off_len, dtype=torch.int32, device=device)
-        self.hdr = torch.zeros(8, dtype=torch.int32, device=device)
+        n = self.n_images
+        self.ptr = torch.empty(n * sz.ptr_cap, dtype=torch.int32, device=device)
+        self.da = torch.empty(n * sz.da_cap, dtype=torch.float32, device=device)
+        self.ind = torch.empty(n * sz.in_cap, dtype=torch.int32, device=device)
+        self.chan_off = torch.empty(n * sz.chan_off_len, dtype=torch.int32, device=device)
+        self.hdr = torch.zeros(n * 8, dtype=torch.int32, device=device)
 
-    def c_struct(self) -> _Map:
-        import torch
+    def c_struct(self, image=0) -> _Map:
+        """The struct of image `image` (image 0 describes the whole batch to the batched calls)."""
+        sz = self.sizes
+        return _Map(ctypes.c_void_p(self.ptr.data_ptr() + 4 * image * sz.ptr_cap), sz.ptr_cap,
+                    ctypes.c_void_p(self.da.data_ptr() + 4 * image * sz.da_cap), sz.da_cap,
+                    ctypes.c_void_p(self.ind.data_ptr() + 4 * image * sz.in_cap), sz.in_cap,
+                    ctypes.c_void_p(self.chan_off.data_ptr() + 4 * image * sz.chan_off_len),
+                    ctypes.c_void_p(self.hdr.data_ptr() + 4 * image * 8))
 
-        return _Map(_dev_ptr(self.ptr, torch.int32), self.ptr.numel(), _dev_ptr(self.da, torch.float32),
-                    self.da.numel(), _dev_ptr(self.ind, torch.int32), self.ind.numel(),
-                    _dev_ptr(self.chan_off, torch.int32), _dev_ptr(self.hdr, torch.int32))
+    def header(self, stream=None, image=0):
+        return cpoconv_map_header_to_host(self, stream, image)
 
-    def header(self, stream=None):
-        return cpoconv_map_header_to_host(self, stream)
-
-    def to_host(self, stream=None):
-        """(ptr, da, ind, chan_off[3, C+1], hdr) as numpy arrays trimmed to their lengths."""
-        hdr = self.header(stream)
-        C = self.shape.C
-        return (self.ptr[:hdr[0]].cpu().numpy(), self.da[:hdr[1]].cpu().numpy(),
-                self.ind[:hdr[2]].cpu().numpy(), self.chan_off.cpu().numpy().reshape(3, C + 1), hdr)
+    def to_host(self, stream=None, image=0):
+        """(ptr, da, ind, chan_off[3, C+1], hdr) of one image as numpy arrays trimmed to their lengths."""
+        hdr = self.header(stream, image)
+        C, sz = self.shape.C, self.sizes
+        p0, d0, i0, c0 = image * sz.ptr_cap, image * sz.da_cap, image * sz.in_cap, image * sz.chan_off_len
+        return (self.ptr[p0:p0 + hdr[0]].cpu().numpy(), self.da[d0:d0 + hdr[1]].cpu().numpy(),
+                self.ind[i0:i0 + hdr[2]].cpu().numpy(),
+                self.chan_off[c0:c0 + sz.chan_off_len].cpu().numpy().reshape(3, C + 1), hdr)
 
 
 def _encode(fn_name: str, act, shape, m: EncodedMap, scratch, stream) -> None:
@@ -260,26 +269,82 @@ def im2col_conv(act, shape, weights, lowered, out, precision: int = 0, stream=No
                              _stream_handle(stream)))
 
 
-def cpoconv_map_header_to_host(m: EncodedMap, stream=None):
-    cm = m.c_struct()
+def cpoconv_map_header_to_host(m: EncodedMap, stream=None, image=0):
+    cm = m.c_struct(image)
     hdr = (ctypes.c_int32 * 8)()
     _check(lib().cpoconv_map_header_to_host(ctypes.byref(cm), hdr, _stream_handle(stream)))
     return [int(v) for v in hdr]
 
 
 class LayerBuffers:
-    """All device buffers one layer needs, allocated once with PyTorch."""
+    """All device buffers one layer (or a batch of n_images inputs of it) needs, allocated once with PyTorch."""
 
-    def __init__(self, shape, device="cuda:0"):
+    def __init__(self, shape, device="cuda:0", n_images=1):
         import torch
 
         self.shape = make_shape(shape)
-        sz = cpoconv_sizes(self.shape)
+        self.n_images = int(n_images)
+        sz = cpoconv_batch_sizes(self.shape, self.n_images)
         self.sizes = sz
         self.device = device
-        self.cpo = EncodedMap(self.shape, device)
-        self.cps = EncodedMap(self.shape, device)
+        self.cpo = EncodedMap(self.shape, device, self.n_images)
+        self.cps = EncodedMap(self.shape, device, self.n_images)
         self.scratch = torch.empty(sz.scratch_bytes, dtype=torch.uint8, device=device)
         self.wt = torch.empty(sz.wt_len, dtype=torch.float32, device=device)
         self.lowered = torch.empty(sz.lowered_bytes, dtype=torch.uint8, device=device)
-        self.out = torch.empty((self.shape.K, sz.Oh, sz.Ow), dtype=torch.float32, device=device)
+        dims = (self.shape.K, sz.Oh, sz.Ow) if self.n_images == 1 else (self.n_images, self.shape.K, sz.Oh, sz.Ow)
+        self.out = torch.empty(dims, dtype=torch.float32, device=device)
+
+
+# ---- batched calls: n_images maps of one shape per launch --------------------------------------
+
+def cpoconv_batch_sizes(shape, n_images: int) -> Sizes:
+    sh, sz = make_shape(shape), Sizes()
+    _check(lib().cpoconv_batch_sizes(ctypes.byref(sh), int(n_images), ctypes.byref(sz)))
+    return sz
+
+
+def _encode_batch(fn_name: str, act, shape, m: EncodedMap, scratch, stream) -> None:
+    import torch
+
+    sh = make_shape(shape)
+    cm = m.c_struct()
+    _check(getattr(lib(), fn_name)(_dev_ptr(act, torch.float32), ctypes.byref(sh), int(m.n_images), ctypes.byref(cm),
+                                   _dev_ptr(scratch), ctypes.c_int64(scratch.numel() * scratch.element_size()),
+                                   _stream_handle(stream)))
+
+
+def cpo_encode_batch(act, shape, m: EncodedMap, scratch, stream=None) -> None:
+    _encode_batch("cpo_encode_batch", act, shape, m, scratch, stream)
+
+
+def cps_encode_batch(act, shape, m: EncodedMap, scratch, stream=None) -> None:
+    _encode_batch("cps_encode_batch", act, shape, m, scratch, stream)
+
+
+def _conv_batch(fn_name: str, m: EncodedMap, shape, wt, out, scratch, stream) -> None:
+    import torch
+
+    sh = make_shape(shape)
+    cm = m.c_struct()
+    _check(getattr(lib(), fn_name)(ctypes.byref(cm), ctypes.byref(sh), int(m.n_images), _dev_ptr(wt, torch.float32),
+                                   _dev_ptr(out, torch.float32), _dev_ptr(scratch),
+                                   ctypes.c_int64(scratch.numel() * scratch.element_size()),
+                                   _stream_handle(stream)))
+
+
+def cpo_conv_batch(m: EncodedMap, shape, wt, out, scratch, stream=None) -> None:
+    _conv_batch("cpo_conv_batch", m, shape, wt, out, scratch, stream)
+
+
+def cps_conv_batch(m: EncodedMap, shape, wt, out, scratch, stream=None) -> None:
+    _conv_batch("cps_conv_batch", m, shape, wt, out, scratch, stream)
+
+
+def im2col_conv_batch(act, shape, n_images: int, weights, lowered, out, precision: int = 0, stream=None) -> None:
+    import torch
+
+    sh = make_shape(shape)
+    _check(lib().im2col_conv_batch(_dev_ptr(act, torch.float32), ctypes.byref(sh), int(n_images),
+                                   _dev_ptr(weights, torch.float32), _dev_ptr(lowered), _dev_ptr(out, torch.float32),
+                                   int(precision), _stream_handle(stream)))

@@ -2,6 +2,7 @@
 // step is queued by the launch_* functions next to the kernels.
 #include <string.h>
 
+#include <algorithm>
 #include <mutex>
 #include <string>
 #include <utility>
@@ -90,6 +91,7 @@ int build_geometry(const cpoconv_shape *s, Geometry *g)
     g->Oh = (g->Ih - s->kh) / s->stride + 1;
     g->Ow = (g->Iw - s->kw) / s->stride + 1;
     g->Kpad = (s->K + 63) / 64 * 64;
+    g->N = 1;
 
     int type_of[kMaxCols], p0_of[kMaxCols];
     int count[kMaxTypes] = {0};
@@ -145,21 +147,14 @@ int64_t max_ptr_len(const Geometry &g)
 // Scratch layout: per-channel stream lengths of the encoder's first pass | the convolution's
 // table of resolved ptr offsets | one int32 per NZE for the indices cps_conv rebuilds | partial
 // sums of the register-tile convolution.
-int64_t scratch_counts_bytes(const Geometry &g)
-{
-    return (16 * static_cast<int64_t>(g.C + 1) + 255) / 256 * 256;
-}
+// (each region holds g.N images back to back, with the per-image strides below)
+int64_t counts_stride(const Geometry &g) { return 4 * static_cast<int64_t>(g.C + 1); }                       // ints
+int64_t indices_stride(const Geometry &g) { return static_cast<int64_t>(g.C) * g.H * g.W; }                 // ints
+int64_t mtab_stride(const Geometry &g) { return static_cast<int64_t>(g.C) * std::max(g.n_types, 1) * (g.Ow + 1); }   // ints
 
-int64_t scratch_indices_bytes(const Geometry &g)
-{
-    return (4 * static_cast<int64_t>(g.C) * g.H * g.W + 255) / 256 * 256;
-}
-
-int64_t scratch_mtab_bytes(const Geometry &g)
-{
-    const int types = g.n_types > 0 ? g.n_types : 1;
-    return (4 * static_cast<int64_t>(g.C) * types * (g.Ow + 1) + 255) / 256 * 256;
-}
+int64_t scratch_counts_bytes(const Geometry &g) { return (4 * counts_stride(g) * g.N + 255) / 256 * 256; }
+int64_t scratch_indices_bytes(const Geometry &g) { return (4 * indices_stride(g) * g.N + 255) / 256 * 256; }
+int64_t scratch_mtab_bytes(const Geometry &g) { return (4 * mtab_stride(g) * g.N + 255) / 256 * 256; }
 
 int64_t scratch_bytes_for(const Geometry &g)
 {
@@ -173,11 +168,25 @@ using namespace cpoconv;
 
 extern "C" {
 
+static int batch_geometry(const cpoconv_shape *shape, int n_images, Geometry *g)
+{
+    const int rc = build_geometry(shape, g);
+    if (rc != CPOCONV_OK) return rc;
+    if (n_images < 1 || n_images > CPOCONV_MAX_BATCH) return CPOCONV_ERR_SHAPE;
+    g->N = n_images;
+    return CPOCONV_OK;
+}
+
 int cpoconv_sizes(const cpoconv_shape *shape, cpoconv_sizes_t *sizes)
+{
+    return cpoconv_batch_sizes(shape, 1, sizes);
+}
+
+int cpoconv_batch_sizes(const cpoconv_shape *shape, int n_images, cpoconv_sizes_t *sizes)
 {
     if (!shape || !sizes) return CPOCONV_ERR_NULL;
     Geometry g;
-    const int rc = build_geometry(shape, &g);
+    const int rc = batch_geometry(shape, n_images, &g);
     if (rc != CPOCONV_OK) return rc;
     const int64_t chw = static_cast<int64_t>(g.C) * g.H * g.W;
     sizes->ptr_cap = max_ptr_len(g);
@@ -185,7 +194,7 @@ int cpoconv_sizes(const cpoconv_shape *shape, cpoconv_sizes_t *sizes)
     sizes->in_cap = chw;
     sizes->chan_off_len = 3 * static_cast<int64_t>(g.C + 1);
     sizes->wt_len = static_cast<int64_t>(g.C) * g.kh * g.kw * g.Kpad;
-    sizes->out_len = static_cast<int64_t>(g.K) * g.Oh * g.Ow;
+    sizes->out_len = static_cast<int64_t>(g.N) * g.K * g.Oh * g.Ow;
     sizes->lowered_bytes = im2col_scratch_bytes(g);
     sizes->scratch_bytes = scratch_bytes_for(g);
     sizes->Oh = g.Oh;
@@ -193,13 +202,13 @@ int cpoconv_sizes(const cpoconv_shape *shape, cpoconv_sizes_t *sizes)
     return CPOCONV_OK;
 }
 
-static int encode_common(const float *act, const cpoconv_shape *shape, const cpoconv_map *map,
+static int encode_common(const float *act, const cpoconv_shape *shape, int n_images, const cpoconv_map *map,
                          void *scratch, int64_t scratch_bytes, void *stream, int algo)
 {
     if (!act || !shape || !map || !scratch) return CPOCONV_ERR_NULL;
     if (!map->ptr || !map->da || !map->in || !map->chan_off || !map->hdr) return CPOCONV_ERR_NULL;
     Geometry g;
-    const int rc = build_geometry(shape, &g);
+    const int rc = batch_geometry(shape, n_images, &g);
     if (rc != CPOCONV_OK) return rc;
     const int64_t chw = static_cast<int64_t>(g.C) * g.H * g.W;
     if (map->ptr_cap < max_ptr_len(g) || map->da_cap < chw || map->in_cap < chw)
@@ -211,13 +220,13 @@ static int encode_common(const float *act, const cpoconv_shape *shape, const cpo
 int cpo_encode(const float *act, const cpoconv_shape *shape, const cpoconv_map *map,
                void *scratch, int64_t scratch_bytes, void *stream)
 {
-    return encode_common(act, shape, map, scratch, scratch_bytes, stream, CPOCONV_ALGO_CPO);
+    return encode_common(act, shape, 1, map, scratch, scratch_bytes, stream, CPOCONV_ALGO_CPO);
 }
 
 int cps_encode(const float *act, const cpoconv_shape *shape, const cpoconv_map *map,
                void *scratch, int64_t scratch_bytes, void *stream)
 {
-    return encode_common(act, shape, map, scratch, scratch_bytes, stream, CPOCONV_ALGO_CPS);
+    return encode_common(act, shape, 1, map, scratch, scratch_bytes, stream, CPOCONV_ALGO_CPS);
 }
 
 int cpoconv_prepare_weights(const float *weights, const cpoconv_shape *shape, float *wt,
@@ -230,14 +239,17 @@ int cpoconv_prepare_weights(const float *weights, const cpoconv_shape *shape, fl
     return launch_prepare_weights(weights, g, wt, static_cast<hipStream_t>(stream));
 }
 
-static int conv_common(const cpoconv_map *map, const cpoconv_shape *shape, const float *wt,
+static int conv_common(const cpoconv_map *map, const cpoconv_shape *shape, int n_images, const float *wt,
                        float *out, void *scratch, int64_t scratch_bytes, void *stream, int algo)
 {
     if (!map || !shape || !wt || !out || !scratch) return CPOCONV_ERR_NULL;
     if (!map->ptr || !map->da || !map->in || !map->chan_off || !map->hdr) return CPOCONV_ERR_NULL;
     Geometry g;
-    const int rc = build_geometry(shape, &g);
+    const int rc = batch_geometry(shape, n_images, &g);
     if (rc != CPOCONV_OK) return rc;
+    const int64_t chw = static_cast<int64_t>(g.C) * g.H * g.W;
+    if (g.N > 1 && (map->ptr_cap < max_ptr_len(g) || map->da_cap < chw || map->in_cap < chw))
+        return CPOCONV_ERR_SMALL;   // the capacities are the strides between images
     if (scratch_bytes < scratch_bytes_for(g)) return CPOCONV_ERR_SMALL;
     return launch_sparse_conv(*map, g, algo, wt, out, scratch, static_cast<hipStream_t>(stream));
 }
@@ -245,21 +257,51 @@ static int conv_common(const cpoconv_map *map, const cpoconv_shape *shape, const
 int cpo_conv(const cpoconv_map *map, const cpoconv_shape *shape, const float *wt, float *out,
              void *scratch, int64_t scratch_bytes, void *stream)
 {
-    return conv_common(map, shape, wt, out, scratch, scratch_bytes, stream, CPOCONV_ALGO_CPO);
+    return conv_common(map, shape, 1, wt, out, scratch, scratch_bytes, stream, CPOCONV_ALGO_CPO);
 }
 
 int cps_conv(const cpoconv_map *map, const cpoconv_shape *shape, const float *wt, float *out,
              void *scratch, int64_t scratch_bytes, void *stream)
 {
-    return conv_common(map, shape, wt, out, scratch, scratch_bytes, stream, CPOCONV_ALGO_CPS);
+    return conv_common(map, shape, 1, wt, out, scratch, scratch_bytes, stream, CPOCONV_ALGO_CPS);
+}
+
+int cpo_encode_batch(const float *act, const cpoconv_shape *shape, int n_images, const cpoconv_map *maps,
+                     void *scratch, int64_t scratch_bytes, void *stream)
+{
+    return encode_common(act, shape, n_images, maps, scratch, scratch_bytes, stream, CPOCONV_ALGO_CPO);
+}
+
+int cps_encode_batch(const float *act, const cpoconv_shape *shape, int n_images, const cpoconv_map *maps,
+                     void *scratch, int64_t scratch_bytes, void *stream)
+{
+    return encode_common(act, shape, n_images, maps, scratch, scratch_bytes, stream, CPOCONV_ALGO_CPS);
+}
+
+int cpo_conv_batch(const cpoconv_map *maps, const cpoconv_shape *shape, int n_images, const float *wt,
+                   float *out, void *scratch, int64_t scratch_bytes, void *stream)
+{
+    return conv_common(maps, shape, n_images, wt, out, scratch, scratch_bytes, stream, CPOCONV_ALGO_CPO);
+}
+
+int cps_conv_batch(const cpoconv_map *maps, const cpoconv_shape *shape, int n_images, const float *wt,
+                   float *out, void *scratch, int64_t scratch_bytes, void *stream)
+{
+    return conv_common(maps, shape, n_images, wt, out, scratch, scratch_bytes, stream, CPOCONV_ALGO_CPS);
 }
 
 int im2col_conv(const float *act, const cpoconv_shape *shape, const float *weights, void *lowered,
                 float *out, int precision, void *stream)
 {
+    return im2col_conv_batch(act, shape, 1, weights, lowered, out, precision, stream);
+}
+
+int im2col_conv_batch(const float *act, const cpoconv_shape *shape, int n_images, const float *weights,
+                      void *lowered, float *out, int precision, void *stream)
+{
     if (!act || !shape || !weights || !lowered || !out) return CPOCONV_ERR_NULL;
     Geometry g;
-    const int rc = build_geometry(shape, &g);
+    const int rc = batch_geometry(shape, n_images, &g);
     if (rc != CPOCONV_OK) return rc;
     if (precision != 0 && precision != 1) return CPOCONV_ERR_ALGO;
     if (reinterpret_cast<uintptr_t>(lowered) % 16 != 0) return CPOCONV_ERR_SHAPE;   // vector accesses

@@ -25,11 +25,19 @@ struct Geometry {
     int32_t top;                     // overlap type CPS packs, -1 if none
     int32_t top_slot;                // its slot in type_id, -1 if none
     int32_t Kpad;                    // K rounded up to a multiple of 64
+    int32_t N;                       // images in the launch (1 unless a batched entry point)
     uint8_t type_id[kMaxTypes];      // present types, ascending
     uint16_t type_begin[kMaxTypes + 1];  // column range of each present type
     uint8_t col_j[kMaxCols];         // padded column
     uint8_t col_p0[kMaxCols];        // first partition holding it
     uint8_t col_what[kMaxCols];      // column inside that partition
+};
+
+// Element strides between consecutive images of a batched launch (image 0 is at the base pointers).
+struct BatchStrides {
+    int64_t ptr, da, in;   // streams and side band: the per-image capacities of the map
+    int64_t indices;       // what the convolution reads as IN: the stream itself or the rebuilt CPS indices
+    int64_t mtab, partial, out;
 };
 
 int check_shape(const cpoconv_shape *s);           // CPOCONV_OK or CPOCONV_ERR_SHAPE
@@ -72,20 +80,24 @@ int launch_sparse_conv(const cpoconv_map &map, const Geometry &g, int algo, cons
 bool tile_kernel_supports(const Geometry &g);
 int64_t tile_kernel_partial_bytes(const Geometry &g);
 int launch_sparse_conv_tile(const cpoconv_map &map, const int32_t *indices, const int32_t *mtab, const Geometry &g, const float *wt,
-                            float *out, float *partial, hipStream_t stream);
+                            float *out, float *partial, BatchStrides bs, hipStream_t stream);
 // strip SpMV kernel (spmv_conv_strip.hip)
 bool strip_kernel_supports(const Geometry &g);
 bool strip_kernel_preferred(const Geometry &g);
 int64_t strip_kernel_partial_bytes(const Geometry &g);
 int launch_sparse_conv_strip(const cpoconv_map &map, const int32_t *indices, const int32_t *mtab, const Geometry &g,
-                             const float *wt, float *out, float *partial, hipStream_t stream);
+                             const float *wt, float *out, float *partial, BatchStrides bs, hipStream_t stream);
 // byte offsets of the regions of the caller's scratch buffer
 int64_t scratch_counts_bytes(const Geometry &g);
 int64_t scratch_indices_bytes(const Geometry &g);
 int64_t scratch_mtab_bytes(const Geometry &g);
+// per-image strides inside those regions, in 4-byte elements
+int64_t counts_stride(const Geometry &g);
+int64_t indices_stride(const Geometry &g);
+int64_t mtab_stride(const Geometry &g);
 // out[k][y][x] = sum over channel slices of partial[slice][y][x][k] (spmv_conv.hip)
 int launch_reduce_transpose(const Geometry &g, const float *partial, int slices, int Ypad, int Xpad, float *out,
-                            hipStream_t stream);
+                            hipStream_t stream);   // per image: partial advances by slices*Ypad*Xpad*Kpad, out by K*Oh*Ow
 
 // Sum over the channel slices of one output element: four interleaved running sums, then
 // pairwise.  Every kernel that adds slices uses this order, so they agree bit for bit.

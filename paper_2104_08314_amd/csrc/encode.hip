@@ -64,10 +64,21 @@ __device__ __forceinline__ int set4_entries(unsigned long long mask)
 }
 
 template <bool kCountOnly>
-__global__ __launch_bounds__(kThreads) void encode_kernel(const Geometry g, const float *__restrict__ act,
+__global__ __launch_bounds__(kThreads) void encode_kernel(const Geometry g, const float *__restrict__ act_all,
                                                          const int cps, const int kChunk,
-                                                         int32_t *__restrict__ counts, const cpoconv_map map)
+                                                         int32_t *__restrict__ counts_all, const cpoconv_map maps)
 {
+    // image blockIdx.y of the launch: its map is image 0's advanced by the per-image capacities
+    const int image = blockIdx.y;
+    const float *__restrict__ act = act_all + static_cast<int64_t>(image) * g.C * g.H * g.W;
+    int32_t *__restrict__ counts = counts_all + static_cast<int64_t>(image) * 4 * (g.C + 1);
+    cpoconv_map map = maps;
+    map.ptr += image * maps.ptr_cap;
+    map.da += image * maps.da_cap;
+    map.in += image * maps.in_cap;
+    map.chan_off += static_cast<int64_t>(image) * 3 * (g.C + 1);
+    map.hdr += image * 8;
+
     extern __shared__ float tile[];                    // kChunk x Wt, Wt odd: conflict-free column reads
     __shared__ uint16_t cnt_q[kMaxChunks][kMaxCols];   // NZEs per (row chunk, column), then their
     __shared__ uint16_t ecnt_q[kMaxChunks][kMaxCols];  //   exclusive sums over the chunks; same for IN
@@ -302,12 +313,12 @@ int launch_encode(const float *act, const Geometry &g, const cpoconv_map &map, i
     int32_t *counts = static_cast<int32_t *>(scratch);
     {
         KernelTimer timer("encode_count", stream);
-        hipLaunchKernelGGL(encode_kernel<true>, dim3(g.C), dim3(kThreads), lds, stream, g, act, cps, chunk, counts, map);
+        hipLaunchKernelGGL(encode_kernel<true>, dim3(g.C, g.N), dim3(kThreads), lds, stream, g, act, cps, chunk, counts, map);
     }
     CPOCONV_HIP_TRY(hipGetLastError());
     {
         KernelTimer timer("encode_write", stream);
-        hipLaunchKernelGGL(encode_kernel<false>, dim3(g.C), dim3(kThreads), lds, stream, g, act, cps, chunk, counts, map);
+        hipLaunchKernelGGL(encode_kernel<false>, dim3(g.C, g.N), dim3(kThreads), lds, stream, g, act, cps, chunk, counts, map);
     }
     CPOCONV_HIP_TRY(hipGetLastError());
     return CPOCONV_OK;

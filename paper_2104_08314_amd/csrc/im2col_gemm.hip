@@ -31,9 +31,13 @@ constexpr int kLowThreads = 256;
 constexpr int kLowCols = 1024;  // lowered-matrix columns per workgroup
 
 template <typename T>
-__global__ __launch_bounds__(kLowThreads) void im2col_lower_kernel(const Geometry g, const float *__restrict__ act,
-                                                                  T *__restrict__ lowered, const int ldb)
+__global__ __launch_bounds__(kLowThreads) void im2col_lower_kernel(const Geometry g, const float *__restrict__ act_all,
+                                                                  T *__restrict__ lowered_all, const int ldb,
+                                                                  const int64_t image_stride)
 {
+    // image blockIdx.y: its own lowered matrix, image_stride elements after the previous one
+    const float *__restrict__ act = act_all + static_cast<int64_t>(blockIdx.y) * g.C * g.H * g.W;
+    T *__restrict__ lowered = lowered_all + blockIdx.y * image_stride;
     const int N = g.Oh * g.Ow;
     const int chunks = (N + kLowCols - 1) / kLowCols;
     const int row = blockIdx.x / chunks;                  // (c*kh + l)*kw + w
@@ -51,9 +55,13 @@ __global__ __launch_bounds__(kLowThreads) void im2col_lower_kernel(const Geometr
 // bf16 lowered matrix, laid out for the matrix cores: [ceil(Kd/4)][ldb][4], i.e. the four
 // consecutive contraction indices one MFMA lane consumes sit next to each other (8 bytes) and
 // consecutive output positions follow each other.  Rows beyond Kd are zero.
-__global__ __launch_bounds__(kLowThreads) void im2col_lower_bf16_kernel(const Geometry g, const float *__restrict__ act,
-                                                                       uint16_t *__restrict__ lowered, const int ldb)
+__global__ __launch_bounds__(kLowThreads) void im2col_lower_bf16_kernel(const Geometry g,
+                                                                       const float *__restrict__ act_all,
+                                                                       uint16_t *__restrict__ lowered_all, const int ldb,
+                                                                       const int64_t image_stride)
 {
+    const float *__restrict__ act = act_all + static_cast<int64_t>(blockIdx.y) * g.C * g.H * g.W;
+    uint16_t *__restrict__ lowered = lowered_all + blockIdx.y * image_stride;
     const int N = g.Oh * g.Ow, Kd = g.C * g.kh * g.kw;
     const int chunks = (N + kLowCols - 1) / kLowCols;
     const int k4 = blockIdx.x / chunks;
@@ -92,15 +100,20 @@ constexpr int kMaxSplitK = 16;
 constexpr int kBK32 = 32;
 
 template <bool kVecA>
-__global__ __launch_bounds__(kGemmThreads) void gemm_f32_kernel(const float *__restrict__ A, const float *__restrict__ B,
-                                                               float *__restrict__ C, int M, int N, int Kd, int ldb,
-                                                               int k_per_split, int64_t split_stride)
+__global__ __launch_bounds__(kGemmThreads) void gemm_f32_kernel(const float *__restrict__ A, const float *__restrict__ B_all,
+                                                               float *__restrict__ C_all, int M, int N, int Kd, int ldb,
+                                                               int k_per_split, int64_t split_stride, int ntn,
+                                                               int64_t b_image_stride)
 {
+    // batched: blockIdx.x = image * ntn + column tile; every image has its own B and its own M x N C
+    const int image = blockIdx.x / ntn;
+    const float *__restrict__ B = B_all + image * b_image_stride;
+    float *__restrict__ C = C_all + static_cast<int64_t>(image) * M * N;
     __shared__ __attribute__((aligned(16))) float At[2][kBK32][kBM];
     __shared__ __attribute__((aligned(16))) float Bs[2][kBK32][kBN];
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int wm = wave >> 1, wn = wave & 1;
-    const int m0 = blockIdx.y * kBM, n0 = blockIdx.x * kBN;
+    const int m0 = blockIdx.y * kBM, n0 = (blockIdx.x % ntn) * kBN;
     const int k_begin = blockIdx.z * k_per_split, k_end = min(Kd, k_begin + k_per_split);
     const int li = lane & 31, lk = lane >> 5;
     floatx16 acc = {0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0};
@@ -209,15 +222,19 @@ constexpr int kPad16 = 8;   // keeps rows 8-byte aligned and spreads the 32 oper
 
 template <bool kVecA>
 __global__ __launch_bounds__(kGemmThreads) void gemm_bf16_kernel(const float *__restrict__ A,
-                                                                const uint16_t *__restrict__ B,
-                                                                float *__restrict__ C, int M, int N, int Kd, int ldb,
-                                                                int k_per_split, int64_t split_stride)
+                                                                const uint16_t *__restrict__ B_all,
+                                                                float *__restrict__ C_all, int M, int N, int Kd, int ldb,
+                                                                int k_per_split, int64_t split_stride, int ntn,
+                                                                int64_t b_image_stride)
 {
+    const int image = blockIdx.x / ntn;   // batched as in the fp32 kernel
+    const uint16_t *__restrict__ B = B_all + image * b_image_stride;
+    float *__restrict__ C = C_all + static_cast<int64_t>(image) * M * N;
     __shared__ __attribute__((aligned(16))) uint16_t As[2][kBM][kBK16 + kPad16];
     __shared__ __attribute__((aligned(16))) uint16_t Bs[2][kBK16 / 4][kBN][4];
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int wm = wave >> 1, wn = wave & 1;
-    const int m0 = blockIdx.y * kBM, n0 = blockIdx.x * kBN;
+    const int m0 = blockIdx.y * kBM, n0 = (blockIdx.x % ntn) * kBN;
     const int k_begin = blockIdx.z * k_per_split, k_end = min(Kd, k_begin + k_per_split);
     const int li = lane & 31, lk = lane >> 5;
     floatx16 acc = {0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0};
@@ -300,7 +317,7 @@ int im2col_ldb(const Geometry &g) { return (g.Oh * g.Ow + 3) / 4 * 4; }
 int im2col_splits(const Geometry &g)
 {
     const int N = g.Oh * g.Ow, Kd = g.C * g.kh * g.kw, M = g.K;
-    const int tiles = ((N + kBN - 1) / kBN) * ((M + kBM - 1) / kBM);
+    const int tiles = ((N + kBN - 1) / kBN) * ((M + kBM - 1) / kBM) * g.N;
     int s = (384 + tiles / 2) / tiles;
     const int cap = Kd / 128;                       // at least four 32-deep steps per slice
     if (s > cap) s = cap;
@@ -309,11 +326,17 @@ int im2col_splits(const Geometry &g)
     return s;
 }
 
-int64_t im2col_scratch_bytes(const Geometry &g)
+// bytes of one image's lowered matrix (the bf16 variant rounds Kd up to 4), 256-byte aligned
+static int64_t lowered_image_bytes(const Geometry &g)
 {
     const int64_t Kd = static_cast<int64_t>(g.C) * g.kh * g.kw;
-    const int64_t low = ((Kd + 3) * im2col_ldb(g) * 4 + 255) / 256 * 256;   // bf16 variant: Kd rounded up to 4
-    return low + static_cast<int64_t>(kMaxSplitK) * g.K * g.Oh * g.Ow * 4;
+    return ((Kd + 3) * im2col_ldb(g) * 4 + 255) / 256 * 256;
+}
+
+int64_t im2col_scratch_bytes(const Geometry &g)
+{
+    const int64_t partial = static_cast<int64_t>(g.N == 1 ? kMaxSplitK : im2col_splits(g)) * g.N * g.K * g.Oh * g.Ow * 4;
+    return lowered_image_bytes(g) * g.N + partial;
 }
 
 int launch_im2col_conv(const float *act, const Geometry &g, const float *w, void *lowered, float *out,
@@ -325,40 +348,41 @@ int launch_im2col_conv(const float *act, const Geometry &g, const float *w, void
     const int splits = im2col_splits(g);
     const int k_per_split = ((Kd + splits - 1) / splits + kBK32 - 1) / kBK32 * kBK32;
     const int nsplit = (Kd + k_per_split - 1) / k_per_split;
-    const int64_t low_bytes = (static_cast<int64_t>(Kd + 3) * ldb * 4 + 255) / 256 * 256;
-    float *partial = reinterpret_cast<float *>(static_cast<char *>(lowered) + low_bytes);
+    const int64_t low_bytes = lowered_image_bytes(g);
+    float *partial = reinterpret_cast<float *>(static_cast<char *>(lowered) + low_bytes * g.N);
     float *dst = nsplit > 1 ? partial : out;
-    const dim3 ggrid((N + kBN - 1) / kBN, (M + kBM - 1) / kBM, nsplit);
+    const int ntn = (N + kBN - 1) / kBN;
+    const dim3 ggrid(ntn * g.N, (M + kBM - 1) / kBM, nsplit);
     const bool vec_a = Kd % 4 == 0 && reinterpret_cast<uintptr_t>(w) % 16 == 0;
-    const int64_t mn = static_cast<int64_t>(M) * N;
+    const int64_t mn = static_cast<int64_t>(M) * N * g.N;   // the whole batch: one split-K slice
     if (precision == 0) {
         {
             KernelTimer timer("im2col_lower_f32", stream);
-            hipLaunchKernelGGL(im2col_lower_kernel<float>, dim3(static_cast<unsigned>(Kd) * chunks), dim3(kLowThreads), 0,
-                               stream, g, act, static_cast<float *>(lowered), ldb);
+            hipLaunchKernelGGL(im2col_lower_kernel<float>, dim3(static_cast<unsigned>(Kd) * chunks, g.N), dim3(kLowThreads),
+                               0, stream, g, act, static_cast<float *>(lowered), ldb, low_bytes / 4);
         }
         CPOCONV_HIP_TRY(hipGetLastError());
         KernelTimer timer("gemm_f32", stream);
         if (vec_a)
             hipLaunchKernelGGL(gemm_f32_kernel<true>, ggrid, dim3(kGemmThreads), 0, stream, w,
-                               static_cast<const float *>(lowered), dst, M, N, Kd, ldb, k_per_split, mn);
+                               static_cast<const float *>(lowered), dst, M, N, Kd, ldb, k_per_split, mn, ntn, low_bytes / 4);
         else
             hipLaunchKernelGGL(gemm_f32_kernel<false>, ggrid, dim3(kGemmThreads), 0, stream, w,
-                               static_cast<const float *>(lowered), dst, M, N, Kd, ldb, k_per_split, mn);
+                               static_cast<const float *>(lowered), dst, M, N, Kd, ldb, k_per_split, mn, ntn, low_bytes / 4);
     } else {
         {
             KernelTimer timer("im2col_lower_bf16", stream);
-            hipLaunchKernelGGL(im2col_lower_bf16_kernel, dim3(static_cast<unsigned>((Kd + 3) / 4) * chunks),
-                               dim3(kLowThreads), 0, stream, g, act, static_cast<uint16_t *>(lowered), ldb);
+            hipLaunchKernelGGL(im2col_lower_bf16_kernel, dim3(static_cast<unsigned>((Kd + 3) / 4) * chunks, g.N),
+                               dim3(kLowThreads), 0, stream, g, act, static_cast<uint16_t *>(lowered), ldb, low_bytes / 2);
         }
         CPOCONV_HIP_TRY(hipGetLastError());
         KernelTimer timer("gemm_bf16", stream);
         if (vec_a)
             hipLaunchKernelGGL(gemm_bf16_kernel<true>, ggrid, dim3(kGemmThreads), 0, stream, w,
-                               static_cast<const uint16_t *>(lowered), dst, M, N, Kd, ldb, k_per_split, mn);
+                               static_cast<const uint16_t *>(lowered), dst, M, N, Kd, ldb, k_per_split, mn, ntn, low_bytes / 2);
         else
             hipLaunchKernelGGL(gemm_bf16_kernel<false>, ggrid, dim3(kGemmThreads), 0, stream, w,
-                               static_cast<const uint16_t *>(lowered), dst, M, N, Kd, ldb, k_per_split, mn);
+                               static_cast<const uint16_t *>(lowered), dst, M, N, Kd, ldb, k_per_split, mn, ntn, low_bytes / 2);
     }
     CPOCONV_HIP_TRY(hipGetLastError());
     if (nsplit > 1) {

@@ -59,13 +59,19 @@ __device__ __forceinline__ float bcast_f(float v, int src)
 // ---------------------------------------------------------------------------------------
 constexpr int kExpThreads = 256;
 
-__global__ __launch_bounds__(kExpThreads) void conv_prologue_kernel(const Geometry g, const int32_t *__restrict__ ptr,
-                                                                  const int32_t *__restrict__ in,
-                                                                  const int32_t *__restrict__ chan_off,
-                                                                  int32_t *__restrict__ mtab,
-                                                                  int32_t *__restrict__ in_full)
+__global__ __launch_bounds__(kExpThreads) void conv_prologue_kernel(const Geometry g, const int32_t *__restrict__ ptr_all,
+                                                                  const int32_t *__restrict__ in_all,
+                                                                  const int32_t *__restrict__ chan_off_all,
+                                                                  int32_t *__restrict__ mtab_all,
+                                                                  int32_t *__restrict__ in_full_all, const BatchStrides bs)
 {
     __shared__ int32_t wave_a[kExpThreads / kLanes], wave_b[kExpThreads / kLanes];
+    const int image = blockIdx.y;
+    const int32_t *__restrict__ ptr = ptr_all + image * bs.ptr;
+    const int32_t *__restrict__ in = in_all + image * bs.in;
+    const int32_t *__restrict__ chan_off = chan_off_all + static_cast<int64_t>(image) * 3 * (g.C + 1);
+    int32_t *__restrict__ mtab = mtab_all + image * bs.mtab;
+    int32_t *__restrict__ in_full = in_full_all ? in_full_all + image * bs.indices : nullptr;
     const int c = blockIdx.x, tid = threadIdx.x, lane = lane_id(), wave = tid / kLanes;
     const int da0 = chan_off[(g.C + 1) + c], da1 = chan_off[(g.C + 1) + c + 1];
     const int in0 = chan_off[2 * (g.C + 1) + c], in1 = chan_off[2 * (g.C + 1) + c + 1];
@@ -160,13 +166,20 @@ constexpr int kTY = 8, kTX = 8;
 constexpr int kRW = kTY / kConvWaves;              // output rows per wavefront
 constexpr int kMspan = kTX + kMaxTypes + 1;        // partitions a tile can reach, plus one
 
-__global__ __launch_bounds__(kConvThreads) void spmv_conv_lds_kernel(const Geometry g, const int32_t *__restrict__ ptr,
-                                                                    const float *__restrict__ da,
-                                                                    const int32_t *__restrict__ in,
-                                                                    const int32_t *__restrict__ chan_off,
+__global__ __launch_bounds__(kConvThreads) void spmv_conv_lds_kernel(const Geometry g, const int32_t *__restrict__ ptr_all,
+                                                                    const float *__restrict__ da_all,
+                                                                    const int32_t *__restrict__ in_all,
+                                                                    const int32_t *__restrict__ chan_off_all,
                                                                     const float *__restrict__ wt,
-                                                                    float *__restrict__ out)
+                                                                    float *__restrict__ out_all, const BatchStrides bs)
 {
+    const int ngroups = g.Kpad / kLanes;
+    const int image = blockIdx.z / ngroups;
+    const int32_t *__restrict__ ptr = ptr_all + image * bs.ptr;
+    const float *__restrict__ da = da_all + image * bs.da;
+    const int32_t *__restrict__ in = in_all + image * bs.indices;
+    const int32_t *__restrict__ chan_off = chan_off_all + static_cast<int64_t>(image) * 3 * (g.C + 1);
+    float *__restrict__ out = out_all + image * bs.out;
     extern __shared__ float smem[];
     float *acc = smem;                               // kTY*kTX*64
     float *wl = smem + kTY * kTX * kLanes;           // kh*kw*64: weights of the current channel
@@ -174,7 +187,7 @@ __global__ __launch_bounds__(kConvThreads) void spmv_conv_lds_kernel(const Geome
     __shared__ int32_t type_da0[kMaxTypes];          // DA start of each type inside the channel
 
     const int tid = threadIdx.x, lane = lane_id(), wave = tid / kLanes;
-    const int x0 = blockIdx.x * kTX, y0 = blockIdx.y * kTY, k0 = blockIdx.z * kLanes;
+    const int x0 = blockIdx.x * kTX, y0 = blockIdx.y * kTY, k0 = (blockIdx.z % ngroups) * kLanes;
     const int ylo = y0 + wave * kRW;                       // this wavefront's output rows
     const int yhi = min(min(ylo + kRW, y0 + kTY), g.Oh);
     const int taps = g.kh * g.kw;
@@ -281,11 +294,16 @@ __global__ __launch_bounds__(kConvThreads) void spmv_conv_lds_kernel(const Geome
 constexpr int kProWaves = 4;
 
 __global__ __launch_bounds__(kProWaves *kLanes) void conv_prologue_wave_kernel(const Geometry g,
-                                                                              const int32_t *__restrict__ ptr,
-                                                                              const int32_t *__restrict__ chan_off,
-                                                                              int32_t *__restrict__ mtab)
+                                                                              const int32_t *__restrict__ ptr_all,
+                                                                              const int32_t *__restrict__ chan_off_all,
+                                                                              int32_t *__restrict__ mtab_all,
+                                                                              const BatchStrides bs)
 {
     __shared__ int32_t stage_all[kProWaves * kStageInts];
+    const int image = blockIdx.y;
+    const int32_t *__restrict__ ptr = ptr_all + image * bs.ptr;
+    const int32_t *__restrict__ chan_off = chan_off_all + static_cast<int64_t>(image) * 3 * (g.C + 1);
+    int32_t *__restrict__ mtab = mtab_all + image * bs.mtab;
     const int lane = lane_id(), wave = threadIdx.x / kLanes;
     const int c = blockIdx.x * kProWaves + wave;
     if (c >= g.C) return;   // the whole wavefront leaves; the kernel has no workgroup barrier
@@ -322,13 +340,16 @@ __global__ __launch_bounds__(kProWaves *kLanes) void conv_prologue_wave_kernel(c
 // 64 kernels, 16 columns): reads coalesced along k, writes runs along x via LDS.
 constexpr int kEpiCols = 16;
 
-__global__ __launch_bounds__(256) void reduce_transpose_kernel(const Geometry g, const float *__restrict__ partial,
-                                                              int slices, int Ypad, int Xpad, float *__restrict__ out)
+__global__ __launch_bounds__(256) void reduce_transpose_kernel(const Geometry g, const float *__restrict__ partial_all,
+                                                              int slices, int Ypad, int Xpad, float *__restrict__ out_all)
 {
     __shared__ float t[kLanes][kEpiCols + 1];
-    const int y = blockIdx.x, kb = blockIdx.y * kLanes, xb = blockIdx.z * kEpiCols;
+    const int ngroups = g.Kpad / kLanes, image = blockIdx.y / ngroups;
+    const int y = blockIdx.x, kb = (blockIdx.y % ngroups) * kLanes, xb = blockIdx.z * kEpiCols;
     const int tid = threadIdx.x, lane = tid & (kLanes - 1), wave = tid / kLanes;
     const int64_t slice_stride = static_cast<int64_t>(Ypad) * Xpad * g.Kpad;
+    const float *__restrict__ partial = partial_all + image * slices * slice_stride;
+    float *__restrict__ out = out_all + static_cast<int64_t>(image) * g.K * g.Oh * g.Ow;
 #pragma unroll
     for (int u = 0; u < kEpiCols / 4; ++u) {
         const int x = xb + wave * (kEpiCols / 4) + u;
@@ -348,7 +369,7 @@ int launch_reduce_transpose(const Geometry &g, const float *partial, int slices,
                             hipStream_t stream)
 {
     KernelTimer timer("reduce_transpose", stream);
-    hipLaunchKernelGGL(reduce_transpose_kernel, dim3(g.Oh, g.Kpad / kLanes, (g.Ow + kEpiCols - 1) / kEpiCols), dim3(256),
+    hipLaunchKernelGGL(reduce_transpose_kernel, dim3(g.Oh, (g.Kpad / kLanes) * g.N, (g.Ow + kEpiCols - 1) / kEpiCols), dim3(256),
                        0, stream, g, partial, slices, Ypad, Xpad, out);
     CPOCONV_HIP_TRY(hipGetLastError());
     return CPOCONV_OK;
@@ -362,9 +383,13 @@ int launch_sparse_conv(const cpoconv_map &map, const Geometry &g, int algo, cons
     const int64_t after_mtab = scratch_counts_bytes(g) + scratch_mtab_bytes(g);
     int32_t *in_full = nullptr;
     const int32_t *indices = map.in;
+    BatchStrides bs;
+    bs.ptr = map.ptr_cap; bs.da = map.da_cap; bs.in = map.in_cap; bs.indices = map.in_cap;
+    bs.mtab = mtab_stride(g); bs.partial = 0; bs.out = static_cast<int64_t>(g.K) * g.Oh * g.Ow;
     if (algo == CPOCONV_ALGO_CPS && g.top_slot >= 0) {
         in_full = reinterpret_cast<int32_t *>(base + after_mtab);
         indices = in_full;
+        bs.indices = indices_stride(g);
     }
     const bool strip = strip_kernel_preferred(g) || (strip_kernel_supports(g) && !tile_kernel_supports(g));
     const bool tile = strip || tile_kernel_supports(g);
@@ -377,27 +402,22 @@ int launch_sparse_conv(const cpoconv_map &map, const Geometry &g, int algo, cons
     if ((tile && !in_kernel) || in_full != nullptr) {
         KernelTimer timer("conv_prologue", stream);
         if (in_full == nullptr && resolve_in_kernel_ok(g))
-            hipLaunchKernelGGL(conv_prologue_wave_kernel, dim3((g.C + kProWaves - 1) / kProWaves),
-                               dim3(kProWaves * kLanes), 0, stream, g, map.ptr, map.chan_off, mtab);
+            hipLaunchKernelGGL(conv_prologue_wave_kernel, dim3((g.C + kProWaves - 1) / kProWaves, g.N),
+                               dim3(kProWaves * kLanes), 0, stream, g, map.ptr, map.chan_off, mtab, bs);
         else
-            hipLaunchKernelGGL(conv_prologue_kernel, dim3(g.C), dim3(kExpThreads), 0, stream, g, map.ptr, map.in,
-                               map.chan_off, mtab, in_full);
+            hipLaunchKernelGGL(conv_prologue_kernel, dim3(g.C, g.N), dim3(kExpThreads), 0, stream, g, map.ptr, map.in,
+                               map.chan_off, mtab, in_full, bs);
         CPOCONV_HIP_TRY(hipGetLastError());
     }
-    if (strip) {
-        float *partial = reinterpret_cast<float *>(base + after_mtab + scratch_indices_bytes(g));
-        return launch_sparse_conv_strip(map, indices, mtab, g, wt, out, partial, stream);
-    }
-    if (tile) {
-        float *partial = reinterpret_cast<float *>(base + after_mtab + scratch_indices_bytes(g));
-        return launch_sparse_conv_tile(map, indices, mtab, g, wt, out, partial, stream);
-    }
-    const dim3 grid((g.Ow + kTX - 1) / kTX, (g.Oh + kTY - 1) / kTY, g.Kpad / kLanes);
+    float *partial = reinterpret_cast<float *>(base + after_mtab + scratch_indices_bytes(g));
+    if (strip) return launch_sparse_conv_strip(map, indices, mtab, g, wt, out, partial, bs, stream);
+    if (tile) return launch_sparse_conv_tile(map, indices, mtab, g, wt, out, partial, bs, stream);
+    const dim3 grid((g.Ow + kTX - 1) / kTX, (g.Oh + kTY - 1) / kTY, (g.Kpad / kLanes) * g.N);
     const size_t lds = (static_cast<size_t>(kTY) * kTX + static_cast<size_t>(g.kh) * g.kw) * kLanes * sizeof(float);
     {
         KernelTimer timer("spmv_conv_lds", stream);
         hipLaunchKernelGGL(spmv_conv_lds_kernel, grid, dim3(kConvThreads), lds, stream, g, map.ptr, map.da, indices,
-                           map.chan_off, wt, out);
+                           map.chan_off, wt, out, bs);
     }
     CPOCONV_HIP_TRY(hipGetLastError());
     return CPOCONV_OK;

@@ -44,6 +44,7 @@ struct StripArgs {
     float *partial;           // [slices][Ypad][Xpad][Kpad]
     float *out;               // K x Oh x Ow
     int32_t slices;           // channel slices across workgroups
+    BatchStrides bs;          // image n of the launch: every buffer advanced n strides
     int32_t Ypad, Xpad;
     int32_t bands;            // wavefronts per workgroup
     int32_t batch;            // channels per table refill (multiple of G)
@@ -51,7 +52,7 @@ struct StripArgs {
 };
 
 template <int KH, int KW, int S, int TY, int TX, int G>
-__global__ __launch_bounds__(kMaxBands *kLanes) void spmv_conv_strip_kernel(const Geometry g, const StripArgs a)
+__global__ __launch_bounds__(kMaxBands *kLanes) void spmv_conv_strip_kernel(const Geometry g, const StripArgs a_launch)
 {
     constexpr int RH = (TY - 1) * S + KH;      // rows of the padded input behind one tile
     constexpr int RW = (TX - 1) * S + KW;      // columns behind the strip
@@ -60,6 +61,17 @@ __global__ __launch_bounds__(kMaxBands *kLanes) void spmv_conv_strip_kernel(cons
     constexpr int TAPS = KH * KW;
     constexpr int SPAN = TX + KW + 1;          // table slots per (channel, type): partitions p_lo-1 ..
     constexpr int IT = 4;                      // decode items whose loads are in flight together
+
+    const int ngroups = g.Kpad / kLanes;
+    const int image = blockIdx.z / (ngroups * a_launch.slices);
+    StripArgs a = a_launch;
+    a.da += image * a.bs.da;
+    a.in += image * a.bs.indices;
+    if (a.mtab != nullptr) a.mtab += image * a.bs.mtab;
+    a.ptr += image * a.bs.ptr;
+    a.chan_off += static_cast<int64_t>(image) * 3 * (g.C + 1);
+    a.partial += image * a.bs.partial;
+    a.out += image * a.bs.out;
 
     extern __shared__ int32_t smem[];
     // layout: tab[batch][n_types][SPAN] | stage[bands][kStageInts] | wl[G][TAPS][64] | patch[G][RW][PH]
@@ -74,8 +86,7 @@ __global__ __launch_bounds__(kMaxBands *kLanes) void spmv_conv_strip_kernel(cons
     const int yb = blockIdx.y * a.bands * TY;               // first output row of the workgroup
     const int y0 = yb + wave * TY;                          // first output row of this wavefront
     const int PH = (a.bands * TY - 1) * S + KH;             // patch height: rows behind the workgroup
-    const int ngroups = g.Kpad / kLanes;
-    const int kg = blockIdx.z % ngroups, slice = blockIdx.z / ngroups;
+    const int kg = blockIdx.z % ngroups, slice = (blockIdx.z / ngroups) % a.slices;
     const int kbase = kg * kLanes;
     const int per_slice = (g.C + a.slices - 1) / a.slices;
     const int c_begin = slice * per_slice, c_end = min(g.C, c_begin + per_slice);
@@ -262,7 +273,7 @@ StripPlan strip_plan(const Geometry &g)
     p.chunks = (RW * g.Ih + kLanes - 1) / kLanes;   // a strip's partitions hold at most RW columns of Ih rows
     // about one workgroup per compute unit (measured best: the workgroups are large), each slice
     // keeping four channels or more
-    const int wgs = ((g.Ow + TX - 1) / TX) * p.row_blocks * (g.Kpad / kLanes);
+    const int wgs = ((g.Ow + TX - 1) / TX) * p.row_blocks * (g.Kpad / kLanes) * g.N;
     int s = 256 / wgs;
     const int cap = (g.C + 3) / 4;
     if (s > cap) s = cap;
@@ -282,7 +293,7 @@ StripPlan strip_plan(const Geometry &g)
 
 template <int KH, int KW, int S, int TY, int TX, int G>
 int launch_strip(const cpoconv_map &map, const int32_t *indices, const int32_t *mtab, const Geometry &g,
-                 const float *wt, float *out, float *partial, hipStream_t stream)
+                 const float *wt, float *out, float *partial, BatchStrides bs, hipStream_t stream)
 {
     const StripPlan p = strip_plan<KH, KW, S, TY, TX, G>(g);
     const int ntx = (g.Ow + TX - 1) / TX;
@@ -291,10 +302,12 @@ int launch_strip(const cpoconv_map &map, const int32_t *indices, const int32_t *
     a.partial = partial; a.out = out;
     a.slices = p.slices; a.Ypad = p.row_blocks * p.bands * TY; a.Xpad = ntx * TX;
     a.bands = p.bands; a.batch = p.batch; a.chunks = p.chunks;
+    bs.partial = static_cast<int64_t>(p.slices) * a.Ypad * a.Xpad * g.Kpad;
+    a.bs = bs;
     {
         KernelTimer timer("spmv_conv_strip", stream);
         hipLaunchKernelGGL((spmv_conv_strip_kernel<KH, KW, S, TY, TX, G>),
-                           dim3(ntx, p.row_blocks, (g.Kpad / kLanes) * p.slices), dim3(p.bands * kLanes), p.lds, stream,
+                           dim3(ntx, p.row_blocks, (g.Kpad / kLanes) * p.slices * g.N), dim3(p.bands * kLanes), p.lds, stream,
                            g, a);
     }
     CPOCONV_HIP_TRY(hipGetLastError());
@@ -334,7 +347,7 @@ int64_t strip_kernel_partial_bytes(const Geometry &g)
 #define CPOCONV_STRIP_BYTES(KH, KW, S, TY, TX, G)                                               \
     [&]() -> int64_t {                                                                          \
         const StripPlan p = strip_plan<KH, KW, S, TY, TX, G>(g);                                \
-        return 4 * static_cast<int64_t>(p.slices) * p.Ypad * ((g.Ow + TX - 1) / TX * TX) * g.Kpad; \
+        return 4 * static_cast<int64_t>(p.slices) * p.Ypad * ((g.Ow + TX - 1) / TX * TX) * g.Kpad * g.N; \
     }()
     CPOCONV_STRIP_DISPATCH(CPOCONV_STRIP_BYTES)
 #undef CPOCONV_STRIP_BYTES
@@ -342,10 +355,10 @@ int64_t strip_kernel_partial_bytes(const Geometry &g)
 }
 
 int launch_sparse_conv_strip(const cpoconv_map &map, const int32_t *indices, const int32_t *mtab, const Geometry &g,
-                             const float *wt, float *out, float *partial, hipStream_t stream)
+                             const float *wt, float *out, float *partial, BatchStrides bs, hipStream_t stream)
 {
 #define CPOCONV_STRIP_LAUNCH(KH, KW, S, TY, TX, G) \
-    launch_strip<KH, KW, S, TY, TX, G>(map, indices, mtab, g, wt, out, partial, stream)
+    launch_strip<KH, KW, S, TY, TX, G>(map, indices, mtab, g, wt, out, partial, bs, stream)
     CPOCONV_STRIP_DISPATCH(CPOCONV_STRIP_LAUNCH)
 #undef CPOCONV_STRIP_LAUNCH
     return CPOCONV_ERR_SHAPE;

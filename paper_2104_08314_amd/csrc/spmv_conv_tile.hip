@@ -41,13 +41,14 @@ struct TileArgs {
     float *partial;           // [slices][Ypad][Xpad][Kpad]
     float *out;               // K x Oh x Ow, written directly when there is one slice
     int32_t slices;           // channel slices across workgroups
+    BatchStrides bs;          // image n of the launch: every buffer advanced n strides
     int32_t Ypad, Xpad;
     int32_t batch;            // channels per table refill
     int32_t red_slots;        // accumulator-sized LDS buffers available to the reduction
 };
 
 template <int KH, int KW, int S, int TY, int TX, int KPL, int NW>
-__global__ __launch_bounds__(NW *kLanes) void spmv_conv_tile_kernel(const Geometry g, const TileArgs a)
+__global__ __launch_bounds__(NW *kLanes) void spmv_conv_tile_kernel(const Geometry g, const TileArgs a_launch)
 {
     constexpr int kWavesPerWg = NW;
     constexpr int RH = (TY - 1) * S + KH;      // rows of the input patch behind the tile
@@ -63,12 +64,19 @@ __global__ __launch_bounds__(NW *kLanes) void spmv_conv_tile_kernel(const Geomet
     // layout: tab[batch][n_types][SPAN_MAX] | patch[NW][G][NCELL] ; the reduction buffers
     // overlay all of it after the channel loop
     int32_t *tab = smem;
-    float *patch_all = reinterpret_cast<float *>(tab + a.batch * g.n_types * SPAN_MAX);
+    float *patch_all = reinterpret_cast<float *>(tab + a_launch.batch * g.n_types * SPAN_MAX);
 
     const int tid = threadIdx.x, lane = lane_id(), wave = tid / kLanes;
     const int x0 = blockIdx.x * TX, y0 = blockIdx.y * TY;
     const int ngroups = g.Kpad / (kLanes * KPL);
-    const int kg = blockIdx.z % ngroups, slice = blockIdx.z / ngroups;
+    const int kg = blockIdx.z % ngroups, slice = (blockIdx.z / ngroups) % a_launch.slices;
+    const int image = blockIdx.z / (ngroups * a_launch.slices);
+    TileArgs a = a_launch;
+    a.da += image * a.bs.da;
+    a.in += image * a.bs.indices;
+    a.mtab += image * a.bs.mtab;
+    a.partial += image * a.bs.partial;
+    a.out += image * a.bs.out;
     const int kbase = kg * kLanes * KPL;
     float *patch = patch_all + wave * (G * NCELL);   // G private patches per wavefront
 
@@ -331,7 +339,7 @@ TilePlan plan_for(const Geometry &g)
     TilePlan p;
     p.ty = 4; p.tx = 8; p.kpl = 1; p.nw = 8;
     const int ntiles = ((g.Ow + p.tx - 1) / p.tx) * ((g.Oh + p.ty - 1) / p.ty);
-    const int wgs = ntiles * (g.Kpad / (kLanes * p.kpl));
+    const int wgs = ntiles * (g.Kpad / (kLanes * p.kpl)) * g.N;
     int s = (512 + wgs / 2) / wgs;
     const int cap = (g.C + 7) / 8;
     if (s > cap) s = cap;
@@ -343,7 +351,7 @@ TilePlan plan_for(const Geometry &g)
 
 template <int KH, int KW, int S, int TY, int TX, int KPL, int NW>
 int launch_tile(const cpoconv_map &map, const int32_t *indices, const int32_t *mtab, const Geometry &g,
-                const float *wt, float *out, float *partial, int slices, hipStream_t stream)
+                const float *wt, float *out, float *partial, int slices, BatchStrides bs, hipStream_t stream)
 {
     constexpr int RH = (TY - 1) * S + KH, RW = (TX - 1) * S + KW, NCELL = RH * RW;
     constexpr int SPAN_MAX = TX + KW + 1;
@@ -355,6 +363,8 @@ int launch_tile(const cpoconv_map &map, const int32_t *indices, const int32_t *m
     TileArgs a;
     a.da = map.da; a.in = indices; a.mtab = mtab; a.wt = wt;
     a.partial = partial; a.out = out; a.slices = slices; a.Ypad = nty * TY; a.Xpad = ntx * TX; a.batch = batch;
+    bs.partial = static_cast<int64_t>(slices) * a.Ypad * a.Xpad * g.Kpad;
+    a.bs = bs;
     const size_t work = (static_cast<size_t>(g.n_types) * SPAN_MAX * batch + NW * kGroup * NCELL) * 4;
     const size_t acc_bytes = static_cast<size_t>(TY) * TX * KPL * kLanes * 4;
     const size_t transpose = static_cast<size_t>(TY) * TX * (KPL * kLanes + 1) * 4;
@@ -367,7 +377,7 @@ int launch_tile(const cpoconv_map &map, const int32_t *indices, const int32_t *m
     if (transpose > lds) lds = transpose;
     {
         KernelTimer timer("spmv_conv_tile", stream);
-        hipLaunchKernelGGL((spmv_conv_tile_kernel<KH, KW, S, TY, TX, KPL, NW>), dim3(ntx, nty, ngroups * slices),
+        hipLaunchKernelGGL((spmv_conv_tile_kernel<KH, KW, S, TY, TX, KPL, NW>), dim3(ntx, nty, ngroups * slices * g.N),
                            dim3(NW * kLanes), lds, stream, g, a);
     }
     CPOCONV_HIP_TRY(hipGetLastError());
@@ -387,18 +397,18 @@ bool tile_kernel_supports(const Geometry &g)
 int64_t tile_kernel_partial_bytes(const Geometry &g)
 {
     if (!tile_kernel_supports(g)) return 0;
-    // room for the largest slice count and the smallest tile height the planner may choose
-    const int64_t Ypad = (g.Oh + 3) / 4 * 4, Xpad = (g.Ow + 7) / 8 * 8;
-    return 4 * Ypad * Xpad * g.Kpad * kMaxSlices;
+    const TilePlan p = plan_for(g);
+    const int64_t Ypad = (g.Oh + p.ty - 1) / p.ty * p.ty, Xpad = (g.Ow + p.tx - 1) / p.tx * p.tx;
+    return 4 * Ypad * Xpad * g.Kpad * p.slices * g.N;
 }
 
 int launch_sparse_conv_tile(const cpoconv_map &map, const int32_t *indices, const int32_t *mtab, const Geometry &g,
-                            const float *wt, float *out, float *partial, hipStream_t stream)
+                            const float *wt, float *out, float *partial, BatchStrides bs, hipStream_t stream)
 {
     const TilePlan p = plan_for(g);
 #define CPOCONV_TILE(KH, KW, S)                    \
     if (g.kh == KH && g.kw == KW && g.stride == S) \
-        return launch_tile<KH, KW, S, 4, 8, 1, 8>(map, indices, mtab, g, wt, out, partial, p.slices, stream);
+        return launch_tile<KH, KW, S, 4, 8, 1, 8>(map, indices, mtab, g, wt, out, partial, p.slices, bs, stream);
     CPOCONV_TILE(3, 3, 1)
     CPOCONV_TILE(3, 3, 2)
     CPOCONV_TILE(5, 5, 1)

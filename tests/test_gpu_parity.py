@@ -252,3 +252,87 @@ def test_selection_end_to_end_on_measured_times(api):
         assert algo == oracle.select_layer_algo(times["im2col"], times["cpo"], times["cps"], mode)
         expect = {0: api.ALGO_CPO, 1: api.ALGO_CPS}[mode] if sum(times[sparse]) < sum(times["im2col"]) else api.ALGO_IM2COL
         assert algo == expect
+
+
+# --- batched calls: n_images maps per launch, every image equal to its single-image result ----
+BATCH_CASES = [
+    # (n_images, shape) - strip kernel / register-tile kernel / generic kernel, ragged tiles, strides
+    (3, (5, 12, 13, 70, 3, 3, 1, 1)),
+    (4, (20, 9, 11, 66, 3, 3, 1, 1)),
+    (2, (18, 13, 9, 3, 3, 3, 2, 1)),
+    (3, (3, 10, 12, 4, 5, 5, 1, 2)),
+    (2, (2, 30, 30, 3, 11, 11, 4, 2)),
+    (5, (33, 21, 37, 4, 3, 3, 1, 0)),
+    (40, (4, 8, 8, 5, 3, 3, 1, 1)),               # enough images that no layer is sliced over channels
+    (2, (3, 70, 33, 4, 3, 3, 1, 1)),
+]
+
+
+def _batch_inputs(n_images, shape, seed):
+    acts = []
+    for n in range(n_images):
+        # densities differ per image; image 1 is all zero, so its streams are empty
+        act, w = workloads.random_case(seed + n, *shape, zero_frac=(0.3, 0.9, 0.6)[n % 3],
+                                       zero_channels=1 if shape[0] > 2 else 0)
+        if n == 1:
+            act[...] = 0.0
+        acts.append(act)
+    return np.stack(acts), w
+
+
+@pytest.mark.parametrize("case", BATCH_CASES, ids=lambda c: f"n{c[0]}-" + "x".join(map(str, c[1])))
+def test_batched_calls(api, case):
+    n_images, shape = case
+    acts, w_np = _batch_inputs(n_images, shape, 505)
+    _say(f"[case] batch n={n_images} shape={shape}")
+    buf = api.LayerBuffers(shape, n_images=n_images)
+    act = torch.from_numpy(acts).cuda()
+    w = torch.from_numpy(w_np).cuda()
+    api.cpoconv_prepare_weights(w, shape, buf.wt)
+    api.cpo_encode_batch(act, shape, buf.cpo, buf.scratch)
+    api.cps_encode_batch(act, shape, buf.cps, buf.scratch)
+    torch.cuda.synchronize()
+    refs = []
+    for n in range(n_images):
+        _assert_same_map(buf.cpo.to_host(image=n), oracle.cpo_encode(acts[n], shape), api.ALGO_CPO)
+        _assert_same_map(buf.cps.to_host(image=n), oracle.cps_encode(acts[n], shape), api.ALGO_CPS)
+        refs.append(oracle.conv_direct(acts[n], w_np, shape))
+    ref = np.stack(refs)
+    scale = max(float(np.abs(ref).max()), 1e-30)
+    for label, fn, m in (("cpo", api.cpo_conv_batch, buf.cpo), ("cps", api.cps_conv_batch, buf.cps)):
+        _say(f"[step] {label}_conv_batch")
+        buf.out.fill_(float("nan"))
+        fn(m, shape, buf.wt, buf.out, buf.scratch)
+        torch.cuda.synchronize()
+        got = buf.out.cpu().numpy().reshape(ref.shape)
+        assert np.isfinite(got).all(), label
+        assert float(np.abs(got - ref).max()) <= FP32_TOL * scale, label
+    for prec, tol in ((0, FP32_TOL), (1, BF16_TOL)):
+        _say(f"[step] im2col_conv_batch precision={prec}")
+        buf.out.fill_(float("nan"))
+        api.im2col_conv_batch(act, shape, n_images, w, buf.lowered, buf.out, prec)
+        torch.cuda.synchronize()
+        got = buf.out.cpu().numpy().reshape(ref.shape)
+        assert np.isfinite(got).all(), prec
+        assert float(np.abs(got - ref).max()) <= tol * scale, prec
+
+
+def test_batched_workload_layers(api):
+    """Two workload layers at full size with eight images each, sampled against the oracle."""
+    for name, n_images in (("cfg3.256@14", 8), ("cfg5.l05.128@28s1", 4)):
+        spec = {s.name: s for s in workloads.all_layers()}[name]
+        shape = spec.shape_tuple
+        _say(f"[case] batched {name} n={n_images}")
+        acts = np.stack([workloads.make_activation(spec, m) for m in range(n_images)])
+        w_np = workloads.make_weights(spec)
+        buf = api.LayerBuffers(shape, n_images=n_images)
+        act, w = torch.from_numpy(acts).cuda(), torch.from_numpy(w_np).cuda()
+        api.cpoconv_prepare_weights(w, shape, buf.wt)
+        api.cpo_encode_batch(act, shape, buf.cpo, buf.scratch)
+        api.cpo_conv_batch(buf.cpo, shape, buf.wt, buf.out, buf.scratch)
+        torch.cuda.synchronize()
+        got = buf.out.cpu().numpy()
+        for n in (0, n_images - 1):
+            _assert_same_map(buf.cpo.to_host(image=n), oracle.cpo_encode(acts[n], shape), api.ALGO_CPO)
+            ref = oracle.conv_direct(acts[n], w_np, shape)
+            assert float(np.abs(got[n] - ref).max()) <= FP32_TOL * float(np.abs(ref).max())
