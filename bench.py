@@ -256,6 +256,62 @@ def offline_selection(api, torch, workloads, run, spec, reps, m_inputs=5):
                "favour_space": names[api.select_layer_algo(t["im2col"], t["cpo"], t["cps"], 1)]}
 
 
+def batch_supplement(api, torch, workloads, spec, n_images, reps):
+    """The same layer with n_images inputs per launch (the batched entry points): per-image times,
+    and the SpMV kernel's achieved rate where launches are long enough to be throughput bound.
+    A supplement: `value` and `roofline` of the bench line stay on the batch-1 workload."""
+    import numpy as np
+
+    shape = spec.shape_tuple
+    acts = np.stack([workloads.make_activation(spec, m % 5) for m in range(n_images)])
+    buf = api.LayerBuffers(shape, n_images=n_images)
+    act, w = torch.from_numpy(acts).cuda(), torch.from_numpy(workloads.make_weights(spec)).cuda()
+    api.cpoconv_prepare_weights(w, shape, buf.wt)
+    api.cps_encode_batch(act, shape, buf.cps, buf.scratch)
+    stages = {
+        "cpo_encode": lambda: api.cpo_encode_batch(act, shape, buf.cpo, buf.scratch),
+        "cpo_conv": lambda: api.cpo_conv_batch(buf.cpo, shape, buf.wt, buf.out, buf.scratch),
+        "cps_conv": lambda: api.cps_conv_batch(buf.cps, shape, buf.wt, buf.out, buf.scratch),
+        "im2col_f32": lambda: api.im2col_conv_batch(act, shape, n_images, w, buf.lowered, buf.out, 0),
+        "im2col_bf16": lambda: api.im2col_conv_batch(act, shape, n_images, w, buf.lowered, buf.out, 1),
+    }
+    stages["cpo_encode"]()
+    us = {}
+    for k, fn in stages.items():
+        for _ in range(3):
+            fn()
+        us[k] = _time_us(torch, fn, reps)
+    flops = sum(sparse_flops(spec, a) for a in acts)
+    nnz = int(sum(((a.view(np.uint32) & 0x7FFFFFFF) != 0).sum() for a in acts))
+    enc_bytes = 4 * acts.size + 8 * nnz
+    torch.cuda.synchronize()
+    api.cpoconv_kernel_timing(True)
+    for _ in range(5):
+        stages["cpo_encode"]()
+        stages["cpo_conv"]()
+    torch.cuda.synchronize()
+    kt = api.cpoconv_kernel_timing_read()
+    api.cpoconv_kernel_timing(False)
+    overhead = event_pair_overhead_us(torch)
+    kern = {k: round(max(v[0] - overhead, 0.1), 2) for k, v in kt.items()}
+    conv_kernel = next((k for k in kern if k.startswith("spmv_conv")), None)
+    out = {
+        "n_images": n_images,
+        "per_image_us": {k: round(v / n_images, 3) for k, v in us.items()},
+        "cpo_total_per_image_us": round((us["cpo_encode"] + us["cpo_conv"]) / n_images, 3),
+        "speedup_cpo_vs_im2col_f32": round(us["im2col_f32"] / (us["cpo_encode"] + us["cpo_conv"]), 4),
+        "kernel_us": kern,
+        "encode_hbm_gbs": round(enc_bytes / (us["cpo_encode"] * 1e-6) / 1e9, 1),
+        "encode_hbm_frac": round(enc_bytes / (us["cpo_encode"] * 1e-6) / 1e9 / HBM_PEAK_GBS, 4),
+    }
+    if conv_kernel:
+        tf = flops / (kern[conv_kernel] * 1e-6) / 1e12
+        out["spmv_kernel"] = {"kernel": conv_kernel, "bound": "alu", "achieved": round(tf, 2), "peak": FP32_VECTOR_PEAK_TFLOPS,
+                              "unit": "TFLOP/s", "frac": round(tf / FP32_VECTOR_PEAK_TFLOPS, 4),
+                              "algorithmic_flops": flops}
+    return out
+
+
 def cpu_baseline(spec, act_np, w_np):
     """The CPU oracle as it stands, one thread, on the same layer: CPO encode + Algorithm 2."""
     import oracle
@@ -305,6 +361,8 @@ def main():
                     help="also measure every layer of the five workloads (per-layer report on stderr and "
                          "in gpurun_out/layers.json)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--batch", type=int, default=32,
+                    help="images per launch of the batched supplement (0 to skip it)")
     ap.add_argument("--no-cold", action="store_true", help="skip the cold-cache timing of the stages")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also launch a plain elementwise kernel that reads and writes 256 MiB, five times: the "
@@ -404,6 +462,8 @@ def main():
         result["layer"]["cold_us"] = cold
         result["layer"]["cold_note"] = ("median of 15 single calls, each after a 1 GiB device-memory sweep, less "
                                         "an empty event pair; 'us' above are warm back-to-back averages")
+    if args.batch > 0:
+        result["batch_supplement"] = batch_supplement(api, torch, workloads, spec, args.batch, reps=10)
     if not args.no_cpu_baseline:
         result["cpu_baseline"] = cpu_baseline(spec, run.act_np, run.w_np)
 

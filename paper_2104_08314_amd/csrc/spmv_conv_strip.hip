@@ -49,6 +49,7 @@ struct StripArgs {
     int32_t bands;            // wavefronts per workgroup
     int32_t batch;            // channels per table refill (multiple of G)
     int32_t chunks;           // upper bound of 64-NZE chunks of one channel's strip
+    int32_t chunks_magic;     // ceil(2^16 / chunks): item / chunks == (item * magic) >> 16 for item < 1024
 };
 
 template <int KH, int KW, int S, int TY, int TX, int G>
@@ -80,7 +81,8 @@ __global__ __launch_bounds__(kMaxBands *kLanes) void spmv_conv_strip_kernel(cons
     float *wl = reinterpret_cast<float *>(stage + a.bands * kStageInts);
     float *patch = wl + G * TAPS * kLanes;
 
-    const int tid = threadIdx.x, lane = lane_id(), wave = tid / kLanes;
+    const int tid = threadIdx.x, lane = lane_id();
+    const int wave = uni(tid / kLanes);   // in a scalar register: everything derived from it stays scalar
     const int nthreads = a.bands * kLanes;
     const int x0 = blockIdx.x * TX;
     const int yb = blockIdx.y * a.bands * TY;               // first output row of the workgroup
@@ -133,8 +135,8 @@ __global__ __launch_bounds__(kMaxBands *kLanes) void spmv_conv_strip_kernel(cons
             __syncthreads();
             for (int i = tid; i < ng * RW * PH; i += nthreads) patch[i] = 0.0f;
             // weights of the group's channels for this workgroup's 64 kernels (coalesced rows of 64)
-            for (int i = tid; i < ng * TAPS * kLanes; i += nthreads)
-                wl[i] = a.wt[(static_cast<int64_t>(cb + g0) * TAPS + i / kLanes) * g.Kpad + kbase + (i & (kLanes - 1))];
+            for (int row = wave; row < ng * TAPS; row += a.bands)
+                wl[row * kLanes + lane] = a.wt[(static_cast<int64_t>(cb + g0) * TAPS + row) * g.Kpad + kbase + lane];
             __syncthreads();
 
             // ---- decode: work item = (channel of the group, 64-NZE chunk of its main-type range);
@@ -150,7 +152,7 @@ __global__ __launch_bounds__(kMaxBands *kLanes) void spmv_conv_strip_kernel(cons
                     const int item = it0 + u * a.bands;
                     idxv[u] = -1; valv[u] = 0.0f; nv[u] = 0;
                     if (item < nitems) {
-                        const int gi = item / a.chunks, ch = item - gi * a.chunks;
+                        const int gi = (item * a.chunks_magic) >> 16, ch = item - gi * a.chunks;
                         const int32_t *row = tab + ((g0 + gi) * g.n_types + main_slot) * SPAN;
                         const int first = uni(row[0]), last = uni(row[phi - plo_main + 1]);
                         const int n = first + ch * kLanes + lane;
@@ -162,13 +164,15 @@ __global__ __launch_bounds__(kMaxBands *kLanes) void spmv_conv_strip_kernel(cons
                 for (int u = 0; u < IT; ++u) {
                     const int item = it0 + u * a.bands;
                     if (item >= nitems) continue;
-                    const int gi = item / a.chunks, ch = item - gi * a.chunks;
+                    const int gi = (item * a.chunks_magic) >> 16, ch = item - gi * a.chunks;
                     float *pt = patch + gi * RW * PH;
                     const int32_t *rows = tab + ((g0 + gi) * g.n_types) * SPAN;
                     int bound[SPAN];
 #pragma unroll
                     for (int e = 0; e < SPAN; ++e) bound[e] = uni(rows[main_slot * SPAN + e]);
-                    scatter(idxv[u], valv[u], nv[u], bound, plo_main, pt);
+                    // chunks past the strip's last NZE of the channel hold nothing
+                    const int last_main = uni(rows[main_slot * SPAN + phi - plo_main + 1]);
+                    if (bound[0] + ch * kLanes < last_main) scatter(idxv[u], valv[u], nv[u], bound, plo_main, pt);
                     if (ch != 0) continue;
                     // the lower overlap types (edge columns): few NZEs, loaded on demand
                     for (int i = 0; i < main_slot; ++i) {
@@ -213,7 +217,10 @@ __global__ __launch_bounds__(kMaxBands *kLanes) void spmv_conv_strip_kernel(cons
 #pragma unroll
                         for (int r = 0; r < RH; ++r) {
                             const int cellno = q * RH + r;
-                            if (bits[cellno / kLanes] & (1ull << (cellno % kLanes))) {
+                            // (tested on 32-bit halves: a single scalar bit-compare per cell)
+                            const unsigned half = (cellno % kLanes) < 32 ? static_cast<unsigned>(bits[cellno / kLanes])
+                                                                          : static_cast<unsigned>(bits[cellno / kLanes] >> 32);
+                            if ((half >> (cellno % 32)) & 1u) {
                                 const float v = __int_as_float(
                                     __builtin_amdgcn_readlane(__float_as_int(cell[cellno / kLanes]), cellno % kLanes));
 #pragma unroll
@@ -302,6 +309,7 @@ int launch_strip(const cpoconv_map &map, const int32_t *indices, const int32_t *
     a.partial = partial; a.out = out;
     a.slices = p.slices; a.Ypad = p.row_blocks * p.bands * TY; a.Xpad = ntx * TX;
     a.bands = p.bands; a.batch = p.batch; a.chunks = p.chunks;
+    a.chunks_magic = (65536 + p.chunks - 1) / p.chunks;
     bs.partial = static_cast<int64_t>(p.slices) * a.Ypad * a.Xpad * g.Kpad;
     a.bs = bs;
     {

@@ -66,7 +66,8 @@ __global__ __launch_bounds__(NW *kLanes) void spmv_conv_tile_kernel(const Geomet
     int32_t *tab = smem;
     float *patch_all = reinterpret_cast<float *>(tab + a_launch.batch * g.n_types * SPAN_MAX);
 
-    const int tid = threadIdx.x, lane = lane_id(), wave = tid / kLanes;
+    const int tid = threadIdx.x, lane = lane_id();
+    const int wave = uni(tid / kLanes);   // in a scalar register: everything derived from it stays scalar
     const int x0 = blockIdx.x * TX, y0 = blockIdx.y * TY;
     const int ngroups = g.Kpad / (kLanes * KPL);
     const int kg = blockIdx.z % ngroups, slice = (blockIdx.z / ngroups) % a_launch.slices;
@@ -234,7 +235,10 @@ __global__ __launch_bounds__(NW *kLanes) void spmv_conv_tile_kernel(const Geomet
 #pragma unroll
                     for (int r = 0; r < RH; ++r) {
                         const int cellno = q * RH + r;
-                        if (bits[cellno / kLanes] & (1ull << (cellno % kLanes))) {
+                        // (tested on 32-bit halves: a single scalar bit-compare per cell)
+                        const unsigned half = (cellno % kLanes) < 32 ? static_cast<unsigned>(bits[cellno / kLanes])
+                                                                      : static_cast<unsigned>(bits[cellno / kLanes] >> 32);
+                        if ((half >> (cellno % 32)) & 1u) {
                             const float v = __int_as_float(
                                 __builtin_amdgcn_readlane(__float_as_int(cell[cellno / kLanes]), cellno % kLanes));
 #pragma unroll
