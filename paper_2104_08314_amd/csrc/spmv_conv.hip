@@ -338,7 +338,7 @@ __global__ __launch_bounds__(kProWaves *kLanes) void conv_prologue_wave_kernel(c
 
 // out[k][y][x] = sum over slices of partial[slice][y][x][k]; one workgroup per (output row,
 // 64 kernels, 16 columns): reads coalesced along k, writes runs along x via LDS.
-constexpr int kEpiCols = 16;
+constexpr int kEpiCols = 4;
 
 __global__ __launch_bounds__(256) void reduce_transpose_kernel(const Geometry g, const float *__restrict__ partial_all,
                                                               int slices, int Ypad, int Xpad, float *__restrict__ out_all)

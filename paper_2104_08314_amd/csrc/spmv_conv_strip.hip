@@ -52,7 +52,7 @@ struct StripArgs {
     int32_t chunks_magic;     // ceil(2^16 / chunks): item / chunks == (item * magic) >> 16 for item < 1024
 };
 
-template <int KH, int KW, int S, int TY, int TX, int G>
+template <int KH, int KW, int S, int TY, int TX, int G, int KPL>
 __global__ __launch_bounds__(kMaxBands *kLanes) void spmv_conv_strip_kernel(const Geometry g, const StripArgs a_launch)
 {
     constexpr int RH = (TY - 1) * S + KH;      // rows of the padded input behind one tile
@@ -63,7 +63,7 @@ __global__ __launch_bounds__(kMaxBands *kLanes) void spmv_conv_strip_kernel(cons
     constexpr int SPAN = TX + KW + 1;          // table slots per (channel, type): partitions p_lo-1 ..
     constexpr int IT = 4;                      // decode items whose loads are in flight together
 
-    const int ngroups = g.Kpad / kLanes;
+    const int ngroups = g.Kpad / (kLanes * KPL);   // a wavefront holds KPL kernels per lane
     const int image = blockIdx.z / (ngroups * a_launch.slices);
     StripArgs a = a_launch;
     a.da += image * a.bs.da;
@@ -75,11 +75,11 @@ __global__ __launch_bounds__(kMaxBands *kLanes) void spmv_conv_strip_kernel(cons
     a.out += image * a.bs.out;
 
     extern __shared__ int32_t smem[];
-    // layout: tab[batch][n_types][SPAN] | stage[bands][kStageInts] | wl[G][TAPS][64] | patch[G][RW][PH]
+    // layout: tab[batch][n_types][SPAN] | stage[bands][kStageInts] | wl[G][TAPS][KPL*64] | patch[G][RW][PH]
     int32_t *tab = smem;
     int32_t *stage = tab + a.batch * g.n_types * SPAN;
     float *wl = reinterpret_cast<float *>(stage + a.bands * kStageInts);
-    float *patch = wl + G * TAPS * kLanes;
+    float *patch = wl + G * TAPS * KPL * kLanes;
 
     const int tid = threadIdx.x, lane = lane_id();
     const int wave = uni(tid / kLanes);   // in a scalar register: everything derived from it stays scalar
@@ -89,15 +89,17 @@ __global__ __launch_bounds__(kMaxBands *kLanes) void spmv_conv_strip_kernel(cons
     const int y0 = yb + wave * TY;                          // first output row of this wavefront
     const int PH = (a.bands * TY - 1) * S + KH;             // patch height: rows behind the workgroup
     const int kg = blockIdx.z % ngroups, slice = (blockIdx.z / ngroups) % a.slices;
-    const int kbase = kg * kLanes;
+    const int kbase = kg * kLanes * KPL;
     const int per_slice = (g.C + a.slices - 1) / a.slices;
     const int c_begin = slice * per_slice, c_end = min(g.C, c_begin + per_slice);
 
-    float acc[TY][TX];
+    float acc[TY][TX][KPL];
 #pragma unroll
     for (int y = 0; y < TY; ++y)
 #pragma unroll
-        for (int x = 0; x < TX; ++x) acc[y][x] = 0.0f;
+        for (int x = 0; x < TX; ++x)
+#pragma unroll
+            for (int kk = 0; kk < KPL; ++kk) acc[y][x][kk] = 0.0f;
 
     // one NZE -> its cell of the patch.  n is its position in DA; the partition is the number of
     // table boundaries at or below n.
@@ -136,7 +138,10 @@ __global__ __launch_bounds__(kMaxBands *kLanes) void spmv_conv_strip_kernel(cons
             for (int i = tid; i < ng * RW * PH; i += nthreads) patch[i] = 0.0f;
             // weights of the group's channels for this workgroup's 64 kernels (coalesced rows of 64)
             for (int row = wave; row < ng * TAPS; row += a.bands)
-                wl[row * kLanes + lane] = a.wt[(static_cast<int64_t>(cb + g0) * TAPS + row) * g.Kpad + kbase + lane];
+#pragma unroll
+                for (int kk = 0; kk < KPL; ++kk)
+                    wl[(row * KPL + kk) * kLanes + lane] =
+                        a.wt[(static_cast<int64_t>(cb + g0) * TAPS + row) * g.Kpad + kbase + kk * kLanes + lane];
             __syncthreads();
 
             // ---- decode: work item = (channel of the group, 64-NZE chunk of its main-type range);
@@ -209,9 +214,11 @@ __global__ __launch_bounds__(kMaxBands *kLanes) void spmv_conv_strip_kernel(cons
                         any = any || bits[d] != 0ull;
                     }
                     if (!any) continue;
-                    float w[TAPS];
+                    float w[TAPS][KPL];
 #pragma unroll
-                    for (int tp = 0; tp < TAPS; ++tp) w[tp] = wl[(gi * TAPS + tp) * kLanes + lane];
+                    for (int tp = 0; tp < TAPS; ++tp)
+#pragma unroll
+                        for (int kk = 0; kk < KPL; ++kk) w[tp][kk] = wl[((gi * TAPS + tp) * KPL + kk) * kLanes + lane];
 #pragma unroll
                     for (int q = 0; q < RW; ++q) {
 #pragma unroll
@@ -229,8 +236,10 @@ __global__ __launch_bounds__(kMaxBands *kLanes) void spmv_conv_strip_kernel(cons
 #pragma unroll
                                     for (int ww = 0; ww < KW; ++ww) {
                                         if ((q - ww) < 0 || (q - ww) % S != 0 || (q - ww) / S >= TX) continue;
-                                        acc[(r - l) / S][(q - ww) / S] =
-                                            fmaf(v, w[l * KW + ww], acc[(r - l) / S][(q - ww) / S]);
+#pragma unroll
+                                        for (int kk = 0; kk < KPL; ++kk)
+                                            acc[(r - l) / S][(q - ww) / S][kk] =
+                                                fmaf(v, w[l * KW + ww][kk], acc[(r - l) / S][(q - ww) / S][kk]);
                                     }
                                 }
                             }
@@ -241,24 +250,30 @@ __global__ __launch_bounds__(kMaxBands *kLanes) void spmv_conv_strip_kernel(cons
         }
     }
 
-    const int k = kbase + lane;
     if (a.slices == 1) {
-        if (k < g.K)
 #pragma unroll
-            for (int y = 0; y < TY; ++y)
+        for (int kk = 0; kk < KPL; ++kk) {
+            const int k = kbase + kk * kLanes + lane;
+            if (k < g.K)
 #pragma unroll
-                for (int x = 0; x < TX; ++x)
-                    if (y0 + y < g.Oh && x0 + x < g.Ow)
-                        a.out[(static_cast<int64_t>(k) * g.Oh + y0 + y) * g.Ow + x0 + x] = acc[y][x];
+                for (int y = 0; y < TY; ++y)
+#pragma unroll
+                    for (int x = 0; x < TX; ++x)
+                        if (y0 + y < g.Oh && x0 + x < g.Ow)
+                            a.out[(static_cast<int64_t>(k) * g.Oh + y0 + y) * g.Ow + x0 + x] = acc[y][x][kk];
+        }
         return;
     }
     // partial sums of this channel slice, kernel index fastest
     if (y0 < g.Oh) {
-        float *dst = a.partial + ((static_cast<int64_t>(slice) * a.Ypad + y0) * a.Xpad + x0) * g.Kpad + k;
+        float *dst = a.partial + ((static_cast<int64_t>(slice) * a.Ypad + y0) * a.Xpad + x0) * g.Kpad + kbase + lane;
 #pragma unroll
         for (int y = 0; y < TY; ++y)
 #pragma unroll
-            for (int x = 0; x < TX; ++x) dst[(static_cast<int64_t>(y) * a.Xpad + x) * g.Kpad] = acc[y][x];
+            for (int x = 0; x < TX; ++x)
+#pragma unroll
+                for (int kk = 0; kk < KPL; ++kk)
+                    dst[(static_cast<int64_t>(y) * a.Xpad + x) * g.Kpad + kk * kLanes] = acc[y][x][kk];
     }
 }
 
@@ -267,7 +282,7 @@ struct StripPlan {
     size_t lds;
 };
 
-template <int KH, int KW, int S, int TY, int TX, int G>
+template <int KH, int KW, int S, int TY, int TX, int G, int KPL>
 StripPlan strip_plan(const Geometry &g)
 {
     constexpr int RW = (TX - 1) * S + KW, SPAN = TX + KW + 1;
@@ -280,7 +295,7 @@ StripPlan strip_plan(const Geometry &g)
     p.chunks = (RW * g.Ih + kLanes - 1) / kLanes;   // a strip's partitions hold at most RW columns of Ih rows
     // about one workgroup per compute unit (measured best: the workgroups are large), each slice
     // keeping four channels or more
-    const int wgs = ((g.Ow + TX - 1) / TX) * p.row_blocks * (g.Kpad / kLanes) * g.N;
+    const int wgs = ((g.Ow + TX - 1) / TX) * p.row_blocks * (g.Kpad / (kLanes * KPL)) * g.N;
     int s = 256 / wgs;
     const int cap = (g.C + 3) / 4;
     if (s > cap) s = cap;
@@ -293,16 +308,16 @@ StripPlan strip_plan(const Geometry &g)
     if (batch > 64) batch = 64;
     p.batch = batch;
     p.lds = (static_cast<size_t>(batch) * g.n_types * SPAN + static_cast<size_t>(p.bands) * kStageInts +
-             static_cast<size_t>(G) * KH * KW * kLanes +
+             static_cast<size_t>(G) * KH * KW * KPL * kLanes +
              static_cast<size_t>(G) * RW * PH) * 4;
     return p;
 }
 
-template <int KH, int KW, int S, int TY, int TX, int G>
+template <int KH, int KW, int S, int TY, int TX, int G, int KPL>
 int launch_strip(const cpoconv_map &map, const int32_t *indices, const int32_t *mtab, const Geometry &g,
                  const float *wt, float *out, float *partial, BatchStrides bs, hipStream_t stream)
 {
-    const StripPlan p = strip_plan<KH, KW, S, TY, TX, G>(g);
+    const StripPlan p = strip_plan<KH, KW, S, TY, TX, G, KPL>(g);
     const int ntx = (g.Ow + TX - 1) / TX;
     StripArgs a;
     a.da = map.da; a.in = indices; a.mtab = mtab; a.ptr = map.ptr; a.chan_off = map.chan_off; a.wt = wt;
@@ -314,8 +329,8 @@ int launch_strip(const cpoconv_map &map, const int32_t *indices, const int32_t *
     a.bs = bs;
     {
         KernelTimer timer("spmv_conv_strip", stream);
-        hipLaunchKernelGGL((spmv_conv_strip_kernel<KH, KW, S, TY, TX, G>),
-                           dim3(ntx, p.row_blocks, (g.Kpad / kLanes) * p.slices * g.N), dim3(p.bands * kLanes), p.lds, stream,
+        hipLaunchKernelGGL((spmv_conv_strip_kernel<KH, KW, S, TY, TX, G, KPL>),
+                           dim3(ntx, p.row_blocks, (g.Kpad / (kLanes * KPL)) * p.slices * g.N), dim3(p.bands * kLanes), p.lds, stream,
                            g, a);
     }
     CPOCONV_HIP_TRY(hipGetLastError());
@@ -343,18 +358,21 @@ bool strip_kernel_preferred(const Geometry &g)
     return g.stride == 1 && g.Oh * g.Ow >= 2048 && g.Kpad >= 128;
 }
 
-#define CPOCONV_STRIP_DISPATCH(CALL)                                              \
-    if (g.kh == 3 && g.kw == 3 && g.stride == 1) return CALL(3, 3, 1, 4, 4, 8);   \
-    if (g.kh == 3 && g.kw == 3 && g.stride == 2) return CALL(3, 3, 2, 4, 4, 8);   \
-    if (g.kh == 5 && g.kw == 5 && g.stride == 1) return CALL(5, 5, 1, 4, 4, 8);   \
-    if (g.kh == 7 && g.kw == 7 && g.stride == 2) return CALL(7, 7, 2, 4, 4, 4);
+// 3 x 3 layers whose padded kernel count is a multiple of 128 keep two kernels per lane: the
+// scalar work of a visited cell (bit test, broadcast) then feeds twice the FMAs
+#define CPOCONV_STRIP_DISPATCH(CALL)                                                                     \
+    if (g.kh == 3 && g.kw == 3 && g.stride == 1 && g.Kpad % 128 == 0) return CALL(3, 3, 1, 4, 4, 8, 2);  \
+    if (g.kh == 3 && g.kw == 3 && g.stride == 1) return CALL(3, 3, 1, 4, 4, 8, 1);                       \
+    if (g.kh == 3 && g.kw == 3 && g.stride == 2) return CALL(3, 3, 2, 4, 4, 8, 1);                       \
+    if (g.kh == 5 && g.kw == 5 && g.stride == 1) return CALL(5, 5, 1, 4, 4, 8, 1);                       \
+    if (g.kh == 7 && g.kw == 7 && g.stride == 2) return CALL(7, 7, 2, 4, 4, 4, 1);
 
 int64_t strip_kernel_partial_bytes(const Geometry &g)
 {
     if (!strip_kernel_supports(g)) return 0;
-#define CPOCONV_STRIP_BYTES(KH, KW, S, TY, TX, G)                                               \
+#define CPOCONV_STRIP_BYTES(KH, KW, S, TY, TX, G, KPL)                                          \
     [&]() -> int64_t {                                                                          \
-        const StripPlan p = strip_plan<KH, KW, S, TY, TX, G>(g);                                \
+        const StripPlan p = strip_plan<KH, KW, S, TY, TX, G, KPL>(g);                           \
         return 4 * static_cast<int64_t>(p.slices) * p.Ypad * ((g.Ow + TX - 1) / TX * TX) * g.Kpad * g.N; \
     }()
     CPOCONV_STRIP_DISPATCH(CPOCONV_STRIP_BYTES)
@@ -365,8 +383,8 @@ int64_t strip_kernel_partial_bytes(const Geometry &g)
 int launch_sparse_conv_strip(const cpoconv_map &map, const int32_t *indices, const int32_t *mtab, const Geometry &g,
                              const float *wt, float *out, float *partial, BatchStrides bs, hipStream_t stream)
 {
-#define CPOCONV_STRIP_LAUNCH(KH, KW, S, TY, TX, G) \
-    launch_strip<KH, KW, S, TY, TX, G>(map, indices, mtab, g, wt, out, partial, bs, stream)
+#define CPOCONV_STRIP_LAUNCH(KH, KW, S, TY, TX, G, KPL) \
+    launch_strip<KH, KW, S, TY, TX, G, KPL>(map, indices, mtab, g, wt, out, partial, bs, stream)
     CPOCONV_STRIP_DISPATCH(CPOCONV_STRIP_LAUNCH)
 #undef CPOCONV_STRIP_LAUNCH
     return CPOCONV_ERR_SHAPE;
