@@ -190,9 +190,9 @@ def kernel_roofline(stage, kernel, us, fig, spec, lens):
     out_bytes = 4 * K * spec.Oh * spec.Ow
     hbm = lambda b: {"bound": "hbm", "achieved": b / t / 1e9, "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": b / t / 1e9 / HBM_PEAK_GBS, "algorithmic_bytes": b}
-    if kernel == "encode_count":
+    if kernel == "encode_count":      # layers of more than 256 channels: a first launch publishes the lengths
         return hbm(4 * C * H * W)
-    if kernel == "encode_write":
+    if kernel == "encode":
         return hbm(fig[stage + "_bytes"])
     if kernel == "conv_prologue":
         b = 4 * lens["ptr"] + 4 * C * 2 * (spec.Ow + 1)

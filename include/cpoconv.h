@@ -71,7 +71,8 @@ typedef struct {
  *   chan_off     3*(C+1) int32: offset of every channel in ptr, then in da, then in in, each
  *                list closed by the total.  Side band for parallel readers (Algorithm 2
  *                leaves "indexing relative to each channel" out).
- *   hdr          8 int32: |ptr|, |DA|, |IN|, algorithm (CPOCONV_ALGO_CPO / _CPS), C, Ow, 0, 0.
+ *   hdr          8 int32: |ptr|, |DA|, |IN|, algorithm (CPOCONV_ALGO_CPO / _CPS), C, Ow, 0, and a
+ *                failure flag (0, or 1 if the encoder gave up: see cpo_encode).
  */
 typedef struct {
     int32_t *ptr;
@@ -102,10 +103,24 @@ typedef struct {
 int cpoconv_sizes(const cpoconv_shape *shape, cpoconv_sizes_t *sizes);
 
 /*
+ * Prepares a scratch buffer (zero fill, queued on stream).  Required once after the buffer is
+ * allocated and before its first use by any call below; after that the library keeps what it
+ * needs in it consistent from call to call, provided nothing else writes to the buffer and the
+ * calls that share it are ordered (one stream, or explicit dependencies).  The encoders keep an
+ * epoch counter and the per-channel stream lengths of the running call there (Algorithm 1 appends
+ * channel after channel: a channel's position is the sum of the lengths before it).
+ * Errors: NULL, SHAPE (bytes < 0), HIP.
+ */
+int cpoconv_scratch_init(void *scratch, int64_t bytes, void *stream);
+
+/*
  * CPO encoding of one activation map (Algorithm 1; partition / overlap-type geometry of
  * Sections 3.1-3.2).  Reads act, writes every stream of *map, chan_off and hdr.  scratch:
- * device memory of at least sizes.scratch_bytes bytes, contents irrelevant on entry,
- * clobbered.  Streams, counts and indices are bit-exact functions of act and shape.
+ * device memory of at least sizes.scratch_bytes bytes prepared by cpoconv_scratch_init; its
+ * other contents are clobbered.  Streams, counts and indices are bit-exact functions of act and
+ * shape.  With a scratch buffer that was never prepared (or was overwritten by something else)
+ * the result is unspecified; every wait inside the encoder is bounded, and a workgroup whose
+ * wait runs out writes no stream and sets hdr[7] to 1 (otherwise 0).
  * Errors: NULL, SHAPE, SMALL (a capacity or scratch_bytes below the requirement), HIP.
  */
 int cpo_encode(const float *act, const cpoconv_shape *shape, const cpoconv_map *map,

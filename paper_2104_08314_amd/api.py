@@ -75,7 +75,7 @@ EXPORTS = (
     "cpoconv_sizes", "cpo_encode", "cps_encode", "cpoconv_prepare_weights", "cpo_conv", "cps_conv",
     "im2col_conv", "select_layer_algo", "cpoconv_map_header_to_host", "cpoconv_geometry",
     "cpoconv_strerror", "cpoconv_last_hip_error", "cpoconv_kernel_timing", "cpoconv_kernel_timing_read",
-    "cpoconv_batch_sizes", "cpo_encode_batch", "cps_encode_batch", "cpo_conv_batch", "cps_conv_batch",
+    "cpoconv_scratch_init", "cpoconv_batch_sizes", "cpo_encode_batch", "cps_encode_batch", "cpo_conv_batch", "cps_conv_batch",
     "im2col_conv_batch",
 )
 
@@ -290,6 +290,7 @@ class LayerBuffers:
         self.cpo = EncodedMap(self.shape, device, self.n_images)
         self.cps = EncodedMap(self.shape, device, self.n_images)
         self.scratch = torch.empty(sz.scratch_bytes, dtype=torch.uint8, device=device)
+        cpoconv_scratch_init(self.scratch)
         self.wt = torch.empty(sz.wt_len, dtype=torch.float32, device=device)
         self.lowered = torch.empty(sz.lowered_bytes, dtype=torch.uint8, device=device)
         dims = (self.shape.K, sz.Oh, sz.Ow) if self.n_images == 1 else (self.n_images, self.shape.K, sz.Oh, sz.Ow)
@@ -297,6 +298,12 @@ class LayerBuffers:
 
 
 # ---- batched calls: n_images maps of one shape per launch --------------------------------------
+
+def cpoconv_scratch_init(scratch, stream=None) -> None:
+    """Zero-fills a scratch buffer: required once before its first use (see include/cpoconv.h)."""
+    _check(lib().cpoconv_scratch_init(_dev_ptr(scratch), ctypes.c_int64(scratch.numel() * scratch.element_size()),
+                                      _stream_handle(stream)))
+
 
 def cpoconv_batch_sizes(shape, n_images: int) -> Sizes:
     sh, sz = make_shape(shape), Sizes()

@@ -144,15 +144,20 @@ int64_t max_ptr_len(const Geometry &g)
     return per_channel * g.C;
 }
 
-// Scratch layout: per-channel stream lengths of the encoder's first pass | the convolution's
+// Scratch layout: the encoder's look-back words (epoch, tickets, per-channel stream lengths) | the convolution's
 // table of resolved ptr offsets | one int32 per NZE for the indices cps_conv rebuilds | partial
 // sums of the register-tile convolution.
 // (each region holds g.N images back to back, with the per-image strides below)
-int64_t counts_stride(const Geometry &g) { return 4 * static_cast<int64_t>(g.C + 1); }                       // ints
 int64_t indices_stride(const Geometry &g) { return static_cast<int64_t>(g.C) * g.H * g.W; }                 // ints
 int64_t mtab_stride(const Geometry &g) { return static_cast<int64_t>(g.C) * std::max(g.n_types, 1) * (g.Ow + 1); }   // ints
 
-int64_t scratch_counts_bytes(const Geometry &g) { return (4 * counts_stride(g) * g.N + 255) / 256 * 256; }
+// encoder look-back words (8 bytes each): 8 + CPOCONV_MAX_BATCH control words, then two per
+// (image, channel) with at least 256 channel slots per image
+int64_t scratch_counts_bytes(const Geometry &g)
+{
+    const int64_t slots = static_cast<int64_t>(g.N) * std::max(g.C, 256);
+    return (8 * (8 + CPOCONV_MAX_BATCH + 2 * slots) + 255) / 256 * 256;
+}
 int64_t scratch_indices_bytes(const Geometry &g) { return (4 * indices_stride(g) * g.N + 255) / 256 * 256; }
 int64_t scratch_mtab_bytes(const Geometry &g) { return (4 * mtab_stride(g) * g.N + 255) / 256 * 256; }
 
@@ -215,6 +220,14 @@ static int encode_common(const float *act, const cpoconv_shape *shape, int n_ima
         return CPOCONV_ERR_SMALL;
     if (scratch_bytes < scratch_bytes_for(g)) return CPOCONV_ERR_SMALL;
     return launch_encode(act, g, *map, algo, scratch, static_cast<hipStream_t>(stream));
+}
+
+int cpoconv_scratch_init(void *scratch, int64_t bytes, void *stream)
+{
+    if (!scratch) return CPOCONV_ERR_NULL;
+    if (bytes < 0) return CPOCONV_ERR_SHAPE;
+    CPOCONV_HIP_TRY(hipMemsetAsync(scratch, 0, static_cast<size_t>(bytes), static_cast<hipStream_t>(stream)));
+    return CPOCONV_OK;
 }
 
 int cpo_encode(const float *act, const cpoconv_shape *shape, const cpoconv_map *map,

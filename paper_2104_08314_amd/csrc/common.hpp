@@ -92,7 +92,6 @@ int64_t scratch_counts_bytes(const Geometry &g);
 int64_t scratch_indices_bytes(const Geometry &g);
 int64_t scratch_mtab_bytes(const Geometry &g);
 // per-image strides inside those regions, in 4-byte elements
-int64_t counts_stride(const Geometry &g);
 int64_t indices_stride(const Geometry &g);
 int64_t mtab_stride(const Geometry &g);
 // out[k][y][x] = sum over channel slices of partial[slice][y][x][k] (spmv_conv.hip)

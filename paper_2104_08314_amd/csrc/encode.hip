@@ -11,9 +11,14 @@
 //   scatter  each wavefront takes whole columns with lane = padded row: a ballot rebuilds the
 //            bitmap, the popcount of the lower lanes is the rank of an NZE inside its column,
 //            so a column is written as one contiguous, coalesced run.
-// A first launch only counts (per-channel lengths of ptr / DA / IN); the second launch
-// recomputes the counts from LDS, sums the lengths of the channels before its own and writes
-// the streams.  All of it is integer / bit work on the fp32 bit patterns: outputs are exact.
+// One launch: a channel's position in the packed streams is the sum of the lengths of the
+// channels before it, so every workgroup publishes its three lengths in the scratch buffer and
+// reads those of its predecessors (a look-back over individual lengths, not a chain).  The
+// lengths travel inside 64-bit atomics tagged with the call's epoch - no other memory is
+// communicated, so no fence is needed - and the wait on a predecessor is bounded: a workgroup
+// that gives up writes nothing and raises hdr[7].  Workgroups only ever wait for lower block
+// indices, which the hardware dispatches first.  All of it is integer / bit work on the fp32 bit
+// patterns: outputs are exact.
 #include "common.hpp"
 
 namespace cpoconv {
@@ -63,15 +68,43 @@ __device__ __forceinline__ int set4_entries(unsigned long long mask)
     return n;
 }
 
-template <bool kCountOnly>
+// Scratch words of the look-back (unsigned 64-bit): [8 + n] the epoch of image slot n,
+// incremented by the workgroup of the last channel once its own look-back is complete (every
+// channel before it has then published, hence started and read the epoch); from word kCtrlWords
+// on, two words per (image, channel): {tag, |DA|} and {tag, |IN| + (|ptr| << 17)}, at a position
+// that does not depend on the layer (image * 256 + channel), so a word is only ever tagged from
+// one epoch counter.  tag = epoch % (2^32 - 2) + 1 of the call that wrote the word: never 0, the
+// initial state, and never 2^32 - 1, which marks lengths published by a separate launch.
+constexpr int kCtrlWords = 8 + CPOCONV_MAX_BATCH;
+constexpr unsigned long long kTagTwoLaunches = 0xFFFFFFFFull;
+// Reading C/2 lengths past the caches per workgroup costs more than a second launch once there
+// are many channels (measured: 4 us saved at 128 channels, 5 us lost at 512).  Beyond this many
+// channels a first launch only publishes the lengths and the second reads them as ordinary data.
+constexpr int kSinglePassChannels = 256;
+enum EncodeMode { kSinglePass = 0, kPublishOnly = 1, kPublished = 2 };
+constexpr int kSpinLimit = 1 << 14;   // polls of one predecessor before the encoder gives up
+
+__device__ __forceinline__ unsigned long long peek(const unsigned long long *p)
+{
+    return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+__device__ __forceinline__ void poke(unsigned long long *p, unsigned long long v)
+{
+    __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+
+template <int kMode>
 __global__ __launch_bounds__(kThreads) void encode_kernel(const Geometry g, const float *__restrict__ act_all,
                                                          const int cps, const int kChunk,
-                                                         int32_t *__restrict__ counts_all, const cpoconv_map maps)
+                                                         unsigned long long *__restrict__ ctrl, const cpoconv_map maps)
 {
     // image blockIdx.y of the launch: its map is image 0's advanced by the per-image capacities
     const int image = blockIdx.y;
     const float *__restrict__ act = act_all + static_cast<int64_t>(image) * g.C * g.H * g.W;
-    int32_t *__restrict__ counts = counts_all + static_cast<int64_t>(image) * 4 * (g.C + 1);
+    const unsigned long long epoch = kMode == kSinglePass ? peek(ctrl + 8 + image) : 0ull;
+    const unsigned long long tag = kMode == kSinglePass ? epoch % 0xFFFFFFFEull + 1ull : kTagTwoLaunches;
+    unsigned long long *flags = ctrl + kCtrlWords +
+                                2 * static_cast<int64_t>(image) * (kMode == kSinglePass ? kSinglePassChannels : g.C);
     cpoconv_map map = maps;
     map.ptr += image * maps.ptr_cap;
     map.da += image * maps.da_cap;
@@ -88,7 +121,7 @@ __global__ __launch_bounds__(kThreads) void encode_kernel(const Geometry g, cons
     __shared__ int32_t tbl[kMaxCols];                  // one ptr segment under construction
     __shared__ int32_t type_base[kMaxTypes + 1];       // NZEs of the channel before each type
     __shared__ int32_t wave_tot[2][kWaves];
-    __shared__ int32_t chan_base[3];
+    __shared__ int32_t chan_base[4];                   // ptr / DA / IN start of the channel, look-back failures
 
     const int c = blockIdx.x;
     const int lane = lane_id(), wave = wave_id(), tid = threadIdx.x;
@@ -113,16 +146,8 @@ __global__ __launch_bounds__(kThreads) void encode_kernel(const Geometry g, cons
         col_p0[tid] = g.col_p0[tid];
         col_wh[tid] = g.col_what[tid];
     }
-    int a0 = 0, a1 = 0, a2 = 0;
-    if (!kCountOnly) {
-        // start of this channel in the three streams: lengths of the channels before it
-        for (int cc = tid; cc < c; cc += kThreads) {
-            a0 += counts[4 * cc + 0];
-            a1 += counts[4 * cc + 1];
-            a2 += counts[4 * cc + 2];
-        }
-        if (tid < 3) chan_base[tid] = 0;
-    }
+    if (tid < 4) chan_base[tid] = 0;
+    if (kMode != kPublishOnly && tid == 0 && c == 0) map.hdr[7] = 0;   // raised by a workgroup that gives up its look-back
     __syncthreads();
 
     // ---- counts: one thread per column ---------------------------------------------------------
@@ -157,19 +182,11 @@ __global__ __launch_bounds__(kThreads) void encode_kernel(const Geometry g, cons
             }
         const int ni = wave_inclusive_sum(n), ei = wave_inclusive_sum(e);
         if (lane == kLanes - 1) { wave_tot[0][wave] = ni; wave_tot[1][wave] = ei; }
-        if (!kCountOnly) {
-            a0 = wave_sum(a0); a1 = wave_sum(a1); a2 = wave_sum(a2);
-        }
         __syncthreads();
         int nb = 0, eb = 0;
         for (int w = 0; w < wave; ++w) { nb += wave_tot[0][w]; eb += wave_tot[1][w]; }
         if (tid < kMaxCols) { col_excl[tid + 1] = nb + ni; ecol_excl[tid + 1] = eb + ei; }
         if (tid == 0) { col_excl[0] = 0; ecol_excl[0] = 0; }
-        if (!kCountOnly && lane == 0) {
-            atomicAdd(&chan_base[0], a0);
-            atomicAdd(&chan_base[1], a1);
-            atomicAdd(&chan_base[2], a2);
-        }
     }
     __syncthreads();
     if (tid <= g.n_types) type_base[tid] = col_excl[g.type_begin[tid]];
@@ -185,13 +202,47 @@ __global__ __launch_bounds__(kThreads) void encode_kernel(const Geometry g, cons
         }
     }
 
-    if (kCountOnly) {
-        if (tid == 0) {
-            counts[4 * c + 0] = ptr_c;
-            counts[4 * c + 1] = nnz_c;
-            counts[4 * c + 2] = in_c;
-            counts[4 * c + 3] = 0;
+    // ---- look-back: publish this channel's lengths, add up those of the channels before it --------
+    if (kMode != kPublished && tid == 0) {
+        poke(flags + 2 * c, (tag << 32) | static_cast<unsigned>(nnz_c));
+        poke(flags + 2 * c + 1, (tag << 32) | static_cast<unsigned>(in_c) | (static_cast<unsigned>(ptr_c) << 17));
+    }
+    if (kMode == kPublishOnly) return;
+    {
+        int a0 = 0, a1 = 0, a2 = 0, failed = 0;
+        for (int cc = tid; cc < c; cc += kThreads) {
+            unsigned long long w0, w1;
+            if (kMode == kPublished) {   // written by the launch before this one: ordinary loads
+                w0 = flags[2 * cc];
+                w1 = flags[2 * cc + 1];
+            } else {
+                w0 = peek(flags + 2 * cc);
+                w1 = peek(flags + 2 * cc + 1);
+                for (int spin = 0; ((w0 >> 32) != tag || (w1 >> 32) != tag) && spin < kSpinLimit; ++spin) {
+                    __builtin_amdgcn_s_sleep(8);
+                    w0 = peek(flags + 2 * cc);
+                    w1 = peek(flags + 2 * cc + 1);
+                }
+            }
+            if ((w0 >> 32) != tag || (w1 >> 32) != tag) { failed = 1; break; }
+            a1 += static_cast<int>(w0 & 0xFFFFFFFFull);
+            a2 += static_cast<int>(w1 & 0x1FFFFull);
+            a0 += static_cast<int>((w1 >> 17) & 0x7FFFull);
         }
+        a0 = wave_sum(a0); a1 = wave_sum(a1); a2 = wave_sum(a2); failed = wave_sum(failed);
+        if (lane == 0) {
+            atomicAdd(&chan_base[0], a0);
+            atomicAdd(&chan_base[1], a1);
+            atomicAdd(&chan_base[2], a2);
+            atomicAdd(&chan_base[3], failed);
+        }
+    }
+    __syncthreads();
+    // the last channel has seen every other channel's lengths, so all of them have read the epoch:
+    // it may move on (one writer per image; the next call is ordered after this launch)
+    if (kMode == kSinglePass && tid == 0 && c == g.C - 1 && chan_base[3] == 0) poke(ctrl + 8 + image, epoch + 1ull);
+    if (chan_base[3] != 0) {   // a predecessor never showed up (scratch not initialised?): write nothing
+        if (tid == 0) atomicOr(&map.hdr[7], 1);
         return;
     }
 
@@ -211,7 +262,6 @@ __global__ __launch_bounds__(kThreads) void encode_kernel(const Geometry g, cons
             map.hdr[4] = g.C;
             map.hdr[5] = g.Ow;
             map.hdr[6] = 0;
-            map.hdr[7] = 0;
         }
     }
 
@@ -310,15 +360,19 @@ int launch_encode(const float *act, const Geometry &g, const cpoconv_map &map, i
     const size_t row_bytes = static_cast<size_t>(g.W | 1) * sizeof(float);
     const int chunk = kLanes * row_bytes <= kTileBytesMax ? kLanes : kChunkWide;   // 32 rows always fit: W <= 256
     const size_t lds = chunk * row_bytes;
-    int32_t *counts = static_cast<int32_t *>(scratch);
-    {
-        KernelTimer timer("encode_count", stream);
-        hipLaunchKernelGGL(encode_kernel<true>, dim3(g.C, g.N), dim3(kThreads), lds, stream, g, act, cps, chunk, counts, map);
-    }
-    CPOCONV_HIP_TRY(hipGetLastError());
-    {
-        KernelTimer timer("encode_write", stream);
-        hipLaunchKernelGGL(encode_kernel<false>, dim3(g.C, g.N), dim3(kThreads), lds, stream, g, act, cps, chunk, counts, map);
+    unsigned long long *ctrl = static_cast<unsigned long long *>(scratch);
+    if (g.C <= kSinglePassChannels) {
+        KernelTimer timer("encode", stream);
+        hipLaunchKernelGGL(encode_kernel<kSinglePass>, dim3(g.C, g.N), dim3(kThreads), lds, stream, g, act, cps, chunk, ctrl, map);
+    } else {
+        {
+            KernelTimer timer("encode_count", stream);
+            hipLaunchKernelGGL(encode_kernel<kPublishOnly>, dim3(g.C, g.N), dim3(kThreads), lds, stream, g, act, cps, chunk,
+                               ctrl, map);
+        }
+        CPOCONV_HIP_TRY(hipGetLastError());
+        KernelTimer timer("encode", stream);
+        hipLaunchKernelGGL(encode_kernel<kPublished>, dim3(g.C, g.N), dim3(kThreads), lds, stream, g, act, cps, chunk, ctrl, map);
     }
     CPOCONV_HIP_TRY(hipGetLastError());
     return CPOCONV_OK;

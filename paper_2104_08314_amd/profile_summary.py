@@ -32,14 +32,13 @@ def _find(directory, suffix):
 
 def short_name(name):
     """Kernel name as the library's timing aid reports it: no template arguments, parameters,
-    namespaces or _kernel suffix; the encoder's two instantiations are encode_count and
-    encode_write, the fp32 lowering is im2col_lower_f32."""
+    namespaces or _kernel suffix; the encoder's publish-only instantiation is encode_count, the
+    fp32 lowering is im2col_lower_f32."""
     name = name.replace("(anonymous namespace)::", "")
     base = re.split(r"[<(]", name, 1)[0].replace("void ", "").split("::")[-1].strip()
     if base == "encode_kernel":
-        m = re.search(r"encode_kernel<\(?(?:bool\))?\s*(\w+)", name)
-        flag = m.group(1) if m else "?"
-        return "encode_count" if flag in ("true", "1") else "encode_write"
+        m = re.search(r"encode_kernel<\(?(?:[\w:]+\))?\s*(\w+)", name)
+        return "encode_count" if (m and m.group(1) == "1") else "encode"
     if base == "im2col_lower_kernel":
         return "im2col_lower_f32"
     return base[:-len("_kernel")] if base.endswith("_kernel") else base

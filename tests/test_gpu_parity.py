@@ -336,3 +336,20 @@ def test_batched_workload_layers(api):
             _assert_same_map(buf.cpo.to_host(image=n), oracle.cpo_encode(acts[n], shape), api.ALGO_CPO)
             ref = oracle.conv_direct(acts[n], w_np, shape)
             assert float(np.abs(got[n] - ref).max()) <= FP32_TOL * float(np.abs(ref).max())
+
+
+# --- the scratch buffer: prepared once, shared between shapes -------------------------------------
+def test_scratch_shared_between_shapes(api):
+    """One scratch buffer serves layers of different channel counts in turn (the encoders' epoch
+    and stream-length words live in it)."""
+    shapes = [(40, 30, 29, 7, 3, 3, 1, 1), (3, 7, 9, 2, 3, 3, 1, 1), (20, 9, 11, 66, 3, 3, 1, 1)]
+    sizes = [api.cpoconv_sizes(s).scratch_bytes for s in shapes]
+    scratch = torch.empty(max(sizes), dtype=torch.uint8, device="cuda")
+    api.cpoconv_scratch_init(scratch)
+    for rnd in range(3):
+        for i, shape in enumerate(shapes):
+            act_np, _ = workloads.random_case(700 + 10 * rnd + i, *shape, zero_frac=0.6, zero_channels=1)
+            _say(f"[case] shared scratch round {rnd} shape={shape}")
+            m = api.EncodedMap(shape)
+            api.cps_encode(torch.from_numpy(act_np).cuda(), shape, m, scratch)
+            _assert_same_map(m.to_host(), oracle.cps_encode(act_np, shape), api.ALGO_CPS)
