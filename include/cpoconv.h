@@ -103,7 +103,7 @@ typedef struct {
 int cpoconv_sizes(const cpoconv_shape *shape, cpoconv_sizes_t *sizes);
 
 /*
- * Prepares a scratch buffer (zero fill, queued on stream).  Required once after the buffer is
+ * Prepares a scratch buffer (zero fill by a kernel queued on stream).  Required once after the buffer is
  * allocated and before its first use by any call below; after that the library keeps what it
  * needs in it consistent from call to call, provided nothing else writes to the buffer and the
  * calls that share it are ordered (one stream, or explicit dependencies).  The encoders keep an

@@ -226,8 +226,7 @@ int cpoconv_scratch_init(void *scratch, int64_t bytes, void *stream)
 {
     if (!scratch) return CPOCONV_ERR_NULL;
     if (bytes < 0) return CPOCONV_ERR_SHAPE;
-    CPOCONV_HIP_TRY(hipMemsetAsync(scratch, 0, static_cast<size_t>(bytes), static_cast<hipStream_t>(stream)));
-    return CPOCONV_OK;
+    return launch_zero_fill(scratch, bytes, static_cast<hipStream_t>(stream));
 }
 
 int cpo_encode(const float *act, const cpoconv_shape *shape, const cpoconv_map *map,

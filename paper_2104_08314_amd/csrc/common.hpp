@@ -74,6 +74,7 @@ private:
 int launch_encode(const float *act, const Geometry &g, const cpoconv_map &map, int algo,
                   void *scratch, hipStream_t stream);
 int launch_prepare_weights(const float *w, const Geometry &g, float *wt, hipStream_t stream);
+int launch_zero_fill(void *buffer, int64_t bytes, hipStream_t stream);
 int launch_sparse_conv(const cpoconv_map &map, const Geometry &g, int algo, const float *wt,
                        float *out, void *scratch, hipStream_t stream);
 // register-tile SpMV kernel (spmv_conv_tile.hip)

@@ -21,6 +21,8 @@
 // patterns: outputs are exact.
 #include "common.hpp"
 
+#include <algorithm>
+
 namespace cpoconv {
 
 namespace {
@@ -337,6 +339,17 @@ __global__ __launch_bounds__(kThreads) void encode_kernel(const Geometry g, cons
     }
 }
 
+// zero fill of a scratch buffer (a kernel rather than a memset node, so that a caller may capture
+// the call in a graph)
+__global__ __launch_bounds__(256) void zero_fill_kernel(uint32_t *__restrict__ words, const int64_t n_words,
+                                                       unsigned char *__restrict__ tail, const int n_tail)
+{
+    for (int64_t i = blockIdx.x * static_cast<int64_t>(blockDim.x) + threadIdx.x; i < n_words;
+         i += static_cast<int64_t>(gridDim.x) * blockDim.x)
+        words[i] = 0u;
+    if (blockIdx.x == 0 && static_cast<int>(threadIdx.x) < n_tail) tail[threadIdx.x] = 0;
+}
+
 __global__ __launch_bounds__(256) void prepare_weights_kernel(const Geometry g, const float *__restrict__ w,
                                                              float *__restrict__ wt)
 {
@@ -374,6 +387,26 @@ int launch_encode(const float *act, const Geometry &g, const cpoconv_map &map, i
         KernelTimer timer("encode", stream);
         hipLaunchKernelGGL(encode_kernel<kPublished>, dim3(g.C, g.N), dim3(kThreads), lds, stream, g, act, cps, chunk, ctrl, map);
     }
+    CPOCONV_HIP_TRY(hipGetLastError());
+    return CPOCONV_OK;
+}
+
+int launch_zero_fill(void *buffer, int64_t bytes, hipStream_t stream)
+{
+    if (bytes == 0) return CPOCONV_OK;
+    // leading bytes up to 4-byte alignment and trailing bytes are written one by one
+    unsigned char *p = static_cast<unsigned char *>(buffer);
+    const int64_t head = std::min<int64_t>(bytes, (4 - reinterpret_cast<uintptr_t>(p) % 4) % 4);
+    const int64_t n_words = (bytes - head) / 4;
+    const int n_tail = static_cast<int>(bytes - head - 4 * n_words);
+    if (head > 0) {
+        hipLaunchKernelGGL(zero_fill_kernel, dim3(1), dim3(256), 0, stream, nullptr, 0, p, static_cast<int>(head));
+        CPOCONV_HIP_TRY(hipGetLastError());
+    }
+    const int64_t want = (n_words + 255) / 256;
+    const int blocks = static_cast<int>(want < 1 ? 1 : (want > 2048 ? 2048 : want));
+    hipLaunchKernelGGL(zero_fill_kernel, dim3(blocks), dim3(256), 0, stream, reinterpret_cast<uint32_t *>(p + head), n_words,
+                       p + head + 4 * n_words, n_tail);
     CPOCONV_HIP_TRY(hipGetLastError());
     return CPOCONV_OK;
 }
