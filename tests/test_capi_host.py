@@ -119,3 +119,28 @@ def test_select_layer_algo_matches_oracle_and_rules():
         api.select_layer_algo([1.0], [1.0], [1.0], 2)
     with pytest.raises(api.CpoconvError):
         api.select_layer_algo([1.0], None, [1.0], 0)
+
+
+def test_batch_sizes_and_batch_argument_checks():
+    lib = api.lib()
+    shape = (6, 10, 12, 70, 3, 3, 1, 1)
+    one_img, batch = api.cpoconv_sizes(shape), api.cpoconv_batch_sizes(shape, 5)
+    # per-image capacities do not change; outputs and scratch cover the whole batch
+    assert (batch.ptr_cap, batch.da_cap, batch.in_cap, batch.chan_off_len, batch.wt_len) == \
+           (one_img.ptr_cap, one_img.da_cap, one_img.in_cap, one_img.chan_off_len, one_img.wt_len)
+    assert batch.out_len == 5 * one_img.out_len
+    assert batch.scratch_bytes >= one_img.scratch_bytes
+    assert batch.lowered_bytes >= 5 * 4 * 6 * 9 * one_img.Oh * one_img.Ow
+    good, sz = api.Shape(*shape), api.Sizes()
+    for n in (0, -1, 1025):
+        assert lib.cpoconv_batch_sizes(ctypes.byref(good), n, ctypes.byref(sz)) == api.ERR_SHAPE
+    one = ctypes.c_void_p(256)
+    big = api._Map(256, 1 << 20, 256, 1 << 20, 256, 1 << 20, 256, 256)
+    assert lib.cpo_encode_batch(one, ctypes.byref(good), 0, ctypes.byref(big), one, ctypes.c_int64(1 << 40), None) == api.ERR_SHAPE
+    assert lib.cpo_encode_batch(one, ctypes.byref(good), 3, ctypes.byref(big), one, ctypes.c_int64(8), None) == api.ERR_SMALL
+    tight = api._Map(256, 10, 256, 1 << 20, 256, 1 << 20, 256, 256)   # ptr capacity below one image's
+    assert lib.cps_conv_batch(ctypes.byref(tight), ctypes.byref(good), 3, one, one, one, ctypes.c_int64(1 << 40), None) == api.ERR_SMALL
+    assert lib.cpo_conv_batch(ctypes.byref(big), ctypes.byref(good), 3, None, one, one, ctypes.c_int64(1 << 40), None) == api.ERR_NULL
+    assert lib.im2col_conv_batch(one, ctypes.byref(good), 2000, one, one, one, 0, None) == api.ERR_SHAPE
+    assert lib.cpoconv_scratch_init(None, ctypes.c_int64(16), None) == api.ERR_NULL
+    assert lib.cpoconv_scratch_init(one, ctypes.c_int64(-1), None) == api.ERR_SHAPE
