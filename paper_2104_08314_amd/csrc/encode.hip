@@ -44,13 +44,16 @@ __device__ __forceinline__ bool is_nze(float v)
     return (__float_as_uint(v) & 0x7fffffffu) != 0u;
 }
 
+// inclusive sum over the 64 lanes: shifts inside rows of 16 lanes, then the last lane of a row
+// added to the rows after it
 __device__ __forceinline__ int wave_inclusive_sum(int v)
 {
-#pragma unroll
-    for (int d = 1; d < kLanes; d <<= 1) {
-        const int n = __shfl_up(v, d, kLanes);
-        if (lane_id() >= d) v += n;
-    }
+    v += __builtin_amdgcn_update_dpp(0, v, 0x111, 0xf, 0xf, false);   // row_shr:1
+    v += __builtin_amdgcn_update_dpp(0, v, 0x112, 0xf, 0xf, false);   // row_shr:2
+    v += __builtin_amdgcn_update_dpp(0, v, 0x114, 0xf, 0xf, false);   // row_shr:4
+    v += __builtin_amdgcn_update_dpp(0, v, 0x118, 0xf, 0xf, false);   // row_shr:8
+    v += __builtin_amdgcn_update_dpp(0, v, 0x142, 0xa, 0xf, false);   // row_bcast:15 -> rows 1, 3
+    v += __builtin_amdgcn_update_dpp(0, v, 0x143, 0xc, 0xf, false);   // row_bcast:31 -> rows 2, 3
     return v;
 }
 
@@ -123,6 +126,7 @@ __global__ __launch_bounds__(kThreads) void encode_kernel(const Geometry g, cons
     __shared__ int32_t tbl[kMaxCols];                  // one ptr segment under construction
     __shared__ int32_t type_base[kMaxTypes + 1];       // NZEs of the channel before each type
     __shared__ int32_t wave_tot[2][kWaves];
+    __shared__ uint8_t mask_part[kMaxCols][kWaves];    // a column's row bitmap in pieces, one per wavefront
     __shared__ int32_t chan_base[4];                   // ptr / DA / IN start of the channel, look-back failures
 
     const int c = blockIdx.x;
@@ -152,19 +156,32 @@ __global__ __launch_bounds__(kThreads) void encode_kernel(const Geometry g, cons
     if (kMode != kPublishOnly && tid == 0 && c == 0) map.hdr[7] = 0;   // raised by a workgroup that gives up its look-back
     __syncthreads();
 
-    // ---- counts: one thread per column ---------------------------------------------------------
+    // ---- counts: every wavefront takes kChunk / 8 rows of the chunk (lane = column in stream
+    // order) and leaves its part of every column's row bitmap in LDS; one thread per column then
+    // puts the eight parts together ------------------------------------------------------------
+    const int rows_per_wave = kChunk / kWaves;   // 8, or 4 for wide maps
     for (int q = 0; q < nchunks; ++q) {
         if (q > 0) {
             __syncthreads();   // every thread is done with the previous chunk
             load_tile(q);
             __syncthreads();
         }
+        for (int vi = lane; vi < g.n_cols; vi += kLanes) {
+            const int jr = col_jr[vi];
+            unsigned bits = 0;
+#pragma unroll
+            for (int rr = 0; rr < 8; ++rr) {
+                const int r = wave * rows_per_wave + rr, hr = q * kChunk + r - g.pad;
+                if (rr < rows_per_wave && hr >= 0 && hr < g.H) bits |= static_cast<unsigned>(is_nze(tile[r * Wt + jr])) << rr;
+            }
+            mask_part[vi][wave] = static_cast<uint8_t>(bits);
+        }
+        __syncthreads();
         if (tid < g.n_cols) {
-            const int jr = col_jr[tid];
-            const int r_lo = max(0, g.pad - q * kChunk), r_hi = min(kChunk, g.pad + g.H - q * kChunk);
             unsigned long long mask = 0;
-            for (int r = r_lo; r < r_hi; ++r)
-                mask |= static_cast<unsigned long long>(is_nze(tile[r * Wt + jr])) << r;
+#pragma unroll
+            for (int w = 0; w < kWaves; ++w)
+                mask |= static_cast<unsigned long long>(mask_part[tid][w]) << (w * rows_per_wave);
             cnt_q[q][tid] = static_cast<uint16_t>(__popcll(mask));
             ecnt_q[q][tid] = static_cast<uint16_t>((tid >= top_begin && tid < top_end) ? set4_entries(mask)
                                                                                       : __popcll(mask));
