@@ -152,10 +152,10 @@ int64_t indices_stride(const Geometry &g) { return static_cast<int64_t>(g.C) * g
 int64_t mtab_stride(const Geometry &g) { return static_cast<int64_t>(g.C) * std::max(g.n_types, 1) * (g.Ow + 1); }   // ints
 
 // encoder look-back words (8 bytes each): 8 + CPOCONV_MAX_BATCH control words, then two per
-// (image, channel) with at least 256 channel slots per image
+// (image, channel) with at least 512 channel slots per image
 int64_t scratch_counts_bytes(const Geometry &g)
 {
-    const int64_t slots = static_cast<int64_t>(g.N) * std::max(g.C, 256);
+    const int64_t slots = static_cast<int64_t>(g.N) * std::max(g.C, 512);
     return (8 * (8 + CPOCONV_MAX_BATCH + 2 * slots) + 255) / 256 * 256;
 }
 int64_t scratch_indices_bytes(const Geometry &g) { return (4 * indices_stride(g) * g.N + 255) / 256 * 256; }

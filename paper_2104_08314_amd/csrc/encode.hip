@@ -77,15 +77,15 @@ __device__ __forceinline__ int set4_entries(unsigned long long mask)
 // incremented by the workgroup of the last channel once its own look-back is complete (every
 // channel before it has then published, hence started and read the epoch); from word kCtrlWords
 // on, two words per (image, channel): {tag, |DA|} and {tag, |IN| + (|ptr| << 17)}, at a position
-// that does not depend on the layer (image * 256 + channel), so a word is only ever tagged from
+// that does not depend on the layer (image * 512 + channel), so a word is only ever tagged from
 // one epoch counter.  tag = epoch % (2^32 - 2) + 1 of the call that wrote the word: never 0, the
 // initial state, and never 2^32 - 1, which marks lengths published by a separate launch.
 constexpr int kCtrlWords = 8 + CPOCONV_MAX_BATCH;
 constexpr unsigned long long kTagTwoLaunches = 0xFFFFFFFFull;
-// Reading C/2 lengths past the caches per workgroup costs more than a second launch once there
-// are many channels (measured: 4 us saved at 128 channels, 5 us lost at 512).  Beyond this many
-// channels a first launch only publishes the lengths and the second reads them as ordinary data.
-constexpr int kSinglePassChannels = 256;
+// Every workgroup reads C/2 lengths past the caches, C*C/2 loads in all: up to 512 channels that is
+// cheaper than a second launch (measured: 4 us saved at 128 channels, 1.5 us at 512).  Beyond, a
+// first launch only publishes the lengths and the second reads them as ordinary data.
+constexpr int kSinglePassChannels = 512;
 enum EncodeMode { kSinglePass = 0, kPublishOnly = 1, kPublished = 2 };
 constexpr int kSpinLimit = 1 << 14;   // polls of one predecessor before the encoder gives up
 
