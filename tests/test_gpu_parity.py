@@ -130,6 +130,7 @@ EDGE_SHAPES = [
     (17, 15, 14, 5, 7, 7, 2, 3),
     (40, 30, 29, 70, 3, 3, 1, 1),     # several channel slices, ragged tiles
     (33, 21, 37, 4, 3, 3, 1, 0),      # VALID padding in the register-tile kernel
+    (520, 5, 6, 3, 3, 3, 1, 1),       # more channels than the encoder's single-launch look-back takes
 ]
 
 
