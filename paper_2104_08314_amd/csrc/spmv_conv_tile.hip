@@ -44,7 +44,6 @@ struct TileArgs {
     BatchStrides bs;          // image n of the launch: every buffer advanced n strides
     int32_t Ypad, Xpad;
     int32_t batch;            // channels per table refill
-    int32_t red_slots;        // accumulator-sized LDS buffers available to the reduction
 };
 
 template <int KH, int KW, int S, int TY, int TX, int KPL, int NW>
@@ -264,63 +263,69 @@ __global__ __launch_bounds__(NW *kLanes) void spmv_conv_tile_kernel(const Geomet
         }
     }
 
-    // ---- add the wavefronts' accumulators: fixed binary tree (w += w + stride), so the order
-    // of additions never changes.  Senders park their registers in LDS, 16 bytes per lane.
+    // ---- add the wavefronts' accumulators.  Every wavefront parks its registers in LDS (16 bytes
+    // per lane and access); after one barrier wavefront w adds, always in wavefront order, the
+    // copies of accumulator group w and stores that part of the tile itself, so the stores are
+    // spread over the workgroup too.
     constexpr int KW64 = KPL * kLanes;
     constexpr int A = TY * TX * KPL;           // accumulators per lane
     static_assert(A % 4 == 0, "tile accumulators must pack into float4");
+    constexpr int A4 = A / 4;
     float4 *red4 = reinterpret_cast<float4 *>(smem);
+    float *red = reinterpret_cast<float *>(smem);
     auto acc_at = [&](int n) -> float & { return acc[n / (TX * KPL)][(n / KPL) % TX][n % KPL]; };
-    for (int stride = 1; stride < kWavesPerWg; stride *= 2) {
-        const int npairs = (kWavesPerWg - stride + 2 * stride - 1) / (2 * stride);   // receivers w with w + stride < NW
-        const bool sender = (wave % (2 * stride)) == stride;
-        const bool receiver = (wave % (2 * stride)) == 0 && wave + stride < kWavesPerWg;
-        const int pair = wave / (2 * stride);
-        for (int first = 0; first < npairs; first += a.red_slots) {
-            __syncthreads();
-            if (sender && pair >= first && pair < first + a.red_slots) {
-                float4 *dst = red4 + (pair - first) * (A / 4) * kLanes + lane;
+    __syncthreads();   // table and patches are no longer in use: the parking area overlays them
+    {
+        float4 *dst = red4 + wave * A4 * kLanes + lane;
 #pragma unroll
-                for (int j = 0; j < A / 4; ++j)
-                    dst[j * kLanes] = make_float4(acc_at(4 * j), acc_at(4 * j + 1), acc_at(4 * j + 2), acc_at(4 * j + 3));
-            }
-            __syncthreads();
-            if (receiver && pair >= first && pair < first + a.red_slots) {
-                const float4 *src = red4 + (pair - first) * (A / 4) * kLanes + lane;
+        for (int j = 0; j < A4; ++j)
+            dst[j * kLanes] = make_float4(acc_at(4 * j), acc_at(4 * j + 1), acc_at(4 * j + 2), acc_at(4 * j + 3));
+    }
+    __syncthreads();
+    constexpr int LDT = KW64 + 1;              // row stride of the transposed tile (bank conflicts)
+    float4 sums[(A4 + kWavesPerWg - 1) / kWavesPerWg];
 #pragma unroll
-                for (int j = 0; j < A / 4; ++j) {
-                    const float4 v = src[j * kLanes];
-                    acc_at(4 * j) += v.x; acc_at(4 * j + 1) += v.y; acc_at(4 * j + 2) += v.z; acc_at(4 * j + 3) += v.w;
-                }
+    for (int jj = 0; jj < (A4 + kWavesPerWg - 1) / kWavesPerWg; ++jj) {
+        const int j = wave + jj * kWavesPerWg;
+        float4 t = make_float4(0.f, 0.f, 0.f, 0.f);
+        if (j < A4) {
+            t = red4[j * kLanes + lane];
+#pragma unroll
+            for (int w2 = 1; w2 < kWavesPerWg; ++w2) {
+                const float4 v = red4[(w2 * A4 + j) * kLanes + lane];
+                t.x += v.x; t.y += v.y; t.z += v.z; t.w += v.w;
             }
         }
+        sums[jj] = t;
     }
-    float *red = reinterpret_cast<float *>(smem);
     if (a.slices > 1) {
         // partial sums of this channel slice, kernel index fastest
-        if (wave == 0) {
-            float *dst = a.partial + ((static_cast<int64_t>(slice) * a.Ypad + y0) * a.Xpad + x0) * g.Kpad + kbase + lane;
 #pragma unroll
-            for (int y = 0; y < TY; ++y)
+        for (int jj = 0; jj < (A4 + kWavesPerWg - 1) / kWavesPerWg; ++jj) {
+            const int j = wave + jj * kWavesPerWg;
+            if (j >= A4) continue;
+            const float e[4] = {sums[jj].x, sums[jj].y, sums[jj].z, sums[jj].w};
 #pragma unroll
-                for (int x = 0; x < TX; ++x)
-#pragma unroll
-                    for (int k = 0; k < KPL; ++k)
-                        dst[(static_cast<int64_t>(y) * a.Xpad + x) * g.Kpad + k * kLanes] = acc[y][x][k];
+            for (int u = 0; u < 4; ++u) {
+                const int n = 4 * j + u, y = n / (TX * KPL), x = (n / KPL) % TX, k = n % KPL;
+                a.partial[((static_cast<int64_t>(slice) * a.Ypad + y0 + y) * a.Xpad + x0 + x) * g.Kpad + kbase + k * kLanes + lane] = e[u];
+            }
         }
         return;   // a second kernel adds the slices
     }
-    // one slice: transpose through LDS (row stride KW64+1 against bank conflicts) and store the
-    // K x Oh x Ow output directly, TX consecutive x per kernel and row
-    constexpr int LDT = KW64 + 1;
-    __syncthreads();
-    if (wave == 0) {
+    // one slice: transpose through LDS and store the K x Oh x Ow output directly, TX consecutive x
+    // per kernel and row
+    __syncthreads();   // every wavefront has read the parked copies: the area is free again
 #pragma unroll
-        for (int y = 0; y < TY; ++y)
+    for (int jj = 0; jj < (A4 + kWavesPerWg - 1) / kWavesPerWg; ++jj) {
+        const int j = wave + jj * kWavesPerWg;
+        if (j >= A4) continue;
+        const float e[4] = {sums[jj].x, sums[jj].y, sums[jj].z, sums[jj].w};
 #pragma unroll
-            for (int x = 0; x < TX; ++x)
-#pragma unroll
-                for (int k = 0; k < KPL; ++k) red[(y * TX + x) * LDT + k * kLanes + lane] = acc[y][x][k];
+        for (int u = 0; u < 4; ++u) {
+            const int n = 4 * j + u, y = n / (TX * KPL), x = (n / KPL) % TX, k = n % KPL;
+            red[(y * TX + x) * LDT + k * kLanes + lane] = e[u];
+        }
     }
     __syncthreads();
     for (int i = tid; i < TY * TX * KW64; i += kWavesPerWg * kLanes) {
@@ -370,14 +375,10 @@ int launch_tile(const cpoconv_map &map, const int32_t *indices, const int32_t *m
     bs.partial = static_cast<int64_t>(slices) * a.Ypad * a.Xpad * g.Kpad;
     a.bs = bs;
     const size_t work = (static_cast<size_t>(g.n_types) * SPAN_MAX * batch + NW * kGroup * NCELL) * 4;
-    const size_t acc_bytes = static_cast<size_t>(TY) * TX * KPL * kLanes * 4;
+    const size_t park = static_cast<size_t>(NW) * TY * TX * KPL * kLanes * 4;   // every wavefront's accumulators
     const size_t transpose = static_cast<size_t>(TY) * TX * (KPL * kLanes + 1) * 4;
-    int red_slots = static_cast<int>((48 * 1024) / acc_bytes);
-    if (red_slots > NW / 2) red_slots = NW / 2;
-    if (red_slots < 1) red_slots = 1;
-    a.red_slots = red_slots;
     size_t lds = work;
-    if (red_slots * acc_bytes > lds) lds = red_slots * acc_bytes;
+    if (park > lds) lds = park;
     if (transpose > lds) lds = transpose;
     {
         KernelTimer timer("spmv_conv_tile", stream);
