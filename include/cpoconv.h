@@ -157,6 +157,19 @@ int cps_conv(const cpoconv_map *map, const cpoconv_shape *shape, const float *wt
              void *scratch, int64_t scratch_bytes, void *stream);
 
 /*
+ * Encoding and convolution of one layer in one call: exactly cpo_encode (cps_encode) followed by
+ * cpo_conv (cps_conv) on the same map, scratch buffer and stream - same streams, same output -
+ * which is how a layer runs at inference time and what the per-layer selection of Section 3.5
+ * times against im2col.  Knowing that the convolution follows, the encoder also leaves the
+ * resolved partition offsets in the scratch buffer, so a CPO convolution starts without a pass
+ * over ptr of its own.  Arguments, layouts and errors as the separate calls.
+ */
+int cpo_encode_conv(const float *act, const cpoconv_shape *shape, const cpoconv_map *map, const float *wt,
+                    float *out, void *scratch, int64_t scratch_bytes, void *stream);
+int cps_encode_conv(const float *act, const cpoconv_shape *shape, const cpoconv_map *map, const float *wt,
+                    float *out, void *scratch, int64_t scratch_bytes, void *stream);
+
+/*
  * The comparator of Section 3.1: im2col lowering (lowered matrix C*kh*kw x Oh*Ow, row
  * (c*kh + l)*kw + w, column y*Ow + x, holds the padded input at (c, y*stride + l,
  * x*stride + w)) followed by a dense matrix product with the K x C*kh*kw kernel matrix on
@@ -198,6 +211,10 @@ int cps_conv_batch(const cpoconv_map *maps, const cpoconv_shape *shape, int n_im
                    float *out, void *scratch, int64_t scratch_bytes, void *stream);
 int im2col_conv_batch(const float *act, const cpoconv_shape *shape, int n_images, const float *weights,
                       void *lowered, float *out, int precision, void *stream);
+int cpo_encode_conv_batch(const float *act, const cpoconv_shape *shape, int n_images, const cpoconv_map *maps,
+                          const float *wt, float *out, void *scratch, int64_t scratch_bytes, void *stream);
+int cps_encode_conv_batch(const float *act, const cpoconv_shape *shape, int n_images, const cpoconv_map *maps,
+                          const float *wt, float *out, void *scratch, int64_t scratch_bytes, void *stream);
 
 /*
  * Offline per-layer selection (Section 3.5).  Host only.  t_*: times of the three methods on

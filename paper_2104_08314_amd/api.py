@@ -76,7 +76,7 @@ EXPORTS = (
     "im2col_conv", "select_layer_algo", "cpoconv_map_header_to_host", "cpoconv_geometry",
     "cpoconv_strerror", "cpoconv_last_hip_error", "cpoconv_kernel_timing", "cpoconv_kernel_timing_read",
     "cpoconv_scratch_init", "cpoconv_batch_sizes", "cpo_encode_batch", "cps_encode_batch", "cpo_conv_batch", "cps_conv_batch",
-    "im2col_conv_batch",
+    "im2col_conv_batch", "cpo_encode_conv", "cps_encode_conv", "cpo_encode_conv_batch", "cps_encode_conv_batch",
 )
 
 
@@ -355,3 +355,26 @@ def im2col_conv_batch(act, shape, n_images: int, weights, lowered, out, precisio
     _check(lib().im2col_conv_batch(_dev_ptr(act, torch.float32), ctypes.byref(sh), int(n_images),
                                    _dev_ptr(weights, torch.float32), _dev_ptr(lowered), _dev_ptr(out, torch.float32),
                                    int(precision), _stream_handle(stream)))
+
+
+# ---- encoding + convolution of a layer in one call ---------------------------------------------
+
+def _encode_conv(fn_name: str, act, shape, m: EncodedMap, wt, out, scratch, stream) -> None:
+    import torch
+
+    sh = make_shape(shape)
+    cm = m.c_struct()
+    args = [_dev_ptr(act, torch.float32), ctypes.byref(sh)]
+    if fn_name.endswith("_batch"):
+        args.append(int(m.n_images))
+    args += [ctypes.byref(cm), _dev_ptr(wt, torch.float32), _dev_ptr(out, torch.float32), _dev_ptr(scratch),
+             ctypes.c_int64(scratch.numel() * scratch.element_size()), _stream_handle(stream)]
+    _check(getattr(lib(), fn_name)(*args))
+
+
+def cpo_encode_conv(act, shape, m: EncodedMap, wt, out, scratch, stream=None) -> None:
+    _encode_conv("cpo_encode_conv" if m.n_images == 1 else "cpo_encode_conv_batch", act, shape, m, wt, out, scratch, stream)
+
+
+def cps_encode_conv(act, shape, m: EncodedMap, wt, out, scratch, stream=None) -> None:
+    _encode_conv("cps_encode_conv" if m.n_images == 1 else "cps_encode_conv_batch", act, shape, m, wt, out, scratch, stream)

@@ -278,6 +278,50 @@ int cps_conv(const cpoconv_map *map, const cpoconv_shape *shape, const float *wt
     return conv_common(map, shape, 1, wt, out, scratch, scratch_bytes, stream, CPOCONV_ALGO_CPS);
 }
 
+static int encode_conv_common(const float *act, const cpoconv_shape *shape, int n_images, const cpoconv_map *map,
+                              const float *wt, float *out, void *scratch, int64_t scratch_bytes, void *stream, int algo)
+{
+    if (!act || !shape || !map || !wt || !out || !scratch) return CPOCONV_ERR_NULL;
+    if (!map->ptr || !map->da || !map->in || !map->chan_off || !map->hdr) return CPOCONV_ERR_NULL;
+    Geometry g;
+    const int rc = batch_geometry(shape, n_images, &g);
+    if (rc != CPOCONV_OK) return rc;
+    const int64_t chw = static_cast<int64_t>(g.C) * g.H * g.W;
+    if (map->ptr_cap < max_ptr_len(g) || map->da_cap < chw || map->in_cap < chw) return CPOCONV_ERR_SMALL;
+    if (scratch_bytes < scratch_bytes_for(g)) return CPOCONV_ERR_SMALL;
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    // the encoder also leaves the table of resolved ptr offsets: the convolution needs no prologue
+    // of its own for a CPO map (a CPS map still has its indices rebuilt by one)
+    const bool table = (algo == CPOCONV_ALGO_CPO || g.top_slot < 0) && sparse_conv_uses_prologue(g);
+    const int erc = launch_encode(act, g, *map, algo, scratch, st, table);
+    if (erc != CPOCONV_OK) return erc;
+    return launch_sparse_conv(*map, g, algo, wt, out, scratch, st, table);
+}
+
+int cpo_encode_conv(const float *act, const cpoconv_shape *shape, const cpoconv_map *map, const float *wt,
+                    float *out, void *scratch, int64_t scratch_bytes, void *stream)
+{
+    return encode_conv_common(act, shape, 1, map, wt, out, scratch, scratch_bytes, stream, CPOCONV_ALGO_CPO);
+}
+
+int cps_encode_conv(const float *act, const cpoconv_shape *shape, const cpoconv_map *map, const float *wt,
+                    float *out, void *scratch, int64_t scratch_bytes, void *stream)
+{
+    return encode_conv_common(act, shape, 1, map, wt, out, scratch, scratch_bytes, stream, CPOCONV_ALGO_CPS);
+}
+
+int cpo_encode_conv_batch(const float *act, const cpoconv_shape *shape, int n_images, const cpoconv_map *maps,
+                          const float *wt, float *out, void *scratch, int64_t scratch_bytes, void *stream)
+{
+    return encode_conv_common(act, shape, n_images, maps, wt, out, scratch, scratch_bytes, stream, CPOCONV_ALGO_CPO);
+}
+
+int cps_encode_conv_batch(const float *act, const cpoconv_shape *shape, int n_images, const cpoconv_map *maps,
+                          const float *wt, float *out, void *scratch, int64_t scratch_bytes, void *stream)
+{
+    return encode_conv_common(act, shape, n_images, maps, wt, out, scratch, scratch_bytes, stream, CPOCONV_ALGO_CPS);
+}
+
 int cpo_encode_batch(const float *act, const cpoconv_shape *shape, int n_images, const cpoconv_map *maps,
                      void *scratch, int64_t scratch_bytes, void *stream)
 {

@@ -101,7 +101,8 @@ __device__ __forceinline__ void poke(unsigned long long *p, unsigned long long v
 template <int kMode>
 __global__ __launch_bounds__(kThreads) void encode_kernel(const Geometry g, const float *__restrict__ act_all,
                                                          const int cps, const int kChunk,
-                                                         unsigned long long *__restrict__ ctrl, const cpoconv_map maps)
+                                                         unsigned long long *__restrict__ ctrl, const cpoconv_map maps,
+                                                         int32_t *__restrict__ mtab_all, const int64_t mtab_stride)
 {
     // image blockIdx.y of the launch: its map is image 0's advanced by the per-image capacities
     const int image = blockIdx.y;
@@ -284,6 +285,23 @@ __global__ __launch_bounds__(kThreads) void encode_kernel(const Geometry g, cons
         }
     }
 
+    // ---- for a convolution that follows in the same call: the table of absolute DA offsets after
+    // every partition (what Algorithm 2 gets by forward-filling ptr), per present type ----------
+    if (mtab_all != nullptr) {
+        for (int i = 0; i < g.n_types; ++i) {
+            int32_t *row = mtab_all + image * mtab_stride + (static_cast<int64_t>(c) * g.n_types + i) * (g.Ow + 1);
+            const int cb = g.type_begin[i], ce = g.type_begin[i + 1];
+            const int base = type_base[i], at = da_off + base;
+            const int p_first = cb < ce ? col_p0[cb] : g.Ow;        // partitions before it hold nothing of the type
+            for (int k = tid; k <= p_first; k += kThreads) row[k] = at;
+            for (int vi = cb + tid; vi < ce; vi += kThreads) {
+                const int p_end = vi + 1 < ce ? col_p0[vi + 1] : g.Ow;
+                const int upto = at + col_excl[vi + 1] - base;
+                for (int pp = col_p0[vi]; pp < p_end; ++pp) row[1 + pp] = upto;
+            }
+        }
+    }
+
     // ---- ptr of this channel -------------------------------------------------------------
     if (nnz_c == 0) {
         if (tid == 0) map.ptr[ptr_off] = CPOCONV_NPC;
@@ -384,8 +402,11 @@ __global__ __launch_bounds__(256) void prepare_weights_kernel(const Geometry g, 
 }  // namespace
 
 int launch_encode(const float *act, const Geometry &g, const cpoconv_map &map, int algo, void *scratch,
-                  hipStream_t stream)
+                  hipStream_t stream, bool write_table)
 {
+    // the table of resolved ptr offsets, for a convolution launched by the same call
+    int32_t *mtab = write_table ? reinterpret_cast<int32_t *>(static_cast<char *>(scratch) + scratch_counts_bytes(g)) : nullptr;
+    const int64_t mstride = mtab_stride(g);
     const int cps = algo == CPOCONV_ALGO_CPS ? 1 : 0;
     const size_t row_bytes = static_cast<size_t>(g.W | 1) * sizeof(float);
     const int chunk = kLanes * row_bytes <= kTileBytesMax ? kLanes : kChunkWide;   // 32 rows always fit: W <= 256
@@ -393,16 +414,18 @@ int launch_encode(const float *act, const Geometry &g, const cpoconv_map &map, i
     unsigned long long *ctrl = static_cast<unsigned long long *>(scratch);
     if (g.C <= kSinglePassChannels) {
         KernelTimer timer("encode", stream);
-        hipLaunchKernelGGL(encode_kernel<kSinglePass>, dim3(g.C, g.N), dim3(kThreads), lds, stream, g, act, cps, chunk, ctrl, map);
+        hipLaunchKernelGGL(encode_kernel<kSinglePass>, dim3(g.C, g.N), dim3(kThreads), lds, stream, g, act, cps, chunk, ctrl, map,
+                           mtab, mstride);
     } else {
         {
             KernelTimer timer("encode_count", stream);
             hipLaunchKernelGGL(encode_kernel<kPublishOnly>, dim3(g.C, g.N), dim3(kThreads), lds, stream, g, act, cps, chunk,
-                               ctrl, map);
+                               ctrl, map, static_cast<int32_t *>(nullptr), mstride);
         }
         CPOCONV_HIP_TRY(hipGetLastError());
         KernelTimer timer("encode", stream);
-        hipLaunchKernelGGL(encode_kernel<kPublished>, dim3(g.C, g.N), dim3(kThreads), lds, stream, g, act, cps, chunk, ctrl, map);
+        hipLaunchKernelGGL(encode_kernel<kPublished>, dim3(g.C, g.N), dim3(kThreads), lds, stream, g, act, cps, chunk, ctrl, map,
+                           mtab, mstride);
     }
     CPOCONV_HIP_TRY(hipGetLastError());
     return CPOCONV_OK;

@@ -375,8 +375,17 @@ int launch_reduce_transpose(const Geometry &g, const float *partial, int slices,
     return CPOCONV_OK;
 }
 
+// Would a CPO convolution of this layer run conv_prologue first?  (Then an encoder that runs in
+// the same call can leave the table instead; the strip kernel mostly resolves ptr itself.)
+bool sparse_conv_uses_prologue(const Geometry &g)
+{
+    const bool strip = strip_kernel_preferred(g) || (strip_kernel_supports(g) && !tile_kernel_supports(g));
+    const bool tile = strip || tile_kernel_supports(g);
+    return tile && !(strip && resolve_in_kernel_ok(g));
+}
+
 int launch_sparse_conv(const cpoconv_map &map, const Geometry &g, int algo, const float *wt, float *out,
-                       void *scratch, hipStream_t stream)
+                       void *scratch, hipStream_t stream, bool table_ready)
 {
     char *base = static_cast<char *>(scratch);
     int32_t *mtab = reinterpret_cast<int32_t *>(base + scratch_counts_bytes(g));
@@ -397,9 +406,10 @@ int launch_sparse_conv(const cpoconv_map &map, const Geometry &g, int algo, cons
     // 1-4 us faster than a prologue launch; in the register-tile kernel, where many more workgroups
     // would repeat the work, it was slower).  Otherwise, and for the index reconstruction of CPS,
     // a prologue kernel runs first.
-    const bool in_kernel = strip && in_full == nullptr && resolve_in_kernel_ok(g);
+    // (table_ready: the encoder of the same call left the table in the scratch buffer)
+    const bool in_kernel = strip && in_full == nullptr && !table_ready && resolve_in_kernel_ok(g);
     if (in_kernel) mtab = nullptr;
-    if ((tile && !in_kernel) || in_full != nullptr) {
+    if ((tile && !in_kernel && !table_ready) || in_full != nullptr) {
         KernelTimer timer("conv_prologue", stream);
         if (in_full == nullptr && resolve_in_kernel_ok(g))
             hipLaunchKernelGGL(conv_prologue_wave_kernel, dim3((g.C + kProWaves - 1) / kProWaves, g.N),

@@ -75,6 +75,19 @@ def _check_layer(api, act_np, w_np, shape, convs=True, name=""):
         err = float(np.abs(got - ref).max())
         assert np.isfinite(got).all(), label
         assert err <= FP32_TOL * scale, (label, err, scale)
+    # encoding + convolution in one call: the same streams and the same output, bit for bit
+    for label, fused, conv, m, ref_map, code in (("cpo", api.cpo_encode_conv, api.cpo_conv, buf.cpo, ref_cpo, api.ALGO_CPO),
+                                                 ("cps", api.cps_encode_conv, api.cps_conv, buf.cps, ref_cps, api.ALGO_CPS)):
+        _say(f"[step] {label}_encode_conv")
+        conv(m, shape, buf.wt, buf.out, buf.scratch)
+        torch.cuda.synchronize()
+        separate = buf.out.clone()
+        m.da.fill_(-3.0)
+        buf.out.fill_(float("nan"))
+        fused(act, shape, m, buf.wt, buf.out, buf.scratch)
+        torch.cuda.synchronize()
+        _assert_same_map(m.to_host(), ref_map, code)
+        assert torch.equal(buf.out, separate), label
     for prec, tol in ((0, FP32_TOL), (1, BF16_TOL)):
         _say(f"[step] im2col_conv precision={prec}")
         buf.out.fill_(float("nan"))
@@ -304,6 +317,14 @@ def test_batched_calls(api, case):
         _say(f"[step] {label}_conv_batch")
         buf.out.fill_(float("nan"))
         fn(m, shape, buf.wt, buf.out, buf.scratch)
+        torch.cuda.synchronize()
+        got = buf.out.cpu().numpy().reshape(ref.shape)
+        assert np.isfinite(got).all(), label
+        assert float(np.abs(got - ref).max()) <= FP32_TOL * scale, label
+    for label, fused, m in (("cpo", api.cpo_encode_conv, buf.cpo), ("cps", api.cps_encode_conv, buf.cps)):
+        _say(f"[step] {label}_encode_conv (batched)")
+        buf.out.fill_(float("nan"))
+        fused(act, shape, m, buf.wt, buf.out, buf.scratch)
         torch.cuda.synchronize()
         got = buf.out.cpu().numpy().reshape(ref.shape)
         assert np.isfinite(got).all(), label
