@@ -326,23 +326,33 @@ def batch_supplement(api, torch, workloads, spec, n_images, reps):
     return out
 
 
-def cpu_baseline(spec, act_np, w_np):
-    """The CPU oracle as it stands, one thread, on the same layer: CPO encode + Algorithm 2."""
+def cpu_baseline(spec, workloads, w_np, inputs=5, repeats=4):
+    """The CPU oracle as it stands, one thread, on the same layer: CPO encode + Algorithm 2 on the
+    layer's `inputs` offline inputs, `repeats` times each (about 10 s of CPU work on config 2)."""
     import oracle
 
     shape = spec.shape_tuple
-    oracle.cpo_encode(act_np, shape)                      # builds / loads the library
-    t0 = time.perf_counter()
-    m = oracle.cpo_encode(act_np, shape)
-    t1 = time.perf_counter()
-    oracle.sparse_conv(m, w_np)
-    t2 = time.perf_counter()
-    oracle.conv_direct(act_np, w_np, shape)
-    t3 = time.perf_counter()
-    return {"value": (t2 - t0) * 1e6, "unit": "us", "cores": 1, "kind": "oracle",
-            "sample": "the whole layer once: oracle CPO encode (%.0f us) + sequential Algorithm 2 convolution "
-                      "(%.0f us), double accumulation, gcc -O2, one thread; dense 7-loop definition of the same "
-                      "layer: %.0f us" % ((t1 - t0) * 1e6, (t2 - t1) * 1e6, (t3 - t2) * 1e6)}
+    acts = [workloads.make_activation(spec, m) for m in range(inputs)]
+    oracle.cpo_encode(acts[0], shape)                     # builds / loads the library
+    enc, conv, dense = [], [], []
+    for act in acts:
+        for _ in range(repeats):
+            t0 = time.perf_counter()
+            m = oracle.cpo_encode(act, shape)
+            t1 = time.perf_counter()
+            oracle.sparse_conv(m, w_np)
+            t2 = time.perf_counter()
+            enc.append((t1 - t0) * 1e6)
+            conv.append((t2 - t1) * 1e6)
+        t0 = time.perf_counter()
+        oracle.conv_direct(act, w_np, shape)
+        dense.append((time.perf_counter() - t0) * 1e6)
+    med = lambda v: sorted(v)[len(v) // 2]
+    return {"value": med(enc) + med(conv), "unit": "us", "cores": 1, "kind": "oracle",
+            "sample": "the whole layer, %d inputs x %d repeats, medians: oracle CPO encode (%.0f us) + sequential "
+                      "Algorithm 2 convolution (%.0f us), double accumulation, gcc -O2, one thread; dense 7-loop "
+                      "definition of the same layer, once per input: %.0f us"
+                      % (inputs, repeats, med(enc), med(conv), med(dense))}
 
 
 def traffic_from_profiles(kernel_key):
@@ -479,7 +489,7 @@ def main():
     if args.batch > 0:
         result["batch_supplement"] = batch_supplement(api, torch, workloads, spec, args.batch, reps=10)
     if not args.no_cpu_baseline:
-        result["cpu_baseline"] = cpu_baseline(spec, run.act_np, run.w_np)
+        result["cpu_baseline"] = cpu_baseline(spec, workloads, run.w_np)
 
     if args.all_layers:
         rows = []
