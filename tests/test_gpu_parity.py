@@ -375,3 +375,37 @@ def test_scratch_shared_between_shapes(api):
             m = api.EncodedMap(shape)
             api.cps_encode(torch.from_numpy(act_np).cuda(), shape, m, scratch)
             _assert_same_map(m.to_host(), oracle.cps_encode(act_np, shape), api.ALGO_CPS)
+
+
+def test_layer_call_replays_in_a_hip_graph(api):
+    """A captured cpo_encode_conv + im2col_conv replays correctly on new inputs: the library queues
+    kernels only (no memset nodes), and the encoder's epoch lives on the device, so a replay is a new call."""
+    shape = (24, 20, 19, 70, 3, 3, 1, 1)
+    inputs = [workloads.random_case(800 + i, *shape, zero_frac=z, zero_channels=2)[0] for i, z in enumerate((0.5, 0.8, 0.3, 0.6))]
+    _, w_np = workloads.random_case(800, *shape, zero_frac=0.5)
+    buf = api.LayerBuffers(shape)
+    w = torch.from_numpy(w_np).cuda()
+    api.cpoconv_prepare_weights(w, shape, buf.wt)
+    act = torch.from_numpy(inputs[0]).cuda()
+    out_dense = torch.empty_like(buf.out)
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    _say("[case] graph capture")
+    with torch.cuda.graph(graph):
+        api.cpo_encode_conv(act, shape, buf.cpo, buf.wt, buf.out, buf.scratch)
+        api.im2col_conv(act, shape, w, buf.lowered, out_dense, 0)
+    for rnd, act_np in enumerate(inputs):
+        _say(f"[step] replay {rnd}")
+        act.copy_(torch.from_numpy(act_np))          # eager work between the replays
+        buf.out.fill_(float("nan"))
+        out_dense.fill_(float("nan"))
+        graph.replay()
+        torch.cuda.synchronize()
+        ref = oracle.conv_direct(act_np, w_np, shape)
+        scale = float(np.abs(ref).max())
+        _assert_same_map(buf.cpo.to_host(), oracle.cpo_encode(act_np, shape), api.ALGO_CPO)
+        assert float(np.abs(buf.out.cpu().numpy() - ref).max()) <= FP32_TOL * scale
+        assert float(np.abs(out_dense.cpu().numpy() - ref).max()) <= FP32_TOL * scale
+        # an eager call between replays shares the scratch buffer and the epoch
+        api.cps_encode(act, shape, buf.cps, buf.scratch)
+        _assert_same_map(buf.cps.to_host(), oracle.cps_encode(act_np, shape), api.ALGO_CPS)
