@@ -402,3 +402,32 @@ def test_random_tiny_layers_brute_force():
         assert np.array_equal(oracle.sparse_conv(oracle.cpo_encode(act, shape), w), ref), shape
         assert np.array_equal(oracle.sparse_conv(oracle.cps_encode(act, shape), w), ref), shape
         done += 1
+
+
+@pytest.mark.parametrize("shape", [(3, 9, 8, 2, 7, 1, 1, 0), (2, 6, 11, 2, 3, 1, 1, 0), (4, 5, 5, 3, 1, 1, 1, 0)],
+                         ids=lambda s: "x".join(map(str, s)))
+def test_kw_1_streams_are_the_special_case_of_the_si(shape):
+    """K_w = 1 (SI, "CPO/CPS Encoding Algorithm K_w = 1"): no overlap regions, every column is its
+    own sub-matrix.  Per live channel ptr is [0, running NZE count after column 0, 1, ..], IN holds
+    the row of each NZE, DA the values column by column; an empty channel is one NPC entry.  The
+    general encoder must produce exactly that, and CPS has nothing to pack."""
+    C, H, W = shape[:3]
+    act, w = workloads.random_case(31, *shape, zero_frac=0.6, zero_channels=1)
+    ptr, da, ind = [], [], []
+    for c in range(C):
+        if not np.any(act[c] != 0):
+            ptr.append(oracle.NPC)
+            continue
+        ptr.append(0)
+        running = 0
+        for j in range(W):
+            for h in range(H):
+                if act[c, h, j] != 0:
+                    da.append(act[c, h, j]); ind.append(h); running += 1
+            ptr.append(running)
+    for enc in (oracle.cpo_encode(act, shape), oracle.cps_encode(act, shape)):
+        assert enc.ptr.tolist() == ptr
+        assert enc.ind.tolist() == ind
+        assert np.array_equal(enc.da, np.array(da, np.float32))
+    assert np.array_equal(oracle.sparse_conv(oracle.cpo_encode(act, shape), w), oracle.conv_direct(act, w, shape)) or \
+        np.allclose(oracle.sparse_conv(oracle.cpo_encode(act, shape), w), oracle.conv_direct(act, w, shape), rtol=0, atol=1e-5)
