@@ -301,7 +301,9 @@ StripPlan strip_plan(const Geometry &g)
     if (s > cap) s = cap;
     if (s > kMaxSlices) s = kMaxSlices;
     if (s < 1) s = 1;
-    p.slices = s;
+    // no empty slices: with ceil(C / s) channels each, fewer slices may already cover the layer
+    const int per_slice = (g.C + s - 1) / s;
+    p.slices = (g.C + per_slice - 1) / per_slice;
     int batch = kStripTabBytes / (g.n_types * SPAN * 4);
     batch = batch / G * G;
     if (batch < G) batch = G;

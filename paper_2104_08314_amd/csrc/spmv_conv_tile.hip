@@ -354,7 +354,9 @@ TilePlan plan_for(const Geometry &g)
     if (s > cap) s = cap;
     if (s > kMaxSlices) s = kMaxSlices;
     if (s < 1) s = 1;
-    p.slices = s;
+    // no empty slices: with ceil(C / s) channels each, fewer slices may already cover the layer
+    const int per_slice = (g.C + s - 1) / s;
+    p.slices = (g.C + per_slice - 1) / per_slice;
     return p;
 }
 
