@@ -351,12 +351,14 @@ bool strip_kernel_supports(const Geometry &g)
 
 // Measured on MI355X over the workload layers: the strip kernel wins where one channel slice
 // would leave the register-tile kernel few workgroups with long serial channel loops or where
-// its shared patch saves decoding: layers of few channels, 5 x 5 kernels, and wide 3 x 3 stride 1
-// maps with 128 kernels or more.  Elsewhere the register-tile kernel is as fast or faster.
+// its shared patch saves decoding: layers of few channels, 5 x 5 kernels, and wide 3 x 3 maps
+// (stride 1 from 2048 outputs, stride 2 from 784) with 128 kernels or more.  Elsewhere the
+// register-tile kernel is as fast or faster.
 bool strip_kernel_preferred(const Geometry &g)
 {
     if (!strip_kernel_supports(g)) return false;
     if (g.C <= 16 || g.kh == 5) return true;
+    if (g.stride == 2) return g.Oh * g.Ow >= 784 && g.Kpad >= 128;   // 3 x 3 stride 2 from a 56 x 56 map: 46 -> 34 us
     return g.stride == 1 && g.Oh * g.Ow >= 2048 && g.Kpad >= 128;
 }
 
@@ -365,6 +367,7 @@ bool strip_kernel_preferred(const Geometry &g)
 #define CPOCONV_STRIP_DISPATCH(CALL)                                                                     \
     if (g.kh == 3 && g.kw == 3 && g.stride == 1 && g.Kpad % 128 == 0) return CALL(3, 3, 1, 4, 4, 8, 2);  \
     if (g.kh == 3 && g.kw == 3 && g.stride == 1) return CALL(3, 3, 1, 4, 4, 8, 1);                       \
+    if (g.kh == 3 && g.kw == 3 && g.stride == 2 && g.Kpad % 128 == 0) return CALL(3, 3, 2, 4, 4, 8, 2);  \
     if (g.kh == 3 && g.kw == 3 && g.stride == 2) return CALL(3, 3, 2, 4, 4, 8, 1);                       \
     if (g.kh == 5 && g.kw == 5 && g.stride == 1) return CALL(5, 5, 1, 4, 4, 8, 1);                       \
     if (g.kh == 7 && g.kw == 7 && g.stride == 2) return CALL(7, 7, 2, 4, 4, 4, 1);
