@@ -144,6 +144,7 @@ EDGE_SHAPES = [
     (40, 30, 29, 70, 3, 3, 1, 1),     # several channel slices, ragged tiles
     (33, 21, 37, 4, 3, 3, 1, 0),      # VALID padding in the register-tile kernel
     (520, 5, 6, 3, 3, 3, 1, 1),       # more channels than the encoder's single-launch look-back takes
+    (5, 15, 17, 70, 3, 3, 2, 1),      # strip kernel, stride 2, two kernels per lane, ragged
     (3, 17, 17, 70, 7, 1, 1, 0),      # 7 x 1 kernel: the K_w = 1 special case of the SI
     (6, 8, 8, 5, 3, 1, 1, 0),         # 3 x 1
     (3, 17, 17, 4, 1, 7, 1, 0),       # 1 x 7 (K_h = 1): the general algorithm
