@@ -352,14 +352,15 @@ bool strip_kernel_supports(const Geometry &g)
 // Measured on MI355X over the workload layers: the strip kernel wins where one channel slice
 // would leave the register-tile kernel few workgroups with long serial channel loops or where
 // its shared patch saves decoding: layers of few channels, 5 x 5 kernels, and wide 3 x 3 maps
-// (stride 1 from 2048 outputs, stride 2 from 784) with 128 kernels or more.  Elsewhere the
-// register-tile kernel is as fast or faster.
+// (stride 1 from 2048 outputs, or 784 when images are batched; stride 2 from 784 outputs with 128
+// kernels or more).  Elsewhere the register-tile kernel is as fast or faster.
 bool strip_kernel_preferred(const Geometry &g)
 {
     if (!strip_kernel_supports(g)) return false;
     if (g.C <= 16 || g.kh == 5) return true;
     if (g.stride == 2) return g.Oh * g.Ow >= 784 && g.Kpad >= 128;   // 3 x 3 stride 2 from a 56 x 56 map: 46 -> 34 us
-    return g.stride == 1 && g.Oh * g.Ow >= 2048 && g.Kpad >= 128;
+    // stride 1: from 56 x 56 maps on; with several images per launch already from 28 x 28
+    return g.stride == 1 && g.Oh * g.Ow >= (g.N >= 4 ? 784 : 2048);
 }
 
 // 3 x 3 layers whose padded kernel count is a multiple of 128 keep two kernels per lane: the
