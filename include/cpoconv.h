@@ -95,7 +95,8 @@ typedef struct {
     int64_t out_len;       /* K*Oh*Ow                                                      */
     int64_t lowered_bytes; /* im2col scratch: lowered matrix (rows padded to 4 columns) +  */
                            /* split-K partial sums of the matrix product                   */
-    int64_t scratch_bytes; /* scratch for encode and conv calls                            */
+    int64_t scratch_bytes; /* scratch for encode and conv calls (prepare once with          */
+                           /* cpoconv_scratch_init)                                         */
     int32_t Oh, Ow;
 } cpoconv_sizes_t;
 
