@@ -75,6 +75,8 @@ def main():
     ap.add_argument("--stats", help="directory of the --kernel-trace --stats run")
     ap.add_argument("--fetch", help="directory of the --pmc FETCH_SIZE run")
     ap.add_argument("--write", help="directory of the --pmc WRITE_SIZE run")
+    ap.add_argument("--counters", action="append", default=[],
+                    help="directory of a --pmc run with other counters (repeat): per kernel and grid size, the mean of every counter")
     ap.add_argument("--copy-bytes", type=float, help="bytes the calibration kernel reads (= bytes it writes)")
     ap.add_argument("--command", action="append", default=[], help="full command line of a run (repeat)")
     ap.add_argument("--title", default="rocprofv3 summary")
@@ -132,6 +134,24 @@ def main():
         lines.append("")
         for k, b in traffic.items():
             lines.append("traffic_bytes_per_launch[%s]: %.0f" % (k, b))
+        lines.append("")
+    if a.counters:
+        table = defaultdict(lambda: defaultdict(lambda: [0.0, 0]))
+        for directory in a.counters:
+            for path in _find(directory, "counter_collection.csv"):
+                with open(path, newline="") as f:
+                    for r in csv.DictReader(f):
+                        if not any(o in r["Kernel_Name"] for o in OURS):
+                            continue
+                        cell = table["%s grid=%s wg=%s" % (short_name(r["Kernel_Name"]), r["Grid_Size"], r["Workgroup_Size"])][r["Counter_Name"]]
+                        cell[0] += float(r["Counter_Value"])
+                        cell[1] += 1
+        lines.append("hardware counters per launch (mean over launches; SQ_*_CYCLES and SQ_ACTIVE_* / SQ_WAIT_* count in units of 4 cycles)")
+        for kernel in sorted(table):
+            lines.append(kernel)
+            for counter in sorted(table[kernel]):
+                total, n = table[kernel][counter]
+                lines.append("    %-28s %16.0f   (%d launches)" % (counter, total / n, n))
         lines.append("")
     os.makedirs(os.path.dirname(os.path.abspath(a.out)), exist_ok=True)
     with open(a.out, "w") as f:
