@@ -374,6 +374,271 @@ __global__ __launch_bounds__(kThreads) void encode_kernel(const Geometry g, cons
     }
 }
 
+// ---------------------------------------------------------------------------------------------
+// The same encoder for small maps (padded height and width up to 64, the unpadded map within 4 KiB):
+// one WAVEFRONT per channel, eight channels per workgroup.  A 14 x 14 or 7 x 7 map keeps a
+// 512-thread workgroup idle almost everywhere; here every step of a channel is a wavefront-wide
+// operation without workgroup barriers (column bitmaps with lane = column, prefix sums and type
+// bases by lane exchange, scatter with several columns per pass when the map has 32 or 16 rows).
+// Only the look-back is shared: the workgroup publishes its eight channels' lengths, all 512
+// threads read the channels before the group, and each wavefront adds its neighbours' lengths.
+// ---------------------------------------------------------------------------------------------
+constexpr int kSmallTileBytes = 4096;
+// padded maps up to this many elements always take the one-wavefront-per-channel kernel; larger
+// ones from this many channel-images on (four 512-thread workgroups fit a compute unit, 256 units)
+constexpr int kSmallAlways = 18 * 18;
+constexpr int64_t kSmallFromChannels = 1024;
+
+__device__ __forceinline__ void wave_lds_fence()
+{
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+}
+
+template <int kMode>
+__global__ __launch_bounds__(kThreads) void encode_small_kernel(const Geometry g, const float *__restrict__ act_all,
+                                                               const int cps, unsigned long long *__restrict__ ctrl,
+                                                               const cpoconv_map maps, int32_t *__restrict__ mtab_all,
+                                                               const int64_t mtab_stride)
+{
+    extern __shared__ float tiles[];                   // per wavefront: H x Wt floats, then 64 ints of ptr staging
+    __shared__ int32_t grp[kWaves][3];                 // the group's lengths: ptr, DA, IN per channel
+    __shared__ int32_t grp_base[4];                    // lengths of the channels before the group; failures
+
+    const int image = blockIdx.y;
+    const int lane = lane_id(), tid = threadIdx.x;
+    const int wave = __builtin_amdgcn_readfirstlane(wave_id());
+    const int c0 = blockIdx.x * kWaves, c = c0 + wave;
+    const bool live = c < g.C;                         // wavefronts past the last channel only help with the look-back
+    const float *__restrict__ act = act_all + static_cast<int64_t>(image) * g.C * g.H * g.W;
+    const unsigned long long epoch = kMode == kSinglePass ? peek(ctrl + 8 + image) : 0ull;
+    const unsigned long long tag = kMode == kSinglePass ? epoch % 0xFFFFFFFEull + 1ull : kTagTwoLaunches;
+    unsigned long long *flags = ctrl + kCtrlWords +
+                                2 * static_cast<int64_t>(image) * (kMode == kSinglePass ? kSinglePassChannels : g.C);
+    cpoconv_map map = maps;
+    map.ptr += image * maps.ptr_cap;
+    map.da += image * maps.da_cap;
+    map.in += image * maps.in_cap;
+    map.chan_off += static_cast<int64_t>(image) * 3 * (g.C + 1);
+    map.hdr += image * 8;
+
+    const int Wt = g.W | 1;
+    const int per_wave = g.H * Wt + kLanes;            // floats of LDS per wavefront
+    float *tile = tiles + wave * per_wave;
+    int32_t *tblw = reinterpret_cast<int32_t *>(tile + g.H * Wt);
+    const int top_begin = (cps && g.top_slot >= 0) ? g.type_begin[g.top_slot] : kMaxCols + 1;
+    const int top_end = (cps && g.top_slot >= 0) ? g.type_begin[g.top_slot + 1] : 0;
+
+    if (tid < 4) grp_base[tid] = 0;
+    if (kMode != kPublishOnly && tid == 0 && c0 == 0) map.hdr[7] = 0;
+
+    // ---- the channel into LDS (coalesced), then its column bitmaps: lane = column in stream order ----
+    if (live) {
+        const float *chan = act + static_cast<int64_t>(c) * g.H * g.W;
+        for (int i = lane; i < g.H * g.W; i += kLanes) {
+            const int r = i / g.W;
+            tile[r * Wt + (i - r * g.W)] = chan[i];
+        }
+    }
+    wave_lds_fence();
+    const bool col_ok = live && lane < g.n_cols;
+    const int my_jr = col_ok ? static_cast<int>(g.col_j[lane]) - g.pad : 0;
+    const int my_p0 = col_ok ? static_cast<int>(g.col_p0[lane]) : 0;
+    const int next_p0 = (live && lane + 1 < g.n_cols) ? static_cast<int>(g.col_p0[lane + 1]) : -1;
+    unsigned long long colmask = 0;
+    if (col_ok)
+        for (int r = 0; r < g.H; ++r)
+            colmask |= static_cast<unsigned long long>(is_nze(tile[r * Wt + my_jr])) << (r + g.pad);   // bit = padded row
+    const int cnt = __popcll(colmask);
+    const int ecnt = (lane >= top_begin && lane < top_end) ? set4_entries(colmask) : cnt;
+    const int incl = wave_inclusive_sum(cnt), eincl = wave_inclusive_sum(ecnt);
+    const int excl = incl - cnt, eexcl = eincl - ecnt;
+    const int nnz_c = __builtin_amdgcn_readlane(incl, kLanes - 1), in_c = __builtin_amdgcn_readlane(eincl, kLanes - 1);
+    int type_base[kMaxTypes + 1];
+#pragma unroll
+    for (int i = 0; i <= kMaxTypes; ++i) {
+        type_base[i] = nnz_c;
+        if (i <= g.n_types) {
+            const int b = g.type_begin[i];
+            if (b < g.n_cols) type_base[i] = __builtin_amdgcn_readlane(excl, b);
+        }
+    }
+    int ptr_c = 1;  // NPC
+    if (nnz_c > 0) {
+        ptr_c = 0;
+#pragma unroll
+        for (int i = 0; i < kMaxTypes; ++i) {
+            if (i >= g.n_types) continue;
+            if (g.nop3 && g.type_id[i] == 0) ptr_c += 3;
+            else ptr_c += (type_base[i + 1] > type_base[i]) ? 1 + g.Ow : 1;
+        }
+    }
+
+    // ---- look-back, shared by the workgroup -----------------------------------------------------
+    if (lane == 0) {
+        grp[wave][0] = live ? ptr_c : 0;
+        grp[wave][1] = live ? nnz_c : 0;
+        grp[wave][2] = live ? in_c : 0;
+        if (kMode != kPublished && live) {
+            poke(flags + 2 * c, (tag << 32) | static_cast<unsigned>(nnz_c));
+            poke(flags + 2 * c + 1, (tag << 32) | static_cast<unsigned>(in_c) | (static_cast<unsigned>(ptr_c) << 17));
+        }
+    }
+    if (kMode == kPublishOnly) return;
+    __syncthreads();   // grp and grp_base written
+    {
+        int a0 = 0, a1 = 0, a2 = 0, failed = 0;
+        for (int cc = tid; cc < c0; cc += kThreads) {
+            unsigned long long w0, w1;
+            if (kMode == kPublished) {
+                w0 = flags[2 * cc];
+                w1 = flags[2 * cc + 1];
+            } else {
+                w0 = peek(flags + 2 * cc);
+                w1 = peek(flags + 2 * cc + 1);
+                for (int spin = 0; ((w0 >> 32) != tag || (w1 >> 32) != tag) && spin < kSpinLimit; ++spin) {
+                    __builtin_amdgcn_s_sleep(8);
+                    w0 = peek(flags + 2 * cc);
+                    w1 = peek(flags + 2 * cc + 1);
+                }
+            }
+            if ((w0 >> 32) != tag || (w1 >> 32) != tag) { failed = 1; break; }
+            a1 += static_cast<int>(w0 & 0xFFFFFFFFull);
+            a2 += static_cast<int>(w1 & 0x1FFFFull);
+            a0 += static_cast<int>((w1 >> 17) & 0x7FFFull);
+        }
+        a0 = wave_sum(a0); a1 = wave_sum(a1); a2 = wave_sum(a2); failed = wave_sum(failed);
+        if (lane == 0) {
+            atomicAdd(&grp_base[0], a0);
+            atomicAdd(&grp_base[1], a1);
+            atomicAdd(&grp_base[2], a2);
+            atomicAdd(&grp_base[3], failed);
+        }
+    }
+    __syncthreads();
+    const bool failed = grp_base[3] != 0;
+    // the last channel's group has seen every other channel's lengths: the epoch may move on
+    if (kMode == kSinglePass && tid == 0 && c0 + kWaves >= g.C && !failed) poke(ctrl + 8 + image, epoch + 1ull);
+    if (failed) {
+        if (tid == 0) atomicOr(&map.hdr[7], 1);
+        return;
+    }
+    if (!live) return;
+    int ptr_off = grp_base[0], da_off = grp_base[1], in_off = grp_base[2];
+    for (int w = 0; w < wave; ++w) { ptr_off += grp[w][0]; da_off += grp[w][1]; in_off += grp[w][2]; }
+
+    if (lane == 0) {
+        map.chan_off[c] = ptr_off;
+        map.chan_off[(g.C + 1) + c] = da_off;
+        map.chan_off[2 * (g.C + 1) + c] = in_off;
+        if (c == g.C - 1) {
+            map.chan_off[g.C] = ptr_off + ptr_c;
+            map.chan_off[(g.C + 1) + g.C] = da_off + nnz_c;
+            map.chan_off[2 * (g.C + 1) + g.C] = in_off + in_c;
+            map.hdr[0] = ptr_off + ptr_c;
+            map.hdr[1] = da_off + nnz_c;
+            map.hdr[2] = in_off + in_c;
+            map.hdr[3] = cps ? CPOCONV_ALGO_CPS : CPOCONV_ALGO_CPO;
+            map.hdr[4] = g.C;
+            map.hdr[5] = g.Ow;
+            map.hdr[6] = 0;
+        }
+    }
+
+    // ---- the table of absolute DA offsets after every partition, for a convolution of the same call ----
+    if (mtab_all != nullptr) {
+#pragma unroll
+        for (int i = 0; i < kMaxTypes; ++i) {
+            if (i >= g.n_types) continue;
+            int32_t *row = mtab_all + image * mtab_stride + (static_cast<int64_t>(c) * g.n_types + i) * (g.Ow + 1);
+            const int cb = g.type_begin[i], ce = g.type_begin[i + 1];
+            const int at = da_off + type_base[i];
+            const int p_first = cb < ce ? static_cast<int>(g.col_p0[cb]) : g.Ow;
+            for (int k = lane; k <= p_first; k += kLanes) row[k] = at;
+            if (lane >= cb && lane < ce) {
+                const int p_end = lane + 1 < ce ? next_p0 : g.Ow;
+                const int upto = da_off + incl;
+                for (int pp = my_p0; pp < p_end; ++pp) row[1 + pp] = upto;
+            }
+        }
+    }
+
+    // ---- ptr ----------------------------------------------------------------------------------------
+    if (nnz_c == 0) {
+        if (lane == 0) map.ptr[ptr_off] = CPOCONV_NPC;
+        return;
+    }
+    {
+        int seg = ptr_off;
+#pragma unroll
+        for (int i = 0; i < kMaxTypes; ++i) {
+            if (i >= g.n_types) continue;
+            const int cb = g.type_begin[i], ce = g.type_begin[i + 1];
+            const int base = type_base[i];
+            if (g.nop3 && g.type_id[i] == 0) {
+                // [0, NZEs of the first column, NZEs of first + last column]
+                const int n1 = __builtin_amdgcn_readlane(incl, min(cb, kLanes - 1)) - base;
+                const int n2 = __builtin_amdgcn_readlane(incl, min(max(ce - 1, cb), kLanes - 1)) - base;
+                if (lane == 0) { map.ptr[seg] = 0; map.ptr[seg + 1] = n1; map.ptr[seg + 2] = n2; }
+                seg += 3;
+                continue;
+            }
+            if (type_base[i + 1] == base) {
+                if (lane == 0) map.ptr[seg] = CPOCONV_NPF;
+                seg += 1;
+                continue;
+            }
+            tblw[lane] = -1;
+            wave_lds_fence();
+            // cumulative count after the last column first seen in each partition
+            if (lane >= cb && lane < ce && (lane + 1 == ce || next_p0 != my_p0)) tblw[my_p0] = incl - base;
+            wave_lds_fence();
+            if (lane == 0) map.ptr[seg] = g.type_id[i];
+            if (lane < g.Ow) map.ptr[seg + 1 + lane] = tblw[lane];
+            wave_lds_fence();
+            seg += 1 + g.Ow;
+        }
+    }
+
+    // ---- scatter DA and IN: lane = (column of the pass, padded row); 1, 2 or 4 columns per pass -----
+    const int rows_pass = g.Ih <= 16 ? 16 : (g.Ih <= 32 ? 32 : 64);
+    const int cols_pass = kLanes / rows_pass;
+    const int sub = lane / rows_pass, h = lane - sub * rows_pass;     // h: padded row
+    const unsigned long long sub_bits = rows_pass == 64 ? ~0ull : ((1ull << rows_pass) - 1ull);
+    const unsigned long long below = (1ull << h) - 1ull;
+    const int hr = h - g.pad;
+    const bool row_ok = hr >= 0 && hr < g.H;
+    for (int v0 = 0; v0 < g.n_cols; v0 += cols_pass) {
+        const int vi = v0 + sub;
+        const bool on = vi < g.n_cols;
+        const int src = on ? vi : 0;
+        const int jr = __shfl(my_jr, src, kLanes);
+        const int at_da = da_off + __shfl(excl, src, kLanes), at_in = in_off + __shfl(eexcl, src, kLanes);
+        const int what = on ? static_cast<int>(g.col_what[vi]) : 0;
+        const float v = (on && row_ok) ? tile[hr * Wt + jr] : 0.0f;
+        const bool nz = is_nze(v);
+        const unsigned long long all = __ballot(nz);
+        const unsigned long long mask = (all >> (sub * rows_pass)) & sub_bits;
+        const int rank = __popcll(mask & below);
+        const int index = what + h * g.kw;
+        if (nz) map.da[at_da + rank] = v;
+        const bool packed = on && vi >= top_begin && vi < top_end;
+        // set4 of Algorithm 3: the four padded rows 4*(h/4) .. +3
+        const int pattern = static_cast<int>((mask >> (h & ~3)) & 0xFull);
+        const int r = __popc(pattern & ((1 << (h & 3)) - 1));   // rank inside the set
+        const bool emit = packed && nz && r < 2;
+        const unsigned long long emits = (__ballot(emit) >> (sub * rows_pass)) & sub_bits;
+        const int erank = __popcll(emits & below);
+        const int entry = __popc(pattern) >= 3 ? (r == 0 ? index : pattern) : -index;
+        if (packed) {
+            if (emit) map.in[at_in + erank] = entry;
+        } else if (nz) {
+            map.in[at_in + rank] = index;
+        }
+    }
+}
+
 // zero fill of a scratch buffer (a kernel rather than a memset node, so that a caller may capture
 // the call in a graph)
 __global__ __launch_bounds__(256) void zero_fill_kernel(uint32_t *__restrict__ words, const int64_t n_words,
@@ -412,6 +677,32 @@ int launch_encode(const float *act, const Geometry &g, const cpoconv_map &map, i
     const int chunk = kLanes * row_bytes <= kTileBytesMax ? kLanes : kChunkWide;   // 32 rows always fit: W <= 256
     const size_t lds = chunk * row_bytes;
     unsigned long long *ctrl = static_cast<unsigned long long *>(scratch);
+    const size_t small_tile = static_cast<size_t>(g.H) * (g.W | 1) * sizeof(float);
+    // A wavefront walks its channel's rows alone, which costs latency on the larger of the small maps:
+    // those take the path only once workgroups of the other kernel would queue for a compute unit.
+    const bool worth = g.Ih * g.Iw <= kSmallAlways || static_cast<int64_t>(g.N) * g.C >= kSmallFromChannels;
+    if (g.Ih <= kLanes && g.Iw <= kLanes && small_tile <= kSmallTileBytes && worth) {
+        // small maps: one wavefront per channel
+        const size_t lds_small = kWaves * (small_tile + kLanes * sizeof(float));
+        const dim3 grid((g.C + kWaves - 1) / kWaves, g.N);
+        if (g.C <= kSinglePassChannels) {
+            KernelTimer timer("encode", stream);
+            hipLaunchKernelGGL(encode_small_kernel<kSinglePass>, grid, dim3(kThreads), lds_small, stream, g, act, cps, ctrl,
+                               map, mtab, mstride);
+        } else {
+            {
+                KernelTimer timer("encode_count", stream);
+                hipLaunchKernelGGL(encode_small_kernel<kPublishOnly>, grid, dim3(kThreads), lds_small, stream, g, act, cps,
+                                   ctrl, map, static_cast<int32_t *>(nullptr), mstride);
+            }
+            CPOCONV_HIP_TRY(hipGetLastError());
+            KernelTimer timer("encode", stream);
+            hipLaunchKernelGGL(encode_small_kernel<kPublished>, grid, dim3(kThreads), lds_small, stream, g, act, cps, ctrl,
+                               map, mtab, mstride);
+        }
+        CPOCONV_HIP_TRY(hipGetLastError());
+        return CPOCONV_OK;
+    }
     if (g.C <= kSinglePassChannels) {
         KernelTimer timer("encode", stream);
         hipLaunchKernelGGL(encode_kernel<kSinglePass>, dim3(g.C, g.N), dim3(kThreads), lds, stream, g, act, cps, chunk, ctrl, map,

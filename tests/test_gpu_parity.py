@@ -283,6 +283,10 @@ BATCH_CASES = [
     (5, (33, 21, 37, 4, 3, 3, 1, 0)),
     (40, (4, 8, 8, 5, 3, 3, 1, 1)),               # enough images that no layer is sliced over channels
     (2, (3, 70, 33, 4, 3, 3, 1, 1)),
+    # mid-sized maps with >= 1024 channel-images: the one-wavefront-per-channel encoder, in one
+    # launch and (more than 512 channels) in two
+    (3, (400, 20, 22, 3, 3, 3, 1, 1)),
+    (2, (600, 19, 37, 2, 3, 3, 1, 0)),
 ]
 
 
@@ -345,7 +349,7 @@ def test_batched_calls(api, case):
 
 def test_batched_workload_layers(api):
     """Two workload layers at full size with eight images each, sampled against the oracle."""
-    for name, n_images in (("cfg3.256@14", 8), ("cfg5.l05.128@28s1", 4)):
+    for name, n_images in (("cfg3.256@14", 8), ("cfg5.l05.128@28s1", 8)):
         spec = {s.name: s for s in workloads.all_layers()}[name]
         shape = spec.shape_tuple
         _say(f"[case] batched {name} n={n_images}")
