@@ -202,3 +202,37 @@ def select_layer_algo(t_im2col, t_cpo, t_cps, mode: int) -> int:
     c = np.ascontiguousarray(t_cps, dtype=np.float64)
     assert a.size == b.size == c.size
     return int(_load().orc_select(_p(a), _p(b), _p(c), int(a.size), int(mode)))
+
+
+def bias_relu(pre: np.ndarray, bias=None) -> np.ndarray:
+    """What a layer's input is when the layer before it ends in a bias and a ReLU: the input I of
+    Eq. 1 is the output max(0, z) of the activation function (Section "Sparsity and Patterns
+    Motivation").  z = pre + bias[c] is one fp32 addition; every z that is not greater than zero
+    (negative values, both zeros, NaN) becomes +0, so the zeros of the result are exactly the
+    elements the encoders skip."""
+    z = np.asarray(pre, dtype=np.float32)
+    if bias is not None:
+        b = np.asarray(bias, dtype=np.float32)
+        assert b.shape == (z.shape[0],)
+        z = z + b[:, None, None]
+        assert z.dtype == np.float32
+    with np.errstate(invalid="ignore"):
+        return np.where(z > 0, z, np.float32(0.0)).astype(np.float32)
+
+
+def chain_forward(act: np.ndarray, chain) -> list:
+    """Convolution layers run one after the other (Section "Hybrid Inference Over a Target CNN":
+    the conv layers of a CNN, each with the method chosen for it - all methods compute Eq. 1, so
+    the oracle is Eq. 1 per layer).  ``chain`` is a sequence of (shape, weights, bias_in, relu_in):
+    a layer's input is the previous layer's stored fp32 output, passed through ``bias_relu`` with
+    ``bias_in`` when ``relu_in`` is set.  Returns every layer's K x Oh x Ow output."""
+    outs = []
+    x = np.ascontiguousarray(act, dtype=np.float32)
+    for shape, weights, bias_in, relu_in in chain:
+        if relu_in:
+            x = bias_relu(x, bias_in)
+        else:
+            assert bias_in is None
+        x = conv_direct(x, weights, shape)
+        outs.append(x)
+    return outs

@@ -105,3 +105,81 @@ def test_select_layer_algo_rules():
     assert oracle.select_layer_algo(t_im, t_cps, t_cpo, 1) == 2
     assert oracle.select_layer_algo([5.0, 5.0], [4.0, 6.0], [6.0, 4.0], 0) == 0
     assert oracle.select_layer_algo([5.0, 5.0], [4.0, 6.0], [6.0, 4.0], 1) == 0
+
+
+# --- the producer epilogue (bias, ReLU) and chained layers --------------------------------------
+def test_bias_relu_special_values():
+    """Value table: only z > 0 survives; -0, negatives and NaN become +0; denormals and inf stay."""
+    tiny = np.float32(1e-45)                      # smallest denormal
+    pre = np.array([[[-1.5, -0.0, 0.0, 2.5, np.nan, np.inf, -np.inf, tiny, -tiny]]], np.float32)
+    got = oracle.bias_relu(pre)
+    want = np.array([[[0.0, 0.0, 0.0, 2.5, 0.0, np.inf, 0.0, tiny, 0.0]]], np.float32)
+    assert got.dtype == np.float32
+    assert np.array_equal(got.view(np.uint32), want.view(np.uint32))   # bit for bit: zeros are +0
+
+
+def test_bias_relu_adds_the_channel_bias_in_fp32_before_the_threshold():
+    pre = np.array([[[1.0, -1.0]], [[1.0, -1.0]], [[16777216.0, 0.25]]], np.float32)
+    bias = np.array([-1.0, 2.0, 1.0], np.float32)
+    got = oracle.bias_relu(pre, bias)
+    # channel 0: 1-1 = 0 -> 0, -2 -> 0;  channel 1: 3, 1;  channel 2: 2^24 + 1 rounds to 2^24 (one fp32 addition)
+    want = np.array([[[0.0, 0.0]], [[3.0, 1.0]], [[16777216.0, 1.25]]], np.float32)
+    assert np.array_equal(got, want)
+
+
+def test_bias_relu_matches_library_relu():
+    rng = np.random.default_rng(11)
+    pre = rng.standard_normal((5, 9, 7)).astype(np.float32)
+    bias = rng.standard_normal(5).astype(np.float32)
+    lib = torch.relu(torch.from_numpy(pre) + torch.from_numpy(bias)[:, None, None]).numpy()
+    assert np.array_equal(oracle.bias_relu(pre, bias), lib)
+    assert np.array_equal(oracle.bias_relu(np.abs(pre)), np.abs(pre))      # identity on positive maps
+
+
+def test_encoding_of_a_relu_output_holds_exactly_the_positive_elements():
+    rng = np.random.default_rng(12)
+    shape = (4, 9, 10, 3, 3, 3, 1, 1)
+    pre = rng.standard_normal(shape[:3]).astype(np.float32)
+    m = oracle.cpo_encode(oracle.bias_relu(pre), shape)
+    assert m.da.size == int((pre > 0).sum())
+    assert np.array_equal(oracle.decode(m), np.maximum(pre, 0))
+
+
+def _chain_case(seed):
+    rng = np.random.default_rng(seed)
+    shapes = [(3, 11, 12, 5, 3, 3, 1, 1), (5, 11, 12, 4, 3, 3, 2, 1), (4, 6, 6, 6, 5, 5, 1, 2)]
+    chain = []
+    for i, s in enumerate(shapes):
+        w = (rng.standard_normal((s[3], s[0], s[4], s[5])) * 0.3).astype(np.float32)
+        b = None if i == 0 else rng.standard_normal(s[0]).astype(np.float32) * 0.2
+        chain.append((s, w, b, i > 0))
+    act = np.maximum(rng.standard_normal(shapes[0][:3]), 0).astype(np.float32)
+    return act, chain
+
+
+def test_chain_forward_matches_library_network():
+    act, chain = _chain_case(21)
+    outs = oracle.chain_forward(act, chain)
+    x = torch.from_numpy(act).double()[None]
+    for (s, w, b, relu_in), got in zip(chain, outs):
+        if relu_in:
+            x = torch.relu(x + torch.from_numpy(b).double()[None, :, None, None])
+        x = torch.nn.functional.conv2d(x, torch.from_numpy(w).double(), stride=s[6], padding=s[7])
+        assert got.shape == tuple(x.shape[1:])
+        assert np.abs(got - x[0].numpy()).max() <= 1e-5 * float(x.abs().max())
+
+
+def test_chain_of_identity_kernels_is_repeated_relu():
+    """1x1 identity kernels: every layer's output is its (activated) input, so the chain's outputs
+    are pre, relu(pre + b1), relu(relu(pre + b1) + b2)."""
+    rng = np.random.default_rng(22)
+    C = 4
+    pre = rng.standard_normal((C, 6, 5)).astype(np.float32)
+    eye = np.eye(C, dtype=np.float32).reshape(C, C, 1, 1)
+    b1, b2 = rng.standard_normal(C).astype(np.float32), rng.standard_normal(C).astype(np.float32)
+    s = (C, 6, 5, C, 1, 1, 1, 0)
+    outs = oracle.chain_forward(pre, [(s, eye, None, False), (s, eye, b1, True), (s, eye, b2, True)])
+    r1 = np.maximum(pre + b1[:, None, None], 0)
+    assert np.array_equal(outs[0], pre)
+    assert np.array_equal(outs[1], r1)
+    assert np.array_equal(outs[2], np.maximum(r1 + b2[:, None, None], 0))
