@@ -218,6 +218,60 @@ int cps_encode_conv_batch(const float *act, const cpoconv_shape *shape, int n_im
                           const float *wt, float *out, void *scratch, int64_t scratch_bytes, void *stream);
 
 /*
+ * A layer's input taken from the layer before it without storing the activated map.  The input I
+ * of Eq. 1 is the output max(0, z) of a ReLU (Section 3.1); here `pre` holds z before the bias
+ * (N x C x H x W, e.g. the `out` of the previous convolution) and every kernel that reads the
+ * map applies, element by element, z = pre + bias[c] (one fp32 addition; none when bias is NULL)
+ * and then takes z if z > 0, else +0 (negative values, both zeros and NaN give +0).  The streams
+ * are bit for bit those of cpo_encode / cps_encode on that activated map, the convolution that of
+ * im2col_conv on it.  bias: device, C floats, or NULL.  n_images, maps, scratch, lowered: as the
+ * batched calls (n_images = 1 for one map).  Errors as the calls they extend.
+ */
+int cpo_encode_relu(const float *pre, const float *bias, const cpoconv_shape *shape, int n_images,
+                    const cpoconv_map *maps, void *scratch, int64_t scratch_bytes, void *stream);
+int cps_encode_relu(const float *pre, const float *bias, const cpoconv_shape *shape, int n_images,
+                    const cpoconv_map *maps, void *scratch, int64_t scratch_bytes, void *stream);
+int im2col_conv_relu(const float *pre, const float *bias, const cpoconv_shape *shape, int n_images,
+                     const float *weights, void *lowered, float *out, int precision, void *stream);
+
+/*
+ * The conv layers of a network run one after the other, each with the method the offline
+ * selection chose for it (Section 3.5: at inference time the selected method is used at the
+ * layer).  Layer i reads layers[i-1].out (layer 0 reads `act`), which must have its input shape:
+ * C = previous K, H x W = previous Oh x Ow.  With relu_in = 1 the input is max(0, that + bias_in)
+ * applied on the way in, as in the *_relu calls (bias_in may be NULL); with relu_in = 0 it is
+ * taken as stored and bias_in must be NULL.  method: CPOCONV_ALGO_CPO / _CPS (weights = the
+ * prepared layout of cpoconv_prepare_weights; the layer runs as cpo_/cps_encode_conv_batch) or
+ * CPOCONV_ALGO_IM2COL (weights K x C x kh x kw; precision 0 fp32, 1 bf16).  out: device,
+ * n_images x K x Oh x Ow, written by the layer and read by the next one; it holds the sums before
+ * any bias or ReLU.  One map, scratch and lowered buffer serve all layers in turn: sizes from
+ * cpoconv_chain_sizes (the largest any layer needs; *maps is image 0's struct, capacities =
+ * strides between images as in the batched calls); maps / scratch may be NULL if no layer uses
+ * CPO or CPS, lowered if none uses im2col.  After the call the map holds the encoding of the last
+ * CPO / CPS layer.  All arguments are checked before the first launch.
+ * Errors: NULL, SHAPE (also layers that do not fit each other, n_layers outside 1..CPOCONV_MAX_CHAIN),
+ * ALGO (method, precision, relu_in, bias without ReLU), SMALL, HIP.
+ */
+#define CPOCONV_MAX_CHAIN 1024
+typedef struct {
+    cpoconv_shape shape;
+    int32_t method;
+    int32_t precision;
+    int32_t relu_in;
+    const float *bias_in;
+    const float *weights;
+    float *out;
+} cpoconv_chain_layer;
+
+/* Host only.  ptr_cap .. chan_off_len, wt_len, out_len, lowered_bytes, scratch_bytes: the largest
+ * over the layers (per image where cpoconv_batch_sizes is per image); Oh, Ow: of the last layer.
+ * Pointer members of the layers are not read. */
+int cpoconv_chain_sizes(const cpoconv_chain_layer *layers, int n_layers, int n_images, cpoconv_sizes_t *sizes);
+int cpoconv_chain_forward(const float *act, const cpoconv_chain_layer *layers, int n_layers, int n_images,
+                          const cpoconv_map *maps, void *scratch, int64_t scratch_bytes, void *lowered,
+                          int64_t lowered_bytes, void *stream);
+
+/*
  * Offline per-layer selection (Section 3.5).  Host only.  t_*: times of the three methods on
  * the same m_inputs offline inputs, any common unit.  mode 0 "favour time": the smaller total
  * of im2col and CPO; mode 1 "favour space": the smaller total of im2col and CPS; im2col keeps

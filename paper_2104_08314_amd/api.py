@@ -77,6 +77,7 @@ EXPORTS = (
     "cpoconv_strerror", "cpoconv_last_hip_error", "cpoconv_kernel_timing", "cpoconv_kernel_timing_read",
     "cpoconv_scratch_init", "cpoconv_batch_sizes", "cpo_encode_batch", "cps_encode_batch", "cpo_conv_batch", "cps_conv_batch",
     "im2col_conv_batch", "cpo_encode_conv", "cps_encode_conv", "cpo_encode_conv_batch", "cps_encode_conv_batch",
+    "cpo_encode_relu", "cps_encode_relu", "im2col_conv_relu", "cpoconv_chain_sizes", "cpoconv_chain_forward",
 )
 
 
@@ -179,12 +180,12 @@ class EncodedMap:
     """Device buffers of one encoded activation map (cpoconv_map of the C ABI), or of a batch of
     n_images maps: then every buffer holds n_images regions of the per-image capacity."""
 
-    def __init__(self, shape, device="cuda:0", n_images=1):
+    def __init__(self, shape, device="cuda:0", n_images=1, sizes=None):
         import torch
 
         self.shape = make_shape(shape)
         self.n_images = int(n_images)
-        sz = cpoconv_sizes(self.shape)
+        sz = cpoconv_sizes(self.shape) if sizes is None else sizes   # sizes: capacities larger than the shape's own
         self.sizes = sz
         n = self.n_images
         self.ptr = torch.empty(n * sz.ptr_cap, dtype=torch.int32, device=device)
@@ -199,8 +200,17 @@ class EncodedMap:
         return _Map(ctypes.c_void_p(self.ptr.data_ptr() + 4 * image * sz.ptr_cap), sz.ptr_cap,
                     ctypes.c_void_p(self.da.data_ptr() + 4 * image * sz.da_cap), sz.da_cap,
                     ctypes.c_void_p(self.ind.data_ptr() + 4 * image * sz.in_cap), sz.in_cap,
-                    ctypes.c_void_p(self.chan_off.data_ptr() + 4 * image * sz.chan_off_len),
+                    ctypes.c_void_p(self.chan_off.data_ptr() + 4 * image * 3 * (self.shape.C + 1)),
                     ctypes.c_void_p(self.hdr.data_ptr() + 4 * image * 8))
+
+    def view(self, shape) -> "EncodedMap":
+        """The same buffers seen as the map of another layer shape (a chain's layers share one map;
+        the side band's stride between images follows the layer's channel count)."""
+        import copy
+
+        other = copy.copy(self)
+        other.shape = make_shape(shape)
+        return other
 
     def header(self, stream=None, image=0):
         return cpoconv_map_header_to_host(self, stream, image)
@@ -209,10 +219,10 @@ class EncodedMap:
         """(ptr, da, ind, chan_off[3, C+1], hdr) of one image as numpy arrays trimmed to their lengths."""
         hdr = self.header(stream, image)
         C, sz = self.shape.C, self.sizes
-        p0, d0, i0, c0 = image * sz.ptr_cap, image * sz.da_cap, image * sz.in_cap, image * sz.chan_off_len
+        p0, d0, i0, c0 = image * sz.ptr_cap, image * sz.da_cap, image * sz.in_cap, image * 3 * (C + 1)
         return (self.ptr[p0:p0 + hdr[0]].cpu().numpy(), self.da[d0:d0 + hdr[1]].cpu().numpy(),
                 self.ind[i0:i0 + hdr[2]].cpu().numpy(),
-                self.chan_off[c0:c0 + sz.chan_off_len].cpu().numpy().reshape(3, C + 1), hdr)
+                self.chan_off[c0:c0 + 3 * (C + 1)].cpu().numpy().reshape(3, C + 1), hdr)
 
 
 def _encode(fn_name: str, act, shape, m: EncodedMap, scratch, stream) -> None:
@@ -378,3 +388,106 @@ def cpo_encode_conv(act, shape, m: EncodedMap, wt, out, scratch, stream=None) ->
 
 def cps_encode_conv(act, shape, m: EncodedMap, wt, out, scratch, stream=None) -> None:
     _encode_conv("cps_encode_conv" if m.n_images == 1 else "cps_encode_conv_batch", act, shape, m, wt, out, scratch, stream)
+
+
+# ---- a layer's input produced on the way in (bias and ReLU of the layer before it) --------------
+
+def _encode_relu(fn_name: str, pre, bias, shape, m: EncodedMap, scratch, stream) -> None:
+    import torch
+
+    sh = make_shape(shape)
+    cm = m.c_struct()
+    _check(getattr(lib(), fn_name)(_dev_ptr(pre, torch.float32), _dev_ptr(bias, torch.float32), ctypes.byref(sh),
+                                   int(m.n_images), ctypes.byref(cm), _dev_ptr(scratch),
+                                   ctypes.c_int64(scratch.numel() * scratch.element_size()), _stream_handle(stream)))
+
+
+def cpo_encode_relu(pre, bias, shape, m: EncodedMap, scratch, stream=None) -> None:
+    _encode_relu("cpo_encode_relu", pre, bias, shape, m, scratch, stream)
+
+
+def cps_encode_relu(pre, bias, shape, m: EncodedMap, scratch, stream=None) -> None:
+    _encode_relu("cps_encode_relu", pre, bias, shape, m, scratch, stream)
+
+
+def im2col_conv_relu(pre, bias, shape, n_images: int, weights, lowered, out, precision: int = 0, stream=None) -> None:
+    import torch
+
+    sh = make_shape(shape)
+    _check(lib().im2col_conv_relu(_dev_ptr(pre, torch.float32), _dev_ptr(bias, torch.float32), ctypes.byref(sh),
+                                  int(n_images), _dev_ptr(weights, torch.float32), _dev_ptr(lowered),
+                                  _dev_ptr(out, torch.float32), int(precision), _stream_handle(stream)))
+
+
+# ---- chained layers ------------------------------------------------------------------------------
+
+class ChainLayer(ctypes.Structure):
+    _fields_ = [("shape", Shape), ("method", ctypes.c_int32), ("precision", ctypes.c_int32),
+                ("relu_in", ctypes.c_int32), ("bias_in", ctypes.c_void_p), ("weights", ctypes.c_void_p),
+                ("out", ctypes.c_void_p)]
+
+
+def cpoconv_chain_sizes(layers, n_images: int) -> Sizes:
+    """layers: a ctypes array of ChainLayer (pointer members are not read)."""
+    sz = Sizes()
+    _check(lib().cpoconv_chain_sizes(layers, len(layers), int(n_images), ctypes.byref(sz)))
+    return sz
+
+
+class Chain:
+    """Device buffers and the layer table of cpoconv_chain_forward.  weights: K x C x kh x kw device
+    tensors; biases[i] (device tensor or None) and relu_in[i] describe what is applied to layer i's
+    input; methods[i] is ALGO_IM2COL / ALGO_CPO / ALGO_CPS (set_methods changes them later)."""
+
+    def __init__(self, shapes, weights, biases, relu_in, methods, n_images=1, precision=0, device="cuda:0"):
+        import torch
+
+        self.shapes = [make_shape(s) for s in shapes]
+        self.n_images = int(n_images)
+        self.weights, self.biases, self.relu_in = list(weights), list(biases), [int(bool(r)) for r in relu_in]
+        self.precision = int(precision)
+        self.device = device
+        n = len(self.shapes)
+        self.table = (ChainLayer * n)()
+        self.outs, self.prepared = [], [None] * n
+        for i, sh in enumerate(self.shapes):
+            sz = cpoconv_batch_sizes(sh, self.n_images)
+            self.outs.append(torch.empty((self.n_images, sh.K, sz.Oh, sz.Ow), dtype=torch.float32, device=device))
+            self.table[i].shape = sh
+            self.table[i].precision = self.precision
+            self.table[i].relu_in = self.relu_in[i]
+            self.table[i].bias_in = _dev_ptr(self.biases[i], torch.float32).value
+            self.table[i].out = self.outs[i].data_ptr()
+        sz = cpoconv_chain_sizes(self.table, self.n_images)
+        self.sizes = sz
+        self.map = EncodedMap(self.shapes[0], device, self.n_images, sizes=sz)
+        self.scratch = torch.empty(sz.scratch_bytes, dtype=torch.uint8, device=device)
+        cpoconv_scratch_init(self.scratch)
+        self.lowered = torch.empty(sz.lowered_bytes, dtype=torch.uint8, device=device)
+        self.set_methods(methods)
+
+    def set_methods(self, methods) -> None:
+        import torch
+
+        assert len(methods) == len(self.shapes)
+        self.methods = [int(m) for m in methods]
+        for i, (m, sh) in enumerate(zip(self.methods, self.shapes)):
+            self.table[i].method = m
+            if m == ALGO_IM2COL:
+                self.table[i].weights = _dev_ptr(self.weights[i], torch.float32).value
+            else:
+                if self.prepared[i] is None:
+                    wt = torch.empty(cpoconv_sizes(sh).wt_len, dtype=torch.float32, device=self.device)
+                    cpoconv_prepare_weights(self.weights[i], sh, wt)
+                    self.prepared[i] = wt
+                self.table[i].weights = self.prepared[i].data_ptr()
+
+    def forward(self, act, stream=None) -> None:
+        """Runs every layer; layer i's output (before bias / ReLU) lands in outs[i]."""
+        import torch
+
+        cm = self.map.c_struct()
+        _check(lib().cpoconv_chain_forward(_dev_ptr(act, torch.float32), self.table, len(self.shapes), self.n_images,
+                                           ctypes.byref(cm), _dev_ptr(self.scratch),
+                                           ctypes.c_int64(self.scratch.numel()), _dev_ptr(self.lowered),
+                                           ctypes.c_int64(self.lowered.numel()), _stream_handle(stream)))

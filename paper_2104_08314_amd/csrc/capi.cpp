@@ -207,8 +207,10 @@ int cpoconv_batch_sizes(const cpoconv_shape *shape, int n_images, cpoconv_sizes_
     return CPOCONV_OK;
 }
 
+static const Producer kAsStored = {nullptr, 0};
+
 static int encode_common(const float *act, const cpoconv_shape *shape, int n_images, const cpoconv_map *map,
-                         void *scratch, int64_t scratch_bytes, void *stream, int algo)
+                         void *scratch, int64_t scratch_bytes, void *stream, int algo, const Producer &prod = kAsStored)
 {
     if (!act || !shape || !map || !scratch) return CPOCONV_ERR_NULL;
     if (!map->ptr || !map->da || !map->in || !map->chan_off || !map->hdr) return CPOCONV_ERR_NULL;
@@ -219,7 +221,7 @@ static int encode_common(const float *act, const cpoconv_shape *shape, int n_ima
     if (map->ptr_cap < max_ptr_len(g) || map->da_cap < chw || map->in_cap < chw)
         return CPOCONV_ERR_SMALL;
     if (scratch_bytes < scratch_bytes_for(g)) return CPOCONV_ERR_SMALL;
-    return launch_encode(act, g, *map, algo, scratch, static_cast<hipStream_t>(stream));
+    return launch_encode(act, prod, g, *map, algo, scratch, static_cast<hipStream_t>(stream));
 }
 
 int cpoconv_scratch_init(void *scratch, int64_t bytes, void *stream)
@@ -279,7 +281,8 @@ int cps_conv(const cpoconv_map *map, const cpoconv_shape *shape, const float *wt
 }
 
 static int encode_conv_common(const float *act, const cpoconv_shape *shape, int n_images, const cpoconv_map *map,
-                              const float *wt, float *out, void *scratch, int64_t scratch_bytes, void *stream, int algo)
+                              const float *wt, float *out, void *scratch, int64_t scratch_bytes, void *stream, int algo,
+                              const Producer &prod = kAsStored)
 {
     if (!act || !shape || !map || !wt || !out || !scratch) return CPOCONV_ERR_NULL;
     if (!map->ptr || !map->da || !map->in || !map->chan_off || !map->hdr) return CPOCONV_ERR_NULL;
@@ -293,7 +296,7 @@ static int encode_conv_common(const float *act, const cpoconv_shape *shape, int 
     // the encoder also leaves the table of resolved ptr offsets: the convolution needs no prologue
     // of its own for a CPO map (a CPS map still has its indices rebuilt by one)
     const bool table = (algo == CPOCONV_ALGO_CPO || g.top_slot < 0) && sparse_conv_uses_prologue(g);
-    const int erc = launch_encode(act, g, *map, algo, scratch, st, table);
+    const int erc = launch_encode(act, prod, g, *map, algo, scratch, st, table);
     if (erc != CPOCONV_OK) return erc;
     return launch_sparse_conv(*map, g, algo, wt, out, scratch, st, table);
 }
@@ -352,8 +355,8 @@ int im2col_conv(const float *act, const cpoconv_shape *shape, const float *weigh
     return im2col_conv_batch(act, shape, 1, weights, lowered, out, precision, stream);
 }
 
-int im2col_conv_batch(const float *act, const cpoconv_shape *shape, int n_images, const float *weights,
-                      void *lowered, float *out, int precision, void *stream)
+static int im2col_common(const float *act, const cpoconv_shape *shape, int n_images, const float *weights,
+                         void *lowered, float *out, int precision, void *stream, const Producer &prod)
 {
     if (!act || !shape || !weights || !lowered || !out) return CPOCONV_ERR_NULL;
     Geometry g;
@@ -361,8 +364,120 @@ int im2col_conv_batch(const float *act, const cpoconv_shape *shape, int n_images
     if (rc != CPOCONV_OK) return rc;
     if (precision != 0 && precision != 1) return CPOCONV_ERR_ALGO;
     if (reinterpret_cast<uintptr_t>(lowered) % 16 != 0) return CPOCONV_ERR_SHAPE;   // vector accesses
-    return launch_im2col_conv(act, g, weights, lowered, out, precision,
+    return launch_im2col_conv(act, prod, g, weights, lowered, out, precision,
                               static_cast<hipStream_t>(stream));
+}
+
+int im2col_conv_batch(const float *act, const cpoconv_shape *shape, int n_images, const float *weights,
+                      void *lowered, float *out, int precision, void *stream)
+{
+    return im2col_common(act, shape, n_images, weights, lowered, out, precision, stream, kAsStored);
+}
+
+// ---- a layer's input produced on the way in: bias and ReLU of the layer before it ----------------
+int cpo_encode_relu(const float *pre, const float *bias, const cpoconv_shape *shape, int n_images,
+                    const cpoconv_map *maps, void *scratch, int64_t scratch_bytes, void *stream)
+{
+    return encode_common(pre, shape, n_images, maps, scratch, scratch_bytes, stream, CPOCONV_ALGO_CPO, Producer{bias, 1});
+}
+
+int cps_encode_relu(const float *pre, const float *bias, const cpoconv_shape *shape, int n_images,
+                    const cpoconv_map *maps, void *scratch, int64_t scratch_bytes, void *stream)
+{
+    return encode_common(pre, shape, n_images, maps, scratch, scratch_bytes, stream, CPOCONV_ALGO_CPS, Producer{bias, 1});
+}
+
+int im2col_conv_relu(const float *pre, const float *bias, const cpoconv_shape *shape, int n_images,
+                     const float *weights, void *lowered, float *out, int precision, void *stream)
+{
+    return im2col_common(pre, shape, n_images, weights, lowered, out, precision, stream, Producer{bias, 1});
+}
+
+// ---- chained layers -------------------------------------------------------------------------------
+static int chain_check(const cpoconv_chain_layer *layers, int n_layers, int n_images)
+{
+    if (!layers) return CPOCONV_ERR_NULL;
+    if (n_layers < 1 || n_layers > CPOCONV_MAX_CHAIN) return CPOCONV_ERR_SHAPE;
+    Geometry g, prev;
+    for (int i = 0; i < n_layers; ++i) {
+        const cpoconv_chain_layer &l = layers[i];
+        const int rc = batch_geometry(&l.shape, n_images, &g);
+        if (rc != CPOCONV_OK) return rc;
+        if (l.method != CPOCONV_ALGO_IM2COL && l.method != CPOCONV_ALGO_CPO && l.method != CPOCONV_ALGO_CPS)
+            return CPOCONV_ERR_ALGO;
+        if (l.method == CPOCONV_ALGO_IM2COL && l.precision != 0 && l.precision != 1) return CPOCONV_ERR_ALGO;
+        if (l.relu_in != 0 && l.relu_in != 1) return CPOCONV_ERR_ALGO;
+        if (!l.relu_in && l.bias_in) return CPOCONV_ERR_ALGO;      // a bias is only applied in front of the ReLU
+        // a layer reads what the layer before it wrote
+        if (i > 0 && (g.C != prev.K || g.H != prev.Oh || g.W != prev.Ow)) return CPOCONV_ERR_SHAPE;
+        prev = g;
+    }
+    return CPOCONV_OK;
+}
+
+int cpoconv_chain_sizes(const cpoconv_chain_layer *layers, int n_layers, int n_images, cpoconv_sizes_t *sizes)
+{
+    if (!sizes) return CPOCONV_ERR_NULL;
+    const int rc = chain_check(layers, n_layers, n_images);
+    if (rc != CPOCONV_OK) return rc;
+    memset(sizes, 0, sizeof(*sizes));
+    for (int i = 0; i < n_layers; ++i) {
+        cpoconv_sizes_t one;
+        const int src = cpoconv_batch_sizes(&layers[i].shape, n_images, &one);
+        if (src != CPOCONV_OK) return src;
+        sizes->ptr_cap = std::max(sizes->ptr_cap, one.ptr_cap);
+        sizes->da_cap = std::max(sizes->da_cap, one.da_cap);
+        sizes->in_cap = std::max(sizes->in_cap, one.in_cap);
+        sizes->chan_off_len = std::max(sizes->chan_off_len, one.chan_off_len);
+        sizes->wt_len = std::max(sizes->wt_len, one.wt_len);
+        sizes->out_len = std::max(sizes->out_len, one.out_len);
+        sizes->lowered_bytes = std::max(sizes->lowered_bytes, one.lowered_bytes);
+        sizes->scratch_bytes = std::max(sizes->scratch_bytes, one.scratch_bytes);
+        sizes->Oh = one.Oh;
+        sizes->Ow = one.Ow;
+    }
+    return CPOCONV_OK;
+}
+
+int cpoconv_chain_forward(const float *act, const cpoconv_chain_layer *layers, int n_layers, int n_images,
+                          const cpoconv_map *maps, void *scratch, int64_t scratch_bytes, void *lowered,
+                          int64_t lowered_bytes, void *stream)
+{
+    if (!act) return CPOCONV_ERR_NULL;
+    const int rc = chain_check(layers, n_layers, n_images);
+    if (rc != CPOCONV_OK) return rc;
+    // every buffer is checked before the first launch, so a chain runs whole or not at all
+    for (int i = 0; i < n_layers; ++i) {
+        const cpoconv_chain_layer &l = layers[i];
+        if (!l.weights || !l.out) return CPOCONV_ERR_NULL;
+        cpoconv_sizes_t one;
+        const int src = cpoconv_batch_sizes(&l.shape, n_images, &one);
+        if (src != CPOCONV_OK) return src;
+        if (l.method == CPOCONV_ALGO_IM2COL) {
+            if (!lowered) return CPOCONV_ERR_NULL;
+            if (lowered_bytes < one.lowered_bytes) return CPOCONV_ERR_SMALL;
+            if (reinterpret_cast<uintptr_t>(lowered) % 16 != 0) return CPOCONV_ERR_SHAPE;
+        } else {
+            if (!maps || !scratch) return CPOCONV_ERR_NULL;
+            if (!maps->ptr || !maps->da || !maps->in || !maps->chan_off || !maps->hdr) return CPOCONV_ERR_NULL;
+            if (maps->ptr_cap < one.ptr_cap || maps->da_cap < one.da_cap || maps->in_cap < one.in_cap) return CPOCONV_ERR_SMALL;
+            if (scratch_bytes < one.scratch_bytes) return CPOCONV_ERR_SMALL;
+        }
+    }
+    const float *x = act;
+    for (int i = 0; i < n_layers; ++i) {
+        const cpoconv_chain_layer &l = layers[i];
+        const Producer prod{l.relu_in ? l.bias_in : nullptr, l.relu_in};
+        int lrc;
+        if (l.method == CPOCONV_ALGO_IM2COL)
+            lrc = im2col_common(x, &l.shape, n_images, l.weights, lowered, l.out, l.precision, stream, prod);
+        else
+            lrc = encode_conv_common(x, &l.shape, n_images, maps, l.weights, l.out, scratch, scratch_bytes, stream,
+                                     l.method, prod);
+        if (lrc != CPOCONV_OK) return lrc;
+        x = l.out;
+    }
+    return CPOCONV_OK;
 }
 
 int select_layer_algo(const double *t_im2col, const double *t_cpo, const double *t_cps,

@@ -40,6 +40,26 @@ struct BatchStrides {
     int64_t mtab, partial, out;
 };
 
+// What a kernel that reads a dense map applies to every value on the way in: the end of the layer
+// that produced the map (its bias, then the ReLU that makes the input of Eq. 1 sparse), so the
+// activated map itself is never stored.
+struct Producer {
+    const float *bias;   // one float per channel of the map, or nullptr
+    int32_t relu;        // 0: the map is taken as it is (bias unused)
+};
+
+// value of a map element of a channel with bias b: z = v + b (one fp32 addition, none without a
+// bias), then z if z > 0, else +0.  The test is on the bit pattern (0 < bits <= +inf), so negative
+// values, both zeros and NaN give +0 whatever the denormal mode of the comparison would be.
+__device__ __forceinline__ float produced(float v, const Producer &prod, float b)
+{
+    if (prod.relu) {
+        if (prod.bias != nullptr) v += b;
+        v = (__float_as_uint(v) - 1u) < 0x7f800000u ? v : 0.0f;
+    }
+    return v;
+}
+
 int check_shape(const cpoconv_shape *s);           // CPOCONV_OK or CPOCONV_ERR_SHAPE
 int build_geometry(const cpoconv_shape *s, Geometry *g);
 int64_t max_ptr_len(const Geometry &g);
@@ -71,7 +91,7 @@ private:
 };
 
 // launchers (defined next to their kernels)
-int launch_encode(const float *act, const Geometry &g, const cpoconv_map &map, int algo,
+int launch_encode(const float *act, const Producer &prod, const Geometry &g, const cpoconv_map &map, int algo,
                   void *scratch, hipStream_t stream, bool write_table = false);
 int launch_prepare_weights(const float *w, const Geometry &g, float *wt, hipStream_t stream);
 int launch_zero_fill(void *buffer, int64_t bytes, hipStream_t stream);
@@ -116,7 +136,7 @@ __device__ inline float sum_slices(const float *src, int64_t slice_stride, int s
     return (s0 + s1) + (s2 + s3);
 }
 int64_t im2col_scratch_bytes(const Geometry &g);
-int launch_im2col_conv(const float *act, const Geometry &g, const float *w, void *lowered,
+int launch_im2col_conv(const float *act, const Producer &prod, const Geometry &g, const float *w, void *lowered,
                        float *out, int precision, hipStream_t stream);
 
 }  // namespace cpoconv

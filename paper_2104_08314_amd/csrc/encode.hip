@@ -100,7 +100,7 @@ __device__ __forceinline__ void poke(unsigned long long *p, unsigned long long v
 
 template <int kMode>
 __global__ __launch_bounds__(kThreads) void encode_kernel(const Geometry g, const float *__restrict__ act_all,
-                                                         const int cps, const int kChunk,
+                                                         const Producer prod, const int cps, const int kChunk,
                                                          unsigned long long *__restrict__ ctrl, const cpoconv_map maps,
                                                          int32_t *__restrict__ mtab_all, const int64_t mtab_stride)
 {
@@ -137,12 +137,13 @@ __global__ __launch_bounds__(kThreads) void encode_kernel(const Geometry g, cons
     const int top_begin = (cps && g.top_slot >= 0) ? g.type_begin[g.top_slot] : kMaxCols + 1;
     const int top_end = (cps && g.top_slot >= 0) ? g.type_begin[g.top_slot + 1] : 0;
     const float *chan = act + static_cast<int64_t>(c) * g.H * g.W;
+    const float bias_c = (prod.relu && prod.bias != nullptr) ? prod.bias[c] : 0.0f;
 
     auto load_tile = [&](int q) {
         for (int r = wave; r < kChunk; r += kWaves) {
             const int hr = q * kChunk + r - g.pad;
             if (hr < 0 || hr >= g.H) continue;
-            for (int jr = lane; jr < g.W; jr += kLanes) tile[r * Wt + jr] = chan[hr * g.W + jr];
+            for (int jr = lane; jr < g.W; jr += kLanes) tile[r * Wt + jr] = produced(chan[hr * g.W + jr], prod, bias_c);
         }
     };
 
@@ -398,7 +399,8 @@ __device__ __forceinline__ void wave_lds_fence()
 
 template <int kMode>
 __global__ __launch_bounds__(kThreads) void encode_small_kernel(const Geometry g, const float *__restrict__ act_all,
-                                                               const int cps, unsigned long long *__restrict__ ctrl,
+                                                               const Producer prod, const int cps,
+                                                               unsigned long long *__restrict__ ctrl,
                                                                const cpoconv_map maps, int32_t *__restrict__ mtab_all,
                                                                const int64_t mtab_stride)
 {
@@ -436,9 +438,10 @@ __global__ __launch_bounds__(kThreads) void encode_small_kernel(const Geometry g
     // ---- the channel into LDS (coalesced), then its column bitmaps: lane = column in stream order ----
     if (live) {
         const float *chan = act + static_cast<int64_t>(c) * g.H * g.W;
+        const float bias_c = (prod.relu && prod.bias != nullptr) ? prod.bias[c] : 0.0f;
         for (int i = lane; i < g.H * g.W; i += kLanes) {
             const int r = i / g.W;
-            tile[r * Wt + (i - r * g.W)] = chan[i];
+            tile[r * Wt + (i - r * g.W)] = produced(chan[i], prod, bias_c);
         }
     }
     wave_lds_fence();
@@ -666,8 +669,8 @@ __global__ __launch_bounds__(256) void prepare_weights_kernel(const Geometry g, 
 
 }  // namespace
 
-int launch_encode(const float *act, const Geometry &g, const cpoconv_map &map, int algo, void *scratch,
-                  hipStream_t stream, bool write_table)
+int launch_encode(const float *act, const Producer &prod, const Geometry &g, const cpoconv_map &map, int algo,
+                  void *scratch, hipStream_t stream, bool write_table)
 {
     // the table of resolved ptr offsets, for a convolution launched by the same call
     int32_t *mtab = write_table ? reinterpret_cast<int32_t *>(static_cast<char *>(scratch) + scratch_counts_bytes(g)) : nullptr;
@@ -687,17 +690,17 @@ int launch_encode(const float *act, const Geometry &g, const cpoconv_map &map, i
         const dim3 grid((g.C + kWaves - 1) / kWaves, g.N);
         if (g.C <= kSinglePassChannels) {
             KernelTimer timer("encode", stream);
-            hipLaunchKernelGGL(encode_small_kernel<kSinglePass>, grid, dim3(kThreads), lds_small, stream, g, act, cps, ctrl,
+            hipLaunchKernelGGL(encode_small_kernel<kSinglePass>, grid, dim3(kThreads), lds_small, stream, g, act, prod, cps, ctrl,
                                map, mtab, mstride);
         } else {
             {
                 KernelTimer timer("encode_count", stream);
-                hipLaunchKernelGGL(encode_small_kernel<kPublishOnly>, grid, dim3(kThreads), lds_small, stream, g, act, cps,
+                hipLaunchKernelGGL(encode_small_kernel<kPublishOnly>, grid, dim3(kThreads), lds_small, stream, g, act, prod, cps,
                                    ctrl, map, static_cast<int32_t *>(nullptr), mstride);
             }
             CPOCONV_HIP_TRY(hipGetLastError());
             KernelTimer timer("encode", stream);
-            hipLaunchKernelGGL(encode_small_kernel<kPublished>, grid, dim3(kThreads), lds_small, stream, g, act, cps, ctrl,
+            hipLaunchKernelGGL(encode_small_kernel<kPublished>, grid, dim3(kThreads), lds_small, stream, g, act, prod, cps, ctrl,
                                map, mtab, mstride);
         }
         CPOCONV_HIP_TRY(hipGetLastError());
@@ -705,17 +708,17 @@ int launch_encode(const float *act, const Geometry &g, const cpoconv_map &map, i
     }
     if (g.C <= kSinglePassChannels) {
         KernelTimer timer("encode", stream);
-        hipLaunchKernelGGL(encode_kernel<kSinglePass>, dim3(g.C, g.N), dim3(kThreads), lds, stream, g, act, cps, chunk, ctrl, map,
+        hipLaunchKernelGGL(encode_kernel<kSinglePass>, dim3(g.C, g.N), dim3(kThreads), lds, stream, g, act, prod, cps, chunk, ctrl, map,
                            mtab, mstride);
     } else {
         {
             KernelTimer timer("encode_count", stream);
-            hipLaunchKernelGGL(encode_kernel<kPublishOnly>, dim3(g.C, g.N), dim3(kThreads), lds, stream, g, act, cps, chunk,
+            hipLaunchKernelGGL(encode_kernel<kPublishOnly>, dim3(g.C, g.N), dim3(kThreads), lds, stream, g, act, prod, cps, chunk,
                                ctrl, map, static_cast<int32_t *>(nullptr), mstride);
         }
         CPOCONV_HIP_TRY(hipGetLastError());
         KernelTimer timer("encode", stream);
-        hipLaunchKernelGGL(encode_kernel<kPublished>, dim3(g.C, g.N), dim3(kThreads), lds, stream, g, act, cps, chunk, ctrl, map,
+        hipLaunchKernelGGL(encode_kernel<kPublished>, dim3(g.C, g.N), dim3(kThreads), lds, stream, g, act, prod, cps, chunk, ctrl, map,
                            mtab, mstride);
     }
     CPOCONV_HIP_TRY(hipGetLastError());

@@ -32,7 +32,7 @@ constexpr int kLowCols = 1024;  // lowered-matrix columns per workgroup
 
 template <typename T>
 __global__ __launch_bounds__(kLowThreads) void im2col_lower_kernel(const Geometry g, const float *__restrict__ act_all,
-                                                                  T *__restrict__ lowered_all, const int ldb,
+                                                                  const Producer prod, T *__restrict__ lowered_all, const int ldb,
                                                                   const int64_t image_stride)
 {
     // image blockIdx.y: its own lowered matrix, image_stride elements after the previous one
@@ -44,10 +44,11 @@ __global__ __launch_bounds__(kLowThreads) void im2col_lower_kernel(const Geometr
     const int col0 = (blockIdx.x - row * chunks) * kLowCols;
     const int w = row % g.kw, l = (row / g.kw) % g.kh, c = row / (g.kw * g.kh);
     const float *chan = act + static_cast<int64_t>(c) * g.H * g.W;
+    const float bias_c = (prod.relu && prod.bias != nullptr) ? prod.bias[c] : 0.0f;
     for (int col = col0 + threadIdx.x; col < min(col0 + kLowCols, N); col += kLowThreads) {
         const int y = col / g.Ow, x = col - y * g.Ow;
         const int hr = y * g.stride + l - g.pad, jr = x * g.stride + w - g.pad;
-        const float v = (hr >= 0 && hr < g.H && jr >= 0 && jr < g.W) ? chan[hr * g.W + jr] : 0.0f;
+        const float v = (hr >= 0 && hr < g.H && jr >= 0 && jr < g.W) ? produced(chan[hr * g.W + jr], prod, bias_c) : 0.0f;
         lowered[static_cast<int64_t>(row) * ldb + col] = lowered_cast<T>(v);
     }
 }
@@ -56,7 +57,7 @@ __global__ __launch_bounds__(kLowThreads) void im2col_lower_kernel(const Geometr
 // consecutive contraction indices one MFMA lane consumes sit next to each other (8 bytes) and
 // consecutive output positions follow each other.  Rows beyond Kd are zero.
 __global__ __launch_bounds__(kLowThreads) void im2col_lower_bf16_kernel(const Geometry g,
-                                                                       const float *__restrict__ act_all,
+                                                                       const float *__restrict__ act_all, const Producer prod,
                                                                        uint16_t *__restrict__ lowered_all, const int ldb,
                                                                        const int64_t image_stride)
 {
@@ -76,7 +77,9 @@ __global__ __launch_bounds__(kLowThreads) void im2col_lower_bf16_kernel(const Ge
             if (row < Kd) {
                 const int w = row % g.kw, l = (row / g.kw) % g.kh, c = row / (g.kw * g.kh);
                 const int hr = y * g.stride + l - g.pad, jr = x * g.stride + w - g.pad;
-                if (hr >= 0 && hr < g.H && jr >= 0 && jr < g.W) f = act[(static_cast<int64_t>(c) * g.H + hr) * g.W + jr];
+                if (hr >= 0 && hr < g.H && jr >= 0 && jr < g.W)
+                    f = produced(act[(static_cast<int64_t>(c) * g.H + hr) * g.W + jr], prod,
+                                 (prod.relu && prod.bias != nullptr) ? prod.bias[c] : 0.0f);
             }
             v[u] = to_bf16(f);
         }
@@ -339,7 +342,7 @@ int64_t im2col_scratch_bytes(const Geometry &g)
     return lowered_image_bytes(g) * g.N + partial;
 }
 
-int launch_im2col_conv(const float *act, const Geometry &g, const float *w, void *lowered, float *out,
+int launch_im2col_conv(const float *act, const Producer &prod, const Geometry &g, const float *w, void *lowered, float *out,
                        int precision, hipStream_t stream)
 {
     const int N = g.Oh * g.Ow, Kd = g.C * g.kh * g.kw, M = g.K;
@@ -359,7 +362,7 @@ int launch_im2col_conv(const float *act, const Geometry &g, const float *w, void
         {
             KernelTimer timer("im2col_lower_f32", stream);
             hipLaunchKernelGGL(im2col_lower_kernel<float>, dim3(static_cast<unsigned>(Kd) * chunks, g.N), dim3(kLowThreads),
-                               0, stream, g, act, static_cast<float *>(lowered), ldb, low_bytes / 4);
+                               0, stream, g, act, prod, static_cast<float *>(lowered), ldb, low_bytes / 4);
         }
         CPOCONV_HIP_TRY(hipGetLastError());
         KernelTimer timer("gemm_f32", stream);
@@ -373,7 +376,7 @@ int launch_im2col_conv(const float *act, const Geometry &g, const float *w, void
         {
             KernelTimer timer("im2col_lower_bf16", stream);
             hipLaunchKernelGGL(im2col_lower_bf16_kernel, dim3(static_cast<unsigned>((Kd + 3) / 4) * chunks, g.N),
-                               dim3(kLowThreads), 0, stream, g, act, static_cast<uint16_t *>(lowered), ldb, low_bytes / 2);
+                               dim3(kLowThreads), 0, stream, g, act, prod, static_cast<uint16_t *>(lowered), ldb, low_bytes / 2);
         }
         CPOCONV_HIP_TRY(hipGetLastError());
         KernelTimer timer("gemm_bf16", stream);

@@ -188,3 +188,59 @@ def random_case(seed: int, C: int, H: int, W: int, K: int, kh: int, kw: int, str
         dead = rng.choice(C, size=min(zero_channels, C), replace=False)
         act[dead] = 0.0
     return (np.ascontiguousarray(act, dtype=np.float32), np.ascontiguousarray(w, dtype=np.float32))
+
+
+# --- a chained network: the 3x3 layers of workload 5 joined end to end -------------------------
+def chain_specs() -> List[LayerSpec]:
+    """Workload 5's sixteen 3x3 layers as ONE network: every layer takes the output of the layer
+    before it, so the strided layers read the narrower map (64 -> 128, 128 -> 256, 256 -> 512
+    channels, as in the residual networks of the SI layer tables).  ``zero_frac`` is the zero
+    fraction the bias in front of the layer aims at; ``zero_channels`` channels get a bias that
+    switches them off."""
+    out: List[LayerSpec] = []
+    prev_k, hw = 64, 56
+    for spec in _cfg5_layers()[1:]:
+        out.append(LayerSpec(f"chain.l{spec.layer:02d}.{prev_k}to{spec.K}@{hw}s{spec.stride}", 6, spec.layer,
+                             prev_k, hw, hw, spec.K, 3, 3, spec.stride, 1, "relu_gauss", spec.zero_frac,
+                             int(0.05 * prev_k)))
+        prev_k, hw = spec.K, out[-1].Oh
+    return out
+
+
+def _relu_gauss_second_moment(mean: float, sd: float) -> float:
+    """E[max(0, X)^2] for X ~ N(mean, sd^2)."""
+    t = mean / sd
+    cdf = 0.5 * (1.0 + math.erf(t / math.sqrt(2.0)))
+    pdf = math.exp(-0.5 * t * t) / math.sqrt(2.0 * math.pi)
+    return (mean * mean + sd * sd) * cdf + mean * sd * pdf
+
+
+def make_chain(m: int = 0):
+    """Input map of the first layer, the weights of every layer and the bias in front of every
+    layer but the first.  With He-normal weights a layer's output is close to N(0, 2 E[a^2]) for
+    an input a (less what dead channels and padding take away), so the bias that leaves a fraction z of zeros after the ReLU is sd * ppf(1 - z);
+    it gets a 10 % per-channel jitter, and ``zero_channels`` channels are pushed 8 sd below zero."""
+    specs = chain_specs()
+    first = specs[0]
+    act = make_activation(dataclasses.replace(first, zero_channels=0), m)
+    weights, biases = [], []
+    mean, sd = _norm_ppf(1.0 - first.zero_frac), 1.0
+    for i, spec in enumerate(specs):
+        rng = np.random.default_rng(layer_seed(spec) + 104729)
+        if i == 0:
+            biases.append(None)
+        else:
+            # spread of the previous layer's output: its live input channels, the taps that fall on
+            # the map rather than on the padding, the jitter of the bias in front of it
+            prev = specs[i - 1]
+            live = 1.0 - (prev.zero_channels if i > 1 else 0) / prev.C
+            on_map = ((3.0 * prev.H - 2.0) / (3.0 * prev.H)) ** 2 if prev.stride == 1 else 1.0
+            jitter = 1.01 if i > 1 else 1.0
+            sd = math.sqrt(2.0 * live * on_map * _relu_gauss_second_moment(mean, sd * math.sqrt(jitter)))
+            mean = sd * _norm_ppf(1.0 - spec.zero_frac)
+            b = mean + 0.1 * sd * rng.standard_normal(spec.C)
+            dead = rng.choice(spec.C, size=spec.zero_channels, replace=False)
+            b[dead] = -8.0 * sd
+            biases.append(np.ascontiguousarray(b, dtype=np.float32))
+        weights.append(make_weights(spec))
+    return act, weights, biases

@@ -144,3 +144,58 @@ def test_batch_sizes_and_batch_argument_checks():
     assert lib.im2col_conv_batch(one, ctypes.byref(good), 2000, one, one, one, 0, None) == api.ERR_SHAPE
     assert lib.cpoconv_scratch_init(None, ctypes.c_int64(16), None) == api.ERR_NULL
     assert lib.cpoconv_scratch_init(one, ctypes.c_int64(-1), None) == api.ERR_SHAPE
+
+
+def _chain_table(shapes, methods, relu=None, bias=None):
+    table = (api.ChainLayer * len(shapes))()
+    for i, (s, m) in enumerate(zip(shapes, methods)):
+        table[i].shape = api.Shape(*s)
+        table[i].method = m
+        table[i].precision = 0
+        table[i].relu_in = (relu or [0] * len(shapes))[i]
+        table[i].bias_in = (bias or [None] * len(shapes))[i]
+        table[i].weights = 256
+        table[i].out = 256
+    return table
+
+
+def test_chain_sizes_and_argument_checks():
+    lib = api.lib()
+    a, b, c = (6, 10, 12, 9, 3, 3, 1, 1), (9, 10, 12, 5, 3, 3, 2, 1), (5, 5, 6, 7, 5, 5, 1, 2)
+    table = _chain_table([a, b, c], [api.ALGO_CPO, api.ALGO_IM2COL, api.ALGO_CPS], relu=[0, 1, 1])
+    sz = api.cpoconv_chain_sizes(table, 2)
+    each = [api.cpoconv_batch_sizes(s, 2) for s in (a, b, c)]
+    for field in ("ptr_cap", "da_cap", "in_cap", "chan_off_len", "wt_len", "out_len", "lowered_bytes", "scratch_bytes"):
+        assert getattr(sz, field) == max(getattr(e, field) for e in each), field
+    assert (sz.Oh, sz.Ow) == (each[2].Oh, each[2].Ow)
+    out = api.Sizes()
+    # layers that do not fit each other: channels, then height
+    bad = _chain_table([a, (8, 10, 12, 5, 3, 3, 1, 1)], [api.ALGO_CPO] * 2)
+    assert lib.cpoconv_chain_sizes(bad, 2, 1, ctypes.byref(out)) == api.ERR_SHAPE
+    bad = _chain_table([a, (9, 11, 12, 5, 3, 3, 1, 1)], [api.ALGO_CPO] * 2)
+    assert lib.cpoconv_chain_sizes(bad, 2, 1, ctypes.byref(out)) == api.ERR_SHAPE
+    assert lib.cpoconv_chain_sizes(table, 0, 1, ctypes.byref(out)) == api.ERR_SHAPE
+    assert lib.cpoconv_chain_sizes(table, 3, 0, ctypes.byref(out)) == api.ERR_SHAPE
+    assert lib.cpoconv_chain_sizes(None, 3, 1, ctypes.byref(out)) == api.ERR_NULL
+    assert lib.cpoconv_chain_sizes(_chain_table([a], [7]), 1, 1, ctypes.byref(out)) == api.ERR_ALGO
+    assert lib.cpoconv_chain_sizes(_chain_table([a], [api.ALGO_CPO], relu=[2]), 1, 1, ctypes.byref(out)) == api.ERR_ALGO
+    # a bias is only applied in front of the ReLU
+    assert lib.cpoconv_chain_sizes(_chain_table([a], [api.ALGO_CPO], relu=[0], bias=[256]), 1, 1, ctypes.byref(out)) == api.ERR_ALGO
+
+    # cpoconv_chain_forward checks everything before its first launch
+    one, huge = ctypes.c_void_p(256), ctypes.c_int64(1 << 40)
+    big = api._Map(256, 1 << 30, 256, 1 << 30, 256, 1 << 30, 256, 256)
+    assert lib.cpoconv_chain_forward(None, table, 3, 2, ctypes.byref(big), one, huge, one, huge, None) == api.ERR_NULL
+    assert lib.cpoconv_chain_forward(one, table, 3, 2, ctypes.byref(big), one, ctypes.c_int64(64), one, huge, None) == api.ERR_SMALL
+    assert lib.cpoconv_chain_forward(one, table, 3, 2, ctypes.byref(big), one, huge, one, ctypes.c_int64(64), None) == api.ERR_SMALL
+    tight = api._Map(256, 1 << 30, 256, each[0].da_cap - 1, 256, 1 << 30, 256, 256)
+    assert lib.cpoconv_chain_forward(one, table, 3, 2, ctypes.byref(tight), one, huge, one, huge, None) == api.ERR_SMALL
+    assert lib.cpoconv_chain_forward(one, table, 3, 2, None, one, huge, one, huge, None) == api.ERR_NULL          # CPO layers need a map
+    assert lib.cpoconv_chain_forward(one, table, 3, 2, ctypes.byref(big), one, huge, None, huge, None) == api.ERR_NULL   # im2col layer
+    table[2].out = None
+    assert lib.cpoconv_chain_forward(one, table, 3, 2, ctypes.byref(big), one, huge, one, huge, None) == api.ERR_NULL
+    # the fused producers validate like the calls they extend
+    good = api.Shape(*a)
+    assert lib.cpo_encode_relu(None, None, ctypes.byref(good), 1, ctypes.byref(big), one, huge, None) == api.ERR_NULL
+    assert lib.cps_encode_relu(one, None, ctypes.byref(good), 0, ctypes.byref(big), one, huge, None) == api.ERR_SHAPE
+    assert lib.im2col_conv_relu(one, None, ctypes.byref(good), 1, one, one, one, 5, None) == api.ERR_ALGO
