@@ -326,6 +326,67 @@ def batch_supplement(api, torch, workloads, spec, n_images, reps):
     return out
 
 
+def chain_supplement(api, torch, workloads, n_images, reps, m_inputs=5):
+    """The sixteen 3x3 layers of workload 5 joined end to end (each layer reads the stored sums of
+    the one before it and applies bias + ReLU on the way in) through cpoconv_chain_forward: time of
+    the whole chain per image with one method everywhere, and with the per-layer choice of Section
+    3.5 made from each layer timed alone on its own chain input over M input batches."""
+    import numpy as np
+
+    specs = workloads.chain_specs()
+    shapes = [s.shape_tuple for s in specs]
+    _, w_np, b_np = workloads.make_chain()
+    ws = [torch.from_numpy(w).cuda() for w in w_np]
+    bs = [None if b is None else torch.from_numpy(b).cuda() for b in b_np]
+    L = len(specs)
+    chain = api.Chain(shapes, ws, bs, [b is not None for b in b_np], [api.ALGO_IM2COL] * L, n_images=n_images)
+    batches = [torch.from_numpy(np.stack([workloads.make_activation(specs[0], m * n_images + j)
+                                          for j in range(n_images)])).cuda() for m in range(m_inputs)]
+    codes = {"im2col": api.ALGO_IM2COL, "cpo": api.ALGO_CPO, "cps": api.ALGO_CPS}
+    names = {v: k for k, v in codes.items()}
+    whole, per_layer = {}, {k: [[0.0] * m_inputs for _ in range(L)] for k in codes}
+    for k, code in codes.items():
+        chain.set_methods([code] * L)
+        for _ in range(3):
+            chain.forward(batches[0])
+        whole[k] = _time_us(torch, lambda: chain.forward(batches[0]), reps)
+        for m, act in enumerate(batches):
+            chain.forward(act)                                  # every layer's input for this batch
+            for i in range(L):
+                x = act if i == 0 else chain.outs[i - 1]
+                chain.forward(x, first=i, count=1)
+                per_layer[k][i][m] = _time_us(torch, lambda: chain.forward(x, first=i, count=1), max(reps // 2, 5))
+    pick_time = [api.select_layer_algo(per_layer["im2col"][i], per_layer["cpo"][i], per_layer["cps"][i], 0) for i in range(L)]
+    pick_space = [api.select_layer_algo(per_layer["im2col"][i], per_layer["cpo"][i], per_layer["cps"][i], 1) for i in range(L)]
+    for label, picks in (("hybrid_favour_time", pick_time), ("hybrid_favour_space", pick_space)):
+        chain.set_methods(picks)
+        for _ in range(3):
+            chain.forward(batches[0])
+        whole[label] = _time_us(torch, lambda: chain.forward(batches[0]), reps)
+    # realised zero fraction of every layer's input (first batch)
+    chain.set_methods([api.ALGO_IM2COL] * L)
+    chain.forward(batches[0])
+    torch.cuda.synchronize()
+    zeros = []
+    for i in range(L):
+        x = batches[0] if i == 0 else chain.outs[i - 1]
+        z = x if bs[i] is None else x + bs[i][None, :, None, None]
+        zeros.append(round(float((z <= 0).float().mean().item()), 3))
+    not_moved = sum(2 * 4 * s.C * s.H * s.W for s in specs[1:])
+    return {
+        "workload": "chain: workload 5's sixteen 3x3 layers joined end to end, bias + ReLU fused into the reader",
+        "n_images": n_images, "layers": L, "offline_inputs": m_inputs,
+        "per_image_us": {("all_" + k if k in codes else k): round(v / n_images, 2) for k, v in whole.items()},
+        "selection_favour_time": [names[c] for c in pick_time],
+        "selection_favour_space": [names[c] for c in pick_space],
+        "layers_cpo_selected": sum(c == api.ALGO_CPO for c in pick_time),
+        "layers_cps_selected": sum(c == api.ALGO_CPS for c in pick_space),
+        "layer_us_per_image": {k: [round(sum(t) / len(t) / n_images, 2) for t in v] for k, v in per_layer.items()},
+        "input_zero_fraction": zeros,
+        "activated_map_bytes_not_moved_per_image": not_moved,
+    }
+
+
 def cpu_baseline(spec, workloads, w_np, inputs=5, repeats=4):
     """The CPU oracle as it stands, one thread, on the same layer: CPO encode + Algorithm 2 on the
     layer's `inputs` offline inputs, `repeats` times each (about 10 s of CPU work on config 2)."""
@@ -388,6 +449,7 @@ def main():
     ap.add_argument("--batch", type=int, default=32,
                     help="images per launch of the batched supplement (0 to skip it)")
     ap.add_argument("--no-cold", action="store_true", help="skip the cold-cache timing of the stages")
+    ap.add_argument("--no-chain", action="store_true", help="skip the chained-layers supplement")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also launch a plain elementwise kernel that reads and writes 256 MiB, five times: the "
                          "known-size kernel that rocprofv3 FETCH_SIZE / WRITE_SIZE readings are scaled by")
@@ -488,6 +550,9 @@ def main():
                                         "an empty event pair; 'us' above are warm back-to-back averages")
     if args.batch > 0:
         result["batch_supplement"] = batch_supplement(api, torch, workloads, spec, args.batch, reps=10)
+    if not args.no_chain:
+        result["chain_supplement"] = [chain_supplement(api, torch, workloads, n, reps=10)
+                                      for n in ([1, args.batch] if args.batch > 1 else [1])]
     if not args.no_cpu_baseline:
         result["cpu_baseline"] = cpu_baseline(spec, workloads, run.w_np)
 

@@ -482,12 +482,15 @@ class Chain:
                     self.prepared[i] = wt
                 self.table[i].weights = self.prepared[i].data_ptr()
 
-    def forward(self, act, stream=None) -> None:
-        """Runs every layer; layer i's output (before bias / ReLU) lands in outs[i]."""
+    def forward(self, act, stream=None, first=0, count=None) -> None:
+        """Runs every layer; layer i's output (before bias / ReLU) lands in outs[i].  With first /
+        count only layers first .. first+count-1 run, `act` being the input of layer `first`."""
         import torch
 
+        count = len(self.shapes) - first if count is None else count
         cm = self.map.c_struct()
-        _check(lib().cpoconv_chain_forward(_dev_ptr(act, torch.float32), self.table, len(self.shapes), self.n_images,
+        sub = ctypes.cast(ctypes.byref(self.table, first * ctypes.sizeof(ChainLayer)), ctypes.POINTER(ChainLayer))
+        _check(lib().cpoconv_chain_forward(_dev_ptr(act, torch.float32), sub, int(count), self.n_images,
                                            ctypes.byref(cm), _dev_ptr(self.scratch),
                                            ctypes.c_int64(self.scratch.numel()), _dev_ptr(self.lowered),
                                            ctypes.c_int64(self.lowered.numel()), _stream_handle(stream)))
