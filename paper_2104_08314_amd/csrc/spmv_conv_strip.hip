@@ -2,9 +2,11 @@
 //
 // CPO streams are column-major: inside a channel and overlap type the NZEs follow the
 // partitions (columns) and, inside a column, the rows.  ptr therefore delimits exactly the NZEs
-// of a strip of output columns, for all rows at once.  A workgroup owns such a strip (TX output
-// columns, all or up to 16*TY output rows) for 64 output kernels and one slice of the input
-// channels; its wavefronts are the strip's row bands.
+// of a strip of output columns, for all rows at once.  A workgroup owns such a strip (XT*TX
+// output columns, all or up to 16/XT * TY output rows) for 64 output kernels and one slice of the
+// input channels; its wavefronts are TY x TX tiles of the strip: row bands, XT tiles side by side.
+// Wide strips (XT > 1) are for small maps: the whole map is then decoded once per workgroup and
+// the staged weights serve up to sixteen wavefronts.
 //
 // Per group of G channels
 //   decode   the wavefronts share the NZE chunks (64 NZEs each) of the group's channels: load
@@ -46,21 +48,22 @@ struct StripArgs {
     int32_t slices;           // channel slices across workgroups
     BatchStrides bs;          // image n of the launch: every buffer advanced n strides
     int32_t Ypad, Xpad;
-    int32_t bands;            // wavefronts per workgroup
+    int32_t bands;            // row bands per workgroup (wavefronts: bands * XT)
     int32_t batch;            // channels per table refill (multiple of G)
     int32_t chunks;           // upper bound of 64-NZE chunks of one channel's strip
     int32_t chunks_magic;     // ceil(2^16 / chunks): item / chunks == (item * magic) >> 16 for item < 1024
 };
 
-template <int KH, int KW, int S, int TY, int TX, int G, int KPL>
+template <int KH, int KW, int S, int TY, int TX, int G, int KPL, int XT>
 __global__ __launch_bounds__(kMaxBands *kLanes) void spmv_conv_strip_kernel(const Geometry g, const StripArgs a_launch)
 {
     constexpr int RH = (TY - 1) * S + KH;      // rows of the padded input behind one tile
-    constexpr int RW = (TX - 1) * S + KW;      // columns behind the strip
-    constexpr int NCELL = RH * RW;
+    constexpr int RWT = (TX - 1) * S + KW;     // columns behind one tile
+    constexpr int RW = (XT * TX - 1) * S + KW; // columns behind the strip
+    constexpr int NCELL = RH * RWT;
     constexpr int NDREG = (NCELL + kLanes - 1) / kLanes;
     constexpr int TAPS = KH * KW;
-    constexpr int SPAN = TX + KW + 1;          // table slots per (channel, type): partitions p_lo-1 ..
+    constexpr int SPAN = XT * TX + KW + 1;     // table slots per (channel, type): partitions p_lo-1 ..
     constexpr int IT = 4;                      // decode items whose loads are in flight together
 
     const int ngroups = g.Kpad / (kLanes * KPL);   // a wavefront holds KPL kernels per lane
@@ -75,18 +78,21 @@ __global__ __launch_bounds__(kMaxBands *kLanes) void spmv_conv_strip_kernel(cons
     a.out += image * a.bs.out;
 
     extern __shared__ int32_t smem[];
-    // layout: tab[batch][n_types][SPAN] | stage[bands][kStageInts] | wl[G][TAPS][KPL*64] | patch[G][RW][PH]
+    // layout: tab[batch][n_types][SPAN] | stage[wavefronts][kStageInts] | wl[G][TAPS][KPL*64] | patch[G][RW][PH]
+    const int nwaves = a.bands * XT;
     int32_t *tab = smem;
     int32_t *stage = tab + a.batch * g.n_types * SPAN;
-    float *wl = reinterpret_cast<float *>(stage + a.bands * kStageInts);
+    float *wl = reinterpret_cast<float *>(stage + nwaves * kStageInts);
     float *patch = wl + G * TAPS * KPL * kLanes;
 
     const int tid = threadIdx.x, lane = lane_id();
     const int wave = uni(tid / kLanes);   // in a scalar register: everything derived from it stays scalar
-    const int nthreads = a.bands * kLanes;
-    const int x0 = blockIdx.x * TX;
+    const int nthreads = nwaves * kLanes;
+    const int xt = XT == 1 ? 0 : wave / a.bands, band = wave - xt * a.bands;   // this wavefront's tile of the strip
+    const int x0 = blockIdx.x * (TX * XT);                  // first output column of the strip
+    const int xw0 = x0 + xt * TX;                           // first output column of this wavefront
     const int yb = blockIdx.y * a.bands * TY;               // first output row of the workgroup
-    const int y0 = yb + wave * TY;                          // first output row of this wavefront
+    const int y0 = yb + band * TY;                          // first output row of this wavefront
     const int PH = (a.bands * TY - 1) * S + KH;             // patch height: rows behind the workgroup
     const int kg = blockIdx.z % ngroups, slice = (blockIdx.z / ngroups) % a.slices;
     const int kbase = kg * kLanes * KPL;
@@ -128,7 +134,7 @@ __global__ __launch_bounds__(kMaxBands *kLanes) void spmv_conv_strip_kernel(cons
                 tab[idx] = a.mtab[(static_cast<int64_t>(c) * g.n_types + i) * (g.Ow + 1) + p + 1];
             }
         } else {
-            resolve_ptr_rows<SPAN>(g, a.ptr, a.chan_off, cb, nb, x0, tab, stage, wave, a.bands, lane);
+            resolve_ptr_rows<SPAN>(g, a.ptr, a.chan_off, cb, nb, x0, tab, stage, wave, nwaves, lane);
         }
 
         for (int g0 = 0; g0 < nb; g0 += G) {
@@ -137,7 +143,7 @@ __global__ __launch_bounds__(kMaxBands *kLanes) void spmv_conv_strip_kernel(cons
             __syncthreads();
             for (int i = tid; i < ng * RW * PH; i += nthreads) patch[i] = 0.0f;
             // weights of the group's channels for this workgroup's 64 kernels (coalesced rows of 64)
-            for (int row = wave; row < ng * TAPS; row += a.bands)
+            for (int row = wave; row < ng * TAPS; row += nwaves)
 #pragma unroll
                 for (int kk = 0; kk < KPL; ++kk)
                     wl[(row * KPL + kk) * kLanes + lane] =
@@ -147,14 +153,14 @@ __global__ __launch_bounds__(kMaxBands *kLanes) void spmv_conv_strip_kernel(cons
             // ---- decode: work item = (channel of the group, 64-NZE chunk of its main-type range);
             // the loads of IT items are issued before any of them is used ------------------------
             const int nitems = ng * a.chunks;
-            for (int it0 = wave; it0 < nitems; it0 += a.bands * IT) {
+            for (int it0 = wave; it0 < nitems; it0 += nwaves * IT) {
                 int idxv[IT], nv[IT];
                 float valv[IT];
                 const int t_main = g.type_id[main_slot];
-                const int plo_main = max(0, x0 - t_main), phi = min(g.Ow - 1, x0 + TX - 1);
+                const int plo_main = max(0, x0 - t_main), phi = min(g.Ow - 1, x0 + XT * TX - 1);
 #pragma unroll
                 for (int u = 0; u < IT; ++u) {
-                    const int item = it0 + u * a.bands;
+                    const int item = it0 + u * nwaves;
                     idxv[u] = -1; valv[u] = 0.0f; nv[u] = 0;
                     if (item < nitems) {
                         const int gi = (item * a.chunks_magic) >> 16, ch = item - gi * a.chunks;
@@ -167,7 +173,7 @@ __global__ __launch_bounds__(kMaxBands *kLanes) void spmv_conv_strip_kernel(cons
                 }
 #pragma unroll
                 for (int u = 0; u < IT; ++u) {
-                    const int item = it0 + u * a.bands;
+                    const int item = it0 + u * nwaves;
                     if (item >= nitems) continue;
                     const int gi = (item * a.chunks_magic) >> 16, ch = item - gi * a.chunks;
                     float *pt = patch + gi * RW * PH;
@@ -198,10 +204,10 @@ __global__ __launch_bounds__(kMaxBands *kLanes) void spmv_conv_strip_kernel(cons
             __syncthreads();
 
             // ---- apply: every wavefront walks the cells behind its own tile --------------------
-            if (y0 < g.Oh) {
+            if (y0 < g.Oh && xw0 < g.Ow) {
 #pragma unroll 1
                 for (int gi = 0; gi < ng; ++gi) {
-                    const float *pt = patch + gi * RW * PH + wave * TY * S;   // first row of the band
+                    const float *pt = patch + gi * RW * PH + xt * (TX * S) * PH + band * TY * S;   // first cell behind the tile
                     float cell[NDREG];
                     unsigned long long bits[NDREG];
                     bool any = false;
@@ -220,7 +226,7 @@ __global__ __launch_bounds__(kMaxBands *kLanes) void spmv_conv_strip_kernel(cons
 #pragma unroll
                         for (int kk = 0; kk < KPL; ++kk) w[tp][kk] = wl[((gi * TAPS + tp) * KPL + kk) * kLanes + lane];
 #pragma unroll
-                    for (int q = 0; q < RW; ++q) {
+                    for (int q = 0; q < RWT; ++q) {
 #pragma unroll
                         for (int r = 0; r < RH; ++r) {
                             const int cellno = q * RH + r;
@@ -259,14 +265,14 @@ __global__ __launch_bounds__(kMaxBands *kLanes) void spmv_conv_strip_kernel(cons
                 for (int y = 0; y < TY; ++y)
 #pragma unroll
                     for (int x = 0; x < TX; ++x)
-                        if (y0 + y < g.Oh && x0 + x < g.Ow)
-                            a.out[(static_cast<int64_t>(k) * g.Oh + y0 + y) * g.Ow + x0 + x] = acc[y][x][kk];
+                        if (y0 + y < g.Oh && xw0 + x < g.Ow)
+                            a.out[(static_cast<int64_t>(k) * g.Oh + y0 + y) * g.Ow + xw0 + x] = acc[y][x][kk];
         }
         return;
     }
     // partial sums of this channel slice, kernel index fastest
-    if (y0 < g.Oh) {
-        float *dst = a.partial + ((static_cast<int64_t>(slice) * a.Ypad + y0) * a.Xpad + x0) * g.Kpad + kbase + lane;
+    if (y0 < g.Oh && xw0 < g.Ow) {
+        float *dst = a.partial + ((static_cast<int64_t>(slice) * a.Ypad + y0) * a.Xpad + xw0) * g.Kpad + kbase + lane;
 #pragma unroll
         for (int y = 0; y < TY; ++y)
 #pragma unroll
@@ -282,20 +288,21 @@ struct StripPlan {
     size_t lds;
 };
 
-template <int KH, int KW, int S, int TY, int TX, int G, int KPL>
+template <int KH, int KW, int S, int TY, int TX, int G, int KPL, int XT>
 StripPlan strip_plan(const Geometry &g)
 {
-    constexpr int RW = (TX - 1) * S + KW, SPAN = TX + KW + 1;
+    constexpr int RW = (XT * TX - 1) * S + KW, SPAN = XT * TX + KW + 1;
+    constexpr int kBandsMax = kMaxBands / XT;
     StripPlan p;
     const int bands_all = (g.Oh + TY - 1) / TY;
-    p.row_blocks = (bands_all + kMaxBands - 1) / kMaxBands;
+    p.row_blocks = (bands_all + kBandsMax - 1) / kBandsMax;
     p.bands = (bands_all + p.row_blocks - 1) / p.row_blocks;
     const int PH = (p.bands * TY - 1) * S + KH;
     p.Ypad = p.row_blocks * p.bands * TY;
     p.chunks = (RW * g.Ih + kLanes - 1) / kLanes;   // a strip's partitions hold at most RW columns of Ih rows
     // about one workgroup per compute unit (measured best: the workgroups are large), each slice
     // keeping four channels or more
-    const int wgs = ((g.Ow + TX - 1) / TX) * p.row_blocks * (g.Kpad / (kLanes * KPL)) * g.N;
+    const int wgs = ((g.Ow + TX * XT - 1) / (TX * XT)) * p.row_blocks * (g.Kpad / (kLanes * KPL)) * g.N;
     int s = 256 / wgs;
     const int cap = (g.C + 3) / 4;
     if (s > cap) s = cap;
@@ -309,30 +316,30 @@ StripPlan strip_plan(const Geometry &g)
     if (batch < G) batch = G;
     if (batch > 64) batch = 64;
     p.batch = batch;
-    p.lds = (static_cast<size_t>(batch) * g.n_types * SPAN + static_cast<size_t>(p.bands) * kStageInts +
+    p.lds = (static_cast<size_t>(batch) * g.n_types * SPAN + static_cast<size_t>(p.bands) * XT * kStageInts +
              static_cast<size_t>(G) * KH * KW * KPL * kLanes +
              static_cast<size_t>(G) * RW * PH) * 4;
     return p;
 }
 
-template <int KH, int KW, int S, int TY, int TX, int G, int KPL>
+template <int KH, int KW, int S, int TY, int TX, int G, int KPL, int XT>
 int launch_strip(const cpoconv_map &map, const int32_t *indices, const int32_t *mtab, const Geometry &g,
                  const float *wt, float *out, float *partial, BatchStrides bs, hipStream_t stream)
 {
-    const StripPlan p = strip_plan<KH, KW, S, TY, TX, G, KPL>(g);
-    const int ntx = (g.Ow + TX - 1) / TX;
+    const StripPlan p = strip_plan<KH, KW, S, TY, TX, G, KPL, XT>(g);
+    const int ntx = (g.Ow + TX * XT - 1) / (TX * XT);
     StripArgs a;
     a.da = map.da; a.in = indices; a.mtab = mtab; a.ptr = map.ptr; a.chan_off = map.chan_off; a.wt = wt;
     a.partial = partial; a.out = out;
-    a.slices = p.slices; a.Ypad = p.row_blocks * p.bands * TY; a.Xpad = ntx * TX;
+    a.slices = p.slices; a.Ypad = p.row_blocks * p.bands * TY; a.Xpad = ntx * TX * XT;
     a.bands = p.bands; a.batch = p.batch; a.chunks = p.chunks;
     a.chunks_magic = (65536 + p.chunks - 1) / p.chunks;
     bs.partial = static_cast<int64_t>(p.slices) * a.Ypad * a.Xpad * g.Kpad;
     a.bs = bs;
     {
         KernelTimer timer("spmv_conv_strip", stream);
-        hipLaunchKernelGGL((spmv_conv_strip_kernel<KH, KW, S, TY, TX, G, KPL>),
-                           dim3(ntx, p.row_blocks, (g.Kpad / (kLanes * KPL)) * p.slices * g.N), dim3(p.bands * kLanes), p.lds, stream,
+        hipLaunchKernelGGL((spmv_conv_strip_kernel<KH, KW, S, TY, TX, G, KPL, XT>),
+                           dim3(ntx, p.row_blocks, (g.Kpad / (kLanes * KPL)) * p.slices * g.N), dim3(p.bands * XT * kLanes), p.lds, stream,
                            g, a);
     }
     CPOCONV_HIP_TRY(hipGetLastError());
@@ -341,6 +348,23 @@ int launch_strip(const cpoconv_map &map, const int32_t *indices, const int32_t *
 }
 
 }  // namespace
+
+// Column tiles per workgroup.  With several images per launch there are workgroups enough, and the
+// small 3 x 3 maps gain from wide strips: 14 x 14 outputs are one strip of four tiles by four bands
+// (every NZE decoded once per workgroup, weights staged once for sixteen wavefronts), 28 x 28
+// outputs strips of two tiles by seven bands.
+int strip_xt(const Geometry &g)
+{
+#ifndef CPOCONV_XT_MIN_N
+#define CPOCONV_XT_MIN_N 4
+#endif
+    if (g.N < CPOCONV_XT_MIN_N || g.kh != 3) return 1;
+    const int bands_all = (g.Oh + 3) / 4;
+    // at least eight wavefronts must share the strip for the staging to pay
+    if (bands_all * 4 <= kMaxBands && g.Ow > 8 && bands_all * 4 >= 8) return 4;
+    if (bands_all * 2 <= kMaxBands && g.Ow > 4 && bands_all * 2 >= 8) return 2;
+    return 1;
+}
 
 bool strip_kernel_supports(const Geometry &g)
 {
@@ -357,6 +381,7 @@ bool strip_kernel_supports(const Geometry &g)
 bool strip_kernel_preferred(const Geometry &g)
 {
     if (!strip_kernel_supports(g)) return false;
+    if (strip_xt(g) > 1) return true;   // small maps, several images: wide strips
     if (g.C <= 16 || g.kh == 5) return true;
     if (g.stride == 2) return g.Oh * g.Ow >= 784 && g.Kpad >= 128;   // 3 x 3 stride 2 from a 56 x 56 map: 46 -> 34 us
     // stride 1: from 56 x 56 maps on; with several images per launch already from 28 x 28
@@ -365,21 +390,31 @@ bool strip_kernel_preferred(const Geometry &g)
 
 // 3 x 3 layers whose padded kernel count is a multiple of 128 keep two kernels per lane: the
 // scalar work of a visited cell (bit test, broadcast) then feeds twice the FMAs
-#define CPOCONV_STRIP_DISPATCH(CALL)                                                                     \
-    if (g.kh == 3 && g.kw == 3 && g.stride == 1 && g.Kpad % 128 == 0) return CALL(3, 3, 1, 4, 4, 8, 2);  \
-    if (g.kh == 3 && g.kw == 3 && g.stride == 1) return CALL(3, 3, 1, 4, 4, 8, 1);                       \
-    if (g.kh == 3 && g.kw == 3 && g.stride == 2 && g.Kpad % 128 == 0) return CALL(3, 3, 2, 4, 4, 8, 2);  \
-    if (g.kh == 3 && g.kw == 3 && g.stride == 2) return CALL(3, 3, 2, 4, 4, 8, 1);                       \
-    if (g.kh == 5 && g.kw == 5 && g.stride == 1) return CALL(5, 5, 1, 4, 4, 8, 1);                       \
-    if (g.kh == 7 && g.kw == 7 && g.stride == 2) return CALL(7, 7, 2, 4, 4, 4, 1);
+#define CPOCONV_STRIP_3X3(CALL, S)                                                   \
+    if (g.kh == 3 && g.kw == 3 && g.stride == S) {                                   \
+        const int xt = strip_xt(g);                                                  \
+        if (g.Kpad % 128 == 0) {                                                     \
+            if (xt == 4) return CALL(3, 3, S, 4, 4, 8, 2, 4);                        \
+            if (xt == 2) return CALL(3, 3, S, 4, 4, 8, 2, 2);                        \
+            return CALL(3, 3, S, 4, 4, 8, 2, 1);                                     \
+        }                                                                            \
+        if (xt == 4) return CALL(3, 3, S, 4, 4, 8, 1, 4);                            \
+        if (xt == 2) return CALL(3, 3, S, 4, 4, 8, 1, 2);                            \
+        return CALL(3, 3, S, 4, 4, 8, 1, 1);                                         \
+    }
+#define CPOCONV_STRIP_DISPATCH(CALL)                                                 \
+    CPOCONV_STRIP_3X3(CALL, 1)                                                       \
+    CPOCONV_STRIP_3X3(CALL, 2)                                                       \
+    if (g.kh == 5 && g.kw == 5 && g.stride == 1) return CALL(5, 5, 1, 4, 4, 8, 1, 1); \
+    if (g.kh == 7 && g.kw == 7 && g.stride == 2) return CALL(7, 7, 2, 4, 4, 4, 1, 1);
 
 int64_t strip_kernel_partial_bytes(const Geometry &g)
 {
     if (!strip_kernel_supports(g)) return 0;
-#define CPOCONV_STRIP_BYTES(KH, KW, S, TY, TX, G, KPL)                                          \
+#define CPOCONV_STRIP_BYTES(KH, KW, S, TY, TX, G, KPL, XT)                                      \
     [&]() -> int64_t {                                                                          \
-        const StripPlan p = strip_plan<KH, KW, S, TY, TX, G, KPL>(g);                           \
-        return 4 * static_cast<int64_t>(p.slices) * p.Ypad * ((g.Ow + TX - 1) / TX * TX) * g.Kpad * g.N; \
+        const StripPlan p = strip_plan<KH, KW, S, TY, TX, G, KPL, XT>(g);                       \
+        return 4 * static_cast<int64_t>(p.slices) * p.Ypad * ((g.Ow + TX * XT - 1) / (TX * XT) * (TX * XT)) * g.Kpad * g.N; \
     }()
     CPOCONV_STRIP_DISPATCH(CPOCONV_STRIP_BYTES)
 #undef CPOCONV_STRIP_BYTES
@@ -389,8 +424,8 @@ int64_t strip_kernel_partial_bytes(const Geometry &g)
 int launch_sparse_conv_strip(const cpoconv_map &map, const int32_t *indices, const int32_t *mtab, const Geometry &g,
                              const float *wt, float *out, float *partial, BatchStrides bs, hipStream_t stream)
 {
-#define CPOCONV_STRIP_LAUNCH(KH, KW, S, TY, TX, G, KPL) \
-    launch_strip<KH, KW, S, TY, TX, G, KPL>(map, indices, mtab, g, wt, out, partial, bs, stream)
+#define CPOCONV_STRIP_LAUNCH(KH, KW, S, TY, TX, G, KPL, XT) \
+    launch_strip<KH, KW, S, TY, TX, G, KPL, XT>(map, indices, mtab, g, wt, out, partial, bs, stream)
     CPOCONV_STRIP_DISPATCH(CPOCONV_STRIP_LAUNCH)
 #undef CPOCONV_STRIP_LAUNCH
     return CPOCONV_ERR_SHAPE;

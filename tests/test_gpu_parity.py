@@ -287,6 +287,12 @@ BATCH_CASES = [
     # launch and (more than 512 channels) in two
     (3, (400, 20, 22, 3, 3, 3, 1, 1)),
     (2, (600, 19, 37, 2, 3, 3, 1, 0)),
+    # several images of small 3 x 3 maps: strips of two or four tiles per workgroup, stride 1 and 2,
+    # one and two kernels per lane
+    (4, (12, 14, 14, 128, 3, 3, 1, 1)),
+    (4, (18, 13, 9, 70, 3, 3, 2, 1)),
+    (6, (10, 27, 30, 128, 3, 3, 2, 1)),
+    (5, (9, 7, 7, 64, 3, 3, 1, 1)),
 ]
 
 
