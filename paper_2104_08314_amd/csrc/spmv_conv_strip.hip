@@ -6,7 +6,9 @@
 // output columns, all or up to 16/XT * TY output rows) for 64 output kernels and one slice of the
 // input channels; its wavefronts are TY x TX tiles of the strip: row bands, XT tiles side by side.
 // Wide strips (XT > 1) are for small maps: the whole map is then decoded once per workgroup and
-// the staged weights serve up to sixteen wavefronts.
+// the staged weights serve up to sixteen wavefronts.  Maps so small that a strip has fewer than
+// eight tiles share a workgroup between several images of the launch: each image has its own
+// table and patches, the staged weights serve all of them.
 //
 // Per group of G channels
 //   decode   the wavefronts share the NZE chunks (64 NZEs each) of the group's channels: load
@@ -21,6 +23,8 @@
 // No two wavefronts add to the same output, so there is no reduction inside the workgroup.  The
 // tile's sums go to partial[slice][y][x][k] (k fastest: coalesced); a second kernel adds the
 // channel slices in a fixed order and transposes to K x Oh x Ow (one slice: written directly).
+
+#include <algorithm>
 
 #include "common.hpp"
 #include "resolve_ptr.hpp"
@@ -48,7 +52,9 @@ struct StripArgs {
     int32_t slices;           // channel slices across workgroups
     BatchStrides bs;          // image n of the launch: every buffer advanced n strides
     int32_t Ypad, Xpad;
-    int32_t bands;            // row bands per workgroup (wavefronts: bands * XT)
+    int32_t bands;            // row bands per workgroup (wavefronts: bands * XT * imgs)
+    int32_t imgs;             // images sharing a workgroup
+    int32_t n_images;         // images of the launch
     int32_t batch;            // channels per table refill (multiple of G)
     int32_t chunks;           // upper bound of 64-NZE chunks of one channel's strip
     int32_t chunks_magic;     // ceil(2^16 / chunks): item / chunks == (item * magic) >> 16 for item < 1024
@@ -67,7 +73,14 @@ __global__ __launch_bounds__(kMaxBands *kLanes) void spmv_conv_strip_kernel(cons
     constexpr int IT = 4;                      // decode items whose loads are in flight together
 
     const int ngroups = g.Kpad / (kLanes * KPL);   // a wavefront holds KPL kernels per lane
-    const int image = blockIdx.z / (ngroups * a_launch.slices);
+    const int tid = threadIdx.x, lane = lane_id();
+    const int wave_wg = uni(tid / kLanes);           // in a scalar register: everything derived from it stays scalar
+    const int nwaves = a_launch.bands * XT;          // wavefronts of one image
+    const int img_l = wave_wg / nwaves;              // which of the workgroup's images this wavefront works on
+    const int wave = wave_wg - img_l * nwaves;       // wavefront inside the image
+    const int image_raw = (blockIdx.z / (ngroups * a_launch.slices)) * a_launch.imgs + img_l;
+    const bool live = image_raw < a_launch.n_images; // past the launch's last image: only barriers and shared staging
+    const int image = live ? image_raw : 0;
     StripArgs a = a_launch;
     a.da += image * a.bs.da;
     a.in += image * a.bs.indices;
@@ -78,22 +91,23 @@ __global__ __launch_bounds__(kMaxBands *kLanes) void spmv_conv_strip_kernel(cons
     a.out += image * a.bs.out;
 
     extern __shared__ int32_t smem[];
-    // layout: tab[batch][n_types][SPAN] | stage[wavefronts][kStageInts] | wl[G][TAPS][KPL*64] | patch[G][RW][PH]
-    const int nwaves = a.bands * XT;
-    int32_t *tab = smem;
-    int32_t *stage = tab + a.batch * g.n_types * SPAN;
-    float *wl = reinterpret_cast<float *>(stage + nwaves * kStageInts);
-    float *patch = wl + G * TAPS * KPL * kLanes;
+    // layout: tab[imgs][batch][n_types][SPAN] | stage[imgs][wavefronts][kStageInts] | wl[G][TAPS][KPL*64] |
+    //         patch[imgs][G][RW][PH]
+    const int PH = (a.bands * TY - 1) * S + KH;             // patch height: rows behind the workgroup
+    int32_t *tab = smem + img_l * (a.batch * g.n_types * SPAN);
+    int32_t *stage = smem + a.imgs * (a.batch * g.n_types * SPAN) + img_l * (nwaves * kStageInts);
+    float *wl = reinterpret_cast<float *>(smem + a.imgs * (a.batch * g.n_types * SPAN + nwaves * kStageInts));
+    float *patch_all = wl + G * TAPS * KPL * kLanes;
+    float *patch = patch_all + img_l * (G * RW * PH);
 
-    const int tid = threadIdx.x, lane = lane_id();
-    const int wave = uni(tid / kLanes);   // in a scalar register: everything derived from it stays scalar
-    const int nthreads = nwaves * kLanes;
+    const int nthreads = nwaves * kLanes;                   // threads of one image
+    const int tid_img = wave * kLanes + lane;
+    const int nwaves_wg = nwaves * a.imgs;
     const int xt = XT == 1 ? 0 : wave / a.bands, band = wave - xt * a.bands;   // this wavefront's tile of the strip
     const int x0 = blockIdx.x * (TX * XT);                  // first output column of the strip
     const int xw0 = x0 + xt * TX;                           // first output column of this wavefront
     const int yb = blockIdx.y * a.bands * TY;               // first output row of the workgroup
     const int y0 = yb + band * TY;                          // first output row of this wavefront
-    const int PH = (a.bands * TY - 1) * S + KH;             // patch height: rows behind the workgroup
     const int kg = blockIdx.z % ngroups, slice = (blockIdx.z / ngroups) % a.slices;
     const int kbase = kg * kLanes * KPL;
     const int per_slice = (g.C + a.slices - 1) / a.slices;
@@ -125,8 +139,10 @@ __global__ __launch_bounds__(kMaxBands *kLanes) void spmv_conv_strip_kernel(cons
         __syncthreads();   // previous batch's table no longer in use
         // table: DA offset after partition p for the partitions that reach the strip; slot e of
         // (channel, type) holds partition p_lo - 1 + e (clamped: later slots repeat the end)
-        if (a.mtab != nullptr) {
-            for (int idx = tid; idx < nb * g.n_types * SPAN; idx += nthreads) {
+        if (!live) {
+            // nothing to resolve
+        } else if (a.mtab != nullptr) {
+            for (int idx = tid_img; idx < nb * g.n_types * SPAN; idx += nthreads) {
                 const int e = idx % SPAN;
                 const int i = (idx / SPAN) % g.n_types;
                 const int c = cb + idx / (SPAN * g.n_types);
@@ -141,9 +157,9 @@ __global__ __launch_bounds__(kMaxBands *kLanes) void spmv_conv_strip_kernel(cons
             const int ng = min(G, nb - g0);
             // ---- clear the patches of the group (all readers of the previous group are done) ----
             __syncthreads();
-            for (int i = tid; i < ng * RW * PH; i += nthreads) patch[i] = 0.0f;
+            for (int i = tid_img; i < ng * RW * PH; i += nthreads) patch[i] = 0.0f;
             // weights of the group's channels for this workgroup's 64 kernels (coalesced rows of 64)
-            for (int row = wave; row < ng * TAPS; row += nwaves)
+            for (int row = wave_wg; row < ng * TAPS; row += nwaves_wg)
 #pragma unroll
                 for (int kk = 0; kk < KPL; ++kk)
                     wl[(row * KPL + kk) * kLanes + lane] =
@@ -152,7 +168,7 @@ __global__ __launch_bounds__(kMaxBands *kLanes) void spmv_conv_strip_kernel(cons
 
             // ---- decode: work item = (channel of the group, 64-NZE chunk of its main-type range);
             // the loads of IT items are issued before any of them is used ------------------------
-            const int nitems = ng * a.chunks;
+            const int nitems = live ? ng * a.chunks : 0;
             for (int it0 = wave; it0 < nitems; it0 += nwaves * IT) {
                 int idxv[IT], nv[IT];
                 float valv[IT];
@@ -204,7 +220,7 @@ __global__ __launch_bounds__(kMaxBands *kLanes) void spmv_conv_strip_kernel(cons
             __syncthreads();
 
             // ---- apply: every wavefront walks the cells behind its own tile --------------------
-            if (y0 < g.Oh && xw0 < g.Ow) {
+            if (live && y0 < g.Oh && xw0 < g.Ow) {
 #pragma unroll 1
                 for (int gi = 0; gi < ng; ++gi) {
                     const float *pt = patch + gi * RW * PH + xt * (TX * S) * PH + band * TY * S;   // first cell behind the tile
@@ -256,6 +272,7 @@ __global__ __launch_bounds__(kMaxBands *kLanes) void spmv_conv_strip_kernel(cons
         }
     }
 
+    if (!live) return;
     if (a.slices == 1) {
 #pragma unroll
         for (int kk = 0; kk < KPL; ++kk) {
@@ -284,7 +301,7 @@ __global__ __launch_bounds__(kMaxBands *kLanes) void spmv_conv_strip_kernel(cons
 }
 
 struct StripPlan {
-    int bands, row_blocks, slices, batch, chunks, Ypad;
+    int bands, row_blocks, slices, batch, chunks, Ypad, imgs;
     size_t lds;
 };
 
@@ -302,7 +319,10 @@ StripPlan strip_plan(const Geometry &g)
     p.chunks = (RW * g.Ih + kLanes - 1) / kLanes;   // a strip's partitions hold at most RW columns of Ih rows
     // about one workgroup per compute unit (measured best: the workgroups are large), each slice
     // keeping four channels or more
-    const int wgs = ((g.Ow + TX * XT - 1) / (TX * XT)) * p.row_blocks * (g.Kpad / (kLanes * KPL)) * g.N;
+    // images per workgroup: fill the sixteen wavefronts when a strip of the map has few tiles
+    p.imgs = 1;
+    if (XT > 1 && p.bands * XT * 2 <= kMaxBands) p.imgs = std::min(kMaxBands / (p.bands * XT), g.N);
+    const int wgs = ((g.Ow + TX * XT - 1) / (TX * XT)) * p.row_blocks * (g.Kpad / (kLanes * KPL)) * ((g.N + p.imgs - 1) / p.imgs);
     int s = 256 / wgs;
     const int cap = (g.C + 3) / 4;
     if (s > cap) s = cap;
@@ -316,9 +336,9 @@ StripPlan strip_plan(const Geometry &g)
     if (batch < G) batch = G;
     if (batch > 64) batch = 64;
     p.batch = batch;
-    p.lds = (static_cast<size_t>(batch) * g.n_types * SPAN + static_cast<size_t>(p.bands) * XT * kStageInts +
-             static_cast<size_t>(G) * KH * KW * KPL * kLanes +
-             static_cast<size_t>(G) * RW * PH) * 4;
+    p.lds = (p.imgs * (static_cast<size_t>(batch) * g.n_types * SPAN + static_cast<size_t>(p.bands) * XT * kStageInts +
+                       static_cast<size_t>(G) * RW * PH) +
+             static_cast<size_t>(G) * KH * KW * KPL * kLanes) * 4;
     return p;
 }
 
@@ -332,14 +352,15 @@ int launch_strip(const cpoconv_map &map, const int32_t *indices, const int32_t *
     a.da = map.da; a.in = indices; a.mtab = mtab; a.ptr = map.ptr; a.chan_off = map.chan_off; a.wt = wt;
     a.partial = partial; a.out = out;
     a.slices = p.slices; a.Ypad = p.row_blocks * p.bands * TY; a.Xpad = ntx * TX * XT;
-    a.bands = p.bands; a.batch = p.batch; a.chunks = p.chunks;
+    a.bands = p.bands; a.batch = p.batch; a.chunks = p.chunks; a.imgs = p.imgs; a.n_images = g.N;
     a.chunks_magic = (65536 + p.chunks - 1) / p.chunks;
     bs.partial = static_cast<int64_t>(p.slices) * a.Ypad * a.Xpad * g.Kpad;
     a.bs = bs;
     {
         KernelTimer timer("spmv_conv_strip", stream);
         hipLaunchKernelGGL((spmv_conv_strip_kernel<KH, KW, S, TY, TX, G, KPL, XT>),
-                           dim3(ntx, p.row_blocks, (g.Kpad / (kLanes * KPL)) * p.slices * g.N), dim3(p.bands * XT * kLanes), p.lds, stream,
+                           dim3(ntx, p.row_blocks, (g.Kpad / (kLanes * KPL)) * p.slices * ((g.N + p.imgs - 1) / p.imgs)),
+                           dim3(p.bands * XT * p.imgs * kLanes), p.lds, stream,
                            g, a);
     }
     CPOCONV_HIP_TRY(hipGetLastError());
@@ -360,9 +381,8 @@ int strip_xt(const Geometry &g)
 #endif
     if (g.N < CPOCONV_XT_MIN_N || g.kh != 3) return 1;
     const int bands_all = (g.Oh + 3) / 4;
-    // at least eight wavefronts must share the strip for the staging to pay
-    if (bands_all * 4 <= kMaxBands && g.Ow > 8 && bands_all * 4 >= 8) return 4;
-    if (bands_all * 2 <= kMaxBands && g.Ow > 4 && bands_all * 2 >= 8) return 2;
+    if (bands_all * 4 <= kMaxBands && g.Ow > 8) return 4;
+    if (bands_all * 2 <= kMaxBands && g.Ow > 4) return 2;
     return 1;
 }
 
