@@ -289,10 +289,13 @@ BATCH_CASES = [
     (2, (600, 19, 37, 2, 3, 3, 1, 0)),
     # several images of small 3 x 3 maps: strips of two or four tiles per workgroup, stride 1 and 2,
     # one and two kernels per lane
-    (4, (12, 14, 14, 128, 3, 3, 1, 1)),
-    (4, (18, 13, 9, 70, 3, 3, 2, 1)),
-    (6, (10, 27, 30, 128, 3, 3, 2, 1)),
-    (5, (9, 7, 7, 64, 3, 3, 1, 1)),
+    (4, (40, 14, 14, 128, 3, 3, 1, 1)),
+    (8, (36, 13, 9, 70, 3, 3, 2, 1)),             # four images per workgroup
+    (8, (32, 27, 30, 128, 3, 3, 2, 1)),           # two eight-column tiles per strip, two images per workgroup
+    (9, (33, 7, 7, 64, 3, 3, 1, 1)),              # four images per workgroup, the last workgroup with one
+    # several images of wide maps: tiles of eight columns
+    (4, (6, 50, 52, 70, 3, 3, 1, 1)),
+    (4, (5, 46, 47, 128, 3, 3, 1, 1)),
 ]
 
 
