@@ -295,10 +295,13 @@ static int encode_conv_common(const float *act, const cpoconv_shape *shape, int 
     hipStream_t st = static_cast<hipStream_t>(stream);
     // the encoder also leaves the table of resolved ptr offsets: the convolution needs no prologue
     // of its own for a CPO map (a CPS map still has its indices rebuilt by one)
-    const bool table = (algo == CPOCONV_ALGO_CPO || g.top_slot < 0) && sparse_conv_uses_prologue(g);
-    const int erc = launch_encode(act, prod, g, *map, algo, scratch, st, table);
+    // and, for a CPS map, the plain index of every NZE, so that the convolution needs no pass over
+    // IN either; the map itself holds the packed stream as after cps_encode
+    const bool table = sparse_conv_uses_prologue(g);
+    const bool indices = algo == CPOCONV_ALGO_CPS && g.top_slot >= 0;
+    const int erc = launch_encode(act, prod, g, *map, algo, scratch, st, table, indices);
     if (erc != CPOCONV_OK) return erc;
-    return launch_sparse_conv(*map, g, algo, wt, out, scratch, st, table);
+    return launch_sparse_conv(*map, g, algo, wt, out, scratch, st, table, indices);
 }
 
 int cpo_encode_conv(const float *act, const cpoconv_shape *shape, const cpoconv_map *map, const float *wt,

@@ -102,7 +102,8 @@ template <int kMode>
 __global__ __launch_bounds__(kThreads) void encode_kernel(const Geometry g, const float *__restrict__ act_all,
                                                          const Producer prod, const int cps, const int kChunk,
                                                          unsigned long long *__restrict__ ctrl, const cpoconv_map maps,
-                                                         int32_t *__restrict__ mtab_all, const int64_t mtab_stride)
+                                                         int32_t *__restrict__ mtab_all, const int64_t mtab_stride,
+                                                         int32_t *__restrict__ full_all, const int64_t full_stride)
 {
     // image blockIdx.y of the launch: its map is image 0's advanced by the per-image capacities
     const int image = blockIdx.y;
@@ -117,6 +118,8 @@ __global__ __launch_bounds__(kThreads) void encode_kernel(const Geometry g, cons
     map.in += image * maps.in_cap;
     map.chan_off += static_cast<int64_t>(image) * 3 * (g.C + 1);
     map.hdr += image * 8;
+    // for a CPS convolution launched by the same call: the plain index of every NZE, laid out like DA
+    int32_t *__restrict__ full = full_all != nullptr ? full_all + image * full_stride : nullptr;
 
     extern __shared__ float tile[];                    // kChunk x Wt, Wt odd: conflict-free column reads
     __shared__ uint16_t cnt_q[kMaxChunks][kMaxCols];   // NZEs per (row chunk, column), then their
@@ -358,6 +361,7 @@ __global__ __launch_bounds__(kThreads) void encode_kernel(const Geometry g, cons
             const int in_at = in_off + ecol_excl[vi] + ecnt_q[q][vi];
             const int index = static_cast<int>(col_wh[vi]) + (q * kChunk + lane) * g.kw;
             if (nz) map.da[da_at + rank] = v;
+            if (nz && full != nullptr) full[da_at + rank] = index;
             if (vi >= top_begin && vi < top_end) {
                 // set4 of Algorithm 3: the four padded rows 4*(h/4) .. +3
                 const int pattern = static_cast<int>((mask >> (lane & ~3)) & 0xFull);
@@ -402,7 +406,8 @@ __global__ __launch_bounds__(kThreads) void encode_small_kernel(const Geometry g
                                                                const Producer prod, const int cps,
                                                                unsigned long long *__restrict__ ctrl,
                                                                const cpoconv_map maps, int32_t *__restrict__ mtab_all,
-                                                               const int64_t mtab_stride)
+                                                               const int64_t mtab_stride, int32_t *__restrict__ full_all,
+                                                               const int64_t full_stride)
 {
     extern __shared__ float tiles[];                   // per wavefront: H x Wt floats, then 64 ints of ptr staging
     __shared__ int32_t grp[kWaves][3];                 // the group's lengths: ptr, DA, IN per channel
@@ -424,6 +429,7 @@ __global__ __launch_bounds__(kThreads) void encode_small_kernel(const Geometry g
     map.in += image * maps.in_cap;
     map.chan_off += static_cast<int64_t>(image) * 3 * (g.C + 1);
     map.hdr += image * 8;
+    int32_t *__restrict__ full = full_all != nullptr ? full_all + image * full_stride : nullptr;
 
     const int Wt = g.W | 1;
     const int per_wave = g.H * Wt + kLanes;            // floats of LDS per wavefront
@@ -626,6 +632,7 @@ __global__ __launch_bounds__(kThreads) void encode_small_kernel(const Geometry g
         const int rank = __popcll(mask & below);
         const int index = what + h * g.kw;
         if (nz) map.da[at_da + rank] = v;
+        if (nz && full != nullptr) full[at_da + rank] = index;
         const bool packed = on && vi >= top_begin && vi < top_end;
         // set4 of Algorithm 3: the four padded rows 4*(h/4) .. +3
         const int pattern = static_cast<int>((mask >> (h & ~3)) & 0xFull);
@@ -670,8 +677,14 @@ __global__ __launch_bounds__(256) void prepare_weights_kernel(const Geometry g, 
 }  // namespace
 
 int launch_encode(const float *act, const Producer &prod, const Geometry &g, const cpoconv_map &map, int algo,
-                  void *scratch, hipStream_t stream, bool write_table)
+                  void *scratch, hipStream_t stream, bool write_table, bool write_indices)
 {
+    // the plain per-NZE indices, for a CPS convolution launched by the same call (same place and
+    // layout as the convolution's own reconstruction would leave them)
+    int32_t *full = write_indices ? reinterpret_cast<int32_t *>(static_cast<char *>(scratch) + scratch_counts_bytes(g) +
+                                                                scratch_mtab_bytes(g))
+                                  : nullptr;
+    const int64_t fstride = indices_stride(g);
     // the table of resolved ptr offsets, for a convolution launched by the same call
     int32_t *mtab = write_table ? reinterpret_cast<int32_t *>(static_cast<char *>(scratch) + scratch_counts_bytes(g)) : nullptr;
     const int64_t mstride = mtab_stride(g);
@@ -691,17 +704,17 @@ int launch_encode(const float *act, const Producer &prod, const Geometry &g, con
         if (g.C <= kSinglePassChannels) {
             KernelTimer timer("encode", stream);
             hipLaunchKernelGGL(encode_small_kernel<kSinglePass>, grid, dim3(kThreads), lds_small, stream, g, act, prod, cps, ctrl,
-                               map, mtab, mstride);
+                               map, mtab, mstride, full, fstride);
         } else {
             {
                 KernelTimer timer("encode_count", stream);
                 hipLaunchKernelGGL(encode_small_kernel<kPublishOnly>, grid, dim3(kThreads), lds_small, stream, g, act, prod, cps,
-                                   ctrl, map, static_cast<int32_t *>(nullptr), mstride);
+                                   ctrl, map, static_cast<int32_t *>(nullptr), mstride, static_cast<int32_t *>(nullptr), fstride);
             }
             CPOCONV_HIP_TRY(hipGetLastError());
             KernelTimer timer("encode", stream);
             hipLaunchKernelGGL(encode_small_kernel<kPublished>, grid, dim3(kThreads), lds_small, stream, g, act, prod, cps, ctrl,
-                               map, mtab, mstride);
+                               map, mtab, mstride, full, fstride);
         }
         CPOCONV_HIP_TRY(hipGetLastError());
         return CPOCONV_OK;
@@ -709,17 +722,17 @@ int launch_encode(const float *act, const Producer &prod, const Geometry &g, con
     if (g.C <= kSinglePassChannels) {
         KernelTimer timer("encode", stream);
         hipLaunchKernelGGL(encode_kernel<kSinglePass>, dim3(g.C, g.N), dim3(kThreads), lds, stream, g, act, prod, cps, chunk, ctrl, map,
-                           mtab, mstride);
+                           mtab, mstride, full, fstride);
     } else {
         {
             KernelTimer timer("encode_count", stream);
             hipLaunchKernelGGL(encode_kernel<kPublishOnly>, dim3(g.C, g.N), dim3(kThreads), lds, stream, g, act, prod, cps, chunk,
-                               ctrl, map, static_cast<int32_t *>(nullptr), mstride);
+                               ctrl, map, static_cast<int32_t *>(nullptr), mstride, static_cast<int32_t *>(nullptr), fstride);
         }
         CPOCONV_HIP_TRY(hipGetLastError());
         KernelTimer timer("encode", stream);
         hipLaunchKernelGGL(encode_kernel<kPublished>, dim3(g.C, g.N), dim3(kThreads), lds, stream, g, act, prod, cps, chunk, ctrl, map,
-                           mtab, mstride);
+                           mtab, mstride, full, fstride);
     }
     CPOCONV_HIP_TRY(hipGetLastError());
     return CPOCONV_OK;

@@ -385,7 +385,7 @@ bool sparse_conv_uses_prologue(const Geometry &g)
 }
 
 int launch_sparse_conv(const cpoconv_map &map, const Geometry &g, int algo, const float *wt, float *out,
-                       void *scratch, hipStream_t stream, bool table_ready)
+                       void *scratch, hipStream_t stream, bool table_ready, bool indices_ready)
 {
     char *base = static_cast<char *>(scratch);
     int32_t *mtab = reinterpret_cast<int32_t *>(base + scratch_counts_bytes(g));
@@ -406,17 +406,19 @@ int launch_sparse_conv(const cpoconv_map &map, const Geometry &g, int algo, cons
     // 1-4 us faster than a prologue launch; in the register-tile kernel, where many more workgroups
     // would repeat the work, it was slower).  Otherwise, and for the index reconstruction of CPS,
     // a prologue kernel runs first.
-    // (table_ready: the encoder of the same call left the table in the scratch buffer)
-    const bool in_kernel = strip && in_full == nullptr && !table_ready && resolve_in_kernel_ok(g);
+    // (table_ready / indices_ready: the encoder of the same call left the table / the plain CPS
+    // indices in the scratch buffer)
+    const bool expand = in_full != nullptr && !indices_ready;
+    const bool in_kernel = strip && !expand && !table_ready && resolve_in_kernel_ok(g);
     if (in_kernel) mtab = nullptr;
-    if ((tile && !in_kernel && !table_ready) || in_full != nullptr) {
+    if ((tile && !in_kernel && !table_ready) || expand) {
         KernelTimer timer("conv_prologue", stream);
-        if (in_full == nullptr && resolve_in_kernel_ok(g))
+        if (!expand && resolve_in_kernel_ok(g))
             hipLaunchKernelGGL(conv_prologue_wave_kernel, dim3((g.C + kProWaves - 1) / kProWaves, g.N),
                                dim3(kProWaves * kLanes), 0, stream, g, map.ptr, map.chan_off, mtab, bs);
         else
             hipLaunchKernelGGL(conv_prologue_kernel, dim3(g.C, g.N), dim3(kExpThreads), 0, stream, g, map.ptr, map.in,
-                               map.chan_off, mtab, in_full, bs);
+                               map.chan_off, mtab, expand ? in_full : static_cast<int32_t *>(nullptr), bs);
         CPOCONV_HIP_TRY(hipGetLastError());
     }
     float *partial = reinterpret_cast<float *>(base + after_mtab + scratch_indices_bytes(g));

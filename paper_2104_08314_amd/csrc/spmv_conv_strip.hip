@@ -395,7 +395,10 @@ int strip_xt(const Geometry &g)
 // stride-2 layers that write 14 x 14 maps take two such tiles per strip (8.5 -> 7.5).
 inline int strip_wide_xt(const Geometry &g)   // 0: four-column tiles
 {
-    if (g.N < 4 || g.kh != 3) return 0;
+#ifndef CPOCONV_WIDE_MIN_N
+#define CPOCONV_WIDE_MIN_N 4
+#endif
+    if (g.N < CPOCONV_WIDE_MIN_N || g.kh != 3) return 0;
     if (g.stride == 1 && g.Oh * g.Ow >= 2048) return 1;
     if (g.stride == 2 && g.N >= 8 && g.Ow > 8 && g.Ow <= 16 && (g.Oh + 3) / 4 * 2 <= kMaxBands) return 2;
     return 0;
