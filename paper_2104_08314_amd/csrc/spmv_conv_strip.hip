@@ -403,6 +403,24 @@ inline int strip_wide_xt(const Geometry &g)   // 0: four-column tiles
     if (g.stride == 2 && g.N >= 8 && g.Ow > 8 && g.Ow <= 16 && (g.Oh + 3) / 4 * 2 <= kMaxBands) return 2;
     return 0;
 }
+// Four kernels per lane (256 per wavefront): a visited cell then feeds four times the FMAs of its
+// scalar work, and half as many workgroups decode the same NZEs.  It needs 256 kernels or a
+// multiple, several images per launch and at least eight workgroups before any channel slicing
+// (measured per image, 2 -> 4 kernels per lane: 32 images, 256 x 14 x 14 3.6 -> 3.0 us, 512 x 7 x 7
+// 4.0 -> 3.1, 128 x 56 x 56 stride 2 with 256 kernels 12.3 -> 8.8; with fewer than eight workgroups
+// it loses, e.g. 256 x 14 x 14 at four images 8.7 -> 10.3).
+inline bool strip_four_kernels_per_lane(const Geometry &g)
+{
+    if (g.Kpad % 256 != 0 || g.N < 4 || g.kh != 3 || strip_wide_xt(g) != 0) return false;
+    const int xt = strip_xt(g), bands_all = (g.Oh + 3) / 4;
+    const int row_blocks = (bands_all + kMaxBands / xt - 1) / (kMaxBands / xt);
+    const int bands = (bands_all + row_blocks - 1) / row_blocks;
+    int imgs = 1;
+    if (xt > 1 && bands * xt * 2 <= kMaxBands) imgs = std::min(kMaxBands / (bands * xt), static_cast<int>(g.N));
+    const int wgs = ((g.Ow + 4 * xt - 1) / (4 * xt)) * row_blocks * (g.Kpad / 256) * ((g.N + imgs - 1) / imgs);
+    return wgs >= 8;
+}
+
 bool strip_kernel_supports(const Geometry &g)
 {
     if (g.n_types < 1) return false;
@@ -427,14 +445,22 @@ bool strip_kernel_preferred(const Geometry &g)
 
 // 3 x 3 layers whose padded kernel count is a multiple of 128 keep two kernels per lane: the
 // scalar work of a visited cell (bit test, broadcast) then feeds twice the FMAs
+#ifndef CPOCONV_WIDE_KPL1
+#define CPOCONV_WIDE_KPL1 0
+#endif
 #define CPOCONV_STRIP_WIDE(CALL, S, XTW)                                             \
     if (g.kh == 3 && g.kw == 3 && g.stride == S && strip_wide_xt(g) == XTW) {        \
-        if (g.Kpad % 128 == 0) return CALL(3, 3, S, 4, 8, 8, 2, XTW);                \
+        if (g.Kpad % 128 == 0 && !CPOCONV_WIDE_KPL1) return CALL(3, 3, S, 4, 8, 8, 2, XTW); \
         return CALL(3, 3, S, 4, 8, 8, 1, XTW);                                       \
     }
 #define CPOCONV_STRIP_3X3(CALL, S)                                                   \
     if (g.kh == 3 && g.kw == 3 && g.stride == S) {                                   \
         const int xt = strip_xt(g);                                                  \
+        if (strip_four_kernels_per_lane(g)) {                                        \
+            if (xt == 4) return CALL(3, 3, S, 4, 4, 8, 4, 4);                        \
+            if (xt == 2) return CALL(3, 3, S, 4, 4, 8, 4, 2);                        \
+            return CALL(3, 3, S, 4, 4, 8, 4, 1);                                     \
+        }                                                                            \
         if (g.Kpad % 128 == 0) {                                                     \
             if (xt == 4) return CALL(3, 3, S, 4, 4, 8, 2, 4);                        \
             if (xt == 2) return CALL(3, 3, S, 4, 4, 8, 2, 2);                        \

@@ -293,6 +293,12 @@ BATCH_CASES = [
     (8, (36, 13, 9, 70, 3, 3, 2, 1)),             # four images per workgroup
     (8, (32, 27, 30, 128, 3, 3, 2, 1)),           # two eight-column tiles per strip, two images per workgroup
     (9, (33, 7, 7, 64, 3, 3, 1, 1)),              # four images per workgroup, the last workgroup with one
+    # 256 kernels or a multiple, eight workgroups or more: four kernels per lane (strips of 4, 2, 1 tiles)
+    (8, (33, 14, 14, 256, 3, 3, 1, 1)),
+    (16, (32, 7, 7, 512, 3, 3, 1, 1)),
+    (4, (32, 28, 28, 256, 3, 3, 1, 1)),
+    (4, (32, 40, 22, 250, 3, 3, 1, 1)),
+    (4, (32, 80, 22, 256, 3, 3, 2, 1)),
     # several images of wide maps: tiles of eight columns
     (4, (6, 50, 52, 70, 3, 3, 1, 1)),
     (4, (5, 46, 47, 128, 3, 3, 1, 1)),
