@@ -391,18 +391,17 @@ int strip_xt(const Geometry &g)
 }
 
 // Tiles of eight columns (measured with 32 images per launch): on 56 x 56 stride-1 maps the wider
-// tile visits fewer halo cells per output (15.7 -> 13.8 us per image at 128 channels); the
-// stride-2 layers that write 14 x 14 maps take two such tiles per strip (8.5 -> 7.5).
-inline int strip_wide_xt(const Geometry &g)   // 0: four-column tiles
+// tile visits fewer halo cells per output (15.7 -> 13.8 us per image at 128 channels).
+inline int strip_wide_xt(const Geometry &g)   // 0: four-column tiles, else the strip's number of eight-column tiles
 {
 #ifndef CPOCONV_WIDE_MIN_N
 #define CPOCONV_WIDE_MIN_N 4
 #endif
     if (g.N < CPOCONV_WIDE_MIN_N || g.kh != 3) return 0;
     if (g.stride == 1 && g.Oh * g.Ow >= 2048) return 1;
-    if (g.stride == 2 && g.N >= 8 && g.Ow > 8 && g.Ow <= 16 && (g.Oh + 3) / 4 * 2 <= kMaxBands) return 2;
     return 0;
 }
+
 // Four kernels per lane (256 per wavefront): a visited cell then feeds four times the FMAs of its
 // scalar work, and half as many workgroups decode the same NZEs.  It needs 256 kernels or a
 // multiple, several images per launch and at least eight workgroups before any channel slicing
@@ -445,12 +444,9 @@ bool strip_kernel_preferred(const Geometry &g)
 
 // 3 x 3 layers whose padded kernel count is a multiple of 128 keep two kernels per lane: the
 // scalar work of a visited cell (bit test, broadcast) then feeds twice the FMAs
-#ifndef CPOCONV_WIDE_KPL1
-#define CPOCONV_WIDE_KPL1 0
-#endif
 #define CPOCONV_STRIP_WIDE(CALL, S, XTW)                                             \
     if (g.kh == 3 && g.kw == 3 && g.stride == S && strip_wide_xt(g) == XTW) {        \
-        if (g.Kpad % 128 == 0 && !CPOCONV_WIDE_KPL1) return CALL(3, 3, S, 4, 8, 8, 2, XTW); \
+        if (g.Kpad % 128 == 0) return CALL(3, 3, S, 4, 8, 8, 2, XTW);                \
         return CALL(3, 3, S, 4, 8, 8, 1, XTW);                                       \
     }
 #define CPOCONV_STRIP_3X3(CALL, S)                                                   \
@@ -472,7 +468,6 @@ bool strip_kernel_preferred(const Geometry &g)
     }
 #define CPOCONV_STRIP_DISPATCH(CALL)                                                 \
     CPOCONV_STRIP_WIDE(CALL, 1, 1)                                                   \
-    CPOCONV_STRIP_WIDE(CALL, 2, 2)                                                   \
     CPOCONV_STRIP_3X3(CALL, 1)                                                       \
     CPOCONV_STRIP_3X3(CALL, 2)                                                       \
     if (g.kh == 5 && g.kw == 5 && g.stride == 1) return CALL(5, 5, 1, 4, 4, 8, 1, 1); \

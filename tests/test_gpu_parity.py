@@ -291,7 +291,7 @@ BATCH_CASES = [
     # one and two kernels per lane
     (4, (40, 14, 14, 128, 3, 3, 1, 1)),
     (8, (36, 13, 9, 70, 3, 3, 2, 1)),             # four images per workgroup
-    (8, (32, 27, 30, 128, 3, 3, 2, 1)),           # two eight-column tiles per strip, two images per workgroup
+    (8, (32, 27, 30, 128, 3, 3, 2, 1)),           # stride 2, four tiles per strip
     (9, (33, 7, 7, 64, 3, 3, 1, 1)),              # four images per workgroup, the last workgroup with one
     # 256 kernels or a multiple, eight workgroups or more: four kernels per lane (strips of 4, 2, 1 tiles)
     (8, (33, 14, 14, 256, 3, 3, 1, 1)),
