@@ -317,13 +317,14 @@ StripPlan strip_plan(const Geometry &g)
     const int PH = (p.bands * TY - 1) * S + KH;
     p.Ypad = p.row_blocks * p.bands * TY;
     p.chunks = (RW * g.Ih + kLanes - 1) / kLanes;   // a strip's partitions hold at most RW columns of Ih rows
-    // about one workgroup per compute unit (measured best: the workgroups are large), each slice
-    // keeping four channels or more
     // images per workgroup: fill the sixteen wavefronts when a strip of the map has few tiles
     p.imgs = 1;
     if (XT > 1 && p.bands * XT * 2 <= kMaxBands) p.imgs = std::min(kMaxBands / (p.bands * XT), g.N);
     const int wgs = ((g.Ow + TX * XT - 1) / (TX * XT)) * p.row_blocks * (g.Kpad / (kLanes * KPL)) * ((g.N + p.imgs - 1) / p.imgs);
-    int s = 256 / wgs;
+    // channel slices: one workgroup of fourteen wavefronts or more per compute unit, or as many
+    // smaller ones as give fourteen wavefronts (measured best), each slice keeping four channels or more
+    const int nw = p.bands * XT * p.imgs;
+    int s = (256 * std::max(14, nw)) / (wgs * nw);
     const int cap = (g.C + 3) / 4;
     if (s > cap) s = cap;
     if (s > kMaxSlices) s = kMaxSlices;
