@@ -27,7 +27,11 @@ namespace {
 
 constexpr int kTabBytes = 8 * 1024;  // LDS budget of the per-channel range table
 constexpr int kGroup = 4;
-constexpr int kChunksAhead = 4;
+// 64-NZE chunks of a channel whose loads are issued ahead.  The scatter of every such chunk is
+// compiled branch-free (predicated), so chunks past the channel's NZEs still cost their arithmetic:
+// two instead of four took 1.5 us off the 14 x 14 and 28 x 28 layers at batch 1; further chunks
+// of dense channels are loaded on demand.
+constexpr int kChunksAhead = 2;
 constexpr int kMaxSlices = 16;
 
 __device__ __forceinline__ int lane_id() { return threadIdx.x & (kLanes - 1); }
