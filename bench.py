@@ -450,6 +450,8 @@ def main():
                     help="images per launch of the batched supplement (0 to skip it)")
     ap.add_argument("--no-cold", action="store_true", help="skip the cold-cache timing of the stages")
     ap.add_argument("--no-chain", action="store_true", help="skip the chained-layers supplement")
+    ap.add_argument("--chain-only", action="store_true",
+                    help="run only the chained-layers supplement, with --batch images per launch, and print it")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also launch a plain elementwise kernel that reads and writes 256 MiB, five times: the "
                          "known-size kernel that rocprofv3 FETCH_SIZE / WRITE_SIZE readings are scaled by")
@@ -474,6 +476,10 @@ def main():
             torch.mul(src, 1.0, out=dst)
         torch.cuda.synchronize()
         del src, dst
+
+    if args.chain_only:
+        print(json.dumps(chain_supplement(api, torch, workloads, max(args.batch, 1), reps=10)))
+        return
 
     spec = workloads.layers(args.config)[0]
     run, row, times, fig = measure_layer(api, torch, workloads, spec, reps=max(args.steps, 20), warm=max(args.warmup, 5))

@@ -18,7 +18,7 @@ from collections import defaultdict
 
 csv.field_size_limit(1 << 30)
 
-OURS = ("encode_kernel", "conv_prologue_kernel", "spmv_conv_tile_kernel", "spmv_conv_strip_kernel",
+OURS = ("encode_kernel", "encode_small_kernel", "conv_prologue_kernel", "conv_prologue_wave_kernel", "zero_fill_kernel", "spmv_conv_tile_kernel", "spmv_conv_strip_kernel",
         "spmv_conv_lds_kernel", "reduce_transpose_kernel", "im2col_lower_kernel", "im2col_lower_bf16_kernel",
         "gemm_f32_kernel", "gemm_bf16_kernel", "splitk_reduce_kernel", "prepare_weights_kernel")
 
@@ -92,9 +92,16 @@ def main():
         whole = sum(r[3] for r in rows)
         lines.append("kernel-trace statistics (durations in microseconds)")
         lines.append("%-34s %8s %10s %10s %10s %7s" % ("kernel", "calls", "avg_us", "min_us", "max_us", "share%"))
+        shared = defaultdict(int)
+        for r in rows:
+            shared[r[0]] += 1
         for name, calls, avg, tot, mn, mx, full in sorted(rows, key=lambda r: -r[3]):
             if not any(o in full for o in OURS):
                 continue
+            if shared[name] > 1:   # several instantiations of one kernel template: tell them apart
+                m = re.search(r"<([^>]*)>", full.replace("(anonymous namespace)::", ""))
+                if m:
+                    name += "<" + m.group(1).replace(" ", "") + ">"
             lines.append("%-34s %8d %10.2f %10.2f %10.2f %7.2f" % (name, calls, avg / 1e3, mn / 1e3, mx / 1e3, 100 * tot / whole))
         other = sum(r[3] for r in rows if not any(o in r[6] for o in OURS))
         lines.append("%-34s %8s %10s %10s %10s %7.2f" % ("(kernels of other libraries)", "", "", "", "", 100 * other / whole))
