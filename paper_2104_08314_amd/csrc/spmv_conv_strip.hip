@@ -36,6 +36,7 @@ namespace {
 constexpr int kMaxBands = 16;        // wavefronts (row bands) per workgroup
 constexpr int kStripTabBytes = 6 * 1024;
 constexpr int kMaxSlices = 32;
+constexpr size_t kLdsBytes = 160 * 1024;   // LDS of a compute unit
 
 __device__ __forceinline__ int lane_id() { return threadIdx.x & (kLanes - 1); }
 __device__ __forceinline__ int uni(int v) { return __builtin_amdgcn_readfirstlane(v); }
@@ -320,6 +321,17 @@ StripPlan strip_plan(const Geometry &g)
     // images per workgroup: fill the sixteen wavefronts when a strip of the map has few tiles
     p.imgs = 1;
     if (XT > 1 && p.bands * XT * 2 <= kMaxBands) p.imgs = std::min(kMaxBands / (p.bands * XT), g.N);
+    int batch = kStripTabBytes / (g.n_types * SPAN * 4);
+    batch = batch / G * G;
+    if (batch < G) batch = G;
+    if (batch > 64) batch = 64;
+    p.batch = batch;
+    auto lds_bytes = [&](int imgs) {
+        return (imgs * (static_cast<size_t>(batch) * g.n_types * SPAN + static_cast<size_t>(p.bands) * XT * kStageInts +
+                        static_cast<size_t>(G) * RW * PH) +
+                static_cast<size_t>(G) * KH * KW * KPL * kLanes) * 4;
+    };
+    while (p.imgs > 1 && lds_bytes(p.imgs) > kLdsBytes) --p.imgs;   // everything has to fit the compute unit's LDS
     const int wgs = ((g.Ow + TX * XT - 1) / (TX * XT)) * p.row_blocks * (g.Kpad / (kLanes * KPL)) * ((g.N + p.imgs - 1) / p.imgs);
     // channel slices: one workgroup of fourteen wavefronts or more per compute unit, or as many
     // smaller ones as give fourteen wavefronts (measured best), each slice keeping four channels or more
@@ -332,14 +344,7 @@ StripPlan strip_plan(const Geometry &g)
     // no empty slices: with ceil(C / s) channels each, fewer slices may already cover the layer
     const int per_slice = (g.C + s - 1) / s;
     p.slices = (g.C + per_slice - 1) / per_slice;
-    int batch = kStripTabBytes / (g.n_types * SPAN * 4);
-    batch = batch / G * G;
-    if (batch < G) batch = G;
-    if (batch > 64) batch = 64;
-    p.batch = batch;
-    p.lds = (p.imgs * (static_cast<size_t>(batch) * g.n_types * SPAN + static_cast<size_t>(p.bands) * XT * kStageInts +
-                       static_cast<size_t>(G) * RW * PH) +
-             static_cast<size_t>(G) * KH * KW * KPL * kLanes) * 4;
+    p.lds = lds_bytes(p.imgs);
     return p;
 }
 
