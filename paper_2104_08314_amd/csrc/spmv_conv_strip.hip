@@ -450,7 +450,15 @@ bool strip_kernel_preferred(const Geometry &g)
 
 // 3 x 3 layers whose padded kernel count is a multiple of 128 keep two kernels per lane: the
 // scalar work of a visited cell (bit test, broadcast) then feeds twice the FMAs
+// (seven columns where they divide the map's width: 56-wide maps, 13.9 -> 12.7 us per image at 128
+// channels and 32 images, 6.0 -> 5.6 at 64 channels)
+#define CPOCONV_STRIP_TX7(CALL)                                                      \
+    if (g.kh == 3 && g.kw == 3 && g.stride == 1 && strip_wide_xt(g) == 1 && g.Ow % 7 == 0) { \
+        if (g.Kpad % 128 == 0) return CALL(3, 3, 1, 4, 7, 8, 2, 1);                  \
+        return CALL(3, 3, 1, 4, 7, 8, 1, 1);                                         \
+    }
 #define CPOCONV_STRIP_WIDE(CALL, S, XTW)                                             \
+    CPOCONV_STRIP_TX7(CALL)                                                          \
     if (g.kh == 3 && g.kw == 3 && g.stride == S && strip_wide_xt(g) == XTW) {        \
         if (g.Kpad % 128 == 0) return CALL(3, 3, S, 4, 8, 8, 2, XTW);                \
         return CALL(3, 3, S, 4, 8, 8, 1, XTW);                                       \

@@ -299,9 +299,11 @@ BATCH_CASES = [
     (4, (32, 28, 28, 256, 3, 3, 1, 1)),
     (4, (32, 40, 22, 250, 3, 3, 1, 1)),
     (4, (32, 80, 22, 256, 3, 3, 2, 1)),
-    # several images of wide maps: tiles of eight columns
+    # several images of wide maps: tiles of eight columns, or seven where seven divides the width
     (4, (6, 50, 52, 70, 3, 3, 1, 1)),
     (4, (5, 46, 47, 128, 3, 3, 1, 1)),
+    (4, (6, 47, 49, 70, 3, 3, 1, 1)),
+    (4, (5, 56, 56, 128, 3, 3, 1, 1)),
 ]
 
 
