@@ -463,9 +463,17 @@ bool strip_kernel_preferred(const Geometry &g)
         if (g.Kpad % 128 == 0) return CALL(3, 3, S, 4, 8, 8, 2, XTW);                \
         return CALL(3, 3, S, 4, 8, 8, 1, XTW);                                       \
     }
+// (28-wide outputs without four kernels per lane: two seven-column tiles per strip divide the map
+// exactly: 128 x 28 x 28 4.6 -> 4.1 us per image at 32 images)
+#define CPOCONV_TX7X2_CASES(CALL, S)                                                 \
+        if (xt == 2 && g.Ow % 14 == 0 && !strip_four_kernels_per_lane(g)) {          \
+            if (g.Kpad % 128 == 0) return CALL(3, 3, S, 4, 7, 8, 2, 2);              \
+            return CALL(3, 3, S, 4, 7, 8, 1, 2);                                     \
+        }
 #define CPOCONV_STRIP_3X3(CALL, S)                                                   \
     if (g.kh == 3 && g.kw == 3 && g.stride == S) {                                   \
         const int xt = strip_xt(g);                                                  \
+        CPOCONV_TX7X2_CASES(CALL, S)                                                 \
         if (strip_four_kernels_per_lane(g)) {                                        \
             if (xt == 4) return CALL(3, 3, S, 4, 4, 8, 4, 4);                        \
             if (xt == 2) return CALL(3, 3, S, 4, 4, 8, 4, 2);                        \

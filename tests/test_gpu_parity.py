@@ -290,6 +290,8 @@ BATCH_CASES = [
     # several images of small 3 x 3 maps: strips of two or four tiles per workgroup, stride 1 and 2,
     # one and two kernels per lane
     (4, (40, 14, 14, 128, 3, 3, 1, 1)),
+    (4, (33, 28, 28, 70, 3, 3, 1, 1)),            # two seven-column tiles per strip
+    (4, (32, 55, 56, 128, 3, 3, 2, 1)),           # the same at stride 2, two kernels per lane
     (8, (36, 13, 9, 70, 3, 3, 2, 1)),             # four images per workgroup
     (8, (32, 27, 30, 128, 3, 3, 2, 1)),           # stride 2, four tiles per strip
     (9, (33, 7, 7, 64, 3, 3, 1, 1)),              # four images per workgroup, the last workgroup with one
