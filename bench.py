@@ -443,8 +443,8 @@ def main():
     ap.add_argument("--warmup", type=int, default=20)
     ap.add_argument("--config", type=int, default=2, help="workload whose first layer is timed")
     ap.add_argument("--all-layers", action="store_true",
-                    help="also measure every layer of the five workloads (per-layer report on stderr and "
-                         "in gpurun_out/layers.json)")
+                    help="also measure every layer of the five workloads (per-layer report on stderr)")
+    ap.add_argument("--layers-json", default=None, help="with --all-layers: also write the per-layer rows to this file")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--batch", type=int, default=32,
                     help="images per launch of the batched supplement (0 to skip it)")
@@ -575,9 +575,9 @@ def main():
                   file=sys.stderr, flush=True)
             del r
             torch.cuda.empty_cache()
-        os.makedirs(os.path.join(ROOT, "gpurun_out"), exist_ok=True)
-        with open(os.path.join(ROOT, "gpurun_out", "layers.json"), "w") as f:
-            json.dump(rows, f, indent=1)
+        if args.layers_json:
+            with open(args.layers_json, "w") as f:
+                json.dump(rows, f, indent=1)
         cfg5 = [r for r in rows if r["layer"].startswith("cfg5")]
         result["config5_end_to_end_us"] = {
             "all_im2col_f32": round(sum(r["us"]["im2col_f32"] for r in cfg5), 1),
