@@ -295,6 +295,8 @@ BATCH_CASES = [
     (8, (36, 13, 9, 70, 3, 3, 2, 1)),             # four images per workgroup
     (8, (32, 27, 30, 128, 3, 3, 2, 1)),           # stride 2, four tiles per strip
     (9, (33, 7, 7, 64, 3, 3, 1, 1)),              # four images per workgroup, the last workgroup with one
+    (4, (32, 29, 31, 64, 3, 3, 2, 0)),            # wide strips without padding (three-entry NOP segments)
+    (4, (32, 12, 12, 64, 3, 3, 1, 2)),            # padding wider than the overlap: a single overlap type
     # 256 kernels or a multiple, eight workgroups or more: four kernels per lane (strips of 4, 2, 1 tiles)
     (8, (33, 14, 14, 256, 3, 3, 1, 1)),
     (16, (32, 7, 7, 512, 3, 3, 1, 1)),
