@@ -29,11 +29,11 @@ namespace {
 
 constexpr int kThreads = 512;
 constexpr int kWaves = kThreads / kLanes;
-// Padded rows handled per pass (lane = row inside the chunk): 64, or 32 for maps so wide that
-// 64 rows would not fit the LDS tile.  Both are multiples of 4, so a set4 never straddles chunks.
-constexpr int kChunkWide = 32;
-constexpr int kMaxChunks = (CPOCONV_MAX_I + kChunkWide - 1) / kChunkWide;
-constexpr size_t kTileBytesMax = 40 * 1024;
+// Padded rows handled per pass (lane = row inside the chunk): 64, a multiple of 4, so a set4 never
+// straddles chunks.  The widest map's chunk (64 rows of 257 floats) takes 66 KB of LDS; chunks of 32
+// rows for wide maps kept the tile within 40 KB but made the 224 x 224 map twice as many passes
+// (104 -> 72 us at three channels).
+constexpr int kMaxChunks = (CPOCONV_MAX_I + kLanes - 1) / kLanes;
 
 __device__ __forceinline__ int lane_id() { return threadIdx.x & (kLanes - 1); }
 __device__ __forceinline__ int wave_id() { return threadIdx.x / kLanes; }
@@ -164,7 +164,7 @@ __global__ __launch_bounds__(kThreads) void encode_kernel(const Geometry g, cons
     // ---- counts: every wavefront takes kChunk / 8 rows of the chunk (lane = column in stream
     // order) and leaves its part of every column's row bitmap in LDS; one thread per column then
     // puts the eight parts together ------------------------------------------------------------
-    const int rows_per_wave = kChunk / kWaves;   // 8, or 4 for wide maps
+    const int rows_per_wave = kChunk / kWaves;   // 8
     for (int q = 0; q < nchunks; ++q) {
         if (q > 0) {
             __syncthreads();   // every thread is done with the previous chunk
@@ -690,7 +690,7 @@ int launch_encode(const float *act, const Producer &prod, const Geometry &g, con
     const int64_t mstride = mtab_stride(g);
     const int cps = algo == CPOCONV_ALGO_CPS ? 1 : 0;
     const size_t row_bytes = static_cast<size_t>(g.W | 1) * sizeof(float);
-    const int chunk = kLanes * row_bytes <= kTileBytesMax ? kLanes : kChunkWide;   // 32 rows always fit: W <= 256
+    const int chunk = kLanes;
     const size_t lds = chunk * row_bytes;
     unsigned long long *ctrl = static_cast<unsigned long long *>(scratch);
     const size_t small_tile = static_cast<size_t>(g.H) * (g.W | 1) * sizeof(float);
