@@ -225,3 +225,14 @@ def test_chain_workload_batched_bf16_comparator(api):
     act1, _, _ = workloads.make_chain(1)
     _say("[case] chain workload, 7 layers, bf16 im2col, 2 images")
     _check_chain(api, np.stack([act0, act1]), shapes, w_np[:7], b_np[:7], [api.ALGO_IM2COL] * 7, tol=BF16_TOL, precision=1)
+
+
+def test_chain_workload_eight_images(api):
+    """Eight images through the whole chained workload: the batched launch shapes of the sparse
+    kernels (wide strips, workgroups shared by images, several kernels per lane) on chained data."""
+    specs = workloads.chain_specs()
+    shapes = [s.shape_tuple for s in specs]
+    act0, w_np, b_np = workloads.make_chain()
+    acts = np.stack([act0] + [workloads.make_activation(specs[0], m) for m in range(1, 8)])
+    _say("[case] chain workload, 8 images, all CPO")
+    _check_chain(api, acts, shapes, w_np, b_np, [api.ALGO_CPO] * len(specs))
