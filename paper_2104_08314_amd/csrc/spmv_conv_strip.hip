@@ -3,8 +3,8 @@
 // CPO streams are column-major: inside a channel and overlap type the NZEs follow the
 // partitions (columns) and, inside a column, the rows.  ptr therefore delimits exactly the NZEs
 // of a strip of output columns, for all rows at once.  A workgroup owns such a strip (XT*TX
-// output columns, all or up to 16/XT * TY output rows) for 64 output kernels and one slice of the
-// input channels; its wavefronts are TY x TX tiles of the strip: row bands, XT tiles side by side.
+// output columns, all or up to 16/XT * TY output rows) for 64*KPL output kernels (KPL per lane)
+// and one slice of the input channels; its wavefronts are TY x TX tiles of the strip: row bands, XT tiles side by side.
 // Wide strips (XT > 1) are for small maps: the whole map is then decoded once per workgroup and
 // the staged weights serve up to sixteen wavefronts.  Maps so small that a strip has fewer than
 // eight tiles share a workgroup between several images of the launch: each image has its own
@@ -16,10 +16,11 @@
 //            pointers), split the index into padded row and column inside the partition, and
 //            drop the value at its cell of the channel's LDS patch of the padded input;
 //   apply    every wavefront reads the cells behind its TY x TX tile one per lane, takes a ballot
-//            of the non-zero ones and walks them in a fully unrolled loop: a clear bit costs three
-//            scalar instructions, a set bit broadcasts the value from its lane (lanes are the 64
-//            output kernels, so the NZE is a scalar operand) and issues the kh*(pType+1) FMAs of
-//            convSpMv that land in the tile, with compile-time registers for sums and weights.
+//            of the non-zero ones and walks them in a fully unrolled loop: a clear bit costs a
+//            scalar bit test and an untaken branch, a set bit broadcasts the value from its lane
+//            (lanes are output kernels, so the NZE is a scalar operand) and issues the
+//            kh*(pType+1) FMAs of convSpMv that land in the tile, KPL times, with compile-time
+//            registers for sums and weights.
 // No two wavefronts add to the same output, so there is no reduction inside the workgroup.  The
 // tile's sums go to partial[slice][y][x][k] (k fastest: coalesced); a second kernel adds the
 // channel slices in a fixed order and transposes to K x Oh x Ow (one slice: written directly).
