@@ -283,6 +283,7 @@ BATCH_CASES = [
     (5, (33, 21, 37, 4, 3, 3, 1, 0)),
     (40, (4, 8, 8, 5, 3, 3, 1, 1)),               # enough images that no layer is sliced over channels
     (2, (3, 70, 33, 4, 3, 3, 1, 1)),
+    (1024, (2, 5, 6, 3, 3, 3, 1, 1)),             # the largest batch the calls take
     # mid-sized maps with >= 1024 channel-images: the one-wavefront-per-channel encoder, in one
     # launch and (more than 512 channels) in two
     (3, (400, 20, 22, 3, 3, 3, 1, 1)),
