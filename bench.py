@@ -73,6 +73,7 @@ class LayerRun:
         api.cpoconv_prepare_weights(self.w, self.shape, self.buf.wt)   # once per layer, untimed
         torch.cuda.synchronize()
         b = self.buf
+        self.map16 = api.EncodedMap(self.shape, in_bits=16)   # compact map: int16 IN entries
         self.stages = {
             "cpo_encode": lambda: api.cpo_encode(self.act, self.shape, b.cpo, b.scratch),
             "cpo_conv": lambda: api.cpo_conv(b.cpo, self.shape, b.wt, b.out, b.scratch),
@@ -81,6 +82,7 @@ class LayerRun:
             # a layer in one call (encode + convolution): what the selection compares with im2col
             "cpo_layer": lambda: api.cpo_encode_conv(self.act, self.shape, b.cpo, b.wt, b.out, b.scratch),
             "cps_layer": lambda: api.cps_encode_conv(self.act, self.shape, b.cps, b.wt, b.out, b.scratch),
+            "cpo_layer_in16": lambda: api.cpo_encode_conv(self.act, self.shape, self.map16, b.wt, b.out, b.scratch),
             "im2col_f32": lambda: api.im2col_conv(self.act, self.shape, self.w, b.lowered, b.out, 0),
             "im2col_bf16": lambda: api.im2col_conv(self.act, self.shape, self.w, b.lowered, b.out, 1),
         }
@@ -134,12 +136,18 @@ def algorithmic_figures(spec, lens, act_np):
         "cr_cps": S / float(ptr + nnz + lens["in_cps"]),
         "cr_cpo_with_side_band": S / float(ptr + 2 * nnz + 3 * (C + 1)),
         "cr_cps_with_side_band": S / float(ptr + nnz + lens["in_cps"] + 3 * (C + 1)),
+        # in bytes, against the fp32 lowered matrix: int32 IN entries, and the compact map's int16 ones
+        "cr_bytes_cpo": 4.0 * S / (4 * ptr + 4 * nnz + 4 * nnz),
+        "cr_bytes_cpo_in16": 4.0 * S / (4 * ptr + 4 * nnz + 2 * nnz),
+        "cr_bytes_cps_in16": 4.0 * S / (4 * ptr + 4 * nnz + 2 * lens["in_cps"]),
     }
 
 
 def stage_roofline(name, us, fig):
     """Roofline entry of one stage: the bound that binds and the achieved fraction of it."""
     t = us * 1e-6
+    if name.endswith("_in16"):       # the compact map: same work, narrower IN entries
+        name = name[:-len("_in16")]
     if name.endswith("_layer"):      # encode + convolution in one call: both stages' bytes, the convolution's flops
         algo = name[:3]
         b = fig[algo + "_encode_bytes"] + fig[algo + "_conv_bytes"]
@@ -250,6 +258,8 @@ def measure_layer(api, torch, workloads, spec, reps, warm):
         "cr_cpo": fig["cr_cpo"], "cr_cps": fig["cr_cps"],
         "cr_cpo_with_side_band": fig["cr_cpo_with_side_band"],
         "cr_cps_with_side_band": fig["cr_cps_with_side_band"],
+        "cr_bytes_cpo": fig["cr_bytes_cpo"], "cr_bytes_cpo_in16": fig["cr_bytes_cpo_in16"],
+        "cr_bytes_cps_in16": fig["cr_bytes_cps_in16"],
         "roofline": {k: stage_roofline(k, v, fig) for k, v in times.items()},
     }
     return run, row, times, fig

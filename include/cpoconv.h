@@ -71,8 +71,16 @@ typedef struct {
  *   chan_off     3*(C+1) int32: offset of every channel in ptr, then in da, then in in, each
  *                list closed by the total.  Side band for parallel readers (Algorithm 2
  *                leaves "indexing relative to each channel" out).
- *   hdr          8 int32: |ptr|, |DA|, |IN|, algorithm (CPOCONV_ALGO_CPO / _CPS), C, Ow, 0, and a
- *                failure flag (0, or 1 if the encoder gave up: see cpo_encode).
+ *   hdr          8 int32: |ptr|, |DA|, |IN|, algorithm (CPOCONV_ALGO_CPO / _CPS), C, Ow, the width
+ *                of an IN entry in bits (32 or 16), and a failure flag (0, or 1 if the encoder
+ *                gave up: see cpo_encode).
+ *   in_bits      width of the IN entries: 0 or 32 for int32; 16 for a compact map whose `in`
+ *                points at int16 entries (in_cap still counts entries).  Every IN entry is an
+ *                index below (H + 2 pad) * kw <= 2816, the negative of one, or a row pattern
+ *                below 16, so the narrow stream holds exactly the same values; the paper counts
+ *                the size of the structure in elements (SI, space complexity), the narrow
+ *                entries shrink it in bytes.  Encoders write, convolutions read, the width the
+ *                map declares.  Any other value: CPOCONV_ERR_ALGO.
  */
 typedef struct {
     int32_t *ptr;
@@ -83,6 +91,7 @@ typedef struct {
     int64_t in_cap;
     int32_t *chan_off;
     int32_t *hdr;
+    int32_t in_bits;
 } cpoconv_map;
 
 /* Buffer sizes for one layer shape (elements unless named bytes). */

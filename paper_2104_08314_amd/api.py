@@ -38,7 +38,7 @@ class _Map(ctypes.Structure):
         ("ptr", ctypes.c_void_p), ("ptr_cap", ctypes.c_int64),
         ("da", ctypes.c_void_p), ("da_cap", ctypes.c_int64),
         ("ind", ctypes.c_void_p), ("in_cap", ctypes.c_int64),
-        ("chan_off", ctypes.c_void_p), ("hdr", ctypes.c_void_p),
+        ("chan_off", ctypes.c_void_p), ("hdr", ctypes.c_void_p), ("in_bits", ctypes.c_int32),
     ]
 
 
@@ -180,17 +180,18 @@ class EncodedMap:
     """Device buffers of one encoded activation map (cpoconv_map of the C ABI), or of a batch of
     n_images maps: then every buffer holds n_images regions of the per-image capacity."""
 
-    def __init__(self, shape, device="cuda:0", n_images=1, sizes=None):
+    def __init__(self, shape, device="cuda:0", n_images=1, sizes=None, in_bits=32):
         import torch
 
         self.shape = make_shape(shape)
         self.n_images = int(n_images)
+        self.in_bits = int(in_bits)     # 32, or 16 for a compact map with int16 IN entries
         sz = cpoconv_sizes(self.shape) if sizes is None else sizes   # sizes: capacities larger than the shape's own
         self.sizes = sz
         n = self.n_images
         self.ptr = torch.empty(n * sz.ptr_cap, dtype=torch.int32, device=device)
         self.da = torch.empty(n * sz.da_cap, dtype=torch.float32, device=device)
-        self.ind = torch.empty(n * sz.in_cap, dtype=torch.int32, device=device)
+        self.ind = torch.empty(n * sz.in_cap, dtype=torch.int16 if self.in_bits == 16 else torch.int32, device=device)
         self.chan_off = torch.empty(n * sz.chan_off_len, dtype=torch.int32, device=device)
         self.hdr = torch.zeros(n * 8, dtype=torch.int32, device=device)
 
@@ -199,9 +200,9 @@ class EncodedMap:
         sz = self.sizes
         return _Map(ctypes.c_void_p(self.ptr.data_ptr() + 4 * image * sz.ptr_cap), sz.ptr_cap,
                     ctypes.c_void_p(self.da.data_ptr() + 4 * image * sz.da_cap), sz.da_cap,
-                    ctypes.c_void_p(self.ind.data_ptr() + 4 * image * sz.in_cap), sz.in_cap,
+                    ctypes.c_void_p(self.ind.data_ptr() + self.ind.element_size() * image * sz.in_cap), sz.in_cap,
                     ctypes.c_void_p(self.chan_off.data_ptr() + 4 * image * 3 * (self.shape.C + 1)),
-                    ctypes.c_void_p(self.hdr.data_ptr() + 4 * image * 8))
+                    ctypes.c_void_p(self.hdr.data_ptr() + 4 * image * 8), self.in_bits)
 
     def view(self, shape) -> "EncodedMap":
         """The same buffers seen as the map of another layer shape (a chain's layers share one map;
@@ -289,7 +290,7 @@ def cpoconv_map_header_to_host(m: EncodedMap, stream=None, image=0):
 class LayerBuffers:
     """All device buffers one layer (or a batch of n_images inputs of it) needs, allocated once with PyTorch."""
 
-    def __init__(self, shape, device="cuda:0", n_images=1):
+    def __init__(self, shape, device="cuda:0", n_images=1, in_bits=32):
         import torch
 
         self.shape = make_shape(shape)
@@ -297,8 +298,8 @@ class LayerBuffers:
         sz = cpoconv_batch_sizes(self.shape, self.n_images)
         self.sizes = sz
         self.device = device
-        self.cpo = EncodedMap(self.shape, device, self.n_images)
-        self.cps = EncodedMap(self.shape, device, self.n_images)
+        self.cpo = EncodedMap(self.shape, device, self.n_images, in_bits=in_bits)
+        self.cps = EncodedMap(self.shape, device, self.n_images, in_bits=in_bits)
         self.scratch = torch.empty(sz.scratch_bytes, dtype=torch.uint8, device=device)
         cpoconv_scratch_init(self.scratch)
         self.wt = torch.empty(sz.wt_len, dtype=torch.float32, device=device)
@@ -439,7 +440,7 @@ class Chain:
     tensors; biases[i] (device tensor or None) and relu_in[i] describe what is applied to layer i's
     input; methods[i] is ALGO_IM2COL / ALGO_CPO / ALGO_CPS (set_methods changes them later)."""
 
-    def __init__(self, shapes, weights, biases, relu_in, methods, n_images=1, precision=0, device="cuda:0"):
+    def __init__(self, shapes, weights, biases, relu_in, methods, n_images=1, precision=0, device="cuda:0", in_bits=32):
         import torch
 
         self.shapes = [make_shape(s) for s in shapes]
@@ -460,7 +461,7 @@ class Chain:
             self.table[i].out = self.outs[i].data_ptr()
         sz = cpoconv_chain_sizes(self.table, self.n_images)
         self.sizes = sz
-        self.map = EncodedMap(self.shapes[0], device, self.n_images, sizes=sz)
+        self.map = EncodedMap(self.shapes[0], device, self.n_images, sizes=sz, in_bits=in_bits)
         self.scratch = torch.empty(sz.scratch_bytes, dtype=torch.uint8, device=device)
         cpoconv_scratch_init(self.scratch)
         self.lowered = torch.empty(sz.lowered_bytes, dtype=torch.uint8, device=device)

@@ -214,6 +214,7 @@ static int encode_common(const float *act, const cpoconv_shape *shape, int n_ima
 {
     if (!act || !shape || !map || !scratch) return CPOCONV_ERR_NULL;
     if (!map->ptr || !map->da || !map->in || !map->chan_off || !map->hdr) return CPOCONV_ERR_NULL;
+    if (map->in_bits != 0 && map->in_bits != 16 && map->in_bits != 32) return CPOCONV_ERR_ALGO;
     Geometry g;
     const int rc = batch_geometry(shape, n_images, &g);
     if (rc != CPOCONV_OK) return rc;
@@ -258,6 +259,7 @@ static int conv_common(const cpoconv_map *map, const cpoconv_shape *shape, int n
 {
     if (!map || !shape || !wt || !out || !scratch) return CPOCONV_ERR_NULL;
     if (!map->ptr || !map->da || !map->in || !map->chan_off || !map->hdr) return CPOCONV_ERR_NULL;
+    if (map->in_bits != 0 && map->in_bits != 16 && map->in_bits != 32) return CPOCONV_ERR_ALGO;
     Geometry g;
     const int rc = batch_geometry(shape, n_images, &g);
     if (rc != CPOCONV_OK) return rc;
@@ -286,6 +288,7 @@ static int encode_conv_common(const float *act, const cpoconv_shape *shape, int 
 {
     if (!act || !shape || !map || !wt || !out || !scratch) return CPOCONV_ERR_NULL;
     if (!map->ptr || !map->da || !map->in || !map->chan_off || !map->hdr) return CPOCONV_ERR_NULL;
+    if (map->in_bits != 0 && map->in_bits != 16 && map->in_bits != 32) return CPOCONV_ERR_ALGO;
     Geometry g;
     const int rc = batch_geometry(shape, n_images, &g);
     if (rc != CPOCONV_OK) return rc;
@@ -463,6 +466,7 @@ int cpoconv_chain_forward(const float *act, const cpoconv_chain_layer *layers, i
         } else {
             if (!maps || !scratch) return CPOCONV_ERR_NULL;
             if (!maps->ptr || !maps->da || !maps->in || !maps->chan_off || !maps->hdr) return CPOCONV_ERR_NULL;
+            if (maps->in_bits != 0 && maps->in_bits != 16 && maps->in_bits != 32) return CPOCONV_ERR_ALGO;
             if (maps->ptr_cap < one.ptr_cap || maps->da_cap < one.da_cap || maps->in_cap < one.in_cap) return CPOCONV_ERR_SMALL;
             if (scratch_bytes < one.scratch_bytes) return CPOCONV_ERR_SMALL;
         }

@@ -4,6 +4,8 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
+#include <type_traits>
+
 #include "cpoconv.h"
 
 namespace cpoconv {
@@ -38,7 +40,26 @@ struct BatchStrides {
     int64_t ptr, da, in;   // streams and side band: the per-image capacities of the map
     int64_t indices;       // what the convolution reads as IN: the stream itself or the rebuilt CPS indices
     int64_t mtab, partial, out;
+    int32_t map_in16;      // the map's IN stream holds int16 entries
+    int32_t indices16;     // so does what the convolution reads as IN (the rebuilt CPS indices never do)
 };
+
+// IN entries: int32, or int16 in a compact map (same values).  The stream pointer is typed int32
+// either way; offsets count entries.
+__device__ __forceinline__ int load_index(const int32_t *in, int64_t n, int in16)
+{
+    return in16 ? static_cast<int>(reinterpret_cast<const int16_t *>(in)[n]) : in[n];
+}
+__device__ __forceinline__ void store_index(int32_t *in, int64_t n, int v, int in16)
+{
+    if (in16) reinterpret_cast<int16_t *>(in)[n] = static_cast<int16_t>(v);
+    else in[n] = v;
+}
+template <typename P> __device__ __forceinline__ P *index_advance(P *in, int64_t entries, int in16)
+{
+    using Byte = typename std::conditional<std::is_const<P>::value, const char, char>::type;
+    return reinterpret_cast<P *>(reinterpret_cast<Byte *>(in) + entries * (in16 ? 2 : 4));
+}
 
 // What a kernel that reads a dense map applies to every value on the way in: the end of the layer
 // that produced the map (its bias, then the ReLU that makes the input of Eq. 1 sparse), so the

@@ -115,7 +115,8 @@ __global__ __launch_bounds__(kThreads) void encode_kernel(const Geometry g, cons
     cpoconv_map map = maps;
     map.ptr += image * maps.ptr_cap;
     map.da += image * maps.da_cap;
-    map.in += image * maps.in_cap;
+    const int in16 = maps.in_bits == 16 ? 1 : 0;
+    map.in = index_advance(maps.in, image * maps.in_cap, in16);
     map.chan_off += static_cast<int64_t>(image) * 3 * (g.C + 1);
     map.hdr += image * 8;
     // for a CPS convolution launched by the same call: the plain index of every NZE, laid out like DA
@@ -285,7 +286,7 @@ __global__ __launch_bounds__(kThreads) void encode_kernel(const Geometry g, cons
             map.hdr[3] = cps ? CPOCONV_ALGO_CPS : CPOCONV_ALGO_CPO;
             map.hdr[4] = g.C;
             map.hdr[5] = g.Ow;
-            map.hdr[6] = 0;
+            map.hdr[6] = in16 ? 16 : 32;
         }
     }
 
@@ -371,9 +372,9 @@ __global__ __launch_bounds__(kThreads) void encode_kernel(const Geometry g, cons
                 // first NZE of the set: its index (negated unless a pattern follows);
                 // second NZE: the pattern, or its own negated index
                 const int entry = __popc(pattern) >= 3 ? (r == 0 ? index : pattern) : -index;
-                if (emit) map.in[in_at + erank] = entry;
+                if (emit) store_index(map.in, in_at + erank, entry, in16);
             } else {
-                if (nz) map.in[in_at + rank] = index;
+                if (nz) store_index(map.in, in_at + rank, index, in16);
             }
         }
     }
@@ -426,7 +427,8 @@ __global__ __launch_bounds__(kThreads) void encode_small_kernel(const Geometry g
     cpoconv_map map = maps;
     map.ptr += image * maps.ptr_cap;
     map.da += image * maps.da_cap;
-    map.in += image * maps.in_cap;
+    const int in16 = maps.in_bits == 16 ? 1 : 0;
+    map.in = index_advance(maps.in, image * maps.in_cap, in16);
     map.chan_off += static_cast<int64_t>(image) * 3 * (g.C + 1);
     map.hdr += image * 8;
     int32_t *__restrict__ full = full_all != nullptr ? full_all + image * full_stride : nullptr;
@@ -551,7 +553,7 @@ __global__ __launch_bounds__(kThreads) void encode_small_kernel(const Geometry g
             map.hdr[3] = cps ? CPOCONV_ALGO_CPS : CPOCONV_ALGO_CPO;
             map.hdr[4] = g.C;
             map.hdr[5] = g.Ow;
-            map.hdr[6] = 0;
+            map.hdr[6] = in16 ? 16 : 32;
         }
     }
 
@@ -642,9 +644,9 @@ __global__ __launch_bounds__(kThreads) void encode_small_kernel(const Geometry g
         const int erank = __popcll(emits & below);
         const int entry = __popc(pattern) >= 3 ? (r == 0 ? index : pattern) : -index;
         if (packed) {
-            if (emit) map.in[at_in + erank] = entry;
+            if (emit) store_index(map.in, at_in + erank, entry, in16);
         } else if (nz) {
-            map.in[at_in + rank] = index;
+            store_index(map.in, at_in + rank, index, in16);
         }
     }
 }

@@ -68,7 +68,7 @@ __global__ __launch_bounds__(kExpThreads) void conv_prologue_kernel(const Geomet
     __shared__ int32_t wave_a[kExpThreads / kLanes], wave_b[kExpThreads / kLanes];
     const int image = blockIdx.y;
     const int32_t *__restrict__ ptr = ptr_all + image * bs.ptr;
-    const int32_t *__restrict__ in = in_all + image * bs.in;
+    const int32_t *__restrict__ in = index_advance(in_all, image * bs.in, bs.map_in16);
     const int32_t *__restrict__ chan_off = chan_off_all + static_cast<int64_t>(image) * 3 * (g.C + 1);
     int32_t *__restrict__ mtab = mtab_all + image * bs.mtab;
     int32_t *__restrict__ in_full = in_full_all ? in_full_all + image * bs.indices : nullptr;
@@ -112,7 +112,7 @@ __global__ __launch_bounds__(kExpThreads) void conv_prologue_kernel(const Geomet
     // NZEs of the overlap-kw type: it is the highest type, so it closes the channel
     const int top_count = da1 - top_base;
     const int lower = nnz - top_count;  // NZEs of the other types: their IN entries are plain
-    for (int i = tid; i < lower; i += kExpThreads) in_full[da0 + i] = in[in0 + i];
+    for (int i = tid; i < lower; i += kExpThreads) in_full[da0 + i] = load_index(in, in0 + i, bs.map_in16);
     if (top_count == 0) return;
 
     const int e0 = in0 + lower, n_entries = in1 - e0;
@@ -121,7 +121,7 @@ __global__ __launch_bounds__(kExpThreads) void conv_prologue_kernel(const Geomet
     for (int base = 0; base < n_entries; base += kExpThreads) {
         const int e = base + tid;
         const bool valid = e < n_entries;
-        const int entry = valid ? in[e0 + e] : -1;
+        const int entry = valid ? load_index(in, e0 + e, bs.map_in16) : -1;
         // inclusive max scan of "position if negative"
         int m = wave_inclusive_max(entry < 0 ? e : -1);
         if (lane == kLanes - 1) wave_a[wave] = m;
@@ -130,7 +130,7 @@ __global__ __launch_bounds__(kExpThreads) void conv_prologue_kernel(const Geomet
         for (int w = 0; w < wave; ++w) prev = max(prev, wave_a[w]);
         const int last_neg = max(m, prev);
         const bool is_index = valid && entry >= 0 && (((e - last_neg - 1) & 1) == 0);
-        const int pattern = (is_index && e + 1 < n_entries) ? in[e0 + e + 1] : 0;
+        const int pattern = (is_index && e + 1 < n_entries) ? load_index(in, e0 + e + 1, bs.map_in16) : 0;
         const int emits = !valid ? 0 : (entry < 0 ? 1 : (is_index ? __popc(pattern) : 0));
         int s = wave_inclusive_sum(emits);
         if (lane == kLanes - 1) wave_b[wave] = s;
@@ -177,7 +177,7 @@ __global__ __launch_bounds__(kConvThreads) void spmv_conv_lds_kernel(const Geome
     const int image = blockIdx.z / ngroups;
     const int32_t *__restrict__ ptr = ptr_all + image * bs.ptr;
     const float *__restrict__ da = da_all + image * bs.da;
-    const int32_t *__restrict__ in = in_all + image * bs.indices;
+    const int32_t *__restrict__ in = index_advance(in_all, image * bs.indices, bs.indices16);
     const int32_t *__restrict__ chan_off = chan_off_all + static_cast<int64_t>(image) * 3 * (g.C + 1);
     float *__restrict__ out = out_all + image * bs.out;
     extern __shared__ float smem[];
@@ -252,7 +252,7 @@ __global__ __launch_bounds__(kConvThreads) void spmv_conv_lds_kernel(const Geome
                 for (int n0 = beg; n0 < end; n0 += kLanes) {
                     const int n = n0 + lane;
                     const bool valid = n < end;
-                    const int idx = valid ? in[base + n] : 0;
+                    const int idx = valid ? load_index(in, base + n, bs.indices16) : 0;
                     const float v = valid ? da[base + n] : 0.0f;
                     const int h = idx / g.kw, wh = idx - h * g.kw;   // padded row, column in partition
                     const int qh = h / s, rh = h - qh * s;
@@ -395,10 +395,13 @@ int launch_sparse_conv(const cpoconv_map &map, const Geometry &g, int algo, cons
     BatchStrides bs;
     bs.ptr = map.ptr_cap; bs.da = map.da_cap; bs.in = map.in_cap; bs.indices = map.in_cap;
     bs.mtab = mtab_stride(g); bs.partial = 0; bs.out = static_cast<int64_t>(g.K) * g.Oh * g.Ow;
+    bs.map_in16 = map.in_bits == 16 ? 1 : 0;
+    bs.indices16 = bs.map_in16;
     if (algo == CPOCONV_ALGO_CPS && g.top_slot >= 0) {
         in_full = reinterpret_cast<int32_t *>(base + after_mtab);
         indices = in_full;
         bs.indices = indices_stride(g);
+        bs.indices16 = 0;
     }
     const bool strip = strip_kernel_preferred(g) || (strip_kernel_supports(g) && !tile_kernel_supports(g));
     const bool tile = strip || tile_kernel_supports(g);

@@ -85,7 +85,7 @@ __global__ __launch_bounds__(kMaxBands *kLanes) void spmv_conv_strip_kernel(cons
     const int image = live ? image_raw : 0;
     StripArgs a = a_launch;
     a.da += image * a.bs.da;
-    a.in += image * a.bs.indices;
+    a.in = index_advance(a.in, image * a.bs.indices, a.bs.indices16);
     if (a.mtab != nullptr) a.mtab += image * a.bs.mtab;
     a.ptr += image * a.bs.ptr;
     a.chan_off += static_cast<int64_t>(image) * 3 * (g.C + 1);
@@ -186,7 +186,7 @@ __global__ __launch_bounds__(kMaxBands *kLanes) void spmv_conv_strip_kernel(cons
                         const int first = uni(row[0]), last = uni(row[phi - plo_main + 1]);
                         const int n = first + ch * kLanes + lane;
                         nv[u] = n;
-                        if (n < last) { idxv[u] = a.in[n]; valv[u] = a.da[n]; }
+                        if (n < last) { idxv[u] = load_index(a.in, n, a.bs.indices16); valv[u] = a.da[n]; }
                     }
                 }
 #pragma unroll
@@ -214,7 +214,7 @@ __global__ __launch_bounds__(kMaxBands *kLanes) void spmv_conv_strip_kernel(cons
                         for (int n0 = f; n0 < l; n0 += kLanes) {
                             const int n = n0 + lane;
                             const bool ok = n < l;
-                            scatter(ok ? a.in[n] : -1, ok ? a.da[n] : 0.0f, n, bound, p_lo, pt);
+                            scatter(ok ? load_index(a.in, n, a.bs.indices16) : -1, ok ? a.da[n] : 0.0f, n, bound, p_lo, pt);
                         }
                     }
                 }

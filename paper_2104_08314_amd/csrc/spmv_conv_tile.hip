@@ -77,7 +77,7 @@ __global__ __launch_bounds__(NW *kLanes) void spmv_conv_tile_kernel(const Geomet
     const int image = blockIdx.z / (ngroups * a_launch.slices);
     TileArgs a = a_launch;
     a.da += image * a.bs.da;
-    a.in += image * a.bs.indices;
+    a.in = index_advance(a.in, image * a.bs.indices, a.bs.indices16);
     a.mtab += image * a.bs.mtab;
     a.partial += image * a.bs.partial;
     a.out += image * a.bs.out;
@@ -136,7 +136,7 @@ __global__ __launch_bounds__(NW *kLanes) void spmv_conv_tile_kernel(const Geomet
                     for (int ch = 0; ch < MAXC; ++ch) {
                         const int n = first[gi] + ch * kLanes + lane;
                         const bool ok = n < last[gi];
-                        idxr[gi][ch] = ok ? a.in[n] : -1;
+                        idxr[gi][ch] = ok ? load_index(a.in, n, a.bs.indices16) : -1;
                         valr[gi][ch] = ok ? a.da[n] : 0.0f;
                     }
                 }
@@ -183,7 +183,7 @@ __global__ __launch_bounds__(NW *kLanes) void spmv_conv_tile_kernel(const Geomet
                     for (int n0 = first[gi] + MAXC * kLanes; n0 < last[gi]; n0 += kLanes) {
                         const int n = n0 + lane;
                         const bool ok = n < last[gi];
-                        scatter(ok ? a.in[n] : -1, ok ? a.da[n] : 0.0f, n, bound, p_lo, pt);
+                        scatter(ok ? load_index(a.in, n, a.bs.indices16) : -1, ok ? a.da[n] : 0.0f, n, bound, p_lo, pt);
                     }
                 }
                 // the lower overlap types (edge columns): few NZEs, loaded on demand
@@ -199,7 +199,7 @@ __global__ __launch_bounds__(NW *kLanes) void spmv_conv_tile_kernel(const Geomet
                     for (int n0 = f; n0 < l; n0 += kLanes) {
                         const int n = n0 + lane;
                         const bool ok = n < l;
-                        scatter(ok ? a.in[n] : -1, ok ? a.da[n] : 0.0f, n, bound, p_lo, pt);
+                        scatter(ok ? load_index(a.in, n, a.bs.indices16) : -1, ok ? a.da[n] : 0.0f, n, bound, p_lo, pt);
                     }
                 }
             }

@@ -199,3 +199,14 @@ def test_chain_sizes_and_argument_checks():
     assert lib.cpo_encode_relu(None, None, ctypes.byref(good), 1, ctypes.byref(big), one, huge, None) == api.ERR_NULL
     assert lib.cps_encode_relu(one, None, ctypes.byref(good), 0, ctypes.byref(big), one, huge, None) == api.ERR_SHAPE
     assert lib.im2col_conv_relu(one, None, ctypes.byref(good), 1, one, one, one, 5, None) == api.ERR_ALGO
+
+
+def test_map_index_width_is_validated():
+    lib = api.lib()
+    good = api.Shape(6, 10, 12, 9, 3, 3, 1, 1)
+    one, huge = ctypes.c_void_p(256), ctypes.c_int64(1 << 40)
+    for bits, want in ((8, api.ERR_ALGO), (64, api.ERR_ALGO), (-16, api.ERR_ALGO)):
+        m = api._Map(256, 1 << 20, 256, 1 << 20, 256, 1 << 20, 256, 256, bits)
+        assert lib.cpo_encode(one, ctypes.byref(good), ctypes.byref(m), one, huge, None) == want
+        assert lib.cps_conv(ctypes.byref(m), ctypes.byref(good), one, one, one, huge, None) == want
+        assert lib.cpo_encode_conv(one, ctypes.byref(good), ctypes.byref(m), one, one, one, huge, None) == want

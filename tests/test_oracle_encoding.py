@@ -431,3 +431,17 @@ def test_kw_1_streams_are_the_special_case_of_the_si(shape):
         assert np.array_equal(enc.da, np.array(da, np.float32))
     assert np.array_equal(oracle.sparse_conv(oracle.cpo_encode(act, shape), w), oracle.conv_direct(act, w, shape)) or \
         np.allclose(oracle.sparse_conv(oracle.cpo_encode(act, shape), w), oracle.conv_direct(act, w, shape), rtol=0, atol=1e-5)
+
+
+def test_every_in_entry_fits_sixteen_bits():
+    """A compact map stores IN as int16.  Largest entry: the index of the last padded row and the
+    last column of a partition, (Ih - 1) * kw + kw - 1 with Ih <= 256 and kw <= 11; patterns are
+    below 16; CPS negates indices.  Checked on the tallest maps the library takes."""
+    assert 255 * 11 + 10 < 2 ** 15
+    for shape in [(2, 250, 9, 3, 3, 3, 1, 3), (1, 246, 12, 2, 11, 11, 1, 5), (2, 256, 7, 2, 5, 5, 2, 0)]:
+        act, _ = workloads.random_case(5, *shape, zero_frac=0.3)
+        for m in (oracle.cpo_encode(act, shape), oracle.cps_encode(act, shape)):
+            assert m.ind.size and int(np.abs(m.ind).max()) < 2 ** 15
+            assert np.array_equal(m.ind.astype(np.int16).astype(np.int32), m.ind)
+        Ih, kw = shape[1] + 2 * shape[7], shape[5]
+        assert int(oracle.cpo_encode(act, shape).ind.max()) <= (Ih - 1) * kw + kw - 1
