@@ -236,3 +236,37 @@ def test_chain_workload_eight_images(api):
     acts = np.stack([act0] + [workloads.make_activation(specs[0], m) for m in range(1, 8)])
     _say("[case] chain workload, 8 images, all CPO")
     _check_chain(api, acts, shapes, w_np, b_np, [api.ALGO_CPO] * len(specs))
+
+
+def test_chain_replays_in_a_hip_graph(api):
+    """A captured cpoconv_chain_forward (kernel launches only) replays on new inputs and gives,
+    bit for bit, what the eager call gives; eager calls between the replays share its scratch."""
+    acts, shapes, w_np, b_np = _small_chain(41, 2)
+    ws = [torch.from_numpy(w).cuda() for w in w_np]
+    bs = [None if b is None else torch.from_numpy(b).cuda() for b in b_np]
+    methods = [api.ALGO_CPO, api.ALGO_IM2COL, api.ALGO_CPS, api.ALGO_CPO]
+    chain = api.Chain(shapes, ws, bs, [b is not None for b in b_np], methods, n_images=2)
+    act = torch.from_numpy(acts).cuda()
+    chain.forward(act)
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    _say("[case] chain graph capture")
+    with torch.cuda.graph(graph):
+        chain.forward(act)
+    rng = np.random.default_rng(42)
+    for rnd in range(3):
+        new = np.maximum(rng.standard_normal(acts.shape), 0).astype(np.float32)
+        act.copy_(torch.from_numpy(new))            # eager work between the replays
+        chain.forward(act)
+        torch.cuda.synchronize()
+        eager = [o.clone() for o in chain.outs]
+        for o in chain.outs:
+            o.fill_(float("nan"))
+        _say(f"[step] chain replay {rnd}")
+        graph.replay()
+        torch.cuda.synchronize()
+        for a, b in zip(eager, chain.outs):
+            assert torch.equal(a, b)
+        table = [(s, w, b, b is not None) for s, w, b in zip(shapes, w_np, b_np)]
+        ref = oracle.chain_forward(new[0], table)[-1]
+        assert float(np.abs(chain.outs[-1][0].cpu().numpy() - ref).max()) <= 4 * FP32_TOL * float(np.abs(ref).max())
