@@ -579,12 +579,22 @@ def main():
             _, sel = offline_selection(api, torch, workloads, r, s, reps=10)
             lrow["selection"] = sel
             rows.append(lrow)
-            print(f"{s.name:24s} nnz={lrow['nnz']:7d} enc {lrow['us']['cpo_encode']:6.1f} conv {lrow['us']['cpo_conv']:6.1f} "
-                  f"cpo {lrow['cpo_total_us']:6.1f} cps {lrow['cps_total_us']:6.1f} im2col {lrow['us']['im2col_f32']:8.1f} bf16 {lrow['us']['im2col_bf16']:8.1f} "
-                  f"CR {lrow['cr_cpo']:5.1f}/{lrow['cr_cps']:5.1f} pick {sel['favour_time']}/{sel['favour_space']}",
-                  file=sys.stderr, flush=True)
             del r
             torch.cuda.empty_cache()
+            tail = ""
+            if args.batch > 1:      # the same layer with --batch images per launch, per image
+                bsup = batch_supplement(api, torch, workloads, s, args.batch, reps=5)
+                pi = bsup["per_image_us"]
+                lrow["batched"] = {"n_images": args.batch, "per_image_us": pi,
+                                   "cpo_total_per_image_us": bsup["cpo_total_per_image_us"],
+                                   "speedup_cpo_vs_im2col_f32": bsup["speedup_cpo_vs_im2col_f32"]}
+                tail = (f" | x{args.batch}: cpo {bsup['cpo_total_per_image_us']:5.1f} im2col {pi['im2col_f32']:5.1f} "
+                        f"bf16 {pi['im2col_bf16']:5.1f}")
+                torch.cuda.empty_cache()
+            print(f"{s.name:24s} nnz={lrow['nnz']:7d} enc {lrow['us']['cpo_encode']:6.1f} conv {lrow['us']['cpo_conv']:6.1f} "
+                  f"cpo {lrow['cpo_total_us']:6.1f} cps {lrow['cps_total_us']:6.1f} im2col {lrow['us']['im2col_f32']:8.1f} bf16 {lrow['us']['im2col_bf16']:8.1f} "
+                  f"CR {lrow['cr_cpo']:5.1f}/{lrow['cr_cps']:5.1f} pick {sel['favour_time']}/{sel['favour_space']}" + tail,
+                  file=sys.stderr, flush=True)
         if args.layers_json:
             with open(args.layers_json, "w") as f:
                 json.dump(rows, f, indent=1)
@@ -598,6 +608,15 @@ def main():
             "layers_cpo_selected": sum(r["selection"]["favour_time"] == "cpo" for r in cfg5),
             "layers_cps_selected": sum(r["selection"]["favour_space"] == "cps" for r in cfg5),
         }
+        if args.batch > 1:
+            per = [(r["batched"]["cpo_total_per_image_us"], r["batched"]["per_image_us"]["im2col_f32"]) for r in cfg5]
+            result["config5_end_to_end_us"]["batched"] = {
+                "n_images": args.batch,
+                "all_im2col_f32_per_image": round(sum(i for _, i in per), 1),
+                "all_cpo_per_image": round(sum(c for c, _ in per), 1),
+                "hybrid_per_image": round(sum(min(c, i) for c, i in per), 1),
+                "layers_cpo_faster": sum(c < i for c, i in per),
+            }
     print(json.dumps(result))
 
 
