@@ -377,16 +377,16 @@ int launch_strip(const cpoconv_map &map, const int32_t *indices, const int32_t *
 
 }  // namespace
 
+// Images per launch from which the batched launch shapes below are taken.
+constexpr int kBatchedFromImages = 4;
+
 // Column tiles per workgroup.  With several images per launch there are workgroups enough, and the
 // small 3 x 3 maps gain from wide strips: 14 x 14 outputs are one strip of four tiles by four bands
 // (every NZE decoded once per workgroup, weights staged once for sixteen wavefronts), 28 x 28
 // outputs strips of two tiles by seven bands.
 int strip_xt(const Geometry &g)
 {
-#ifndef CPOCONV_XT_MIN_N
-#define CPOCONV_XT_MIN_N 4
-#endif
-    if (g.N < CPOCONV_XT_MIN_N || g.kh != 3 || g.C < 32) return 1;
+    if (g.N < kBatchedFromImages || g.kh != 3 || g.C < 32) return 1;
     const int bands_all = (g.Oh + 3) / 4;
     int xt = 1;
     if (bands_all * 4 <= kMaxBands && g.Ow > 8) xt = 4;
@@ -401,10 +401,7 @@ int strip_xt(const Geometry &g)
 // tile visits fewer halo cells per output (15.7 -> 13.8 us per image at 128 channels).
 inline int strip_wide_xt(const Geometry &g)   // 0: four-column tiles, else the strip's number of eight-column tiles
 {
-#ifndef CPOCONV_WIDE_MIN_N
-#define CPOCONV_WIDE_MIN_N 4
-#endif
-    if (g.N < CPOCONV_WIDE_MIN_N || g.kh != 3) return 0;
+    if (g.N < kBatchedFromImages || g.kh != 3) return 0;
     if (g.stride == 1 && g.Oh * g.Ow >= 2048) return 1;
     return 0;
 }
@@ -417,7 +414,7 @@ inline int strip_wide_xt(const Geometry &g)   // 0: four-column tiles, else the 
 // it loses, e.g. 256 x 14 x 14 at four images 8.7 -> 10.3).
 inline bool strip_four_kernels_per_lane(const Geometry &g)
 {
-    if (g.Kpad % 256 != 0 || g.N < 4 || g.kh != 3 || strip_wide_xt(g) != 0) return false;
+    if (g.Kpad % 256 != 0 || g.N < kBatchedFromImages || g.kh != 3 || strip_wide_xt(g) != 0) return false;
     const int xt = strip_xt(g), bands_all = (g.Oh + 3) / 4;
     const int row_blocks = (bands_all + kMaxBands / xt - 1) / (kMaxBands / xt);
     const int bands = (bands_all + row_blocks - 1) / row_blocks;
