@@ -332,7 +332,10 @@ def batch_supplement(api, torch, workloads, spec, n_images, reps):
         tf = flops / (kern[conv_kernel] * 1e-6) / 1e12
         out["spmv_kernel"] = {"kernel": conv_kernel, "bound": "alu", "achieved": round(tf, 2), "peak": FP32_VECTOR_PEAK_TFLOPS,
                               "unit": "TFLOP/s", "frac": round(tf / FP32_VECTOR_PEAK_TFLOPS, 4),
-                              "algorithmic_flops": flops}
+                              "algorithmic_flops": flops,
+                              "algorithmic_bytes": 8 * nnz + 4 * w.numel() + 4 * buf.out.numel(),
+                              # HBM bytes per launch from the rocprofv3 counter runs of this very launch shape, if recorded
+                              "traffic": traffic_from_profiles("%s@%dimages" % (conv_kernel, n_images))}
     return out
 
 
@@ -462,6 +465,8 @@ def main():
     ap.add_argument("--no-chain", action="store_true", help="skip the chained-layers supplement")
     ap.add_argument("--chain-only", action="store_true",
                     help="run only the chained-layers supplement, with --batch images per launch, and print it")
+    ap.add_argument("--batch-only", action="store_true",
+                    help="run only the batched supplement of the --config layer, with --batch images per launch, and print it")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also launch a plain elementwise kernel that reads and writes 256 MiB, five times: the "
                          "known-size kernel that rocprofv3 FETCH_SIZE / WRITE_SIZE readings are scaled by")
@@ -492,6 +497,9 @@ def main():
         return
 
     spec = workloads.layers(args.config)[0]
+    if args.batch_only:
+        print(json.dumps(batch_supplement(api, torch, workloads, spec, max(args.batch, 1), reps=10)))
+        return
     run, row, times, fig = measure_layer(api, torch, workloads, spec, reps=max(args.steps, 20), warm=max(args.warmup, 5))
     sel_times, selection = offline_selection(api, torch, workloads, run, spec, reps=20)
 

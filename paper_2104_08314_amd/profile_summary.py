@@ -79,6 +79,7 @@ def main():
                     help="directory of a --pmc run with other counters (repeat): per kernel and grid size, the mean of every counter")
     ap.add_argument("--copy-bytes", type=float, help="bytes the calibration kernel reads (= bytes it writes)")
     ap.add_argument("--command", action="append", default=[], help="full command line of a run (repeat)")
+    ap.add_argument("--key-suffix", default="", help="appended to the kernel names of the traffic_bytes_per_launch lines (e.g. @32images)")
     ap.add_argument("--title", default="rocprofv3 summary")
     ap.add_argument("--out", required=True)
     a = ap.parse_args()
@@ -140,7 +141,7 @@ def main():
                                                              wk[0] if wk else float("nan"), b))
         lines.append("")
         for k, b in traffic.items():
-            lines.append("traffic_bytes_per_launch[%s]: %.0f" % (k, b))
+            lines.append("traffic_bytes_per_launch[%s%s]: %.0f" % (k, a.key_suffix, b))
         lines.append("")
     if a.counters:
         table = defaultdict(lambda: defaultdict(lambda: [0.0, 0]))
