@@ -70,7 +70,7 @@ typedef struct {
  *                da_cap and in_cap >= C*H*W.
  *   chan_off     3*(C+1) int32: offset of every channel in ptr, then in da, then in in, each
  *                list closed by the total.  Side band for parallel readers (Algorithm 2
- *                leaves "indexing relative to each channel" out).
+ *                is written without the per-channel offsets into the streams).
  *   hdr          8 int32: |ptr|, |DA|, |IN|, algorithm (CPOCONV_ALGO_CPO / _CPS), C, Ow, the width
  *                of an IN entry in bits (32 or 16), and a failure flag (0, or 1 if the encoder
  *                gave up: see cpo_encode).
@@ -143,8 +143,8 @@ int cps_encode(const float *act, const cpoconv_shape *shape, const cpoconv_map *
 
 /*
  * Re-lays weights K x C x kh x kw as C x kh x kw x round_up(K,64) (kernel index fastest,
- * zero filled) for cpo_conv / cps_conv: "the kernel is transformed to a row-major vector"
- * (Section 3.3), here once per layer for all kernels.  wt: sizes.wt_len floats.
+ * zero filled) for cpo_conv / cps_conv: Section 3.3 flattens each kernel row by row into a
+ * vector; here that happens once per layer, for all kernels.  wt: sizes.wt_len floats.
  * Errors: NULL, SHAPE, HIP.
  */
 int cpoconv_prepare_weights(const float *weights, const cpoconv_shape *shape, float *wt,

@@ -146,9 +146,9 @@ static float padded(const float *act, const orc_shape *s, int c, int h, int j)
 /*        p, or -1 when no column of this type is first seen in p (Section 3.3: B, C, E  */
 /*        are -1 and D repeats 5 in the worked example).  With VALID padding at stride 1 */
 /*        the NOP type is the three entries [0, n_first_col, n_first_col + n_last_col]   */
-/*        and has no NPF form (Algorithm 1, NOP block; SI: "size of NOP is 3").          */
+/*        and has no NPF form (Algorithm 1, NOP block; SI, size of ptr: NOP takes 3).    */
 /* chan_off: side band, 3*(C+1) entries: ptr / DA / IN offset of every channel and the   */
-/* totals (Algorithm 2 omits "indexing relative to each channel"; a reader that does not */
+/* totals (Algorithm 2 is written without per-channel offsets; a reader that does not   */
 /* walk the channels in order needs it).  lens = |ptr|, |DA|, |IN|.                      */
 /* ------------------------------------------------------------------------------------ */
 int orc_encode(const float *act, const orc_shape *s, int algo, int32_t *ptr, int64_t ptr_cap,
@@ -276,7 +276,7 @@ static int pattern_size(int pattern)
  * index -> padded row h = index / kw and partition column what = index % kw.  The NZE meets
  * kernel row l at output row y = (h - l) / stride when that division is exact, and kernel
  * column what - i*stride at output column part + i for i = 0..pType.  Wk = weights of kernel
- * k and channel c, kh x kw row-major ("the kernel is transformed to a row-major vector"). */
+ * k and channel c, kh x kw flattened row by row (Section 3.3). */
 static void conv_spmv(double *Ok, const float *Wk, const orc_shape *s, int Oh, int Ow, int pType,
                       float value, int part, int index)
 {

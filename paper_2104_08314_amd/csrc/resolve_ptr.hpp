@@ -1,6 +1,6 @@
 // ptr -> absolute DA offsets, inside the convolution kernels.
 //
-// Algorithm 2 reads ptr as "entry -1 takes the previous entry": the NZEs of partition p of an
+// Algorithm 2 reads an entry of -1 in ptr as the entry before it: the NZEs of partition p of an
 // overlap type are DA[e_{p-1} .. e_p) with e the forward-filled cumulative counts.  Live
 // entries never decrease, so the forward fill is a running maximum.  A wavefront resolves the
 // segments of one channel here and writes, per (channel, type), only the table slots of the

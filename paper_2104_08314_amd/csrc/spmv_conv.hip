@@ -49,7 +49,7 @@ __device__ __forceinline__ float bcast_f(float v, int src)
 // Prologue of every convolution call, one workgroup per channel.
 //  (1) ptr -> table of absolute DA offsets: mtab[c][type][0] = first NZE of the type in DA,
 //      mtab[c][type][1+p] = one past the last NZE of partitions 0..p.  This is Algorithm 2's
-//      "an entry of -1 takes the previous entry" applied once for all readers (a running
+//      rule that an entry of -1 stands for the entry before it, applied once for all readers (a running
 //      maximum, since live entries are cumulative counts), with NPC / NPF resolved to empty
 //      ranges.
 //  (2) CPS only - index reconstruction of Algorithm 4: IN_cps -> one index per NZE, laid out
