@@ -400,7 +400,7 @@ def chain_supplement(api, torch, workloads, n_images, reps, m_inputs=5):
     }
 
 
-def cpu_baseline(spec, workloads, w_np, inputs=5, repeats=4):
+def cpu_baseline(spec, workloads, w_np, inputs=5, repeats=10):
     """The CPU oracle as it stands, one thread, on the same layer: CPO encode + Algorithm 2 on the
     layer's `inputs` offline inputs, `repeats` times each (about 10 s of CPU work on config 2)."""
     import oracle
