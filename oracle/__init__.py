@@ -32,7 +32,7 @@ def build(force: bool = False) -> str:
 
 
 class _Shape(ctypes.Structure):
-    _fields_ = [(n, ctypes.c_int32) for n in ("C", "H", "W", "K", "kh", "kw", "stride", "pad")]
+    _fields_ = [(n, ctypes.c_int32) for n in ("C", "H", "W", "K", "kh", "kw", "stride", "pad_h", "pad_w")]
 
 
 _lib = None
@@ -51,7 +51,12 @@ def _p(a: np.ndarray):
 
 
 def _shape(shape) -> _Shape:
-    return _Shape(*[int(v) for v in shape])
+    """(C, H, W, K, kh, kw, stride, pad) pads all four sides alike; a ninth entry gives the
+    columns their own padding: (.., stride, pad_h, pad_w)."""
+    v = [int(x) for x in shape]
+    if len(v) == 8:
+        v.append(v[7])
+    return _Shape(*v)
 
 
 def _check(rc: int, what: str) -> None:
@@ -76,7 +81,7 @@ class Geometry:
 
 def geometry(shape) -> Geometry:
     sh = _shape(shape)
-    Iw = sh.W + 2 * sh.pad
+    Iw = sh.W + 2 * sh.pad_w
     info = np.zeros(6, np.int32)
     cls, p0, what, real = (np.zeros(max(Iw, 1), np.int32) for _ in range(4))
     present = np.zeros(max(sh.kw, 1), np.int32)
@@ -110,7 +115,7 @@ def encode(act: np.ndarray, shape, algo: int) -> EncodedMap:
     ptr_cap = int(lib.orc_max_ptr(ctypes.byref(sh)))
     if ptr_cap < 0:
         raise ValueError("oracle: bad shape")
-    da_cap = (sh.C + 1) * (sh.H + 2 * sh.pad) * (sh.W + 2 * sh.pad)
+    da_cap = (sh.C + 1) * (sh.H + 2 * sh.pad_h) * (sh.W + 2 * sh.pad_w)
     ptr = np.zeros(ptr_cap, np.int32)
     da = np.zeros(da_cap, np.float32)
     ind = np.zeros(da_cap, np.int32)
@@ -131,8 +136,8 @@ def cps_encode(act, shape) -> EncodedMap:
 
 
 def _out_shape(sh: _Shape) -> Tuple[int, int, int]:
-    Oh = (sh.H + 2 * sh.pad - sh.kh) // sh.stride + 1
-    Ow = (sh.W + 2 * sh.pad - sh.kw) // sh.stride + 1
+    Oh = (sh.H + 2 * sh.pad_h - sh.kh) // sh.stride + 1
+    Ow = (sh.W + 2 * sh.pad_w - sh.kw) // sh.stride + 1
     return sh.K, Oh, Ow
 
 

@@ -42,13 +42,15 @@
 #define ORC_TOO_SMALL (-3)
 
 typedef struct {
-    int32_t C, H, W, K, kh, kw, stride, pad;
+    int32_t C, H, W, K, kh, kw, stride;
+    int32_t pad_h, pad_w; /* zero rows above and below, zero columns left and right */
 } orc_shape;
 
 /* ------------------------------------------------------------------------------------ */
 /* Geometry (Sections 3.1-3.2).                                                          */
 /*                                                                                       */
-/* The padded map (Ih x Iw) is cut into Ow horizontal partitions of width kw, partition  */
+/* The padded map (Ih = H + 2 pad_h rows, Iw = W + 2 pad_w columns; Algorithm 1 takes the */
+/* column padding as its own input, Pad_Left) is cut into Ow partitions of width kw, partition */
 /* p starting at column p*stride.  A padded column j lies in m(j) partitions; its        */
 /* overlap type is pType = m(j)-1 (0 = NOP, 1 = overlap2, ..., kw-1 = overlap-kw).  Only */
 /* the first partition that holds the column, p0(j), indexes it; the index of cell       */
@@ -58,8 +60,8 @@ typedef struct {
 static int shape_ok(const orc_shape *s)
 {
     if (s->C < 1 || s->H < 1 || s->W < 1 || s->K < 1) return 0;
-    if (s->kh < 1 || s->kw < 1 || s->stride < 1 || s->pad < 0) return 0;
-    if (s->H + 2 * s->pad < s->kh || s->W + 2 * s->pad < s->kw) return 0;
+    if (s->kh < 1 || s->kw < 1 || s->stride < 1 || s->pad_h < 0 || s->pad_w < 0) return 0;
+    if (s->H + 2 * s->pad_h < s->kh || s->W + 2 * s->pad_w < s->kw) return 0;
     return 1;
 }
 
@@ -75,7 +77,7 @@ int orc_geometry(const orc_shape *s, int32_t *info, int32_t *cls, int32_t *p0, i
                  int32_t *real, int32_t *present)
 {
     if (!shape_ok(s)) return ORC_BAD_SHAPE;
-    int Ih = s->H + 2 * s->pad, Iw = s->W + 2 * s->pad;
+    int Ih = s->H + 2 * s->pad_h, Iw = s->W + 2 * s->pad_w;
     int Oh = (Ih - s->kh) / s->stride + 1, Ow = (Iw - s->kw) / s->stride + 1;
     for (int t = 0; t < s->kw; ++t) present[t] = 0;
     for (int j = 0; j < Iw; ++j) {
@@ -86,7 +88,7 @@ int orc_geometry(const orc_shape *s, int32_t *info, int32_t *cls, int32_t *p0, i
                 ++m;
             }
         }
-        real[j] = (j >= s->pad && j < s->pad + s->W);
+        real[j] = (j >= s->pad_w && j < s->pad_w + s->W);
         if (m == 0) {
             cls[j] = -1; p0[j] = -1; what[j] = -1;
         } else {
@@ -97,7 +99,7 @@ int orc_geometry(const orc_shape *s, int32_t *info, int32_t *cls, int32_t *p0, i
     int top = (s->kw + s->stride - 1) / s->stride - 1;
     if (top < 1 || !present[top]) top = -1;
     info[0] = Ih; info[1] = Iw; info[2] = Oh; info[3] = Ow;
-    info[4] = (s->stride == 1 && s->pad == 0 && s->kw >= 2 && Ow >= 2);
+    info[4] = (s->stride == 1 && s->pad_w == 0 && s->kw >= 2 && Ow >= 2);
     info[5] = top;
     return ORC_OK;
 }
@@ -106,7 +108,7 @@ int orc_geometry(const orc_shape *s, int32_t *info, int32_t *cls, int32_t *p0, i
 int64_t orc_max_ptr(const orc_shape *s)
 {
     if (!shape_ok(s)) return ORC_BAD_SHAPE;
-    int Ow = (s->W + 2 * s->pad - s->kw) / s->stride + 1;
+    int Ow = (s->W + 2 * s->pad_w - s->kw) / s->stride + 1;
     return (int64_t)s->C * s->kw * (1 + Ow) + 3;
 }
 
@@ -123,7 +125,7 @@ static int is_nze(float v)
 /* Padded-map read. */
 static float padded(const float *act, const orc_shape *s, int c, int h, int j)
 {
-    int hr = h - s->pad, jr = j - s->pad;
+    int hr = h - s->pad_h, jr = j - s->pad_w;
     if (hr < 0 || hr >= s->H || jr < 0 || jr >= s->W) return 0.0f;
     return act[((int64_t)c * s->H + hr) * s->W + jr];
 }
@@ -155,7 +157,7 @@ int orc_encode(const float *act, const orc_shape *s, int algo, int32_t *ptr, int
                float *da, int32_t *in, int64_t da_cap, int32_t *chan_off, int64_t *lens)
 {
     if (!shape_ok(s)) return ORC_BAD_SHAPE;
-    int Iw = s->W + 2 * s->pad, Ih = s->H + 2 * s->pad;
+    int Iw = s->W + 2 * s->pad_w, Ih = s->H + 2 * s->pad_h;
     int32_t info[6];
     int32_t *cls = malloc(sizeof(int32_t) * Iw * 4), *p0 = cls + Iw, *what = p0 + Iw,
             *real = what + Iw;
@@ -298,7 +300,7 @@ int orc_sparse_conv(const int32_t *ptr, const float *da, const int32_t *in, cons
                     int algo, const float *weights, float *out)
 {
     if (!shape_ok(s)) return ORC_BAD_SHAPE;
-    int Iw = s->W + 2 * s->pad;
+    int Iw = s->W + 2 * s->pad_w;
     int32_t info[6];
     int32_t *cls = malloc(sizeof(int32_t) * Iw * 4), *p0 = cls + Iw, *what = p0 + Iw,
             *real = what + Iw;
@@ -369,7 +371,7 @@ int orc_decode(const int32_t *ptr, const float *da, const int32_t *in, const orc
                int algo, float *act)
 {
     if (!shape_ok(s)) return ORC_BAD_SHAPE;
-    int Iw = s->W + 2 * s->pad;
+    int Iw = s->W + 2 * s->pad_w;
     int32_t info[6];
     int32_t *cls = malloc(sizeof(int32_t) * Iw * 4), *p0 = cls + Iw, *what = p0 + Iw,
             *real = what + Iw;
@@ -381,7 +383,7 @@ int orc_decode(const int32_t *ptr, const float *da, const int32_t *in, const orc
     int64_t ip = 0, id = 0, ii = 0;
 #define PUT(part, index, value)                                                         \
     do {                                                                                \
-        int hh = (index) / s->kw - s->pad, jj = (part) * s->stride + (index) % s->kw - s->pad; \
+        int hh = (index) / s->kw - s->pad_h, jj = (part) * s->stride + (index) % s->kw - s->pad_w; \
         if (hh < 0 || hh >= s->H || jj < 0 || jj >= s->W) rc = ORC_BAD_SHAPE;          \
         else act[((int64_t)c * s->H + hh) * s->W + jj] = (value);                       \
     } while (0)
@@ -429,12 +431,13 @@ int orc_decode(const int32_t *ptr, const float *da, const int32_t *in, const orc
 /* ------------------------------------------------------------------------------------ */
 
 /* Eq. 1 with batch 1: O(k,y,x) = sum_c sum_l sum_w Ipad(c, y*stride+l, x*stride+w) W(k,c,l,w),
- * cross-correlation (no kernel flip), zero padding on all four sides. */
+ * cross-correlation (no kernel flip), pad_h zero rows above and below, pad_w zero columns left
+ * and right. */
 int orc_conv_direct(const float *act, const orc_shape *s, const float *weights, float *out)
 {
     if (!shape_ok(s)) return ORC_BAD_SHAPE;
-    int Oh = (s->H + 2 * s->pad - s->kh) / s->stride + 1;
-    int Ow = (s->W + 2 * s->pad - s->kw) / s->stride + 1;
+    int Oh = (s->H + 2 * s->pad_h - s->kh) / s->stride + 1;
+    int Ow = (s->W + 2 * s->pad_w - s->kw) / s->stride + 1;
     for (int k = 0; k < s->K; ++k)
         for (int y = 0; y < Oh; ++y)
             for (int x = 0; x < Ow; ++x) {
@@ -454,8 +457,8 @@ int orc_conv_direct(const float *act, const orc_shape *s, const float *weights, 
 int orc_im2col_lower(const float *act, const orc_shape *s, float *lowered)
 {
     if (!shape_ok(s)) return ORC_BAD_SHAPE;
-    int Oh = (s->H + 2 * s->pad - s->kh) / s->stride + 1;
-    int Ow = (s->W + 2 * s->pad - s->kw) / s->stride + 1;
+    int Oh = (s->H + 2 * s->pad_h - s->kh) / s->stride + 1;
+    int Ow = (s->W + 2 * s->pad_w - s->kw) / s->stride + 1;
     int64_t N = (int64_t)Oh * Ow;
     for (int c = 0; c < s->C; ++c)
         for (int l = 0; l < s->kh; ++l)

@@ -21,13 +21,25 @@ SHAPES = [
     (1, 12, 12, 2, 7, 7, 2, 3),
     (4, 6, 5, 5, 1, 3, 1, 0),
     (2, 5, 6, 2, 3, 1, 1, 0),
+    # rows and columns padded differently: (.., stride, pad_h, pad_w)
+    (2, 9, 8, 3, 1, 7, 1, 0, 3),
+    (2, 9, 8, 3, 7, 1, 1, 3, 0),
+    (3, 6, 7, 2, 3, 3, 1, 0, 1),
+    (3, 6, 7, 2, 3, 3, 2, 2, 0),
+    (2, 8, 9, 2, 5, 3, 1, 2, 1),
 ]
+
+
+def _unpack(shape):
+    v = tuple(shape)
+    return v if len(v) == 9 else v + (v[7],)
 
 
 @pytest.mark.parametrize("shape", SHAPES)
 def test_direct_conv_matches_library_convolution(shape):
-    C, H, W, K, kh, kw, s, p = shape
-    act, w = workloads.random_case(11, *shape, zero_frac=0.5)
+    C, H, W, K, kh, kw, s, ph, pw = _unpack(shape)
+    p = (ph, pw)
+    act, w = workloads.random_case(11, *shape[:8], zero_frac=0.5)
     got = oracle.conv_direct(act, w, shape)
     ref = torch.nn.functional.conv2d(torch.from_numpy(act).double()[None],
                                      torch.from_numpy(w).double(), stride=s, padding=p)[0].numpy()
@@ -48,18 +60,24 @@ def test_direct_conv_all_ones_closed_form():
 def test_direct_conv_is_cross_correlation_of_a_delta():
     # One unit NZE at (c0, h0, w0): out[k, y, x] = W[k, c0, h0+p-y*s, w0+p-x*s] where that
     # kernel cell exists (no kernel flip), zero elsewhere.  Derived by hand from Eq. 1.
-    C, H, W, K, kh, kw, s, p = shape = (2, 7, 8, 3, 3, 4, 2, 1)
+    _delta_case((2, 7, 8, 3, 3, 4, 2, 1))
+    _delta_case((2, 7, 8, 3, 3, 4, 2, 2, 0))   # rows and columns padded differently
+    _delta_case((2, 7, 8, 3, 1, 5, 1, 0, 2))
+
+
+def _delta_case(shape):
+    C, H, W, K, kh, kw, s, p, pw = _unpack(shape)
     rng = np.random.default_rng(5)
     w = rng.integers(1, 50, size=(K, C, kh, kw)).astype(np.float32)
     c0, h0, w0 = 1, 4, 5
     act = np.zeros((C, H, W), np.float32)
     act[c0, h0, w0] = 1.0
     out = oracle.conv_direct(act, w, shape)
-    Oh, Ow = (H + 2 * p - kh) // s + 1, (W + 2 * p - kw) // s + 1
+    Oh, Ow = (H + 2 * p - kh) // s + 1, (W + 2 * pw - kw) // s + 1
     expect = np.zeros((K, Oh, Ow), np.float32)
     for y in range(Oh):
         for x in range(Ow):
-            l, ww = h0 + p - y * s, w0 + p - x * s
+            l, ww = h0 + p - y * s, w0 + pw - x * s
             if 0 <= l < kh and 0 <= ww < kw:
                 expect[:, y, x] = w[:, c0, l, ww]
     assert np.array_equal(out, expect)
@@ -68,12 +86,12 @@ def test_direct_conv_is_cross_correlation_of_a_delta():
 
 @pytest.mark.parametrize("shape", SHAPES)
 def test_im2col_lowered_matrix_definition(shape):
-    C, H, W, K, kh, kw, s, p = shape
-    act, w = workloads.random_case(3, *shape, zero_frac=0.4)
+    C, H, W, K, kh, kw, s, ph, pw = _unpack(shape)
+    act, w = workloads.random_case(3, *shape[:8], zero_frac=0.4)
     low = oracle.im2col_lower(act, shape)
-    Oh, Ow = (H + 2 * p - kh) // s + 1, (W + 2 * p - kw) // s + 1
+    Oh, Ow = (H + 2 * ph - kh) // s + 1, (W + 2 * pw - kw) // s + 1
     assert low.shape == (C * kh * kw, Oh * Ow)          # S_im2col = C*kh*kw*Oh*Ow
-    padded = np.pad(act, ((0, 0), (p, p), (p, p)))
+    padded = np.pad(act, ((0, 0), (ph, ph), (pw, pw)))
     for c in range(C):
         for l in range(kh):
             for ww in range(kw):

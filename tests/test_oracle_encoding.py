@@ -124,9 +124,15 @@ def test_set4_rules_hand_derived():
 # independent pure-Python walker: geometry from the definition, stream structure checks
 # ---------------------------------------------------------------------------------------
 
+def _unpack(shape):
+    """(C, H, W, K, kh, kw, stride, pad) or (.., stride, pad_h, pad_w) -> nine values."""
+    v = tuple(shape)
+    return v if len(v) == 9 else v + (v[7],)
+
+
 def _py_geometry(shape):
-    C, H, W, K, kh, kw, s, p = shape
-    Ih, Iw = H + 2 * p, W + 2 * p
+    C, H, W, K, kh, kw, s, ph, p = _unpack(shape)
+    Ih, Iw = H + 2 * ph, W + 2 * p
     Ow = (Iw - kw) // s + 1
     cols = []
     for j in range(Iw):
@@ -139,9 +145,9 @@ def _py_geometry(shape):
 
 def _py_expected_streams(act, shape, algo):
     """Straight from the prose description of the format (Sections 3.2-3.4), as Python lists."""
-    C, H, W, K, kh, kw, s, p = shape
+    C, H, W, K, kh, kw, s, ph, p = _unpack(shape)
     Ih, Iw, Ow, cols, present = _py_geometry(shape)
-    pad = np.pad(act, ((0, 0), (p, p), (p, p)))
+    pad = np.pad(act, ((0, 0), (ph, ph), (p, p)))
     top = -(-kw // s) - 1
     nop3 = s == 1 and p == 0 and kw >= 2 and Ow >= 2
     ptr, da, ind = [], [], []
@@ -197,13 +203,22 @@ CASES = [
     (2, 6, 4, 2, 3, 3, 1, 0),     # Ow = 2 < kw: no overlap-kw type
     (3, 13, 9, 2, 3, 5, 2, 2),
     (2, 9, 9, 2, 3, 3, 1, 2),     # more padding than overlap
+    # rows and columns padded differently (.., stride, pad_h, pad_w): the 1 x n and n x 1 layers
+    # of the SI's layer tables keep their map size with padding in one direction only
+    (3, 9, 8, 2, 1, 7, 1, 0, 3),
+    (3, 9, 8, 2, 7, 1, 1, 3, 0),
+    (2, 7, 6, 2, 1, 3, 1, 0, 1),
+    (2, 7, 6, 2, 3, 1, 1, 1, 0),
+    (3, 7, 9, 2, 3, 3, 1, 0, 1),  # columns padded, rows not
+    (3, 7, 9, 2, 3, 3, 1, 2, 0),  # rows padded, columns VALID: three-entry NOP segment
+    (2, 10, 11, 2, 5, 3, 2, 1, 2),
 ]
 
 
 @pytest.mark.parametrize("shape", CASES)
 @pytest.mark.parametrize("zero_frac", [0.0, 0.5, 0.9])
 def test_streams_match_prose_description(shape, zero_frac):
-    act, _ = workloads.random_case(17, *shape, zero_frac=zero_frac, zero_channels=1 if shape[0] > 2 else 0)
+    act, _ = workloads.random_case(17, *shape[:8], zero_frac=zero_frac, zero_channels=1 if shape[0] > 2 else 0)
     for algo in (0, 1):
         m = oracle.encode(act, shape, algo)
         ptr, da, ind = _py_expected_streams(act, shape, algo)
@@ -214,11 +229,11 @@ def test_streams_match_prose_description(shape, zero_frac):
 
 @pytest.mark.parametrize("shape", CASES)
 def test_round_trip_and_invariants(shape):
-    C, H, W, K, kh, kw, s, p = shape
+    C, H, W, K, kh, kw, s, ph, p = _unpack(shape)
     Ih, Iw, Ow, cols, present = _py_geometry(shape)
     covered = np.array([c["m"] > 0 for c in cols])[p:p + W]
     for seed, zero_frac in itertools.product(range(3), (0.3, 0.7)):
-        act, _ = workloads.random_case(100 + seed, *shape, zero_frac=zero_frac, zero_channels=1)
+        act, _ = workloads.random_case(100 + seed, *shape[:8], zero_frac=zero_frac, zero_channels=1)
         # random_case leaves -0.0 where a negative draw was masked out: those are zeros
         expect = np.where((act != 0) & covered[None, None, :], act, np.float32(0.0))
         nnz = int(np.count_nonzero(expect))
@@ -249,9 +264,9 @@ def test_round_trip_and_invariants(shape):
 def _set4_histogram(act, shape):
     """C''_k of the SI: number of set4 groups with k NZEs in the overlap-kw columns, and the
     NZE count elsewhere, computed with array operations only."""
-    C, H, W, K, kh, kw, s, p = shape
+    C, H, W, K, kh, kw, s, ph, p = _unpack(shape)
     Ih, Iw, Ow, cols, present = _py_geometry(shape)
-    pad = np.pad(act, ((0, 0), (p, p), (p, p))) != 0
+    pad = np.pad(act, ((0, 0), (ph, ph), (p, p))) != 0
     top = -(-kw // s) - 1
     top_cols = [c["j"] for c in cols if c["real"] and c["m"] - 1 == top and top >= 1]
     other_cols = [c["j"] for c in cols if c["real"] and c["m"] > 0 and c["j"] not in top_cols]
@@ -265,9 +280,9 @@ def _set4_histogram(act, shape):
 
 @pytest.mark.parametrize("shape", CASES)
 def test_stream_sizes_match_si_closed_forms(shape):
-    C, H, W, K, kh, kw, s, p = shape
+    C, H, W, K, kh, kw, s, ph, p = _unpack(shape)
     Ih, Iw, Ow, cols, present = _py_geometry(shape)
-    act, _ = workloads.random_case(23, *shape, zero_frac=0.45, zero_channels=1)
+    act, _ = workloads.random_case(23, *shape[:8], zero_frac=0.45, zero_channels=1)
     cpo, cps = oracle.cpo_encode(act, shape), oracle.cps_encode(act, shape)
     hist, elsewhere = _set4_histogram(act, shape)
     # SI, size of IN_CPS: C'_1+2C'_2+3C'_3+4C'_4 (= NZEs outside overlap-kw) + C''_1+2C''_2+2C''_3+2C''_4
@@ -391,11 +406,14 @@ def test_random_tiny_layers_brute_force():
         C, K = int(rng.integers(1, 4)), int(rng.integers(1, 4))
         H, W = int(rng.integers(1, 10)), int(rng.integers(1, 10))
         kh, kw = int(rng.integers(1, 6)), int(rng.integers(1, 6))
-        s, p = int(rng.integers(1, 4)), int(rng.integers(0, 3))
-        if H + 2 * p < kh or W + 2 * p < kw:
+        s, ph, pw = int(rng.integers(1, 4)), int(rng.integers(0, 3)), int(rng.integers(0, 3))
+        # rows and columns padded alike in half of the layers, independently in the others
+        if done % 2 == 0:
+            pw = ph
+        if H + 2 * ph < kh or W + 2 * pw < kw:
             continue
-        shape = (C, H, W, K, kh, kw, s, p)
-        act, w = workloads.random_case(int(rng.integers(1 << 30)), *shape,
+        shape = (C, H, W, K, kh, kw, s, ph) if done % 2 == 0 else (C, H, W, K, kh, kw, s, ph, pw)
+        act, w = workloads.random_case(int(rng.integers(1 << 30)), *shape[:8],
                                        zero_frac=float(rng.choice([0.0, 0.3, 0.6, 0.9])),
                                        zero_channels=int(rng.integers(0, 2)), integer=True)
         ref = oracle.conv_direct(act, w, shape)
@@ -404,15 +422,18 @@ def test_random_tiny_layers_brute_force():
         done += 1
 
 
-@pytest.mark.parametrize("shape", [(3, 9, 8, 2, 7, 1, 1, 0), (2, 6, 11, 2, 3, 1, 1, 0), (4, 5, 5, 3, 1, 1, 1, 0)],
+@pytest.mark.parametrize("shape", [(3, 9, 8, 2, 7, 1, 1, 0), (2, 6, 11, 2, 3, 1, 1, 0), (4, 5, 5, 3, 1, 1, 1, 0),
+                                   (3, 9, 8, 2, 7, 1, 1, 3, 0), (2, 6, 11, 2, 3, 1, 1, 1, 0)],
                          ids=lambda s: "x".join(map(str, s)))
 def test_kw_1_streams_are_the_special_case_of_the_si(shape):
-    """K_w = 1 (SI, "CPO/CPS Encoding Algorithm K_w = 1"): no overlap regions, every column is its
+    """K_w = 1 (SI, the encoding algorithm for K_w = 1): no overlap regions, every column is its
     own sub-matrix.  Per live channel ptr is [0, running NZE count after column 0, 1, ..], IN holds
-    the row of each NZE, DA the values column by column; an empty channel is one NPC entry.  The
-    general encoder must produce exactly that, and CPS has nothing to pack."""
+    the (padded) row of each NZE, DA the values column by column; an empty channel is one NPC
+    entry.  The general encoder must produce exactly that, and CPS has nothing to pack.  The
+    n x 1 layers of the SI's tables keep their map height: rows padded, columns not."""
     C, H, W = shape[:3]
-    act, w = workloads.random_case(31, *shape, zero_frac=0.6, zero_channels=1)
+    ph = shape[7]
+    act, w = workloads.random_case(31, *shape[:8], zero_frac=0.6, zero_channels=1)
     ptr, da, ind = [], [], []
     for c in range(C):
         if not np.any(act[c] != 0):
@@ -423,7 +444,7 @@ def test_kw_1_streams_are_the_special_case_of_the_si(shape):
         for j in range(W):
             for h in range(H):
                 if act[c, h, j] != 0:
-                    da.append(act[c, h, j]); ind.append(h); running += 1
+                    da.append(act[c, h, j]); ind.append(h + ph); running += 1
             ptr.append(running)
     for enc in (oracle.cpo_encode(act, shape), oracle.cps_encode(act, shape)):
         assert enc.ptr.tolist() == ptr
