@@ -555,7 +555,7 @@ def main():
         "ms_per_step": round(ms_per_step, 5),
         "higher_is_better": False, "scaling": "weak", "vs_baseline": None,
         "dtype": "f32", "data": "synthetic",
-        "config": {"workload": f"configs[{args.config - 1}]: {spec.name} 3x3 s{spec.stride} p{spec.pad}, "
+        "config": {"workload": f"configs[{args.config - 1}]: {spec.name} {spec.kh}x{spec.kw} s{spec.stride} p{spec.pad}, "
                                f"C={spec.C} H=W={spec.H} K={spec.K}, batch 1, "
                                f"{100 * (1 - row['density']):.1f}% zeros",
                    "step": "cpo_encode_conv+cps_encode_conv+im2col_conv(fp32)+select_layer_algo(2 modes)"},

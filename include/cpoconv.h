@@ -7,13 +7,16 @@
  *   - Tensors are DEVICE pointers owned by the caller; the library never allocates or frees
  *     device memory and never synchronises unless stated.  Work is queued on `stream`
  *     (a hipStream_t passed as void*, NULL = the default stream) of the current device.
- *   - Batch 1, fp32, square stride and padding.  act is C x H x W row-major; weights are
- *     K x C x kh x kw row-major; out is K x Oh x Ow row-major with
- *     Oh = (H + 2 pad - kh) / stride + 1, Ow = (W + 2 pad - kw) / stride + 1 (floor).
+ *   - Batch 1, fp32, one stride for both directions; pad_h zero rows above and below the map,
+ *     pad_w zero columns left and right of it (Algorithm 1 takes the column padding as an input
+ *     of its own; the 1 x n and n x 1 layers of the SI's layer tables pad one direction only).
+ *     act is C x H x W row-major; weights are K x C x kh x kw row-major; out is K x Oh x Ow
+ *     row-major with Oh = (H + 2 pad_h - kh) / stride + 1, Ow = (W + 2 pad_w - kw) / stride + 1
+ *     (floor).
  *   - Every call returns CPOCONV_OK (0) or a negative CPOCONV_ERR_* code.  Arguments are
  *     validated on the host before anything is queued: a call that returns an error other
  *     than CPOCONV_ERR_HIP has launched nothing.
- *   - Limits: 1 <= kh, kw <= CPOCONV_MAX_K; H + 2 pad, W + 2 pad <= CPOCONV_MAX_I;
+ *   - Limits: 1 <= kh, kw <= CPOCONV_MAX_K; H + 2 pad_h, W + 2 pad_w <= CPOCONV_MAX_I;
  *     C * H * W < 2^31.
  */
 #ifndef CPOCONV_H
@@ -47,7 +50,8 @@ typedef struct {
     int32_t C, H, W;     /* input channels, unpadded map height and width */
     int32_t K;           /* output kernels                                */
     int32_t kh, kw;      /* kernel height and width                       */
-    int32_t stride, pad; /* both directions                               */
+    int32_t stride;      /* both directions                               */
+    int32_t pad_h, pad_w; /* zero rows above and below, zero columns left and right */
 } cpoconv_shape;
 
 /*
@@ -60,7 +64,7 @@ typedef struct {
  *                ptr per channel: CPOCONV_NPC if the channel has no NZE, else per type
  *                CPOCONV_NPF if the type has no NZE, else [pType, e_0 .. e_{Ow-1}] with e_p
  *                the cumulative NZE count of the type after partition p or -1 if partition
- *                p shows no new column of the type; with pad = 0 and stride 1 the NOP type
+ *                p shows no new column of the type; with pad_w = 0 and stride 1 the NOP type
  *                is [0, n_first_column, n_first_column + n_last_column] instead.
  *                IN: index = column inside the first partition holding the cell +
  *                padded row * kw.  CPS differs in the overlap-kw type only: per column and
@@ -76,7 +80,7 @@ typedef struct {
  *                gave up: see cpo_encode).
  *   in_bits      width of the IN entries: 0 or 32 for int32; 16 for a compact map whose `in`
  *                points at int16 entries (in_cap still counts entries).  Every IN entry is an
- *                index below (H + 2 pad) * kw <= 2816, the negative of one, or a row pattern
+ *                index below (H + 2 pad_h) * kw <= 2816, the negative of one, or a row pattern
  *                below 16, so the narrow stream holds exactly the same values; the paper counts
  *                the size of the structure in elements (SI, space complexity), the narrow
  *                entries shrink it in bytes.  Encoders write, convolutions read, the width the

@@ -27,7 +27,7 @@ class CpoconvError(RuntimeError):
 
 
 class Shape(ctypes.Structure):
-    _fields_ = [(n, ctypes.c_int32) for n in ("C", "H", "W", "K", "kh", "kw", "stride", "pad")]
+    _fields_ = [(n, ctypes.c_int32) for n in ("C", "H", "W", "K", "kh", "kw", "stride", "pad_h", "pad_w")]
 
     def as_tuple(self) -> Tuple[int, ...]:
         return tuple(int(getattr(self, n)) for n, _ in self._fields_)
@@ -117,7 +117,14 @@ def _check(rc: int) -> None:
 def make_shape(shape) -> Shape:
     if isinstance(shape, Shape):
         return shape
-    return Shape(*[int(v) for v in shape])
+    # (C, H, W, K, kh, kw, stride, pad) pads rows and columns alike; a ninth entry gives the
+    # columns their own padding: (.., stride, pad_h, pad_w)
+    v = [int(x) for x in shape]
+    if len(v) == 8:
+        v.append(v[7])
+    if len(v) != 9:
+        raise ValueError("a shape has eight or nine entries: (C, H, W, K, kh, kw, stride, pad_h[, pad_w])")
+    return Shape(*v)
 
 
 def cpoconv_sizes(shape) -> Sizes:

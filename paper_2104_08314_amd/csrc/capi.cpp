@@ -65,9 +65,10 @@ int check_shape(const cpoconv_shape *s)
     if (s->C < 1 || s->H < 1 || s->W < 1 || s->K < 1) return CPOCONV_ERR_SHAPE;
     if (s->kh < 1 || s->kw < 1 || s->kh > CPOCONV_MAX_K || s->kw > CPOCONV_MAX_K)
         return CPOCONV_ERR_SHAPE;
-    if (s->stride < 1 || s->pad < 0 || s->pad > CPOCONV_MAX_I) return CPOCONV_ERR_SHAPE;
+    if (s->stride < 1 || s->pad_h < 0 || s->pad_h > CPOCONV_MAX_I || s->pad_w < 0 || s->pad_w > CPOCONV_MAX_I)
+        return CPOCONV_ERR_SHAPE;
     if (s->H > CPOCONV_MAX_I || s->W > CPOCONV_MAX_I) return CPOCONV_ERR_SHAPE;
-    const int Ih = s->H + 2 * s->pad, Iw = s->W + 2 * s->pad;
+    const int Ih = s->H + 2 * s->pad_h, Iw = s->W + 2 * s->pad_w;
     if (Ih > CPOCONV_MAX_I || Iw > CPOCONV_MAX_I) return CPOCONV_ERR_SHAPE;
     if (Ih < s->kh || Iw < s->kw) return CPOCONV_ERR_SHAPE;
     if (static_cast<int64_t>(s->C) * s->H * s->W >= (int64_t{1} << 31)) return CPOCONV_ERR_SHAPE;
@@ -85,9 +86,9 @@ int build_geometry(const cpoconv_shape *s, Geometry *g)
     if (rc != CPOCONV_OK) return rc;
     memset(g, 0, sizeof(*g));
     g->C = s->C; g->H = s->H; g->W = s->W; g->K = s->K;
-    g->kh = s->kh; g->kw = s->kw; g->stride = s->stride; g->pad = s->pad;
-    g->Ih = s->H + 2 * s->pad;
-    g->Iw = s->W + 2 * s->pad;
+    g->kh = s->kh; g->kw = s->kw; g->stride = s->stride; g->pad_h = s->pad_h; g->pad_w = s->pad_w;
+    g->Ih = s->H + 2 * s->pad_h;
+    g->Iw = s->W + 2 * s->pad_w;
     g->Oh = (g->Ih - s->kh) / s->stride + 1;
     g->Ow = (g->Iw - s->kw) / s->stride + 1;
     g->Kpad = (s->K + 63) / 64 * 64;
@@ -102,7 +103,7 @@ int build_geometry(const cpoconv_shape *s, Geometry *g)
         int p_hi = j / s->stride;
         if (p_hi > g->Ow - 1) p_hi = g->Ow - 1;
         const int m = p_hi - p_lo + 1;
-        const bool real = j >= s->pad && j < s->pad + s->W;
+        const bool real = j >= s->pad_w && j < s->pad_w + s->W;
         if (m < 1 || !real) continue;
         type_of[j] = m - 1;
         p0_of[j] = p_lo;
@@ -124,7 +125,7 @@ int build_geometry(const cpoconv_shape *s, Geometry *g)
     }
     g->type_begin[g->n_types] = static_cast<uint16_t>(n);
     g->n_cols = n;
-    g->nop3 = (s->stride == 1 && s->pad == 0 && s->kw >= 2 && g->Ow >= 2) ? 1 : 0;
+    g->nop3 = (s->stride == 1 && s->pad_w == 0 && s->kw >= 2 && g->Ow >= 2) ? 1 : 0;
     g->top = -1;
     g->top_slot = -1;
     const int top = (s->kw + s->stride - 1) / s->stride - 1;

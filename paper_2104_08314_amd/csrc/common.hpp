@@ -19,11 +19,11 @@ constexpr int kLanes = 64;                 // wavefront width on CDNA
 // partition and part of the unpadded map) in stream order: overlap type ascending, then
 // padded column ascending (which is also first-partition ascending).
 struct Geometry {
-    int32_t C, H, W, K, kh, kw, stride, pad;
+    int32_t C, H, W, K, kh, kw, stride, pad_h, pad_w;
     int32_t Ih, Iw, Oh, Ow;
     int32_t n_cols;                  // encoded columns
     int32_t n_types;                 // present overlap types
-    int32_t nop3;                    // NOP type is the 3-entry segment (pad 0, stride 1)
+    int32_t nop3;                    // NOP type is the 3-entry segment (no column padding, stride 1)
     int32_t top;                     // overlap type CPS packs, -1 if none
     int32_t top_slot;                // its slot in type_id, -1 if none
     int32_t Kpad;                    // K rounded up to a multiple of 64

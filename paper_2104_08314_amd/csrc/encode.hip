@@ -145,7 +145,7 @@ __global__ __launch_bounds__(kThreads) void encode_kernel(const Geometry g, cons
 
     auto load_tile = [&](int q) {
         for (int r = wave; r < kChunk; r += kWaves) {
-            const int hr = q * kChunk + r - g.pad;
+            const int hr = q * kChunk + r - g.pad_h;
             if (hr < 0 || hr >= g.H) continue;
             for (int jr = lane; jr < g.W; jr += kLanes) tile[r * Wt + jr] = produced(chan[hr * g.W + jr], prod, bias_c);
         }
@@ -154,7 +154,7 @@ __global__ __launch_bounds__(kThreads) void encode_kernel(const Geometry g, cons
     // the tile's loads first, then everything that does not depend on them
     load_tile(0);
     if (tid < g.n_cols) {
-        col_jr[tid] = static_cast<uint8_t>(g.col_j[tid] - g.pad);
+        col_jr[tid] = static_cast<uint8_t>(g.col_j[tid] - g.pad_w);
         col_p0[tid] = g.col_p0[tid];
         col_wh[tid] = g.col_what[tid];
     }
@@ -177,7 +177,7 @@ __global__ __launch_bounds__(kThreads) void encode_kernel(const Geometry g, cons
             unsigned bits = 0;
 #pragma unroll
             for (int rr = 0; rr < 8; ++rr) {
-                const int r = wave * rows_per_wave + rr, hr = q * kChunk + r - g.pad;
+                const int r = wave * rows_per_wave + rr, hr = q * kChunk + r - g.pad_h;
                 if (rr < rows_per_wave && hr >= 0 && hr < g.H) bits |= static_cast<unsigned>(is_nze(tile[r * Wt + jr])) << rr;
             }
             mask_part[vi][wave] = static_cast<uint8_t>(bits);
@@ -349,7 +349,7 @@ __global__ __launch_bounds__(kThreads) void encode_kernel(const Geometry g, cons
             load_tile(q);
             __syncthreads();
         }
-        const int hr = q * kChunk + lane - g.pad;
+        const int hr = q * kChunk + lane - g.pad_h;
         const bool row_ok = lane < kChunk && hr >= 0 && hr < g.H;
         const unsigned long long below = (1ull << lane) - 1ull;
 #pragma unroll 2
@@ -454,13 +454,13 @@ __global__ __launch_bounds__(kThreads) void encode_small_kernel(const Geometry g
     }
     wave_lds_fence();
     const bool col_ok = live && lane < g.n_cols;
-    const int my_jr = col_ok ? static_cast<int>(g.col_j[lane]) - g.pad : 0;
+    const int my_jr = col_ok ? static_cast<int>(g.col_j[lane]) - g.pad_w : 0;
     const int my_p0 = col_ok ? static_cast<int>(g.col_p0[lane]) : 0;
     const int next_p0 = (live && lane + 1 < g.n_cols) ? static_cast<int>(g.col_p0[lane + 1]) : -1;
     unsigned long long colmask = 0;
     if (col_ok)
         for (int r = 0; r < g.H; ++r)
-            colmask |= static_cast<unsigned long long>(is_nze(tile[r * Wt + my_jr])) << (r + g.pad);   // bit = padded row
+            colmask |= static_cast<unsigned long long>(is_nze(tile[r * Wt + my_jr])) << (r + g.pad_h);   // bit = padded row
     const int cnt = __popcll(colmask);
     const int ecnt = (lane >= top_begin && lane < top_end) ? set4_entries(colmask) : cnt;
     const int incl = wave_inclusive_sum(cnt), eincl = wave_inclusive_sum(ecnt);
@@ -618,7 +618,7 @@ __global__ __launch_bounds__(kThreads) void encode_small_kernel(const Geometry g
     const int sub = lane / rows_pass, h = lane - sub * rows_pass;     // h: padded row
     const unsigned long long sub_bits = rows_pass == 64 ? ~0ull : ((1ull << rows_pass) - 1ull);
     const unsigned long long below = (1ull << h) - 1ull;
-    const int hr = h - g.pad;
+    const int hr = h - g.pad_h;
     const bool row_ok = hr >= 0 && hr < g.H;
     for (int v0 = 0; v0 < g.n_cols; v0 += cols_pass) {
         const int vi = v0 + sub;

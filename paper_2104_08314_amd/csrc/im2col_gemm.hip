@@ -47,7 +47,7 @@ __global__ __launch_bounds__(kLowThreads) void im2col_lower_kernel(const Geometr
     const float bias_c = (prod.relu && prod.bias != nullptr) ? prod.bias[c] : 0.0f;
     for (int col = col0 + threadIdx.x; col < min(col0 + kLowCols, N); col += kLowThreads) {
         const int y = col / g.Ow, x = col - y * g.Ow;
-        const int hr = y * g.stride + l - g.pad, jr = x * g.stride + w - g.pad;
+        const int hr = y * g.stride + l - g.pad_h, jr = x * g.stride + w - g.pad_w;
         const float v = (hr >= 0 && hr < g.H && jr >= 0 && jr < g.W) ? produced(chan[hr * g.W + jr], prod, bias_c) : 0.0f;
         lowered[static_cast<int64_t>(row) * ldb + col] = lowered_cast<T>(v);
     }
@@ -76,7 +76,7 @@ __global__ __launch_bounds__(kLowThreads) void im2col_lower_bf16_kernel(const Ge
             float f = 0.0f;
             if (row < Kd) {
                 const int w = row % g.kw, l = (row / g.kw) % g.kh, c = row / (g.kw * g.kh);
-                const int hr = y * g.stride + l - g.pad, jr = x * g.stride + w - g.pad;
+                const int hr = y * g.stride + l - g.pad_h, jr = x * g.stride + w - g.pad_w;
                 if (hr >= 0 && hr < g.H && jr >= 0 && jr < g.W)
                     f = produced(act[(static_cast<int64_t>(c) * g.H + hr) * g.W + jr], prod,
                                  (prod.relu && prod.bias != nullptr) ? prod.bias[c] : 0.0f);

@@ -11,7 +11,7 @@ from __future__ import annotations
 
 import dataclasses
 import math
-from typing import List, Tuple
+from typing import List, Optional, Tuple
 
 import numpy as np
 
@@ -20,7 +20,8 @@ BASE_SEED = 20210408
 
 @dataclasses.dataclass(frozen=True)
 class LayerSpec:
-    """One convolution layer of a workload (batch 1, fp32, square stride / padding)."""
+    """One convolution layer of a workload (batch 1, fp32, one stride; `pad` rows above and below
+    and as many columns left and right, unless `pad_w` gives the columns their own padding)."""
 
     name: str
     config: int          # workload number, 1..5
@@ -36,6 +37,7 @@ class LayerSpec:
     kind: str            # "relu_gauss" | "clustered" | "bernoulli_halfnormal" | "dense"
     zero_frac: float     # targeted fraction of zeros among live channels
     zero_channels: int   # number of channels forced to all-zero
+    pad_w: Optional[int] = None
 
     @property
     def Ih(self) -> int:
@@ -43,7 +45,7 @@ class LayerSpec:
 
     @property
     def Iw(self) -> int:
-        return self.W + 2 * self.pad
+        return self.W + 2 * (self.pad if self.pad_w is None else self.pad_w)
 
     @property
     def Oh(self) -> int:
@@ -55,7 +57,8 @@ class LayerSpec:
 
     @property
     def shape_tuple(self) -> Tuple[int, ...]:
-        return (self.C, self.H, self.W, self.K, self.kh, self.kw, self.stride, self.pad)
+        base = (self.C, self.H, self.W, self.K, self.kh, self.kw, self.stride, self.pad)
+        return base if self.pad_w is None else base + (self.pad_w,)
 
     @property
     def s_im2col(self) -> int:

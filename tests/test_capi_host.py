@@ -70,14 +70,16 @@ def test_sizes(shape):
 
 def test_bad_arguments_are_rejected_on_the_host():
     lib = api.lib()
-    good = api.Shape(4, 8, 8, 4, 3, 3, 1, 1)
+    good = api.make_shape((4, 8, 8, 4, 3, 3, 1, 1))
     sz = api.Sizes()
     assert lib.cpoconv_sizes(None, ctypes.byref(sz)) == api.ERR_NULL
     assert lib.cpoconv_sizes(ctypes.byref(good), None) == api.ERR_NULL
     for bad in [(0, 8, 8, 4, 3, 3, 1, 1), (4, 8, 8, 4, 3, 3, 0, 1), (4, 8, 8, 4, 3, 3, 1, -1),
                 (4, 2, 8, 4, 5, 3, 1, 1), (4, 8, 8, 4, 12, 3, 1, 1), (4, 300, 8, 4, 3, 3, 1, 1),
-                (4, 8, 255, 4, 3, 3, 1, 1), (4, 8, 8, 0, 3, 3, 1, 1)]:
-        sh = api.Shape(*bad)
+                (4, 8, 255, 4, 3, 3, 1, 1), (4, 8, 8, 0, 3, 3, 1, 1),
+                (4, 8, 8, 4, 3, 3, 1, 1, -1), (4, 8, 8, 4, 3, 3, 1, -1, 1), (4, 8, 250, 4, 3, 3, 1, 0, 4),
+                (4, 8, 2, 4, 3, 5, 1, 2, 1)]:
+        sh = api.make_shape(bad)
         assert lib.cpoconv_sizes(ctypes.byref(sh), ctypes.byref(sz)) == api.ERR_SHAPE, bad
     # encode / conv / im2col: NULL pointers, short buffers, unknown precision -> no launch
     m = api._Map()
@@ -131,7 +133,7 @@ def test_batch_sizes_and_batch_argument_checks():
     assert batch.out_len == 5 * one_img.out_len
     assert batch.scratch_bytes >= one_img.scratch_bytes
     assert batch.lowered_bytes >= 5 * 4 * 6 * 9 * one_img.Oh * one_img.Ow
-    good, sz = api.Shape(*shape), api.Sizes()
+    good, sz = api.make_shape(shape), api.Sizes()
     for n in (0, -1, 1025):
         assert lib.cpoconv_batch_sizes(ctypes.byref(good), n, ctypes.byref(sz)) == api.ERR_SHAPE
     one = ctypes.c_void_p(256)
@@ -149,7 +151,7 @@ def test_batch_sizes_and_batch_argument_checks():
 def _chain_table(shapes, methods, relu=None, bias=None):
     table = (api.ChainLayer * len(shapes))()
     for i, (s, m) in enumerate(zip(shapes, methods)):
-        table[i].shape = api.Shape(*s)
+        table[i].shape = api.make_shape(s)
         table[i].method = m
         table[i].precision = 0
         table[i].relu_in = (relu or [0] * len(shapes))[i]
@@ -195,7 +197,7 @@ def test_chain_sizes_and_argument_checks():
     table[2].out = None
     assert lib.cpoconv_chain_forward(one, table, 3, 2, ctypes.byref(big), one, huge, one, huge, None) == api.ERR_NULL
     # the fused producers validate like the calls they extend
-    good = api.Shape(*a)
+    good = api.make_shape(a)
     assert lib.cpo_encode_relu(None, None, ctypes.byref(good), 1, ctypes.byref(big), one, huge, None) == api.ERR_NULL
     assert lib.cps_encode_relu(one, None, ctypes.byref(good), 0, ctypes.byref(big), one, huge, None) == api.ERR_SHAPE
     assert lib.im2col_conv_relu(one, None, ctypes.byref(good), 1, one, one, one, 5, None) == api.ERR_ALGO
@@ -203,7 +205,7 @@ def test_chain_sizes_and_argument_checks():
 
 def test_map_index_width_is_validated():
     lib = api.lib()
-    good = api.Shape(6, 10, 12, 9, 3, 3, 1, 1)
+    good = api.make_shape((6, 10, 12, 9, 3, 3, 1, 1))
     one, huge = ctypes.c_void_p(256), ctypes.c_int64(1 << 40)
     for bits, want in ((8, api.ERR_ALGO), (64, api.ERR_ALGO), (-16, api.ERR_ALGO)):
         m = api._Map(256, 1 << 20, 256, 1 << 20, 256, 1 << 20, 256, 256, bits)

@@ -148,13 +148,26 @@ EDGE_SHAPES = [
     (3, 17, 17, 70, 7, 1, 1, 0),      # 7 x 1 kernel: the K_w = 1 special case of the SI
     (6, 8, 8, 5, 3, 1, 1, 0),         # 3 x 1
     (3, 17, 17, 4, 1, 7, 1, 0),       # 1 x 7 (K_h = 1): the general algorithm
+    # rows and columns padded differently (.., stride, pad_h, pad_w): the 1 x n and n x 1 layers
+    # that keep their map size, and 3 x 3 layers padded in one direction only
+    (3, 17, 17, 70, 7, 1, 1, 3, 0),
+    (3, 17, 17, 4, 1, 7, 1, 0, 3),
+    (6, 8, 9, 5, 3, 1, 1, 1, 0),
+    (6, 8, 9, 5, 1, 3, 1, 0, 1),
+    (33, 17, 17, 70, 7, 1, 1, 3, 0),
+    (33, 17, 17, 70, 1, 7, 1, 0, 3),
+    (20, 9, 11, 66, 3, 3, 1, 0, 1),   # register-tile kernel, columns padded only
+    (20, 9, 11, 66, 3, 3, 1, 2, 0),   # rows padded, columns not: three-entry NOP segment
+    (5, 15, 17, 70, 3, 3, 2, 0, 1),   # strip kernel, stride 2
+    (3, 70, 33, 4, 3, 3, 1, 0, 2),    # two row chunks in the encoder, no row padding
+    (2, 30, 30, 3, 11, 5, 2, 5, 1),
 ]
 
 
 @pytest.mark.parametrize("shape", EDGE_SHAPES, ids=lambda s: "x".join(map(str, s)))
 @pytest.mark.parametrize("zero_frac", [0.0, 0.55, 0.93])
 def test_edge_shapes(api, shape, zero_frac):
-    act, w = workloads.random_case(91, *shape, zero_frac=zero_frac, zero_channels=1 if shape[0] > 2 else 0)
+    act, w = workloads.random_case(91, *shape[:8], zero_frac=zero_frac, zero_channels=1 if shape[0] > 2 else 0)
     _check_layer(api, act, w, shape, name=f"edge z={zero_frac}")
 
 
@@ -309,6 +322,12 @@ BATCH_CASES = [
     (4, (5, 46, 47, 128, 3, 3, 1, 1)),
     (4, (6, 47, 49, 70, 3, 3, 1, 1)),
     (4, (5, 56, 56, 128, 3, 3, 1, 1)),
+    # rows and columns padded differently
+    (4, (40, 14, 14, 128, 3, 3, 1, 0, 1)),
+    (4, (33, 28, 28, 70, 3, 3, 1, 2, 1)),
+    (8, (33, 17, 17, 70, 1, 7, 1, 0, 3)),
+    (8, (33, 17, 17, 70, 7, 1, 1, 3, 0)),
+    (4, (5, 56, 56, 128, 3, 3, 1, 1, 0)),
 ]
 
 
@@ -316,7 +335,7 @@ def _batch_inputs(n_images, shape, seed):
     acts = []
     for n in range(n_images):
         # densities differ per image; image 1 is all zero, so its streams are empty
-        act, w = workloads.random_case(seed + n, *shape, zero_frac=(0.3, 0.9, 0.6)[n % 3],
+        act, w = workloads.random_case(seed + n, *shape[:8], zero_frac=(0.3, 0.9, 0.6)[n % 3],
                                        zero_channels=1 if shape[0] > 2 else 0)
         if n == 1:
             act[...] = 0.0
