@@ -401,8 +401,12 @@ int launch_tile(const cpoconv_map &map, const int32_t *indices, const int32_t *m
 bool tile_kernel_supports(const Geometry &g)
 {
     if (g.n_types < 1) return false;
-    return (g.kh == 3 && g.kw == 3 && (g.stride == 1 || g.stride == 2)) ||
-           (g.kh == 5 && g.kw == 5 && g.stride == 1) || (g.kh == 7 && g.kw == 7 && g.stride == 2);
+    if ((g.kh == 3 && g.kw == 3 && (g.stride == 1 || g.stride == 2)) ||
+        (g.kh == 5 && g.kw == 5 && g.stride == 1) || (g.kh == 7 && g.kw == 7 && g.stride == 2))
+        return true;
+    // the 1 x n and n x 1 layers of the SI's layer tables (K_h = 1: the general algorithm; K_w = 1:
+    // a single overlap type, the SI's special case)
+    return g.stride == 1 && ((g.kh == 1 && (g.kw == 3 || g.kw == 7)) || (g.kw == 1 && (g.kh == 3 || g.kh == 7)));
 }
 
 int64_t tile_kernel_partial_bytes(const Geometry &g)
@@ -424,6 +428,10 @@ int launch_sparse_conv_tile(const cpoconv_map &map, const int32_t *indices, cons
     CPOCONV_TILE(3, 3, 2)
     CPOCONV_TILE(5, 5, 1)
     CPOCONV_TILE(7, 7, 2)
+    CPOCONV_TILE(1, 7, 1)
+    CPOCONV_TILE(7, 1, 1)
+    CPOCONV_TILE(1, 3, 1)
+    CPOCONV_TILE(3, 1, 1)
 #undef CPOCONV_TILE
     return CPOCONV_ERR_SHAPE;
 }

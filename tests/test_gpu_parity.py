@@ -161,6 +161,11 @@ EDGE_SHAPES = [
     (5, 15, 17, 70, 3, 3, 2, 0, 1),   # strip kernel, stride 2
     (3, 70, 33, 4, 3, 3, 1, 0, 2),    # two row chunks in the encoder, no row padding
     (2, 30, 30, 3, 11, 5, 2, 5, 1),
+    (40, 8, 8, 70, 1, 3, 1, 0, 1),
+    (40, 8, 8, 70, 3, 1, 1, 1, 0),
+    (33, 17, 19, 70, 1, 7, 1, 0, 0),  # 1 x 7 without padding: three-entry NOP segment, six overlap types
+    (33, 19, 17, 70, 7, 1, 1, 0, 0),
+    (33, 17, 19, 5, 1, 7, 1, 1, 2),   # padding narrower than the kernel's reach, rows padded too
 ]
 
 
