@@ -380,14 +380,28 @@ int launch_strip(const cpoconv_map &map, const int32_t *indices, const int32_t *
 // Images per launch from which the batched launch shapes below are taken.
 constexpr int kBatchedFromImages = 4;
 
+// 1 x n and n x 1 kernels at stride 1 (n = 3, 7): the layers of that kind in the SI's layer tables.
+inline bool line_kernel(const Geometry &g)
+{
+    return g.stride == 1 && ((g.kh == 1 && (g.kw == 3 || g.kw == 7)) || (g.kw == 1 && (g.kh == 3 || g.kh == 7)));
+}
+
 // Column tiles per workgroup.  With several images per launch there are workgroups enough, and the
 // small 3 x 3 maps gain from wide strips: 14 x 14 outputs are one strip of four tiles by four bands
 // (every NZE decoded once per workgroup, weights staged once for sixteen wavefronts), 28 x 28
 // outputs strips of two tiles by seven bands.
 int strip_xt(const Geometry &g)
 {
-    if (g.N < kBatchedFromImages || g.kh != 3 || g.C < 32) return 1;
+    if (g.N < kBatchedFromImages || g.C < 32) return 1;
     const int bands_all = (g.Oh + 3) / 4;
+    if (line_kernel(g)) {
+        // 1 x 7 and 7 x 1 layers (17 x 17 maps in the SI's tables): one strip of three six-column
+        // tiles covers up to 18 columns; 1 x 3 and 3 x 1 layers (8 x 8 maps): two four-column tiles
+        if (g.kh == 7 || g.kw == 7) return (g.Ow > 12 && g.Ow <= 18 && bands_all * 3 <= kMaxBands) ? 3 : 1;
+        if (g.Ow <= 4 || g.Ow > 8 || bands_all * 2 > kMaxBands) return 1;
+        return (bands_all * 2 < 8 && g.N < 8) ? 1 : 2;
+    }
+    if (g.kh != 3 || g.kw != 3) return 1;
     int xt = 1;
     if (bands_all * 4 <= kMaxBands && g.Ow > 8) xt = 4;
     else if (bands_all * 2 <= kMaxBands && g.Ow > 4) xt = 2;
@@ -401,7 +415,7 @@ int strip_xt(const Geometry &g)
 // tile visits fewer halo cells per output (15.7 -> 13.8 us per image at 128 channels).
 inline int strip_wide_xt(const Geometry &g)   // 0: four-column tiles, else the strip's number of eight-column tiles
 {
-    if (g.N < kBatchedFromImages || g.kh != 3) return 0;
+    if (g.N < kBatchedFromImages || g.kh != 3 || g.kw != 3) return 0;
     if (g.stride == 1 && g.Oh * g.Ow >= 2048) return 1;
     return 0;
 }
@@ -414,7 +428,7 @@ inline int strip_wide_xt(const Geometry &g)   // 0: four-column tiles, else the 
 // it loses, e.g. 256 x 14 x 14 at four images 8.7 -> 10.3).
 inline bool strip_four_kernels_per_lane(const Geometry &g)
 {
-    if (g.Kpad % 256 != 0 || g.N < kBatchedFromImages || g.kh != 3 || strip_wide_xt(g) != 0) return false;
+    if (g.Kpad % 256 != 0 || g.N < kBatchedFromImages || g.kh != 3 || g.kw != 3 || strip_wide_xt(g) != 0) return false;
     const int xt = strip_xt(g), bands_all = (g.Oh + 3) / 4;
     const int row_blocks = (bands_all + kMaxBands / xt - 1) / (kMaxBands / xt);
     const int bands = (bands_all + row_blocks - 1) / row_blocks;
@@ -427,6 +441,7 @@ inline bool strip_four_kernels_per_lane(const Geometry &g)
 bool strip_kernel_supports(const Geometry &g)
 {
     if (g.n_types < 1) return false;
+    if (line_kernel(g)) return strip_xt(g) > 1;   // only in their batched launch shapes
     return (g.kh == 3 && g.kw == 3 && (g.stride == 1 || g.stride == 2)) ||
            (g.kh == 5 && g.kw == 5 && g.stride == 1) || (g.kh == 7 && g.kw == 7 && g.stride == 2);
 }
@@ -486,7 +501,18 @@ bool strip_kernel_preferred(const Geometry &g)
         if (xt == 2) return CALL(3, 3, S, 4, 4, 8, 1, 2);                            \
         return CALL(3, 3, S, 4, 4, 8, 1, 1);                                         \
     }
+// (kernels per lane: 160 and 192 kernels, frequent in these layers, pad to 192 = 3 x 64)
+#define CPOCONV_STRIP_LINE(CALL, KH, KW, TXW, XTW)                                   \
+    if (g.kh == KH && g.kw == KW && g.stride == 1 && strip_xt(g) == XTW) {           \
+        if (g.Kpad % 192 == 0) return CALL(KH, KW, 1, 4, TXW, 8, 3, XTW);            \
+        if (g.Kpad % 128 == 0) return CALL(KH, KW, 1, 4, TXW, 8, 2, XTW);            \
+        return CALL(KH, KW, 1, 4, TXW, 8, 1, XTW);                                   \
+    }
 #define CPOCONV_STRIP_DISPATCH(CALL)                                                 \
+    CPOCONV_STRIP_LINE(CALL, 1, 7, 6, 3)                                             \
+    CPOCONV_STRIP_LINE(CALL, 7, 1, 6, 3)                                             \
+    CPOCONV_STRIP_LINE(CALL, 1, 3, 4, 2)                                             \
+    CPOCONV_STRIP_LINE(CALL, 3, 1, 4, 2)                                             \
     CPOCONV_STRIP_WIDE(CALL, 1, 1)                                                   \
     CPOCONV_STRIP_3X3(CALL, 1)                                                       \
     CPOCONV_STRIP_3X3(CALL, 2)                                                       \

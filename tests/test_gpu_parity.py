@@ -333,6 +333,20 @@ BATCH_CASES = [
     (8, (33, 17, 17, 70, 1, 7, 1, 0, 3)),
     (8, (33, 17, 17, 70, 7, 1, 1, 3, 0)),
     (4, (5, 56, 56, 128, 3, 3, 1, 1, 0)),
+    # 1 x 7 / 7 x 1: one strip of three six-column tiles; 1 x 3 / 3 x 1: two four-column tiles,
+    # four images per workgroup; one and two kernels per lane
+    (4, (40, 17, 17, 128, 7, 1, 1, 3, 0)),
+    (4, (40, 17, 15, 128, 1, 7, 1, 0, 3)),
+    (4, (40, 18, 18, 70, 1, 7, 1, 0, 3)),
+    (4, (40, 13, 13, 70, 7, 1, 1, 3, 0)),
+    (4, (36, 17, 19, 70, 1, 7, 1, 0, 0)),         # without padding: output 13 wide, three-entry NOP segment
+    (8, (40, 8, 8, 128, 1, 3, 1, 0, 1)),
+    (9, (33, 8, 7, 70, 3, 1, 1, 1, 0)),
+    (8, (40, 8, 8, 70, 3, 1, 1, 0, 0)),
+    (4, (36, 17, 17, 160, 1, 7, 1, 0, 3)),        # 160 kernels pad to 192: three kernels per lane
+    (4, (36, 17, 17, 192, 7, 1, 1, 3, 0)),
+    (8, (36, 8, 8, 384, 1, 3, 1, 0, 1)),
+    (8, (36, 8, 8, 180, 3, 1, 1, 1, 0)),
 ]
 
 
