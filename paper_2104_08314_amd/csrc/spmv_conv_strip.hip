@@ -516,7 +516,11 @@ bool strip_kernel_preferred(const Geometry &g)
     CPOCONV_STRIP_WIDE(CALL, 1, 1)                                                   \
     CPOCONV_STRIP_3X3(CALL, 1)                                                       \
     CPOCONV_STRIP_3X3(CALL, 2)                                                       \
-    if (g.kh == 5 && g.kw == 5 && g.stride == 1) return CALL(5, 5, 1, 4, 4, 8, 1, 1); \
+    if (g.kh == 5 && g.kw == 5 && g.stride == 1) {                                   \
+        if (g.N >= kBatchedFromImages && g.Kpad % 192 == 0) return CALL(5, 5, 1, 4, 4, 4, 3, 1); \
+        if (g.N >= kBatchedFromImages && g.Kpad % 128 == 0) return CALL(5, 5, 1, 4, 4, 4, 2, 1); \
+        return CALL(5, 5, 1, 4, 4, 8, 1, 1);                                         \
+    }                                                                                \
     if (g.kh == 7 && g.kw == 7 && g.stride == 2) return CALL(7, 7, 2, 4, 4, 4, 1, 1);
 
 int64_t strip_kernel_partial_bytes(const Geometry &g)
