@@ -101,7 +101,8 @@ def sparse_flops(spec, act_np):
     """2 x (kernel cells every NZE meets: rows x partitions holding it) x K, counted exactly."""
     import numpy as np
 
-    C, H, W, K, kh, kw, s, p = spec.shape_tuple
+    C, H, W, K, kh, kw, s, p = spec.shape_tuple[:8]
+    pw = p if spec.pad_w is None else spec.pad_w
 
     def meets(n_in, n_out, k):
         cnt = np.zeros(n_in, np.int64)
@@ -110,14 +111,14 @@ def sparse_flops(spec, act_np):
         return cnt
 
     rows = meets(spec.Ih, spec.Oh, kh)[p:p + H]
-    cols = meets(spec.Iw, spec.Ow, kw)[p:p + W]
+    cols = meets(spec.Iw, spec.Ow, kw)[pw:pw + W]
     nz = (act_np.view(np.uint32) & 0x7FFFFFFF) != 0
     return 2.0 * K * float(np.einsum("chw,h,w->", nz.astype(np.int64), rows, cols))
 
 
 def algorithmic_figures(spec, lens, act_np):
     """Bytes and flops the method itself must move / compute for one layer (4-byte elements)."""
-    C, H, W, K, kh, kw, s, p = spec.shape_tuple
+    C, H, W, K, kh, kw, s, p = spec.shape_tuple[:8]
     nnz, ptr = lens["nnz"], lens["ptr"]
     out_elems = K * spec.Oh * spec.Ow
     wbytes = 4 * K * C * kh * kw
@@ -206,7 +207,7 @@ def kernel_times(api, torch, run, reps):
 def kernel_roofline(stage, kernel, us, fig, spec, lens):
     """Roofline entry of one kernel launch: algorithmic bytes or flops of the launch / duration."""
     t = us * 1e-6
-    C, H, W, K, kh, kw, s, p = spec.shape_tuple
+    C, H, W, K, kh, kw, s, p = spec.shape_tuple[:8]
     if stage.endswith("_layer"):     # kernels of the one-call stages belong to its encode or convolution half
         stage = stage[:3] + ("_encode" if kernel.startswith("encode") else "_conv")
     out_bytes = 4 * K * spec.Oh * spec.Ow
@@ -583,7 +584,7 @@ def main():
 
     if args.all_layers:
         rows = []
-        for s in workloads.all_layers():
+        for s in workloads.all_layers() + workloads.line_layers():
             r, lrow, _, _ = measure_layer(api, torch, workloads, s, reps=50, warm=5)
             _, sel = offline_selection(api, torch, workloads, r, s, reps=10)
             lrow["selection"] = sel
@@ -624,6 +625,20 @@ def main():
                 "all_im2col_f32_per_image": round(sum(i for _, i in per), 1),
                 "all_cpo_per_image": round(sum(c for c, _ in per), 1),
                 "hybrid_per_image": round(sum(min(c, i) for c, i in per), 1),
+                "layers_cpo_faster": sum(c < i for c, i in per),
+            }
+        line = [r for r in rows if r["layer"].startswith("line.")]
+        result["line_layers_us"] = {
+            "layers": len(line),
+            "all_im2col_f32": round(sum(r["us"]["im2col_f32"] for r in line), 1),
+            "all_cpo": round(sum(r["cpo_total_us"] for r in line), 1),
+        }
+        if args.batch > 1:
+            per = [(r["batched"]["cpo_total_per_image_us"], r["batched"]["per_image_us"]["im2col_f32"]) for r in line]
+            result["line_layers_us"]["batched"] = {
+                "n_images": args.batch,
+                "all_im2col_f32_per_image": round(sum(i for _, i in per), 1),
+                "all_cpo_per_image": round(sum(c for c, _ in per), 1),
                 "layers_cpo_faster": sum(c < i for c, i in per),
             }
     print(json.dumps(result))

@@ -123,6 +123,21 @@ def all_layers() -> List[LayerSpec]:
     return [spec for cfg in (1, 2, 3, 4, 5) for spec in layers(cfg)]
 
 
+def line_layers() -> List[LayerSpec]:
+    """Layers with 1 x n and n x 1 kernels, shaped like those of the SI's layer tables (17 x 17
+    maps with 128 to 192 channels under 1 x 7 / 7 x 1 kernels, 8 x 8 maps with 384 channels under
+    1 x 3 / 3 x 1), padded in the kernel's direction only so that the map keeps its size.  A
+    supplement to the five workloads (number 7): ReLU-Gaussian inputs, 60 to 80 % zeros."""
+    rows = [
+        ("1x7.128to128@17", 128, 17, 128, 1, 7, 0.60), ("7x1.128to192@17", 128, 17, 192, 7, 1, 0.60),
+        ("1x7.160to160@17", 160, 17, 160, 1, 7, 0.65), ("7x1.160to192@17", 160, 17, 192, 7, 1, 0.65),
+        ("1x7.192to192@17", 192, 17, 192, 1, 7, 0.70), ("7x1.192to192@17", 192, 17, 192, 7, 1, 0.70),
+        ("1x3.384to384@8", 384, 8, 384, 1, 3, 0.80), ("3x1.384to384@8", 384, 8, 384, 3, 1, 0.80),
+    ]
+    return [LayerSpec("line." + name, 7, i, C, hw, hw, K, kh, kw, 1, kh // 2, "relu_gauss", z, int(0.05 * C),
+                      pad_w=kw // 2) for i, (name, C, hw, K, kh, kw, z) in enumerate(rows)]
+
+
 def layer_seed(spec: LayerSpec, m: int = 0) -> int:
     return BASE_SEED + 100 * spec.config + spec.layer + 1000003 * m
 

@@ -116,6 +116,13 @@ def test_workload_5_layers(api, spec):
     _check_layer(api, act, w, spec.shape_tuple, name=spec.name)
 
 
+@pytest.mark.parametrize("spec", workloads.line_layers(), ids=lambda s: s.name)
+def test_line_layers(api, spec):
+    """The 1 x n / n x 1 layers at full size, one image (register-tile kernel)."""
+    act, w = workloads.make_layer(spec)
+    _check_layer(api, act, w, spec.shape_tuple, name=spec.name)
+
+
 # --- edge cases: ragged tiles, strides, paddings, degenerate geometries ----------------------
 EDGE_SHAPES = [
     (1, 4, 4, 1, 3, 3, 1, 1),
@@ -412,8 +419,9 @@ def test_batched_calls(api, case):
 
 def test_batched_workload_layers(api):
     """Two workload layers at full size with eight images each, sampled against the oracle."""
-    for name, n_images in (("cfg3.256@14", 8), ("cfg5.l05.128@28s1", 8)):
-        spec = {s.name: s for s in workloads.all_layers()}[name]
+    for name, n_images in (("cfg3.256@14", 8), ("cfg5.l05.128@28s1", 8), ("line.1x7.160to160@17", 8),
+                           ("line.7x1.128to192@17", 8), ("line.3x1.384to384@8", 8)):
+        spec = {s.name: s for s in workloads.all_layers() + workloads.line_layers()}[name]
         shape = spec.shape_tuple
         _say(f"[case] batched {name} n={n_images}")
         acts = np.stack([workloads.make_activation(spec, m) for m in range(n_images)])

@@ -20,6 +20,18 @@ def test_layer_table_matches_the_five_workloads():
     assert [s.C for s in workloads.layers(5)[1:]] == [64] * 3 + [128] * 4 + [256] * 6 + [512] * 3
 
 
+def test_line_layers_keep_their_map_size():
+    specs = workloads.line_layers()
+    assert len(specs) == 8 and len({s.name for s in specs}) == 8
+    for s in specs:
+        assert (s.kh == 1) != (s.kw == 1) and s.stride == 1
+        assert (s.Oh, s.Ow) == (s.H, s.W)                     # padded in the kernel's direction only
+        assert s.shape_tuple[7:] == (s.kh // 2, s.kw // 2)
+        act = workloads.make_activation(s)
+        assert act.shape == (s.C, s.H, s.W) and (act >= 0).all()
+        assert abs(float((act == 0).mean()) - (s.zero_frac + 0.05 * (1 - s.zero_frac))) < 0.03
+
+
 @pytest.mark.parametrize("name,lo,hi", [("cfg1.16@28", 0.52, 0.60), ("cfg2.128@56", 0.59, 0.61),
                                         ("cfg3.256@14", 0.70, 0.76), ("cfg4a.5x5.64@27", 0.49, 0.51),
                                         ("cfg4b.3x3s2.128@56", 0.63, 0.67), ("cfg5.l16.512@7s1", 0.84, 0.88)])
