@@ -188,6 +188,22 @@ def test_small_chain(api, methods, n_images):
     _check_chain(api, act, shapes, w_np, b_np, table)
 
 
+@pytest.mark.parametrize("n_images", [1, 8])
+def test_chain_of_line_layers(api, n_images):
+    """1 x 7 then 7 x 1 then 3 x 3 (the factorised 7 x 7 of the SI's layer tables): every layer
+    keeps the 17 x 17 map, the first two with padding in one direction only."""
+    rng = np.random.default_rng(41)
+    shapes = [(36, 17, 17, 40, 1, 7, 1, 0, 3), (40, 17, 17, 70, 7, 1, 1, 3, 0), (70, 17, 17, 33, 3, 3, 1, 1)]
+    w_np, b_np = [], []
+    for i, s in enumerate(shapes):
+        w_np.append((rng.standard_normal((s[3], s[0], s[4], s[5])) * np.sqrt(2.0 / (s[0] * s[4] * s[5]))).astype(np.float32))
+        b_np.append(None if i == 0 else (0.3 * rng.standard_normal(s[0])).astype(np.float32))
+    act = np.maximum(rng.standard_normal((n_images,) + shapes[0][:3]), 0).astype(np.float32)
+    for table in ([api.ALGO_CPO] * 3, [api.ALGO_CPS, api.ALGO_IM2COL, api.ALGO_CPO]):
+        _say(f"[case] chain of line layers n={n_images} {table}")
+        _check_chain(api, act, shapes, w_np, b_np, table)
+
+
 def test_chain_relu_in_front_of_the_first_layer_and_method_changes(api):
     """Layer 0 may itself read a pre-activation map; changing the methods reuses the buffers."""
     act, shapes, w_np, b_np = _small_chain(32, 2)
