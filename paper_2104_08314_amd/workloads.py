@@ -101,7 +101,7 @@ def _cfg5_layers() -> List[LayerSpec]:
 
 
 def layers(config: int) -> List[LayerSpec]:
-    """The layers of one of the five workloads."""
+    """The layers of one of the five workloads (7: the supplementary 1 x n / n x 1 layers)."""
     if config == 1:
         return [LayerSpec("cfg1.16@28", 1, 0, 16, 28, 28, 16, 3, 3, 1, 1, "relu_gauss", 0.5, 2)]
     if config == 2:
@@ -116,6 +116,8 @@ def layers(config: int) -> List[LayerSpec]:
         ]
     if config == 5:
         return _cfg5_layers()
+    if config == 7:
+        return line_layers()
     raise ValueError(f"unknown workload {config}")
 
 
