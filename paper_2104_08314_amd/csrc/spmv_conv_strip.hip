@@ -492,6 +492,11 @@ bool strip_kernel_preferred(const Geometry &g)
             if (xt == 2) return CALL(3, 3, S, 4, 4, 8, 4, 2);                        \
             return CALL(3, 3, S, 4, 4, 8, 4, 1);                                     \
         }                                                                            \
+        if (g.Kpad % 192 == 0 && g.N >= kBatchedFromImages) {                        \
+            if (xt == 4) return CALL(3, 3, S, 4, 4, 8, 3, 4);                        \
+            if (xt == 2) return CALL(3, 3, S, 4, 4, 8, 3, 2);                        \
+            return CALL(3, 3, S, 4, 4, 8, 3, 1);                                     \
+        }                                                                            \
         if (g.Kpad % 128 == 0) {                                                     \
             if (xt == 4) return CALL(3, 3, S, 4, 4, 8, 2, 4);                        \
             if (xt == 2) return CALL(3, 3, S, 4, 4, 8, 2, 2);                        \

@@ -354,6 +354,11 @@ BATCH_CASES = [
     (4, (36, 17, 17, 192, 7, 1, 1, 3, 0)),
     (8, (36, 8, 8, 384, 1, 3, 1, 0, 1)),
     (8, (36, 8, 8, 180, 3, 1, 1, 1, 0)),
+    # 3 x 3 with three kernels per lane (kernel counts that pad to a multiple of 192)
+    (4, (33, 17, 17, 192, 3, 3, 1, 1)),
+    (8, (36, 8, 8, 384, 3, 3, 1, 1)),
+    (4, (33, 17, 17, 160, 3, 3, 2, 1)),
+    (4, (33, 30, 31, 190, 3, 3, 1, 1)),
     # 5 x 5 with two and three kernels per lane
     (4, (20, 27, 27, 192, 5, 5, 1, 2)),
     (4, (20, 13, 14, 128, 5, 5, 1, 2)),
