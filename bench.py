@@ -457,13 +457,16 @@ def main():
     ap.add_argument("--warmup", type=int, default=20)
     ap.add_argument("--config", type=int, default=2, help="workload whose first layer is timed")
     ap.add_argument("--all-layers", action="store_true",
-                    help="also measure every layer of the five workloads (per-layer report on stderr)")
+                    help="also measure every layer of the five workloads and the 1 x n / n x 1 layers (per-layer report "
+                         "on stderr); a full run - one without --no-chain - does so anyway")
     ap.add_argument("--layers-json", default=None, help="with --all-layers: also write the per-layer rows to this file")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--batch", type=int, default=32,
                     help="images per launch of the batched supplement (0 to skip it)")
     ap.add_argument("--no-cold", action="store_true", help="skip the cold-cache timing of the stages")
-    ap.add_argument("--no-chain", action="store_true", help="skip the chained-layers supplement")
+    ap.add_argument("--no-chain", action="store_true",
+                    help="skip the supplements beyond the timed layer: the chained layers and, unless --all-layers "
+                         "asks for it, the per-layer table")
     ap.add_argument("--chain-only", action="store_true",
                     help="run only the chained-layers supplement, with --batch images per launch, and print it")
     ap.add_argument("--batch-only", action="store_true",
@@ -582,7 +585,7 @@ def main():
     if not args.no_cpu_baseline:
         result["cpu_baseline"] = cpu_baseline(spec, workloads, run.w_np)
 
-    if args.all_layers:
+    if args.all_layers or not args.no_chain:
         rows = []
         for s in workloads.all_layers() + workloads.line_layers():
             r, lrow, _, _ = measure_layer(api, torch, workloads, s, reps=50, warm=5)
@@ -608,6 +611,16 @@ def main():
         if args.layers_json:
             with open(args.layers_json, "w") as f:
                 json.dump(rows, f, indent=1)
+        # every layer in the bench line itself: times, speed-ups, CR, the binding roofline's fraction per stage
+        result["layers"] = [
+            {"layer": r["layer"], "shape": r["shape"], "nnz": r["nnz"], "zeros": round(1.0 - r["density"], 4),
+             "us": r["us"], "speedup_cpo_vs_im2col_f32": round(r["speedup_cpo_vs_im2col_f32"], 4),
+             "speedup_cps_vs_im2col_f32": round(r["speedup_cps_vs_im2col_f32"], 4),
+             "cr_cpo": round(r["cr_cpo"], 3), "cr_cps": round(r["cr_cps"], 3),
+             "roofline_frac": {k: [v["bound"], round(v["frac"], 5)] for k, v in r["roofline"].items()
+                               if k in ("cpo_encode", "cpo_conv", "cps_conv", "im2col_f32", "im2col_bf16")},
+             "selection": r["selection"], "batched": r.get("batched")}
+            for r in rows]
         cfg5 = [r for r in rows if r["layer"].startswith("cfg5")]
         result["config5_end_to_end_us"] = {
             "all_im2col_f32": round(sum(r["us"]["im2col_f32"] for r in cfg5), 1),
