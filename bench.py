@@ -391,6 +391,8 @@ def chain_supplement(api, torch, workloads, n_images, reps, m_inputs=5):
         "workload": "chain: workload 5's sixteen 3x3 layers joined end to end, bias + ReLU fused into the reader",
         "n_images": n_images, "layers": L, "offline_inputs": m_inputs,
         "per_image_us": {("all_" + k if k in codes else k): round(v / n_images, 2) for k, v in whole.items()},
+        # the paper's figure of merit (Section 4): (T_im2col - T_method) / T_im2col over the conv layers
+        "time_saving_vs_all_im2col": {k: round(1.0 - whole[k] / whole["im2col"], 4) for k in whole if k != "im2col"},
         "selection_favour_time": [names[c] for c in pick_time],
         "selection_favour_space": [names[c] for c in pick_space],
         "layers_cpo_selected": sum(c == api.ALGO_CPO for c in pick_time),
@@ -616,6 +618,10 @@ def main():
             {"layer": r["layer"], "shape": r["shape"], "nnz": r["nnz"], "zeros": round(1.0 - r["density"], 4),
              "us": r["us"], "speedup_cpo_vs_im2col_f32": round(r["speedup_cpo_vs_im2col_f32"], 4),
              "speedup_cps_vs_im2col_f32": round(r["speedup_cps_vs_im2col_f32"], 4),
+             "time_saving_cpo": round(1.0 - r["cpo_total_us"] / r["us"]["im2col_f32"], 4),
+             "time_saving_cps": round(1.0 - r["cps_total_us"] / r["us"]["im2col_f32"], 4),
+             "time_saving_cpo_batched": (round(1.0 - r["batched"]["cpo_total_per_image_us"] /
+                                               r["batched"]["per_image_us"]["im2col_f32"], 4) if r.get("batched") else None),
              "cr_cpo": round(r["cr_cpo"], 3), "cr_cps": round(r["cr_cps"], 3),
              "roofline_frac": {k: [v["bound"], round(v["frac"], 5)] for k, v in r["roofline"].items()
                                if k in ("cpo_encode", "cpo_conv", "cps_conv", "im2col_f32", "im2col_bf16")},
