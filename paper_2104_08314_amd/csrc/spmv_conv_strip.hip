@@ -363,6 +363,7 @@ int launch_strip(const cpoconv_map &map, const int32_t *indices, const int32_t *
     a.chunks_magic = (65536 + p.chunks - 1) / p.chunks;
     bs.partial = static_cast<int64_t>(p.slices) * a.Ypad * a.Xpad * g.Kpad;
     a.bs = bs;
+    if (p.lds > kLdsBytes) return CPOCONV_ERR_SHAPE;   // no launch shape of the dispatch asks for more than a compute unit has
     {
         KernelTimer timer("spmv_conv_strip", stream);
         hipLaunchKernelGGL((spmv_conv_strip_kernel<KH, KW, S, TY, TX, G, KPL, XT>),
@@ -465,16 +466,19 @@ bool strip_kernel_preferred(const Geometry &g)
 // scalar work of a visited cell (bit test, broadcast) then feeds twice the FMAs
 // (seven columns where they divide the map's width: 56-wide maps, 13.9 -> 12.7 us per image at 128
 // channels and 32 images, 6.0 -> 5.6 at 64 channels)
+// Groups of sixteen channels in these wide-tile variants: half the barriers per channel
+// (12.7 -> 12.2 and 5.6 -> 5.3; in the strips of several tiles larger groups gain nothing, and with
+// four kernels per lane they cost images per workgroup: 3.1 -> 5.9 on 7 x 7 maps)
 #define CPOCONV_STRIP_TX7(CALL)                                                      \
     if (g.kh == 3 && g.kw == 3 && g.stride == 1 && strip_wide_xt(g) == 1 && g.Ow % 7 == 0) { \
-        if (g.Kpad % 128 == 0) return CALL(3, 3, 1, 4, 7, 8, 2, 1);                  \
-        return CALL(3, 3, 1, 4, 7, 8, 1, 1);                                         \
+        if (g.Kpad % 128 == 0) return CALL(3, 3, 1, 4, 7, 16, 2, 1);                  \
+        return CALL(3, 3, 1, 4, 7, 16, 1, 1);                                         \
     }
 #define CPOCONV_STRIP_WIDE(CALL, S, XTW)                                             \
     CPOCONV_STRIP_TX7(CALL)                                                          \
     if (g.kh == 3 && g.kw == 3 && g.stride == S && strip_wide_xt(g) == XTW) {        \
-        if (g.Kpad % 128 == 0) return CALL(3, 3, S, 4, 8, 8, 2, XTW);                \
-        return CALL(3, 3, S, 4, 8, 8, 1, XTW);                                       \
+        if (g.Kpad % 128 == 0) return CALL(3, 3, S, 4, 8, 16, 2, XTW);                \
+        return CALL(3, 3, S, 4, 8, 16, 1, XTW);                                       \
     }
 // (28-wide outputs without four kernels per lane: two seven-column tiles per strip divide the map
 // exactly: 128 x 28 x 28 4.6 -> 4.1 us per image at 32 images)
