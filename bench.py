@@ -6,6 +6,10 @@ SpMV conv, im2col lowering + MFMA GEMM (fp32), and the per-layer selection.  Inp
 resident in HBM before the timed region.  Prints ONE JSON line.
 
   python bench.py [--gpus 1] [--steps K] [--warmup W] [--config 2] [--all-layers]
+
+The printed line is a summary of a few KB (contract fields, roofline of the dominant kernel, CPU
+baseline, the timed layer, totals of the supplements); every record measured goes to the file
+--detail-json names, the per-layer table to stderr.
 """
 from __future__ import annotations
 
@@ -403,9 +407,38 @@ def chain_supplement(api, torch, workloads, n_images, reps, m_inputs=5):
     }
 
 
-def cpu_baseline(spec, workloads, w_np, inputs=5, repeats=10):
-    """The CPU oracle as it stands, one thread, on the same layer: CPO encode + Algorithm 2 on the
-    layer's `inputs` offline inputs, `repeats` times each (about 10 s of CPU work on config 2)."""
+def _cpu_model():
+    try:
+        with open("/proc/cpuinfo") as f:
+            for line in f:
+                if line.lower().startswith("model name"):
+                    return line.split(":", 1)[1].strip()
+    except OSError:
+        pass
+    return "unknown"
+
+
+def _oracle_layer_worker(args):
+    """One process of the all-cores leg: the unchanged one-thread oracle on an input of its own."""
+    config, m, repeats = args
+    import oracle
+    from paper_2104_08314_amd import workloads
+
+    spec = workloads.layers(config)[0]
+    act, w = workloads.make_activation(spec, m), workloads.make_weights(spec)
+    oracle.sparse_conv(oracle.cpo_encode(act, spec.shape_tuple), w)
+    t0 = time.perf_counter()
+    for _ in range(repeats):
+        oracle.sparse_conv(oracle.cpo_encode(act, spec.shape_tuple), w)
+    return (time.perf_counter() - t0) / repeats
+
+
+def cpu_baseline(spec, workloads, w_np, config, inputs=5, repeats=10):
+    """The CPU oracle as it stands on the same layer: CPO encode + Algorithm 2 on the layer's
+    `inputs` offline inputs, `repeats` times each, one thread (about 10 s of CPU work on config 2);
+    then the same unchanged oracle in one process per usable host core, each on an input of its
+    own (the oracle itself stays single-threaded: the all-cores figure is layers finished per
+    second by independent copies)."""
     import oracle
 
     shape = spec.shape_tuple
@@ -425,11 +458,32 @@ def cpu_baseline(spec, workloads, w_np, inputs=5, repeats=10):
         oracle.conv_direct(act, w_np, shape)
         dense.append((time.perf_counter() - t0) * 1e6)
     med = lambda v: sorted(v)[len(v) // 2]
-    return {"value": med(enc) + med(conv), "unit": "us", "cores": 1, "kind": "oracle",
-            "sample": "the whole layer, %d inputs x %d repeats, medians: oracle CPO encode (%.0f us) + sequential "
-                      "Algorithm 2 convolution (%.0f us), double accumulation, gcc -O2, one thread; dense 7-loop "
-                      "definition of the same layer, once per input: %.0f us"
-                      % (inputs, repeats, med(enc), med(conv), med(dense))}
+    try:
+        usable = len(os.sched_getaffinity(0))
+    except AttributeError:
+        usable = os.cpu_count() or 1
+    cores = max(1, min(usable, int(os.environ.get("OMP_NUM_THREADS", usable) or usable)))
+    all_cores = None
+    if cores > 1:
+        import multiprocessing as mp
+
+        try:
+            with mp.get_context("fork").Pool(cores) as pool:   # called before this process touches the GPU
+                t0 = time.perf_counter()
+                per = pool.map(_oracle_layer_worker, [(config, m, 4) for m in range(cores)])
+                wall = time.perf_counter() - t0
+            # every process finished 4 layers in about 4 * mean(per) seconds: layers per second over all cores
+            rate = sum(1.0 / p for p in per)
+            all_cores = {"cores": cores, "us_per_layer": round(1e6 / rate, 1),
+                         "kind": "independent one-thread oracle copies, one input each", "wall_s": round(wall, 2)}
+        except Exception as exc:   # the baseline is a report, never a reason to lose the bench line
+            all_cores = {"cores": cores, "error": str(exc)[:120]}
+    return {"value": round(med(enc) + med(conv), 1), "unit": "us", "cores": 1, "kind": "oracle",
+            "cpu_model": _cpu_model(), "host_cores_usable": usable,
+            "encode_us": round(med(enc), 1), "conv_us": round(med(conv), 1), "dense_7loop_us": round(med(dense), 1),
+            "all_cores": all_cores,
+            "sample": "the whole layer (cpo encode + Algorithm 2 conv), %d inputs x %d repeats, medians; plain C, "
+                      "double accumulation, gcc -O2, one thread" % (inputs, repeats)}
 
 
 def traffic_from_profiles(kernel_key):
@@ -452,6 +506,56 @@ def traffic_from_profiles(kernel_key):
     return None
 
 
+def compact_line(full):
+    """The one printed JSON line: the contract's fields, the roofline of the dominant kernel, the
+    CPU baseline and short summaries; everything else measured goes to --detail-json."""
+    keep = ("metric", "value", "unit", "n_gpus", "steps", "warmup", "ms_per_step", "higher_is_better", "scaling",
+            "vs_baseline", "dtype", "data", "config", "roofline", "cpu_baseline", "selection")
+    out = {k: full[k] for k in keep if k in full}
+    row = full["layer"]
+    us = row["us"]
+    r3 = lambda v: None if v is None else round(v, 3)
+    out["layer"] = {
+        "nnz": row["nnz"], "zeros": r3(1.0 - row["density"]),
+        "us": {k: us[k] for k in ("cpo_encode", "cpo_conv", "cps_encode", "cps_conv", "cpo_layer", "cps_layer",
+                                  "im2col_f32", "im2col_bf16") if k in us},
+        "speedup_vs_im2col_f32": {"cpo": r3(row["speedup_cpo_vs_im2col_f32"]), "cps": r3(row["speedup_cps_vs_im2col_f32"])},
+        "speedup_vs_im2col_bf16": {"cpo": r3(us["im2col_bf16"] / us["cpo_layer"]), "cps": r3(us["im2col_bf16"] / us["cps_layer"])},
+        "cr": {"cpo": r3(row["cr_cpo"]), "cps": r3(row["cr_cps"]), "cpo_with_side_band": r3(row["cr_cpo_with_side_band"]),
+               "cps_with_side_band": r3(row["cr_cps_with_side_band"])},
+        "stage_roofline": {k: {"bound": v["bound"], "frac": round(v["frac"], 4),
+                               "hbm_gbs": round(v["achieved"] if v["bound"] == "hbm" else v.get("hbm_gbs", 0.0), 1)}
+                           for k, v in row["roofline"].items()
+                           if k in ("cpo_encode", "cpo_conv", "cps_encode", "cps_conv", "im2col_f32", "im2col_bf16")},
+    }
+    if "cold_us" in row:
+        out["layer"]["cold_us"] = {k: row["cold_us"][k] for k in ("cpo_layer", "cps_layer", "im2col_f32") if k in row["cold_us"]}
+    out["kernels_us"] = {e["stage"] + "/" + e["kernel"]: e["avg_us"] for e in full.get("kernels", [])}
+    b = full.get("batch_supplement")
+    if b:
+        out["batch_supplement"] = {"n_images": b["n_images"], "per_image_us": b["per_image_us"],
+                                   "speedup_cpo_vs_im2col_f32": b["speedup_cpo_vs_im2col_f32"],
+                                   "encode_hbm_frac": b["encode_hbm_frac"],
+                                   "spmv_alu_frac": (b.get("spmv_kernel") or {}).get("frac")}
+    for k in ("config5_end_to_end_us", "line_layers_us"):
+        if k in full:
+            out[k] = full[k]
+    if "layers" in full:
+        ls = full["layers"]
+        out["layers_summary"] = {
+            "layers": len(ls),
+            "cpo_faster_than_im2col_f32": sum(l["time_saving_cpo"] > 0 for l in ls),
+            "cps_faster_than_im2col_f32": sum(l["time_saving_cps"] > 0 for l in ls),
+            "best_time_saving_cpo": max(l["time_saving_cpo"] for l in ls),
+            "cr_cpo_min_max": [min(l["cr_cpo"] for l in ls), max(l["cr_cpo"] for l in ls)],
+        }
+    if "chain_supplement" in full:
+        out["chain_supplement"] = [{"n_images": c["n_images"], "per_image_us": c["per_image_us"],
+                                    "layers_cpo_selected": c["layers_cpo_selected"]} for c in full["chain_supplement"]]
+    out["detail"] = "per-kernel, per-layer and supplement records: --detail-json file; per-layer table on stderr"
+    return out
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -461,7 +565,9 @@ def main():
     ap.add_argument("--all-layers", action="store_true",
                     help="also measure every layer of the five workloads and the 1 x n / n x 1 layers (per-layer report "
                          "on stderr); a full run - one without --no-chain - does so anyway")
-    ap.add_argument("--layers-json", default=None, help="with --all-layers: also write the per-layer rows to this file")
+    ap.add_argument("--detail-json", default=os.path.join(ROOT, "gpurun_out", "bench_detail.json"),
+                    help="file that receives everything measured (per-kernel entries, per-layer rows, supplements); "
+                         "the printed line holds the summary only ('' to skip)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--batch", type=int, default=32,
                     help="images per launch of the batched supplement (0 to skip it)")
@@ -481,9 +587,17 @@ def main():
         sys.exit("bench.py: this build runs on one GPU only (the path is a single-GPU kernel pipeline); "
                  "use --gpus 1")
 
+    from paper_2104_08314_amd import workloads
+
+    # the CPU oracle is timed first, before this process initialises the GPU (its all-cores leg forks)
+    cpu = None
+    if not (args.no_cpu_baseline or args.chain_only or args.batch_only):
+        spec0 = workloads.layers(args.config)[0]
+        cpu = cpu_baseline(spec0, workloads, workloads.make_weights(spec0), args.config)
+
     import torch
 
-    from paper_2104_08314_amd import api, workloads
+    from paper_2104_08314_amd import api
 
     api.lib()
     if not torch.cuda.is_available():
@@ -544,7 +658,8 @@ def main():
             kernels.append(entry)
     # the dominant kernel of the stage that `value` times
     dom = max((e for e in kernels if e["stage"] == "cpo_layer"), key=lambda e: e["avg_us"])
-    roof = {k: dom[k] for k in ("bound", "achieved", "peak", "unit", "frac") if k in dom}
+    roof = {k: (round(dom[k], 4) if isinstance(dom[k], float) else dom[k])
+            for k in ("bound", "achieved", "peak", "unit", "frac") if k in dom}
     roof["kernel"] = dom["kernel"] + " (" + dom["stage"] + ")"
     roof["avg_launch_us"] = dom["avg_us"]
     roof["event_pair_overhead_us"] = round(overhead, 3)
@@ -584,8 +699,8 @@ def main():
     if not args.no_chain:
         result["chain_supplement"] = [chain_supplement(api, torch, workloads, n, reps=10)
                                       for n in ([1, args.batch] if args.batch > 1 else [1])]
-    if not args.no_cpu_baseline:
-        result["cpu_baseline"] = cpu_baseline(spec, workloads, run.w_np)
+    if cpu is not None:
+        result["cpu_baseline"] = cpu
 
     if args.all_layers or not args.no_chain:
         rows = []
@@ -610,9 +725,6 @@ def main():
                   f"cpo {lrow['cpo_total_us']:6.1f} cps {lrow['cps_total_us']:6.1f} im2col {lrow['us']['im2col_f32']:8.1f} bf16 {lrow['us']['im2col_bf16']:8.1f} "
                   f"CR {lrow['cr_cpo']:5.1f}/{lrow['cr_cps']:5.1f} pick {sel['favour_time']}/{sel['favour_space']}" + tail,
                   file=sys.stderr, flush=True)
-        if args.layers_json:
-            with open(args.layers_json, "w") as f:
-                json.dump(rows, f, indent=1)
         # every layer in the bench line itself: times, speed-ups, CR, the binding roofline's fraction per stage
         result["layers"] = [
             {"layer": r["layer"], "shape": r["shape"], "nnz": r["nnz"], "zeros": round(1.0 - r["density"], 4),
@@ -660,7 +772,14 @@ def main():
                 "all_cpo_per_image": round(sum(c for c, _ in per), 1),
                 "layers_cpo_faster": sum(c < i for c, i in per),
             }
-    print(json.dumps(result))
+    if args.detail_json:
+        try:
+            os.makedirs(os.path.dirname(os.path.abspath(args.detail_json)), exist_ok=True)
+            with open(args.detail_json, "w") as f:
+                json.dump(result, f, indent=1)
+        except OSError as exc:
+            print(f"bench.py: could not write {args.detail_json}: {exc}", file=sys.stderr)
+    print(json.dumps(compact_line(result), separators=(",", ":")))
 
 
 if __name__ == "__main__":
