@@ -9,7 +9,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libcpoconv.so")
-SOURCES = ["capi.cpp", "encode.hip", "spmv_conv.hip", "spmv_conv_tile.hip", "spmv_conv_strip.hip", "im2col_gemm.hip"]
+SOURCES = ["capi.cpp", "encode.hip", "spmv_conv.hip", "spmv_conv_tile.hip", "spmv_conv_strip.hip", "spmv_conv_runs.hip", "im2col_gemm.hip"]
 
 COMPILE_FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC",
@@ -18,6 +18,12 @@ COMPILE_FLAGS = [
     "-Wall", "-Wno-unused-function",
     "-I", os.path.join(ROOT, "include"), "-I", CSRC,
 ]
+
+
+# Per-source flags.  The column-run kernel selects one of many code paths per NZE, each adding into
+# its own accumulator registers; merging the common tails of those paths would turn the register
+# numbers into run-time indices and move the accumulators to scratch memory.
+EXTRA_FLAGS = {"spmv_conv_runs.hip": ["-mllvm", "-simplifycfg-sink-common=false"]}
 
 
 def _run(cmd):
@@ -39,7 +45,8 @@ def build(verbose: bool = False) -> str:
     jobs = []
     for src in SOURCES:
         obj = os.path.join(objdir, os.path.splitext(src)[0] + ".o")
-        jobs.append((obj, [hipcc] + COMPILE_FLAGS + ["-x", "hip", "-c", os.path.join(CSRC, src), "-o", obj]))
+        jobs.append((obj, [hipcc] + COMPILE_FLAGS + EXTRA_FLAGS.get(src, []) +
+                     ["-x", "hip", "-c", os.path.join(CSRC, src), "-o", obj]))
     if verbose:
         for _, cmd in jobs:
             print(" ".join(cmd), flush=True)

@@ -164,8 +164,9 @@ int64_t scratch_mtab_bytes(const Geometry &g) { return (4 * mtab_stride(g) * g.N
 
 int64_t scratch_bytes_for(const Geometry &g)
 {
-    const int64_t tile = tile_kernel_partial_bytes(g), strip = strip_kernel_partial_bytes(g);
-    return scratch_counts_bytes(g) + scratch_mtab_bytes(g) + scratch_indices_bytes(g) + (tile > strip ? tile : strip);
+    const int64_t partial = std::max(std::max(tile_kernel_partial_bytes(g), strip_kernel_partial_bytes(g)),
+                                     runs_kernel_partial_bytes(g));
+    return scratch_counts_bytes(g) + scratch_mtab_bytes(g) + scratch_indices_bytes(g) + partial;
 }
 
 }  // namespace cpoconv

@@ -131,6 +131,12 @@ bool strip_kernel_preferred(const Geometry &g);
 int64_t strip_kernel_partial_bytes(const Geometry &g);
 int launch_sparse_conv_strip(const cpoconv_map &map, const int32_t *indices, const int32_t *mtab, const Geometry &g,
                              const float *wt, float *out, float *partial, BatchStrides bs, hipStream_t stream);
+// column-run SpMV kernel (spmv_conv_runs.hip)
+bool runs_kernel_supports(const Geometry &g);
+bool runs_kernel_preferred(const Geometry &g);
+int64_t runs_kernel_partial_bytes(const Geometry &g);
+int launch_sparse_conv_runs(const cpoconv_map &map, const int32_t *indices, const int32_t *mtab, const Geometry &g,
+                            const float *wt, float *out, float *partial, BatchStrides bs, hipStream_t stream);
 // byte offsets of the regions of the caller's scratch buffer
 int64_t scratch_counts_bytes(const Geometry &g);
 int64_t scratch_indices_bytes(const Geometry &g);

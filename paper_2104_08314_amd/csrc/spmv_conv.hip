@@ -379,6 +379,7 @@ int launch_reduce_transpose(const Geometry &g, const float *partial, int slices,
 // the same call can leave the table instead; the strip kernel mostly resolves ptr itself.)
 bool sparse_conv_uses_prologue(const Geometry &g)
 {
+    if (runs_kernel_preferred(g)) return true;
     const bool strip = strip_kernel_preferred(g) || (strip_kernel_supports(g) && !tile_kernel_supports(g));
     const bool tile = strip || tile_kernel_supports(g);
     return tile && !(strip && resolve_in_kernel_ok(g));
@@ -403,8 +404,9 @@ int launch_sparse_conv(const cpoconv_map &map, const Geometry &g, int algo, cons
         bs.indices = indices_stride(g);
         bs.indices16 = 0;
     }
-    const bool strip = strip_kernel_preferred(g) || (strip_kernel_supports(g) && !tile_kernel_supports(g));
-    const bool tile = strip || tile_kernel_supports(g);
+    const bool runs = runs_kernel_preferred(g);
+    const bool strip = !runs && (strip_kernel_preferred(g) || (strip_kernel_supports(g) && !tile_kernel_supports(g)));
+    const bool tile = runs || strip || tile_kernel_supports(g);
     // The strip kernel resolves ptr itself for CPO maps whose segments fit a wavefront (measured:
     // 1-4 us faster than a prologue launch; in the register-tile kernel, where many more workgroups
     // would repeat the work, it was slower).  Otherwise, and for the index reconstruction of CPS,
@@ -425,6 +427,7 @@ int launch_sparse_conv(const cpoconv_map &map, const Geometry &g, int algo, cons
         CPOCONV_HIP_TRY(hipGetLastError());
     }
     float *partial = reinterpret_cast<float *>(base + after_mtab + scratch_indices_bytes(g));
+    if (runs) return launch_sparse_conv_runs(map, indices, mtab, g, wt, out, partial, bs, stream);
     if (strip) return launch_sparse_conv_strip(map, indices, mtab, g, wt, out, partial, bs, stream);
     if (tile) return launch_sparse_conv_tile(map, indices, mtab, g, wt, out, partial, bs, stream);
     const dim3 grid((g.Ow + kTX - 1) / kTX, (g.Oh + kTY - 1) / kTY, (g.Kpad / kLanes) * g.N);
