@@ -145,20 +145,17 @@ int64_t max_ptr_len(const Geometry &g)
     return per_channel * g.C;
 }
 
-// Scratch layout: the encoder's look-back words (epoch, tickets, per-channel stream lengths) | the convolution's
+// Scratch layout: the encoder's look-back words (epochs, per-band stream lengths) | the convolution's
 // table of resolved ptr offsets | one int32 per NZE for the indices cps_conv rebuilds | partial
 // sums of the register-tile convolution.
 // (each region holds g.N images back to back, with the per-image strides below)
 int64_t indices_stride(const Geometry &g) { return static_cast<int64_t>(g.C) * g.H * g.W; }                 // ints
 int64_t mtab_stride(const Geometry &g) { return static_cast<int64_t>(g.C) * std::max(g.n_types, 1) * (g.Ow + 1); }   // ints
 
-// encoder look-back words (8 bytes each): 8 + CPOCONV_MAX_BATCH control words, then two per
-// (image, channel) with at least 512 channel slots per image
-int64_t scratch_counts_bytes(const Geometry &g)
-{
-    const int64_t slots = static_cast<int64_t>(g.N) * std::max(g.C, 512);
-    return (8 * (8 + CPOCONV_MAX_BATCH + 2 * slots) + 255) / 256 * 256;
-}
+// encoder look-back words: the fixed region every scratch buffer starts with (its place and size do
+// not depend on the call, so calls of any shape and batch size may share a buffer), then the words
+// of a call that takes two launches
+int64_t scratch_counts_bytes(const Geometry &g) { return encode_fixed_bytes() + encode_call_flags_bytes(g); }
 int64_t scratch_indices_bytes(const Geometry &g) { return (4 * indices_stride(g) * g.N + 255) / 256 * 256; }
 int64_t scratch_mtab_bytes(const Geometry &g) { return (4 * mtab_stride(g) * g.N + 255) / 256 * 256; }
 
@@ -300,13 +297,10 @@ static int encode_conv_common(const float *act, const cpoconv_shape *shape, int 
     hipStream_t st = static_cast<hipStream_t>(stream);
     // the encoder also leaves the table of resolved ptr offsets: the convolution needs no prologue
     // of its own for a CPO map (a CPS map still has its indices rebuilt by one)
-    // and, for a CPS map, the plain index of every NZE, so that the convolution needs no pass over
-    // IN either; the map itself holds the packed stream as after cps_encode
     const bool table = sparse_conv_uses_prologue(g);
-    const bool indices = algo == CPOCONV_ALGO_CPS && g.top_slot >= 0;
-    const int erc = launch_encode(act, prod, g, *map, algo, scratch, st, table, indices);
+    const int erc = launch_encode(act, prod, g, *map, algo, scratch, st, table);
     if (erc != CPOCONV_OK) return erc;
-    return launch_sparse_conv(*map, g, algo, wt, out, scratch, st, table, indices);
+    return launch_sparse_conv(*map, g, algo, wt, out, scratch, st, table);
 }
 
 int cpo_encode_conv(const float *act, const cpoconv_shape *shape, const cpoconv_map *map, const float *wt,

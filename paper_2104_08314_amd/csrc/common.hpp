@@ -113,12 +113,13 @@ private:
 
 // launchers (defined next to their kernels)
 int launch_encode(const float *act, const Producer &prod, const Geometry &g, const cpoconv_map &map, int algo,
-                  void *scratch, hipStream_t stream, bool write_table = false, bool write_indices = false);
+                  void *scratch, hipStream_t stream, bool write_table = false);
+int64_t encode_fixed_bytes();                        // look-back words every scratch buffer starts with
+int64_t encode_call_flags_bytes(const Geometry &g);  // look-back words of a call that takes two launches
 int launch_prepare_weights(const float *w, const Geometry &g, float *wt, hipStream_t stream);
 int launch_zero_fill(void *buffer, int64_t bytes, hipStream_t stream);
 int launch_sparse_conv(const cpoconv_map &map, const Geometry &g, int algo, const float *wt,
-                       float *out, void *scratch, hipStream_t stream, bool table_ready = false,
-                       bool indices_ready = false);
+                       float *out, void *scratch, hipStream_t stream, bool table_ready = false);
 bool sparse_conv_uses_prologue(const Geometry &g);
 // register-tile SpMV kernel (spmv_conv_tile.hip)
 bool tile_kernel_supports(const Geometry &g);

@@ -386,7 +386,7 @@ bool sparse_conv_uses_prologue(const Geometry &g)
 }
 
 int launch_sparse_conv(const cpoconv_map &map, const Geometry &g, int algo, const float *wt, float *out,
-                       void *scratch, hipStream_t stream, bool table_ready, bool indices_ready)
+                       void *scratch, hipStream_t stream, bool table_ready)
 {
     char *base = static_cast<char *>(scratch);
     int32_t *mtab = reinterpret_cast<int32_t *>(base + scratch_counts_bytes(g));
@@ -411,9 +411,8 @@ int launch_sparse_conv(const cpoconv_map &map, const Geometry &g, int algo, cons
     // 1-4 us faster than a prologue launch; in the register-tile kernel, where many more workgroups
     // would repeat the work, it was slower).  Otherwise, and for the index reconstruction of CPS,
     // a prologue kernel runs first.
-    // (table_ready / indices_ready: the encoder of the same call left the table / the plain CPS
-    // indices in the scratch buffer)
-    const bool expand = in_full != nullptr && !indices_ready;
+    // (table_ready: the encoder of the same call left the table in the scratch buffer)
+    const bool expand = in_full != nullptr;
     const bool in_kernel = strip && !expand && !table_ready && resolve_in_kernel_ok(g);
     if (in_kernel) mtab = nullptr;
     if ((tile && !in_kernel && !table_ready) || expand) {
