@@ -41,6 +41,8 @@ extern "C" {
 #define CPOCONV_ERR_SMALL (-3)       /* a caller buffer is smaller than required           */
 #define CPOCONV_ERR_HIP (-4)         /* a HIP call failed: see cpoconv_last_hip_error()    */
 #define CPOCONV_ERR_ALGO (-5)        /* unknown algorithm / precision / mode value         */
+#define CPOCONV_ERR_MAP (-6)         /* the map's encoder gave up (hdr[7] != 0): the map    */
+                                     /* holds no valid streams                              */
 
 #define CPOCONV_ALGO_IM2COL 0
 #define CPOCONV_ALGO_CPO 1
@@ -133,8 +135,9 @@ int cpoconv_scratch_init(void *scratch, int64_t bytes, void *stream);
  * device memory of at least sizes.scratch_bytes bytes prepared by cpoconv_scratch_init; its
  * other contents are clobbered.  Streams, counts and indices are bit-exact functions of act and
  * shape.  With a scratch buffer that was never prepared (or was overwritten by something else)
- * the result is unspecified; every wait inside the encoder is bounded, and a workgroup whose
- * wait runs out writes no stream and sets hdr[7] to 1 (otherwise 0).
+ * the encoder gives up: every wait inside it is bounded, and a workgroup whose wait runs out, or
+ * whose stream offsets would leave the map's capacities, writes no stream and sets hdr[7] to 1
+ * (otherwise 0); cpoconv_map_header_to_host reports it, convolutions skip such a map.
  * Errors: NULL, SHAPE, SMALL (a capacity or scratch_bytes below the requirement), HIP.
  */
 int cpo_encode(const float *act, const cpoconv_shape *shape, const cpoconv_map *map,
@@ -176,9 +179,7 @@ int cps_conv(const cpoconv_map *map, const cpoconv_shape *shape, const float *wt
  * which is how a layer runs at inference time and what the per-layer selection of Section 3.5
  * times against im2col.  Knowing that the convolution follows, the encoder also leaves the
  * resolved partition offsets in the scratch buffer, so the convolution starts without a pass
- * over ptr of its own; for a CPS map it also leaves there the plain index of every NZE (what
- * Algorithm 4 rebuilds from the packed IN stream), while map->in holds the packed stream exactly
- * as after cps_encode.  Arguments, layouts and errors as the separate calls.
+ * over ptr of its own.  Arguments, layouts and errors as the separate calls.
  */
 int cpo_encode_conv(const float *act, const cpoconv_shape *shape, const cpoconv_map *map, const float *wt,
                     float *out, void *scratch, int64_t scratch_bytes, void *stream);
@@ -296,8 +297,13 @@ int cpoconv_chain_forward(const float *act, const cpoconv_chain_layer *layers, i
 int select_layer_algo(const double *t_im2col, const double *t_cpo, const double *t_cps,
                       int m_inputs, int mode, int *algo_out);
 
-/* Copies map->hdr to the host and waits for the stream: the only synchronising call.
- * Errors: NULL, HIP. */
+/* Copies map->hdr to the host and waits for the stream: the only synchronising call.  hdr_host is
+ * filled in any case; the call returns CPOCONV_ERR_MAP if the header says that the encoder gave up
+ * (hdr[7] != 0, see cpo_encode): such a map holds no valid streams, and every convolution call
+ * given it (or given a map that holds the other algorithm's streams, hdr[3]) leaves `out`
+ * untouched - the kernels read the header themselves, so this also holds for the calls that encode
+ * and convolve in one go, which cannot report it.
+ * Errors: NULL, HIP, MAP. */
 int cpoconv_map_header_to_host(const cpoconv_map *map, int32_t hdr_host[8], void *stream);
 
 /* Host only: partition / overlap-type table of a layer, as the encoders use it.

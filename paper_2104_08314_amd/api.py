@@ -16,7 +16,7 @@ LIB_PATH = os.path.join(_HERE, "libcpoconv.so")
 
 ALGO_IM2COL, ALGO_CPO, ALGO_CPS = 0, 1, 2
 NPF, NPC = -2, -3
-ERR_NULL, ERR_SHAPE, ERR_SMALL, ERR_HIP, ERR_ALGO = -1, -2, -3, -4, -5
+ERR_NULL, ERR_SHAPE, ERR_SMALL, ERR_HIP, ERR_ALGO, ERR_MAP = -1, -2, -3, -4, -5, -6
 MAX_I = 256
 
 
@@ -290,7 +290,12 @@ def im2col_conv(act, shape, weights, lowered, out, precision: int = 0, stream=No
 def cpoconv_map_header_to_host(m: EncodedMap, stream=None, image=0):
     cm = m.c_struct(image)
     hdr = (ctypes.c_int32 * 8)()
-    _check(lib().cpoconv_map_header_to_host(ctypes.byref(cm), hdr, _stream_handle(stream)))
+    rc = lib().cpoconv_map_header_to_host(ctypes.byref(cm), hdr, _stream_handle(stream))
+    if rc == ERR_MAP:      # the header is filled in all the same: the error carries it
+        err = CpoconvError(rc, cpoconv_strerror(rc))
+        err.hdr = [int(v) for v in hdr]
+        raise err
+    _check(rc)
     return [int(v) for v in hdr]
 
 

@@ -509,7 +509,7 @@ int cpoconv_map_header_to_host(const cpoconv_map *map, int32_t hdr_host[8], void
     hipStream_t st = static_cast<hipStream_t>(stream);
     CPOCONV_HIP_TRY(hipMemcpyAsync(hdr_host, map->hdr, 8 * sizeof(int32_t), hipMemcpyDeviceToHost, st));
     CPOCONV_HIP_TRY(hipStreamSynchronize(st));
-    return CPOCONV_OK;
+    return hdr_host[7] != 0 ? CPOCONV_ERR_MAP : CPOCONV_OK;
 }
 
 int cpoconv_geometry(const cpoconv_shape *shape, int32_t info[8], int32_t *col_j,
@@ -568,6 +568,7 @@ const char *cpoconv_strerror(int code)
     case CPOCONV_ERR_SMALL: return "a caller buffer is smaller than required";
     case CPOCONV_ERR_HIP: return "a HIP call failed (see cpoconv_last_hip_error)";
     case CPOCONV_ERR_ALGO: return "unknown algorithm, precision or mode value";
+    case CPOCONV_ERR_MAP: return "the map's encoder gave up (scratch buffer not prepared, or overwritten): no valid streams";
     default: return "unknown error code";
     }
 }

@@ -42,7 +42,17 @@ struct BatchStrides {
     int64_t mtab, partial, out;
     int32_t map_in16;      // the map's IN stream holds int16 entries
     int32_t indices16;     // so does what the convolution reads as IN (the rebuilt CPS indices never do)
+    const int32_t *hdr;    // the map's header (8 ints per image)
+    int32_t algo;          // the algorithm the call expects the map to hold
 };
+
+// A map the convolution must not read: its encoder gave up (hdr[7]), or it holds the other
+// algorithm's streams (hdr[3]).  Every kernel on the convolution side leaves its outputs alone then.
+__device__ __forceinline__ bool map_unusable(const BatchStrides &bs, int image)
+{
+    const int32_t *h = bs.hdr + static_cast<int64_t>(image) * 8;
+    return h[7] != 0 || h[3] != bs.algo;
+}
 
 // IN entries: int32, or int16 in a compact map (same values).  The stream pointer is typed int32
 // either way; offsets count entries.
@@ -147,7 +157,7 @@ int64_t indices_stride(const Geometry &g);
 int64_t mtab_stride(const Geometry &g);
 // out[k][y][x] = sum over channel slices of partial[slice][y][x][k] (spmv_conv.hip)
 int launch_reduce_transpose(const Geometry &g, const float *partial, int slices, int Ypad, int Xpad, float *out,
-                            hipStream_t stream);   // per image: partial advances by slices*Ypad*Xpad*Kpad, out by K*Oh*Ow
+                            const BatchStrides &bs, hipStream_t stream);   // per image: partial advances by slices*Ypad*Xpad*Kpad, out by K*Oh*Ow
 
 // Sum over the channel slices of one output element: four interleaved running sums, then
 // pairwise.  Every kernel that adds slices uses this order, so they agree bit for bit.

@@ -136,6 +136,14 @@ __device__ __forceinline__ void wave_lds_fence()
     __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
 }
 
+// A published length is at most one map's worth of elements; anything larger is not a length (a
+// scratch buffer overwritten by something else) and makes the reader give up before it adds offsets.
+constexpr unsigned kMaxUnitLength = CPOCONV_MAX_I * CPOCONV_MAX_I;
+__device__ __forceinline__ bool lengths_plausible(unsigned long long w0, unsigned long long w1)
+{
+    return (w0 & 0xFFFFFFFFull) <= kMaxUnitLength && (w1 & 0x1FFFFull) <= kMaxUnitLength;
+}
+
 // Lengths one unit published: NZEs, IN entries, and the ptr entries of the whole overlap types it
 // holds (counted as for a live channel).  ok: the words carried the call's tag.
 struct UnitLengths {
@@ -160,7 +168,7 @@ __device__ __forceinline__ UnitLengths read_unit(const unsigned long long *flags
         }
     }
     UnitLengths r;
-    r.ok = (w0 >> 32) == tag && (w1 >> 32) == tag;
+    r.ok = (w0 >> 32) == tag && (w1 >> 32) == tag && lengths_plausible(w0, w1);
     r.nnz = static_cast<int>(w0 & 0xFFFFFFFFull);
     r.in = static_cast<int>(w1 & 0x1FFFFull);
     r.ptr_part = static_cast<int>((w1 >> 17) & 0x7FFFull);
@@ -310,7 +318,7 @@ __global__ __launch_bounds__(kEncThreads) void encode_kernel(const Geometry g, c
                 if (cc < c) {
                     UnitLengths u;
                     if ((w0[j] >> 32) == tag && (w1[j] >> 32) == tag) {
-                        u.ok = true;
+                        u.ok = lengths_plausible(w0[j], w1[j]);
                         u.nnz = static_cast<int>(w0[j] & 0xFFFFFFFFull);
                         u.in = static_cast<int>(w1[j] & 0x1FFFFull);
                         u.ptr_part = static_cast<int>((w1[j] >> 17) & 0x7FFFull);
@@ -684,7 +692,7 @@ __global__ __launch_bounds__(kThreads) void encode_channel_kernel(const Geometry
                     w1 = peek(flags + 2 * cc + 1);
                 }
             }
-            if ((w0 >> 32) != tag || (w1 >> 32) != tag) { failed = 1; break; }
+            if ((w0 >> 32) != tag || (w1 >> 32) != tag || !lengths_plausible(w0, w1)) { failed = 1; break; }
             a1 += static_cast<int>(w0 & 0xFFFFFFFFull);
             a2 += static_cast<int>(w1 & 0x1FFFFull);
             a0 += static_cast<int>((w1 >> 17) & 0x7FFFull);
@@ -943,7 +951,7 @@ __global__ __launch_bounds__(kThreads) void encode_small_kernel(const Geometry g
                     w1 = peek(flags + 2 * cc + 1);
                 }
             }
-            if ((w0 >> 32) != tag || (w1 >> 32) != tag) { failed = 1; break; }
+            if ((w0 >> 32) != tag || (w1 >> 32) != tag || !lengths_plausible(w0, w1)) { failed = 1; break; }
             a1 += static_cast<int>(w0 & 0xFFFFFFFFull);
             a2 += static_cast<int>(w1 & 0x1FFFFull);
             a0 += static_cast<int>((w1 >> 17) & 0x7FFFull);

@@ -67,6 +67,7 @@ __global__ __launch_bounds__(kExpThreads) void conv_prologue_kernel(const Geomet
 {
     __shared__ int32_t wave_a[kExpThreads / kLanes], wave_b[kExpThreads / kLanes];
     const int image = blockIdx.y;
+    if (map_unusable(bs, image)) return;
     const int32_t *__restrict__ ptr = ptr_all + image * bs.ptr;
     const int32_t *__restrict__ in = index_advance(in_all, image * bs.in, bs.map_in16);
     const int32_t *__restrict__ chan_off = chan_off_all + static_cast<int64_t>(image) * 3 * (g.C + 1);
@@ -175,6 +176,7 @@ __global__ __launch_bounds__(kConvThreads) void spmv_conv_lds_kernel(const Geome
 {
     const int ngroups = g.Kpad / kLanes;
     const int image = blockIdx.z / ngroups;
+    if (map_unusable(bs, image)) return;
     const int32_t *__restrict__ ptr = ptr_all + image * bs.ptr;
     const float *__restrict__ da = da_all + image * bs.da;
     const int32_t *__restrict__ in = index_advance(in_all, image * bs.indices, bs.indices16);
@@ -301,6 +303,7 @@ __global__ __launch_bounds__(kProWaves *kLanes) void conv_prologue_wave_kernel(c
 {
     __shared__ int32_t stage_all[kProWaves * kStageInts];
     const int image = blockIdx.y;
+    if (map_unusable(bs, image)) return;
     const int32_t *__restrict__ ptr = ptr_all + image * bs.ptr;
     const int32_t *__restrict__ chan_off = chan_off_all + static_cast<int64_t>(image) * 3 * (g.C + 1);
     int32_t *__restrict__ mtab = mtab_all + image * bs.mtab;
@@ -341,10 +344,12 @@ __global__ __launch_bounds__(kProWaves *kLanes) void conv_prologue_wave_kernel(c
 constexpr int kEpiCols = 4;
 
 __global__ __launch_bounds__(256) void reduce_transpose_kernel(const Geometry g, const float *__restrict__ partial_all,
-                                                              int slices, int Ypad, int Xpad, float *__restrict__ out_all)
+                                                              int slices, int Ypad, int Xpad, float *__restrict__ out_all,
+                                                              const BatchStrides bs)
 {
     __shared__ float t[kLanes][kEpiCols + 1];
     const int ngroups = g.Kpad / kLanes, image = blockIdx.y / ngroups;
+    if (map_unusable(bs, image)) return;
     const int y = blockIdx.x, kb = (blockIdx.y % ngroups) * kLanes, xb = blockIdx.z * kEpiCols;
     const int tid = threadIdx.x, lane = tid & (kLanes - 1), wave = tid / kLanes;
     const int64_t slice_stride = static_cast<int64_t>(Ypad) * Xpad * g.Kpad;
@@ -366,11 +371,11 @@ __global__ __launch_bounds__(256) void reduce_transpose_kernel(const Geometry g,
 }  // namespace
 
 int launch_reduce_transpose(const Geometry &g, const float *partial, int slices, int Ypad, int Xpad, float *out,
-                            hipStream_t stream)
+                            const BatchStrides &bs, hipStream_t stream)
 {
     KernelTimer timer("reduce_transpose", stream);
     hipLaunchKernelGGL(reduce_transpose_kernel, dim3(g.Oh, (g.Kpad / kLanes) * g.N, (g.Ow + kEpiCols - 1) / kEpiCols), dim3(256),
-                       0, stream, g, partial, slices, Ypad, Xpad, out);
+                       0, stream, g, partial, slices, Ypad, Xpad, out, bs);
     CPOCONV_HIP_TRY(hipGetLastError());
     return CPOCONV_OK;
 }
@@ -398,6 +403,8 @@ int launch_sparse_conv(const cpoconv_map &map, const Geometry &g, int algo, cons
     bs.mtab = mtab_stride(g); bs.partial = 0; bs.out = static_cast<int64_t>(g.K) * g.Oh * g.Ow;
     bs.map_in16 = map.in_bits == 16 ? 1 : 0;
     bs.indices16 = bs.map_in16;
+    bs.hdr = map.hdr;
+    bs.algo = algo;
     if (algo == CPOCONV_ALGO_CPS && g.top_slot >= 0) {
         in_full = reinterpret_cast<int32_t *>(base + after_mtab);
         indices = in_full;

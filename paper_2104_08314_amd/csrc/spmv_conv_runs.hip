@@ -164,6 +164,7 @@ __global__ __launch_bounds__(NW *kLanes) void spmv_conv_runs_kernel(
     const int ngroups = g.Kpad / (kLanes * KPL);
     const int kg = blockIdx.z % ngroups, slice = (blockIdx.z / ngroups) % a.slices;
     const int image = blockIdx.z / (ngroups * a.slices);
+    if (map_unusable(a.bs, image)) return;
     const int x0 = blockIdx.x * TX, y0 = blockIdx.y * TY;
     const int kbase = kg * kLanes * KPL;       // this lane holds kernels kbase + lane * KPL .. + KPL - 1
     const char *__restrict__ da = reinterpret_cast<const char *>(da_all + image * a.bs.da);
@@ -325,7 +326,7 @@ int launch_runs(const cpoconv_map &map, const int32_t *indices, const int32_t *m
                                indices, mtab, wt, partial, out);
     }
     CPOCONV_HIP_TRY(hipGetLastError());
-    if (p.slices > 1) return launch_reduce_transpose(g, partial, p.slices, a.Ypad, a.Xpad, out, stream);
+    if (p.slices > 1) return launch_reduce_transpose(g, partial, p.slices, a.Ypad, a.Xpad, out, bs, stream);
     return CPOCONV_OK;
 }
 

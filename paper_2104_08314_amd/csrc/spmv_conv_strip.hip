@@ -81,7 +81,8 @@ __global__ __launch_bounds__(kMaxBands *kLanes) void spmv_conv_strip_kernel(cons
     const int img_l = wave_wg / nwaves;              // which of the workgroup's images this wavefront works on
     const int wave = wave_wg - img_l * nwaves;       // wavefront inside the image
     const int image_raw = (blockIdx.z / (ngroups * a_launch.slices)) * a_launch.imgs + img_l;
-    const bool live = image_raw < a_launch.n_images; // past the launch's last image: only barriers and shared staging
+    // past the launch's last image, or an image whose map must not be read: only barriers and shared staging
+    const bool live = image_raw < a_launch.n_images && !map_unusable(a_launch.bs, image_raw);
     const int image = live ? image_raw : 0;
     StripArgs a = a_launch;
     a.da += image * a.bs.da;
@@ -372,7 +373,7 @@ int launch_strip(const cpoconv_map &map, const int32_t *indices, const int32_t *
                            g, a);
     }
     CPOCONV_HIP_TRY(hipGetLastError());
-    if (p.slices > 1) return launch_reduce_transpose(g, partial, p.slices, a.Ypad, a.Xpad, out, stream);
+    if (p.slices > 1) return launch_reduce_transpose(g, partial, p.slices, a.Ypad, a.Xpad, out, bs, stream);
     return CPOCONV_OK;
 }
 

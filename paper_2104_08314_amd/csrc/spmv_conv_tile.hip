@@ -75,6 +75,7 @@ __global__ __launch_bounds__(NW *kLanes) void spmv_conv_tile_kernel(const Geomet
     const int ngroups = g.Kpad / (kLanes * KPL);
     const int kg = blockIdx.z % ngroups, slice = (blockIdx.z / ngroups) % a_launch.slices;
     const int image = blockIdx.z / (ngroups * a_launch.slices);
+    if (map_unusable(a_launch.bs, image)) return;
     TileArgs a = a_launch;
     a.da += image * a.bs.da;
     a.in = index_advance(a.in, image * a.bs.indices, a.bs.indices16);
@@ -392,7 +393,7 @@ int launch_tile(const cpoconv_map &map, const int32_t *indices, const int32_t *m
                            dim3(NW * kLanes), lds, stream, g, a);
     }
     CPOCONV_HIP_TRY(hipGetLastError());
-    if (slices > 1) return launch_reduce_transpose(g, partial, slices, a.Ypad, a.Xpad, out, stream);
+    if (slices > 1) return launch_reduce_transpose(g, partial, slices, a.Ypad, a.Xpad, out, bs, stream);
     return CPOCONV_OK;
 }
 

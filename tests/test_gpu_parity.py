@@ -46,6 +46,7 @@ def _run_encoders(api, act_np, shape):
 
 def _assert_same_map(got, ref, algo_code):
     ptr, da, ind, chan_off, hdr = got
+    assert hdr[7] == 0                                                     # no encoder workgroup gave up
     assert hdr[0] == ref.ptr.size and hdr[1] == ref.da.size and hdr[2] == ref.ind.size
     assert hdr[3] == algo_code
     assert np.array_equal(ptr, ref.ptr)
