@@ -79,7 +79,9 @@ typedef struct {
  *                is written without the per-channel offsets into the streams).
  *   hdr          8 int32: |ptr|, |DA|, |IN|, algorithm (CPOCONV_ALGO_CPO / _CPS), C, Ow, the width
  *                of an IN entry in bits (32 or 16), and a failure flag (0, or 1 if the encoder
- *                gave up: see cpo_encode).
+ *                gave up: see cpo_encode) - as cpoconv_map_header_to_host returns them.  In
+ *                device memory the last two words are the library's: the width shares its word
+ *                with a stamp of the encoding call, and the flag is raised by storing that stamp.
  *   in_bits      width of the IN entries: 0 or 32 for int32; 16 for a compact map whose `in`
  *                points at int16 entries (in_cap still counts entries).  Every IN entry is an
  *                index below (H + 2 pad_h) * kw <= 2816, the negative of one, or a row pattern

@@ -172,6 +172,8 @@ using namespace cpoconv;
 
 extern "C" {
 
+static const Producer kAsStored = {nullptr, 0};
+
 static int batch_geometry(const cpoconv_shape *shape, int n_images, Geometry *g)
 {
     const int rc = build_geometry(shape, g);
@@ -205,8 +207,6 @@ int cpoconv_batch_sizes(const cpoconv_shape *shape, int n_images, cpoconv_sizes_
     sizes->Ow = g.Ow;
     return CPOCONV_OK;
 }
-
-static const Producer kAsStored = {nullptr, 0};
 
 static int encode_common(const float *act, const cpoconv_shape *shape, int n_images, const cpoconv_map *map,
                          void *scratch, int64_t scratch_bytes, void *stream, int algo, const Producer &prod = kAsStored)
@@ -509,6 +509,11 @@ int cpoconv_map_header_to_host(const cpoconv_map *map, int32_t hdr_host[8], void
     hipStream_t st = static_cast<hipStream_t>(stream);
     CPOCONV_HIP_TRY(hipMemcpyAsync(hdr_host, map->hdr, 8 * sizeof(int32_t), hipMemcpyDeviceToHost, st));
     CPOCONV_HIP_TRY(hipStreamSynchronize(st));
+    // on the device hdr[6] also carries the stamp of the call that wrote the header and hdr[7] the stamp
+    // of the call in which an encoder unit gave up: the caller gets the width and a plain 0 / 1
+    const int32_t stamp = hdr_host[6] >> 8, failed_in = hdr_host[7];
+    hdr_host[6] &= 0xFF;
+    hdr_host[7] = (failed_in != 0 && failed_in == stamp) ? 1 : 0;
     return hdr_host[7] != 0 ? CPOCONV_ERR_MAP : CPOCONV_OK;
 }
 

@@ -46,12 +46,13 @@ struct BatchStrides {
     int32_t algo;          // the algorithm the call expects the map to hold
 };
 
-// A map the convolution must not read: its encoder gave up (hdr[7]), or it holds the other
+// A map the convolution must not read: its encoder gave up (hdr[7] equals the header's stamp), or it holds the other
 // algorithm's streams (hdr[3]).  Every kernel on the convolution side leaves its outputs alone then.
 __device__ __forceinline__ bool map_unusable(const BatchStrides &bs, int image)
 {
     const int32_t *h = bs.hdr + static_cast<int64_t>(image) * 8;
-    return h[7] != 0 || h[3] != bs.algo;
+    const int failed_in = h[7];   // stamp of the call in which an encoder unit gave up; hdr[6] >> 8: stamp of the header
+    return (failed_in != 0 && failed_in == (h[6] >> 8)) || h[3] != bs.algo;
 }
 
 // IN entries: int32, or int16 in a compact map (same values).  The stream pointer is typed int32

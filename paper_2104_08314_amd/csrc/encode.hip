@@ -129,6 +129,20 @@ __device__ __forceinline__ void poke(unsigned long long *p, unsigned long long v
     __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 }
 
+// Failure flag of a map.  hdr[6] carries, above the width of the IN entries, a stamp of the call that
+// wrote the header (derived from the image slot's epoch, which every call advances); a unit that gives
+// up stores the same stamp in hdr[7].  A map is failed when the two agree.  Nothing has to be reset when
+// a call starts - a reset would race with units that give up at once - and a stamp left by an
+// earlier failed call never equals a later call's; the last unit clears such a leftover all the same.
+__device__ __forceinline__ int call_stamp(unsigned long long epoch) { return static_cast<int>(epoch % 0x7FFFFFull) + 1; }
+__device__ __forceinline__ void close_header(int32_t *hdr, int stamp, int in16)   // the last unit, also when it gives up
+{
+    hdr[6] = (in16 ? 16 : 32) | (stamp << 8);
+    const int old = __hip_atomic_load(&hdr[7], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    if (old != 0 && old != stamp) atomicCAS(&hdr[7], old, 0);
+}
+__device__ __forceinline__ void raise_failure(int32_t *hdr, int stamp) { atomicExch(&hdr[7], stamp); }
+
 __device__ __forceinline__ void wave_lds_fence()
 {
     __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
@@ -204,7 +218,8 @@ __global__ __launch_bounds__(kEncThreads) void encode_kernel(const Geometry g, c
     const int vb = plan.band_begin[b], ve = plan.band_begin[b + 1], nb = ve - vb;
     const int my_slot = plan.band_slot[b];
 
-    const unsigned long long epoch = kMode == kSinglePass ? peek(ctrl + 8 + image) : 0ull;
+    const unsigned long long epoch = peek(ctrl + 8 + image);   // one launch: the tag of its words; always: the call's stamp
+    const int stamp = call_stamp(epoch);
     const unsigned long long tag = kMode == kSinglePass ? epoch % 0xFFFFFFFEull + 1ull : kTagTwoLaunches;
     unsigned long long *flags = flags_all + 2 * static_cast<int64_t>(image) * units_stride;
 
@@ -215,7 +230,6 @@ __global__ __launch_bounds__(kEncThreads) void encode_kernel(const Geometry g, c
     map.in = index_advance(maps.in, image * maps.in_cap, in16);
     map.chan_off += static_cast<int64_t>(image) * 3 * (g.C + 1);
     map.hdr += image * 8;
-    if (kMode != kPublishOnly && unit == 0 && lane == 0) map.hdr[7] = 0;   // raised by a band that gives up
 
     // ---- load: lane = (row phase rp, column col); CW columns side by side, 64 / CW rows per pass ------
     int cw_log2 = 0;
@@ -398,9 +412,12 @@ __global__ __launch_bounds__(kEncThreads) void encode_kernel(const Geometry g, c
     // the last unit has seen every other unit's lengths, so all of them have read the epoch: it moves on
     // (one writer per image; the next call is ordered after this launch), also after a failure, so that
     // the words of this call are never taken for the next one's
-    if (kMode == kSinglePass && last_unit && lane == 0) poke(ctrl + 8 + image, epoch + 1ull);
+    if (last_unit && lane == 0) {
+        poke(ctrl + 8 + image, epoch + 1ull);
+        close_header(map.hdr, stamp, in16);
+    }
     if (failed) {
-        if (lane == 0) atomicOr(&map.hdr[7], 1);
+        if (lane == 0) raise_failure(map.hdr, stamp);
         return;
     }
 
@@ -419,7 +436,6 @@ __global__ __launch_bounds__(kEncThreads) void encode_kernel(const Geometry g, c
         map.hdr[3] = cps ? CPOCONV_ALGO_CPS : CPOCONV_ALGO_CPO;
         map.hdr[4] = g.C;
         map.hdr[5] = g.Ow;
-        map.hdr[6] = in16 ? 16 : 32;
     }
 
     // ---- ptr of the band's types and, for a convolution of the same call, the table of absolute DA
@@ -554,7 +570,8 @@ __global__ __launch_bounds__(kThreads) void encode_channel_kernel(const Geometry
     // image blockIdx.y of the launch: its map is image 0's advanced by the per-image capacities
     const int image = blockIdx.y;
     const float *__restrict__ act = act_all + static_cast<int64_t>(image) * g.C * g.H * g.W;
-    const unsigned long long epoch = kMode == kSinglePass ? peek(ctrl + 8 + image) : 0ull;
+    const unsigned long long epoch = peek(ctrl + 8 + image);   // one launch: the tag of its words; always: the call's stamp
+    const int stamp = call_stamp(epoch);
     const unsigned long long tag = kMode == kSinglePass ? epoch % 0xFFFFFFFEull + 1ull : kTagTwoLaunches;
     unsigned long long *flags = flags_all + 2 * static_cast<int64_t>(image) * units_stride;
     cpoconv_map map = maps;
@@ -602,7 +619,6 @@ __global__ __launch_bounds__(kThreads) void encode_channel_kernel(const Geometry
         col_wh[tid] = g.col_what[tid];
     }
     if (tid < 4) chan_base[tid] = 0;
-    if (kMode != kPublishOnly && tid == 0 && c == 0) map.hdr[7] = 0;   // raised by a workgroup that gives up its look-back
     __syncthreads();
 
     // ---- counts: every wavefront takes kChunk / 8 rows of the chunk (lane = column in stream
@@ -709,12 +725,15 @@ __global__ __launch_bounds__(kThreads) void encode_channel_kernel(const Geometry
     // the last channel has seen every other channel's lengths, so all of them have read the epoch:
     // it may move on (one writer per image; the next call is ordered after this launch)
     // (also after a failure, so that the words of this call are never taken for the next one's)
-    if (kMode == kSinglePass && tid == 0 && c == g.C - 1) poke(ctrl + 8 + image, epoch + 1ull);
+    if (tid == 0 && c == g.C - 1) {
+        poke(ctrl + 8 + image, epoch + 1ull);
+        close_header(map.hdr, stamp, in16);
+    }
     // a predecessor never showed up (scratch not initialised?), or the offsets would leave the map's
     // buffers (a scratch buffer overwritten by something else): write nothing
     if (chan_base[3] != 0 || chan_base[0] + ptr_c > maps.ptr_cap || chan_base[1] + nnz_c > maps.da_cap ||
         chan_base[2] + in_c > maps.in_cap) {
-        if (tid == 0) atomicOr(&map.hdr[7], 1);
+        if (tid == 0) raise_failure(map.hdr, stamp);
         return;
     }
 
@@ -733,8 +752,7 @@ __global__ __launch_bounds__(kThreads) void encode_channel_kernel(const Geometry
             map.hdr[3] = cps ? CPOCONV_ALGO_CPS : CPOCONV_ALGO_CPO;
             map.hdr[4] = g.C;
             map.hdr[5] = g.Ow;
-            map.hdr[6] = in16 ? 16 : 32;
-        }
+            }
     }
 
     // ---- for a convolution that follows in the same call: the table of absolute DA offsets after
@@ -859,7 +877,8 @@ __global__ __launch_bounds__(kThreads) void encode_small_kernel(const Geometry g
     const int c0 = blockIdx.x * kWaves, c = c0 + wave;
     const bool live = c < g.C;                         // wavefronts past the last channel only help with the look-back
     const float *__restrict__ act = act_all + static_cast<int64_t>(image) * g.C * g.H * g.W;
-    const unsigned long long epoch = kMode == kSinglePass ? peek(ctrl + 8 + image) : 0ull;
+    const unsigned long long epoch = peek(ctrl + 8 + image);   // one launch: the tag of its words; always: the call's stamp
+    const int stamp = call_stamp(epoch);
     const unsigned long long tag = kMode == kSinglePass ? epoch % 0xFFFFFFFEull + 1ull : kTagTwoLaunches;
     unsigned long long *flags = flags_all + 2 * static_cast<int64_t>(image) * units_stride;
     cpoconv_map map = maps;
@@ -878,7 +897,6 @@ __global__ __launch_bounds__(kThreads) void encode_small_kernel(const Geometry g
     const int top_end = (cps && g.top_slot >= 0) ? g.type_begin[g.top_slot + 1] : 0;
 
     if (tid < 4) grp_base[tid] = 0;
-    if (kMode != kPublishOnly && tid == 0 && c0 == 0) map.hdr[7] = 0;
 
     // ---- the channel into LDS (coalesced), then its column bitmaps: lane = column in stream order ----
     if (live) {
@@ -967,14 +985,17 @@ __global__ __launch_bounds__(kThreads) void encode_small_kernel(const Geometry g
     __syncthreads();
     // the last channel's group has seen every other channel's lengths: the epoch may move on (also
     // after a failure, so that the words of this call are never taken for the next one's)
-    if (kMode == kSinglePass && tid == 0 && c0 + kWaves >= g.C) poke(ctrl + 8 + image, epoch + 1ull);
+    if (tid == 0 && c0 + kWaves >= g.C) {
+        poke(ctrl + 8 + image, epoch + 1ull);
+        close_header(map.hdr, stamp, in16);
+    }
     int group_ptr = 0, group_da = 0, group_in = 0;
     for (int w = 0; w < kWaves; ++w) { group_ptr += grp[w][0]; group_da += grp[w][1]; group_in += grp[w][2]; }
     // a predecessor never showed up, or the offsets would leave the map's buffers: write nothing
     const bool failed = grp_base[3] != 0 || grp_base[0] + group_ptr > maps.ptr_cap || grp_base[1] + group_da > maps.da_cap ||
                         grp_base[2] + group_in > maps.in_cap;
     if (failed) {
-        if (tid == 0) atomicOr(&map.hdr[7], 1);
+        if (tid == 0) raise_failure(map.hdr, stamp);
         return;
     }
     if (!live) return;
@@ -995,8 +1016,7 @@ __global__ __launch_bounds__(kThreads) void encode_small_kernel(const Geometry g
             map.hdr[3] = cps ? CPOCONV_ALGO_CPS : CPOCONV_ALGO_CPO;
             map.hdr[4] = g.C;
             map.hdr[5] = g.Ow;
-            map.hdr[6] = in16 ? 16 : 32;
-        }
+            }
     }
 
     // ---- the table of absolute DA offsets after every partition, for a convolution of the same call ----
