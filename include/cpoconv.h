@@ -145,6 +145,21 @@ int cpoconv_scratch_init(void *scratch, int64_t bytes, void *stream);
 int cpo_encode(const float *act, const cpoconv_shape *shape, const cpoconv_map *map,
                void *scratch, int64_t scratch_bytes, void *stream);
 
+/*
+ * cpo_encode for callers that cannot allocate device memory (code under HIP graph capture, tight
+ * serving loops, harnesses that forbid it): the same encoding, bit for bit, with the encoder's
+ * look-back words kept in a device array of the library instead of a caller's scratch buffer.  The
+ * call allocates nothing and needs no cpoconv_scratch_init.  The array is CPOCONV_STATIC_SCRATCH_BYTES
+ * (2 MiB) per GPU the library runs on, held until the process ends, shared by every call of this
+ * entry point on that GPU and keeping state from call to call: calls that overlap on one GPU race -
+ * order them (one stream, or explicit dependencies).  Layers whose look-back words do not fit the
+ * array (more than 512 channels with so many that the two-launch encoder's words exceed it) are
+ * refused with CPOCONV_ERR_SMALL.  Errors otherwise as cpo_encode; SHAPE also for a device ordinal
+ * of 64 or more.
+ */
+#define CPOCONV_STATIC_SCRATCH_BYTES (2 << 20)
+int cpo_encode_static_scratch(const float *act, const cpoconv_shape *shape, const cpoconv_map *map, void *stream);
+
 /* CPS encoding (Algorithm 3): as cpo_encode, with the overlap-kw indices packed in set4
  * patterns. */
 int cps_encode(const float *act, const cpoconv_shape *shape, const cpoconv_map *map,

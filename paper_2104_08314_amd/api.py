@@ -78,6 +78,7 @@ EXPORTS = (
     "cpoconv_scratch_init", "cpoconv_batch_sizes", "cpo_encode_batch", "cps_encode_batch", "cpo_conv_batch", "cps_conv_batch",
     "im2col_conv_batch", "cpo_encode_conv", "cps_encode_conv", "cpo_encode_conv_batch", "cps_encode_conv_batch",
     "cpo_encode_relu", "cps_encode_relu", "im2col_conv_relu", "cpoconv_chain_sizes", "cpoconv_chain_forward",
+    "cpo_encode_static_scratch",
 )
 
 
@@ -249,6 +250,16 @@ def cpo_encode(act, shape, m: EncodedMap, scratch, stream=None) -> None:
 
 def cps_encode(act, shape, m: EncodedMap, scratch, stream=None) -> None:
     _encode("cps_encode", act, shape, m, scratch, stream)
+
+
+def cpo_encode_static_scratch(act, shape, m: EncodedMap, stream=None) -> None:
+    """cpo_encode without a scratch buffer from the caller (the library's own device array)."""
+    import torch
+
+    sh = make_shape(shape)
+    cm = m.c_struct()
+    _check(lib().cpo_encode_static_scratch(_dev_ptr(act, torch.float32), ctypes.byref(sh), ctypes.byref(cm),
+                                           _stream_handle(stream)))
 
 
 def cpoconv_prepare_weights(weights, shape, wt, stream=None) -> None:

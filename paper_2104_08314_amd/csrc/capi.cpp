@@ -224,6 +224,52 @@ static int encode_common(const float *act, const cpoconv_shape *shape, int n_ima
     return launch_encode(act, prod, g, *map, algo, scratch, static_cast<hipStream_t>(stream));
 }
 
+// ---- an encoder entry point that takes no scratch buffer from the caller ---------------------------
+// The encoder's look-back words live in a file-scope device array (zero at load time, which is the
+// state cpoconv_scratch_init leaves).  Host code never uses the array's name as an address: the
+// device address is asked for once per device and kept.
+namespace {
+constexpr int64_t kStaticScratchBytes = int64_t{2} << 20;
+static __device__ __align__(256) unsigned char scratch[kStaticScratchBytes];
+constexpr int kMaxDevices = 64;
+void *g_static_scratch[kMaxDevices] = {nullptr};
+std::mutex g_static_scratch_mutex;
+
+int static_scratch_of_current_device(void **ptr)
+{
+    int dev = -1;
+    CPOCONV_HIP_TRY(hipGetDevice(&dev));
+    if (dev < 0 || dev >= kMaxDevices) return CPOCONV_ERR_SHAPE;
+    std::lock_guard<std::mutex> lock(g_static_scratch_mutex);
+    if (g_static_scratch[dev] == nullptr) {
+        void *p = nullptr;
+        CPOCONV_HIP_TRY(hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)));   // this device's copy of the array
+        g_static_scratch[dev] = p;
+    }
+    *ptr = g_static_scratch[dev];
+    return CPOCONV_OK;
+}
+}  // namespace
+
+int cpo_encode_static_scratch(const float *act, const cpoconv_shape *shape, const cpoconv_map *map, void *stream)
+{
+    if (!act || !shape || !map) return CPOCONV_ERR_NULL;
+    if (!map->ptr || !map->da || !map->in || !map->chan_off || !map->hdr) return CPOCONV_ERR_NULL;
+    if (map->in_bits != 0 && map->in_bits != 16 && map->in_bits != 32) return CPOCONV_ERR_ALGO;
+    Geometry g;
+    const int rc = build_geometry(shape, &g);
+    if (rc != CPOCONV_OK) return rc;
+    const int64_t chw = static_cast<int64_t>(g.C) * g.H * g.W;
+    if (map->ptr_cap < max_ptr_len(g) || map->da_cap < chw || map->in_cap < chw) return CPOCONV_ERR_SMALL;
+    // the encoder's part of a scratch buffer is all this call needs; layers whose look-back words
+    // do not fit the array (very many channels: the two-launch encoder's own words) are refused
+    if (scratch_counts_bytes(g) > kStaticScratchBytes) return CPOCONV_ERR_SMALL;
+    void *buffer = nullptr;
+    const int src = static_scratch_of_current_device(&buffer);
+    if (src != CPOCONV_OK) return src;
+    return launch_encode(act, kAsStored, g, *map, CPOCONV_ALGO_CPO, buffer, static_cast<hipStream_t>(stream));
+}
+
 int cpoconv_scratch_init(void *scratch, int64_t bytes, void *stream)
 {
     if (!scratch) return CPOCONV_ERR_NULL;
