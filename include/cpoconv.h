@@ -196,7 +196,9 @@ int cps_conv(const cpoconv_map *map, const cpoconv_shape *shape, const float *wt
  * which is how a layer runs at inference time and what the per-layer selection of Section 3.5
  * times against im2col.  Knowing that the convolution follows, the encoder also leaves the
  * resolved partition offsets in the scratch buffer, so the convolution starts without a pass
- * over ptr of its own.  Arguments, layouts and errors as the separate calls.
+ * over ptr of its own; for a CPS map it also leaves there the plain index of every NZE, 16 bits
+ * each (what Algorithm 4 rebuilds from the packed IN stream), while map->in holds the packed stream
+ * exactly as after cps_encode.  Arguments, layouts and errors as the separate calls.
  */
 int cpo_encode_conv(const float *act, const cpoconv_shape *shape, const cpoconv_map *map, const float *wt,
                     float *out, void *scratch, int64_t scratch_bytes, void *stream);

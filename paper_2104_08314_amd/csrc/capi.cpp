@@ -146,17 +146,17 @@ int64_t max_ptr_len(const Geometry &g)
 }
 
 // Scratch layout: the encoder's look-back words (epochs, per-band stream lengths) | the convolution's
-// table of resolved ptr offsets | one int32 per NZE for the indices cps_conv rebuilds | partial
+// table of resolved ptr offsets | one int16 per NZE for the indices cps_conv rebuilds | partial
 // sums of the register-tile convolution.
 // (each region holds g.N images back to back, with the per-image strides below)
-int64_t indices_stride(const Geometry &g) { return static_cast<int64_t>(g.C) * g.H * g.W; }                 // ints
+int64_t indices_stride(const Geometry &g) { return static_cast<int64_t>(g.C) * g.H * g.W; }                 // entries
 int64_t mtab_stride(const Geometry &g) { return static_cast<int64_t>(g.C) * std::max(g.n_types, 1) * (g.Ow + 1); }   // ints
 
 // encoder look-back words: the fixed region every scratch buffer starts with (its place and size do
 // not depend on the call, so calls of any shape and batch size may share a buffer), then the words
 // of a call that takes two launches
 int64_t scratch_counts_bytes(const Geometry &g) { return encode_fixed_bytes() + encode_call_flags_bytes(g); }
-int64_t scratch_indices_bytes(const Geometry &g) { return (4 * indices_stride(g) * g.N + 255) / 256 * 256; }
+int64_t scratch_indices_bytes(const Geometry &g) { return (2 * indices_stride(g) * g.N + 255) / 256 * 256; }   // int16 each
 int64_t scratch_mtab_bytes(const Geometry &g) { return (4 * mtab_stride(g) * g.N + 255) / 256 * 256; }
 
 int64_t scratch_bytes_for(const Geometry &g)
@@ -342,11 +342,13 @@ static int encode_conv_common(const float *act, const cpoconv_shape *shape, int 
     if (scratch_bytes < scratch_bytes_for(g)) return CPOCONV_ERR_SMALL;
     hipStream_t st = static_cast<hipStream_t>(stream);
     // the encoder also leaves the table of resolved ptr offsets: the convolution needs no prologue
-    // of its own for a CPO map (a CPS map still has its indices rebuilt by one)
+    // of its own; for a CPS map it also leaves there the plain index of every NZE (16 bits each: what
+    // Algorithm 4 rebuilds from the packed IN stream, which the map itself holds as after cps_encode)
     const bool table = sparse_conv_uses_prologue(g);
-    const int erc = launch_encode(act, prod, g, *map, algo, scratch, st, table);
+    const bool indices = algo == CPOCONV_ALGO_CPS && g.top_slot >= 0;
+    const int erc = launch_encode(act, prod, g, *map, algo, scratch, st, table, indices);
     if (erc != CPOCONV_OK) return erc;
-    return launch_sparse_conv(*map, g, algo, wt, out, scratch, st, table);
+    return launch_sparse_conv(*map, g, algo, wt, out, scratch, st, table, indices);
 }
 
 int cpo_encode_conv(const float *act, const cpoconv_shape *shape, const cpoconv_map *map, const float *wt,

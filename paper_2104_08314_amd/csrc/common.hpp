@@ -38,10 +38,10 @@ struct Geometry {
 // Element strides between consecutive images of a batched launch (image 0 is at the base pointers).
 struct BatchStrides {
     int64_t ptr, da, in;   // streams and side band: the per-image capacities of the map
-    int64_t indices;       // what the convolution reads as IN: the stream itself or the rebuilt CPS indices
+    int64_t indices;       // what the convolution reads as IN: the stream itself or the rebuilt CPS indices (entries)
     int64_t mtab, partial, out;
     int32_t map_in16;      // the map's IN stream holds int16 entries
-    int32_t indices16;     // so does what the convolution reads as IN (the rebuilt CPS indices never do)
+    int32_t indices16;     // so does what the convolution reads as IN (the rebuilt CPS indices always do)
     const int32_t *hdr;    // the map's header (8 ints per image)
     int32_t algo;          // the algorithm the call expects the map to hold
 };
@@ -124,13 +124,14 @@ private:
 
 // launchers (defined next to their kernels)
 int launch_encode(const float *act, const Producer &prod, const Geometry &g, const cpoconv_map &map, int algo,
-                  void *scratch, hipStream_t stream, bool write_table = false);
+                  void *scratch, hipStream_t stream, bool write_table = false, bool write_indices = false);
 int64_t encode_fixed_bytes();                        // look-back words every scratch buffer starts with
 int64_t encode_call_flags_bytes(const Geometry &g);  // look-back words of a call that takes two launches
 int launch_prepare_weights(const float *w, const Geometry &g, float *wt, hipStream_t stream);
 int launch_zero_fill(void *buffer, int64_t bytes, hipStream_t stream);
 int launch_sparse_conv(const cpoconv_map &map, const Geometry &g, int algo, const float *wt,
-                       float *out, void *scratch, hipStream_t stream, bool table_ready = false);
+                       float *out, void *scratch, hipStream_t stream, bool table_ready = false,
+                       bool indices_ready = false);
 bool sparse_conv_uses_prologue(const Geometry &g);
 // register-tile SpMV kernel (spmv_conv_tile.hip)
 bool tile_kernel_supports(const Geometry &g);

@@ -204,7 +204,8 @@ __global__ __launch_bounds__(kEncThreads) void encode_kernel(const Geometry g, c
                                                             unsigned long long *__restrict__ ctrl,
                                                             unsigned long long *__restrict__ flags_all, const int units_stride,
                                                             const cpoconv_map maps, int32_t *__restrict__ mtab_all,
-                                                            const int64_t mtab_stride)
+                                                            const int64_t mtab_stride, int16_t *__restrict__ full_all,
+                                                            const int64_t full_stride)
 {
     extern __shared__ float lds[];   // per wavefront: tile_floats (band columns x (Ih | 1), column-major), then 64 ints
 
@@ -230,6 +231,8 @@ __global__ __launch_bounds__(kEncThreads) void encode_kernel(const Geometry g, c
     map.in = index_advance(maps.in, image * maps.in_cap, in16);
     map.chan_off += static_cast<int64_t>(image) * 3 * (g.C + 1);
     map.hdr += image * 8;
+    // for a CPS convolution launched by the same call: the plain index of every NZE, laid out like DA
+    int16_t *__restrict__ full = full_all != nullptr ? full_all + image * full_stride : nullptr;
 
     // ---- load: lane = (row phase rp, column col); CW columns side by side, 64 / CW rows per pass ------
     int cw_log2 = 0;
@@ -523,6 +526,7 @@ __global__ __launch_bounds__(kEncThreads) void encode_kernel(const Geometry g, c
             const int rank = __popcll(mask & below);
             const int index = what + h * g.kw;
             if (nz) map.da[at_da + rank] = tile[src * IhP + h];
+            if (nz && full != nullptr) full[at_da + rank] = static_cast<int16_t>(index);
             if (packed) {
                 // set4 of Algorithm 3: the four padded rows 4*(h/4) .. +3
                 const int pattern = static_cast<int>((mask >> (hl & ~3)) & 0xFull);
@@ -565,7 +569,8 @@ __global__ __launch_bounds__(kThreads) void encode_channel_kernel(const Geometry
                                                          unsigned long long *__restrict__ ctrl,
                                                          unsigned long long *__restrict__ flags_all, const int units_stride,
                                                          const cpoconv_map maps, int32_t *__restrict__ mtab_all,
-                                                         const int64_t mtab_stride)
+                                                         const int64_t mtab_stride, int16_t *__restrict__ full_all,
+                                                         const int64_t full_stride)
 {
     // image blockIdx.y of the launch: its map is image 0's advanced by the per-image capacities
     const int image = blockIdx.y;
@@ -581,6 +586,7 @@ __global__ __launch_bounds__(kThreads) void encode_channel_kernel(const Geometry
     map.in = index_advance(maps.in, image * maps.in_cap, in16);
     map.chan_off += static_cast<int64_t>(image) * 3 * (g.C + 1);
     map.hdr += image * 8;
+    int16_t *__restrict__ full = full_all != nullptr ? full_all + image * full_stride : nullptr;   // as in the band kernel
 
     extern __shared__ float tile[];                    // kChunk x Wt, Wt odd: conflict-free column reads
     __shared__ uint16_t cnt_q[kMaxChunks][kMaxCols];   // NZEs per (row chunk, column), then their
@@ -827,6 +833,7 @@ __global__ __launch_bounds__(kThreads) void encode_channel_kernel(const Geometry
             const int in_at = in_off + ecol_excl[vi] + ecnt_q[q][vi];
             const int index = static_cast<int>(col_wh[vi]) + (q * kChunk + lane) * g.kw;
             if (nz) map.da[da_at + rank] = v;
+            if (nz && full != nullptr) full[da_at + rank] = static_cast<int16_t>(index);
             if (vi >= top_begin && vi < top_end) {
                 // set4 of Algorithm 3: the four padded rows 4*(h/4) .. +3
                 const int pattern = static_cast<int>((mask >> (lane & ~3)) & 0xFull);
@@ -865,7 +872,8 @@ __global__ __launch_bounds__(kThreads) void encode_small_kernel(const Geometry g
                                                                unsigned long long *__restrict__ ctrl,
                                                                unsigned long long *__restrict__ flags_all, const int units_stride,
                                                                const cpoconv_map maps, int32_t *__restrict__ mtab_all,
-                                                               const int64_t mtab_stride)
+                                                               const int64_t mtab_stride, int16_t *__restrict__ full_all,
+                                                               const int64_t full_stride)
 {
     extern __shared__ float tiles[];                   // per wavefront: H x Wt floats, then 64 ints of ptr staging
     __shared__ int32_t grp[kWaves][3];                 // the group's lengths: ptr, DA, IN per channel
@@ -888,6 +896,7 @@ __global__ __launch_bounds__(kThreads) void encode_small_kernel(const Geometry g
     map.in = index_advance(maps.in, image * maps.in_cap, in16);
     map.chan_off += static_cast<int64_t>(image) * 3 * (g.C + 1);
     map.hdr += image * 8;
+    int16_t *__restrict__ full = full_all != nullptr ? full_all + image * full_stride : nullptr;
 
     const int Wt = g.W | 1;
     const int per_wave = g.H * Wt + kLanes;            // floats of LDS per wavefront
@@ -1096,6 +1105,7 @@ __global__ __launch_bounds__(kThreads) void encode_small_kernel(const Geometry g
         const int rank = __popcll(mask & below);
         const int index = what + h * g.kw;
         if (nz) map.da[at_da + rank] = v;
+        if (nz && full != nullptr) full[at_da + rank] = static_cast<int16_t>(index);
         const bool packed = on && vi >= top_begin && vi < top_end;
         // set4 of Algorithm 3: the four padded rows 4*(h/4) .. +3
         const int pattern = static_cast<int>((mask >> (h & ~3)) & 0xFull);
@@ -1252,7 +1262,7 @@ int64_t encode_call_flags_bytes(const Geometry &g)
 int64_t encode_fixed_bytes() { return fixed_scratch_bytes(); }
 
 static int launch_encode_bands(const float *act, const Producer &prod, const Geometry &g, const cpoconv_map &map, int cps,
-                               void *scratch, hipStream_t stream, int32_t *mtab, int64_t mstride)
+                               void *scratch, hipStream_t stream, int32_t *mtab, int64_t mstride, int16_t *full, int64_t fstride)
 {
     bool single_pass;
     const EncodePlan plan = plan_encode(g, &single_pass);
@@ -1269,31 +1279,38 @@ static int launch_encode_bands(const float *act, const Producer &prod, const Geo
     if (single_pass) {
         KernelTimer timer("encode", stream);
         hipLaunchKernelGGL(encode_kernel<kSinglePass>, grid, block, lds, stream, g, plan, act, prod, cps, tile_floats,
-                           ctrl, ctrl + kCtrlWords, kUnitsPerImage, map, mtab, mstride);
+                           ctrl, ctrl + kCtrlWords, kUnitsPerImage, map, mtab, mstride, full, fstride);
     } else {
         unsigned long long *call_flags = reinterpret_cast<unsigned long long *>(static_cast<char *>(scratch) + fixed_scratch_bytes());
         {
             KernelTimer timer("encode_count", stream);
             hipLaunchKernelGGL(encode_kernel<kPublishOnly>, grid, block, lds, stream, g, plan, act, prod, cps,
-                               tile_floats, ctrl, call_flags, units, map, static_cast<int32_t *>(nullptr), mstride);
+                               tile_floats, ctrl, call_flags, units, map, static_cast<int32_t *>(nullptr), mstride,
+                               static_cast<int16_t *>(nullptr), fstride);
         }
         CPOCONV_HIP_TRY(hipGetLastError());
         KernelTimer timer("encode", stream);
         hipLaunchKernelGGL(encode_kernel<kPublished>, grid, block, lds, stream, g, plan, act, prod, cps, tile_floats,
-                           ctrl, call_flags, units, map, mtab, mstride);
+                           ctrl, call_flags, units, map, mtab, mstride, full, fstride);
     }
     CPOCONV_HIP_TRY(hipGetLastError());
     return CPOCONV_OK;
 }
 
 int launch_encode(const float *act, const Producer &prod, const Geometry &g, const cpoconv_map &map, int algo,
-                  void *scratch, hipStream_t stream, bool write_table)
+                  void *scratch, hipStream_t stream, bool write_table, bool write_indices)
 {
+    // the plain per-NZE indices, for a CPS convolution launched by the same call (same place and
+    // layout as the convolution's own reconstruction would leave them)
+    int16_t *full = write_indices ? reinterpret_cast<int16_t *>(static_cast<char *>(scratch) + scratch_counts_bytes(g) +
+                                                                scratch_mtab_bytes(g))
+                                  : nullptr;
+    const int64_t fstride = indices_stride(g);
     // the table of resolved ptr offsets, for a convolution launched by the same call
     int32_t *mtab = write_table ? reinterpret_cast<int32_t *>(static_cast<char *>(scratch) + scratch_counts_bytes(g)) : nullptr;
     const int64_t mstride = mtab_stride(g);
     const int cps = algo == CPOCONV_ALGO_CPS ? 1 : 0;
-    if (use_bands(g)) return launch_encode_bands(act, prod, g, map, cps, scratch, stream, mtab, mstride);
+    if (use_bands(g)) return launch_encode_bands(act, prod, g, map, cps, scratch, stream, mtab, mstride, full, fstride);
 
     unsigned long long *ctrl = static_cast<unsigned long long *>(scratch);
     const bool single = channels_single_pass(g);
@@ -1315,17 +1332,17 @@ int launch_encode(const float *act, const Producer &prod, const Geometry &g, con
         if (single) {
             KernelTimer timer("encode", stream);
             hipLaunchKernelGGL(encode_small_kernel<kSinglePass>, grid, dim3(kThreads), lds_small, stream, g, act, prod, cps, ctrl,
-                               flags, units_stride, map, mtab, mstride);
+                               flags, units_stride, map, mtab, mstride, full, fstride);
         } else {
             {
                 KernelTimer timer("encode_count", stream);
                 hipLaunchKernelGGL(encode_small_kernel<kPublishOnly>, grid, dim3(kThreads), lds_small, stream, g, act, prod, cps,
-                                   ctrl, flags, units_stride, map, static_cast<int32_t *>(nullptr), mstride);
+                                   ctrl, flags, units_stride, map, static_cast<int32_t *>(nullptr), mstride, static_cast<int16_t *>(nullptr), fstride);
             }
             CPOCONV_HIP_TRY(hipGetLastError());
             KernelTimer timer("encode", stream);
             hipLaunchKernelGGL(encode_small_kernel<kPublished>, grid, dim3(kThreads), lds_small, stream, g, act, prod, cps, ctrl,
-                               flags, units_stride, map, mtab, mstride);
+                               flags, units_stride, map, mtab, mstride, full, fstride);
         }
         CPOCONV_HIP_TRY(hipGetLastError());
         return CPOCONV_OK;
@@ -1333,17 +1350,17 @@ int launch_encode(const float *act, const Producer &prod, const Geometry &g, con
     if (single) {
         KernelTimer timer("encode", stream);
         hipLaunchKernelGGL(encode_channel_kernel<kSinglePass>, dim3(g.C, g.N), dim3(kThreads), lds, stream, g, act, prod, cps, chunk,
-                           ctrl, flags, units_stride, map, mtab, mstride);
+                           ctrl, flags, units_stride, map, mtab, mstride, full, fstride);
     } else {
         {
             KernelTimer timer("encode_count", stream);
             hipLaunchKernelGGL(encode_channel_kernel<kPublishOnly>, dim3(g.C, g.N), dim3(kThreads), lds, stream, g, act, prod, cps,
-                               chunk, ctrl, flags, units_stride, map, static_cast<int32_t *>(nullptr), mstride);
+                               chunk, ctrl, flags, units_stride, map, static_cast<int32_t *>(nullptr), mstride, static_cast<int16_t *>(nullptr), fstride);
         }
         CPOCONV_HIP_TRY(hipGetLastError());
         KernelTimer timer("encode", stream);
         hipLaunchKernelGGL(encode_channel_kernel<kPublished>, dim3(g.C, g.N), dim3(kThreads), lds, stream, g, act, prod, cps, chunk,
-                           ctrl, flags, units_stride, map, mtab, mstride);
+                           ctrl, flags, units_stride, map, mtab, mstride, full, fstride);
     }
     CPOCONV_HIP_TRY(hipGetLastError());
     return CPOCONV_OK;

@@ -72,7 +72,7 @@ __global__ __launch_bounds__(kExpThreads) void conv_prologue_kernel(const Geomet
     const int32_t *__restrict__ in = index_advance(in_all, image * bs.in, bs.map_in16);
     const int32_t *__restrict__ chan_off = chan_off_all + static_cast<int64_t>(image) * 3 * (g.C + 1);
     int32_t *__restrict__ mtab = mtab_all + image * bs.mtab;
-    int32_t *__restrict__ in_full = in_full_all ? in_full_all + image * bs.indices : nullptr;
+    int16_t *__restrict__ in_full = in_full_all ? reinterpret_cast<int16_t *>(in_full_all) + image * bs.indices : nullptr;   // every index fits 16 bits
     const int c = blockIdx.x, tid = threadIdx.x, lane = lane_id(), wave = tid / kLanes;
     const int da0 = chan_off[(g.C + 1) + c], da1 = chan_off[(g.C + 1) + c + 1];
     const int in0 = chan_off[2 * (g.C + 1) + c], in1 = chan_off[2 * (g.C + 1) + c + 1];
@@ -113,7 +113,7 @@ __global__ __launch_bounds__(kExpThreads) void conv_prologue_kernel(const Geomet
     // NZEs of the overlap-kw type: it is the highest type, so it closes the channel
     const int top_count = da1 - top_base;
     const int lower = nnz - top_count;  // NZEs of the other types: their IN entries are plain
-    for (int i = tid; i < lower; i += kExpThreads) in_full[da0 + i] = load_index(in, in0 + i, bs.map_in16);
+    for (int i = tid; i < lower; i += kExpThreads) in_full[da0 + i] = static_cast<int16_t>(load_index(in, in0 + i, bs.map_in16));
     if (top_count == 0) return;
 
     const int e0 = in0 + lower, n_entries = in1 - e0;
@@ -140,13 +140,13 @@ __global__ __launch_bounds__(kExpThreads) void conv_prologue_kernel(const Geomet
         for (int w = 0; w < wave; ++w) before += wave_b[w];
         const int at = da0 + lower + before + s - emits;
         if (valid && entry < 0) {
-            in_full[at] = -entry;
+            in_full[at] = static_cast<int16_t>(-entry);
         } else if (is_index) {
             // NZEs of the set: first index, then + kw per row after the first set bit
             const int first = __ffs(pattern) - 1;
             int k = 0;
             for (int b = first; b < 4; ++b)
-                if (pattern & (1 << b)) in_full[at + k++] = entry + g.kw * (b - first);
+                if (pattern & (1 << b)) in_full[at + k++] = static_cast<int16_t>(entry + g.kw * (b - first));
         }
         int tot_neg = carry_neg, tot_out = carry_out;
         for (int w = 0; w < kExpThreads / kLanes; ++w) { tot_neg = max(tot_neg, wave_a[w]); tot_out += wave_b[w]; }
@@ -391,7 +391,7 @@ bool sparse_conv_uses_prologue(const Geometry &g)
 }
 
 int launch_sparse_conv(const cpoconv_map &map, const Geometry &g, int algo, const float *wt, float *out,
-                       void *scratch, hipStream_t stream, bool table_ready)
+                       void *scratch, hipStream_t stream, bool table_ready, bool indices_ready)
 {
     char *base = static_cast<char *>(scratch);
     int32_t *mtab = reinterpret_cast<int32_t *>(base + scratch_counts_bytes(g));
@@ -409,7 +409,7 @@ int launch_sparse_conv(const cpoconv_map &map, const Geometry &g, int algo, cons
         in_full = reinterpret_cast<int32_t *>(base + after_mtab);
         indices = in_full;
         bs.indices = indices_stride(g);
-        bs.indices16 = 0;
+        bs.indices16 = 1;
     }
     const bool runs = runs_kernel_preferred(g);
     const bool strip = !runs && (strip_kernel_preferred(g) || (strip_kernel_supports(g) && !tile_kernel_supports(g)));
@@ -418,8 +418,9 @@ int launch_sparse_conv(const cpoconv_map &map, const Geometry &g, int algo, cons
     // 1-4 us faster than a prologue launch; in the register-tile kernel, where many more workgroups
     // would repeat the work, it was slower).  Otherwise, and for the index reconstruction of CPS,
     // a prologue kernel runs first.
-    // (table_ready: the encoder of the same call left the table in the scratch buffer)
-    const bool expand = in_full != nullptr;
+    // (table_ready / indices_ready: the encoder of the same call left the table / the plain CPS
+    // indices in the scratch buffer)
+    const bool expand = in_full != nullptr && !indices_ready;
     const bool in_kernel = strip && !expand && !table_ready && resolve_in_kernel_ok(g);
     if (in_kernel) mtab = nullptr;
     if ((tile && !in_kernel && !table_ready) || expand) {

@@ -345,13 +345,15 @@ bool runs_kernel_supports(const Geometry &g)
     return true;
 }
 
-// Measured over the workload layers: with one to three images per launch the kernel is 1 to 3 us
-// faster per layer than the strip / register-tile kernels (no shared decode stage to wait for, one
-// launch less on the wide maps); from four images on the strip kernel's shared decode wins
-// (config 2 at 32 images: 12.6 against 15.3 us per image).
+// Measured over the workload layers at one to three images per launch: where the tiles alone give
+// every compute unit a workgroup (one channel slice: no partial sums, no second kernel) the kernel
+// is 3 us faster per layer than the strip kernel with its slice sum (config 2: 44 against 47 us for
+// the layer, 64 x 56 x 56: 32 against 35); on the smaller maps, which need channel slices across
+// workgroups either way, it ties with the register-tile kernel, which keeps them.  From four images
+// on the strip kernel's shared decode wins (config 2 at 32 images: 12.6 against 15.3 us per image).
 bool runs_kernel_preferred(const Geometry &g)
 {
-    return runs_kernel_supports(g) && g.N < 4;
+    return runs_kernel_supports(g) && g.N < 4 && runs_plan(g).slices == 1;
 }
 
 int64_t runs_kernel_partial_bytes(const Geometry &g)
