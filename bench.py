@@ -75,6 +75,7 @@ class LayerRun:
         self.act = torch.from_numpy(act_np).cuda()
         self.w = torch.from_numpy(w_np).cuda()
         api.cpoconv_prepare_weights(self.w, self.shape, self.buf.wt)   # once per layer, untimed
+        api.im2col_prepare_weights_bf16(self.w, self.shape, self.buf.wb)   # likewise for the bf16 comparator
         torch.cuda.synchronize()
         b = self.buf
         self.map16 = api.EncodedMap(self.shape, in_bits=16)   # compact map: int16 IN entries
@@ -88,7 +89,7 @@ class LayerRun:
             "cps_layer": lambda: api.cps_encode_conv(self.act, self.shape, b.cps, b.wt, b.out, b.scratch),
             "cpo_layer_in16": lambda: api.cpo_encode_conv(self.act, self.shape, self.map16, b.wt, b.out, b.scratch),
             "im2col_f32": lambda: api.im2col_conv(self.act, self.shape, self.w, b.lowered, b.out, 0),
-            "im2col_bf16": lambda: api.im2col_conv(self.act, self.shape, self.w, b.lowered, b.out, 1),
+            "im2col_bf16": lambda: api.im2col_conv(self.act, self.shape, b.wb, b.lowered, b.out, 2),
         }
 
     def set_input(self, torch, act_np):
@@ -226,7 +227,7 @@ def kernel_roofline(stage, kernel, us, fig, spec, lens):
         if stage == "cps_conv":
             b += 4 * lens["in_cps"] + 4 * lens["nnz"]
         return hbm(b)
-    if kernel in ("spmv_conv_tile", "spmv_conv_strip", "spmv_conv_lds"):
+    if kernel.startswith("spmv_conv_"):   # runs, strip, tile or lds: whichever the layer was given
         r = stage_roofline(stage, us, fig)
         r["algorithmic_flops"] = fig["sparse_flops"]
         r["algorithmic_bytes"] = fig[stage + "_bytes"]
@@ -296,13 +297,14 @@ def batch_supplement(api, torch, workloads, spec, n_images, reps):
     buf = api.LayerBuffers(shape, n_images=n_images)
     act, w = torch.from_numpy(acts).cuda(), torch.from_numpy(workloads.make_weights(spec)).cuda()
     api.cpoconv_prepare_weights(w, shape, buf.wt)
+    api.im2col_prepare_weights_bf16(w, shape, buf.wb)
     api.cps_encode_batch(act, shape, buf.cps, buf.scratch)
     stages = {
         "cpo_encode": lambda: api.cpo_encode_batch(act, shape, buf.cpo, buf.scratch),
         "cpo_conv": lambda: api.cpo_conv_batch(buf.cpo, shape, buf.wt, buf.out, buf.scratch),
         "cps_conv": lambda: api.cps_conv_batch(buf.cps, shape, buf.wt, buf.out, buf.scratch),
         "im2col_f32": lambda: api.im2col_conv_batch(act, shape, n_images, w, buf.lowered, buf.out, 0),
-        "im2col_bf16": lambda: api.im2col_conv_batch(act, shape, n_images, w, buf.lowered, buf.out, 1),
+        "im2col_bf16": lambda: api.im2col_conv_batch(act, shape, n_images, buf.wb, buf.lowered, buf.out, 2),
     }
     stages["cpo_encode"]()
     us = {}

@@ -110,10 +110,13 @@ typedef struct {
     int64_t chan_off_len;  /* 3*(C+1)                                                      */
     int64_t wt_len;        /* prepared weights: C*kh*kw*round_up(K,64) floats              */
     int64_t out_len;       /* K*Oh*Ow                                                      */
-    int64_t lowered_bytes; /* im2col scratch: lowered matrix (rows padded to 4 columns) +  */
-                           /* split-K partial sums of the matrix product                   */
+    int64_t lowered_bytes; /* im2col scratch: lowered matrix (rows padded to 4 columns),   */
+                           /* split-K partial sums of the matrix product, the bf16 kernel  */
+                           /* matrix of a precision-1 call                                 */
     int64_t scratch_bytes; /* scratch for encode and conv calls (prepare once with          */
                            /* cpoconv_scratch_init)                                         */
+    int64_t wb_len;        /* bf16 kernel matrix of im2col_prepare_weights_bf16, in 16-bit  */
+                           /* elements: ceil(C*kh*kw/8) * round_up(K,64) * 8                */
     int32_t Oh, Ow;
 } cpoconv_sizes_t;
 
@@ -210,14 +213,26 @@ int cps_encode_conv(const float *act, const cpoconv_shape *shape, const cpoconv_
  * (c*kh + l)*kw + w, column y*Ow + x, holds the padded input at (c, y*stride + l,
  * x*stride + w)) followed by a dense matrix product with the K x C*kh*kw kernel matrix on
  * the matrix cores.  precision 0: fp32 operands; 1: operands rounded to bf16 (nearest even),
- * fp32 accumulation.  lowered: scratch of sizes.lowered_bytes bytes (lowered matrix, then the
- * partial sums of the product when the contraction is split over workgroups; slices are added
- * in a fixed order).  weights in the K x C x kh x kw layout.
- * lowered must be 16-byte aligned.
+ * fp32 accumulation; 2: as 1 with the kernel matrix already converted - weights then points to
+ * the sizes.wb_len 16-bit elements im2col_prepare_weights_bf16 wrote (same result, bit for bit,
+ * without the conversion launch of every precision-1 call).  lowered: scratch of
+ * sizes.lowered_bytes bytes (lowered matrix, then the partial sums of the product when the
+ * contraction is split over workgroups; slices are added in a fixed order).  weights for
+ * precision 0 and 1: fp32 in the K x C x kh x kw layout.  lowered must be 16-byte aligned, and so
+ * must precision-2 weights.
  * Errors: NULL, SHAPE (also a misaligned lowered), ALGO (precision), HIP.
  */
-int im2col_conv(const float *act, const cpoconv_shape *shape, const float *weights,
+int im2col_conv(const float *act, const cpoconv_shape *shape, const void *weights,
                 void *lowered, float *out, int precision, void *stream);
+
+/*
+ * The kernel matrix of Section 3.1's product (K x C*kh*kw, from weights K x C x kh x kw) rounded to
+ * nearest-even bf16 and laid out as the matrix cores read it: groups of eight consecutive
+ * contraction indices, [ceil(C*kh*kw/8)][round_up(K,64)][8], zero filled.  Done once per layer;
+ * wb (device, 16-byte aligned, sizes.wb_len 16-bit elements) then serves every im2col_conv call
+ * with precision 2.  Errors: NULL, SHAPE (also a misaligned wb), HIP.
+ */
+int im2col_prepare_weights_bf16(const float *weights, const cpoconv_shape *shape, void *wb, void *stream);
 
 /*
  * Batched variants: n_images activation maps of one shape in one launch (the "I_n" of the
@@ -245,7 +260,7 @@ int cpo_conv_batch(const cpoconv_map *maps, const cpoconv_shape *shape, int n_im
                    float *out, void *scratch, int64_t scratch_bytes, void *stream);
 int cps_conv_batch(const cpoconv_map *maps, const cpoconv_shape *shape, int n_images, const float *wt,
                    float *out, void *scratch, int64_t scratch_bytes, void *stream);
-int im2col_conv_batch(const float *act, const cpoconv_shape *shape, int n_images, const float *weights,
+int im2col_conv_batch(const float *act, const cpoconv_shape *shape, int n_images, const void *weights,
                       void *lowered, float *out, int precision, void *stream);
 int cpo_encode_conv_batch(const float *act, const cpoconv_shape *shape, int n_images, const cpoconv_map *maps,
                           const float *wt, float *out, void *scratch, int64_t scratch_bytes, void *stream);
@@ -267,7 +282,7 @@ int cpo_encode_relu(const float *pre, const float *bias, const cpoconv_shape *sh
 int cps_encode_relu(const float *pre, const float *bias, const cpoconv_shape *shape, int n_images,
                     const cpoconv_map *maps, void *scratch, int64_t scratch_bytes, void *stream);
 int im2col_conv_relu(const float *pre, const float *bias, const cpoconv_shape *shape, int n_images,
-                     const float *weights, void *lowered, float *out, int precision, void *stream);
+                     const void *weights, void *lowered, float *out, int precision, void *stream);
 
 /*
  * The conv layers of a network run one after the other, each with the method the offline
@@ -277,7 +292,8 @@ int im2col_conv_relu(const float *pre, const float *bias, const cpoconv_shape *s
  * applied on the way in, as in the *_relu calls (bias_in may be NULL); with relu_in = 0 it is
  * taken as stored and bias_in must be NULL.  method: CPOCONV_ALGO_CPO / _CPS (weights = the
  * prepared layout of cpoconv_prepare_weights; the layer runs as cpo_/cps_encode_conv_batch) or
- * CPOCONV_ALGO_IM2COL (weights K x C x kh x kw; precision 0 fp32, 1 bf16).  out: device,
+ * CPOCONV_ALGO_IM2COL (precision 0 fp32 or 1 bf16: weights K x C x kh x kw; precision 2: the bf16
+ * kernel matrix of im2col_prepare_weights_bf16, passed through the same pointer).  out: device,
  * n_images x K x Oh x Ow, written by the layer and read by the next one; it holds the sums before
  * any bias or ReLU.  One map, scratch and lowered buffer serve all layers in turn: sizes from
  * cpoconv_chain_sizes (the largest any layer needs; *maps is image 0's struct, capacities =

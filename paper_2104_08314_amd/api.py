@@ -44,7 +44,7 @@ class _Map(ctypes.Structure):
 
 class Sizes(ctypes.Structure):
     _fields_ = [(n, ctypes.c_int64) for n in ("ptr_cap", "da_cap", "in_cap", "chan_off_len", "wt_len",
-                                               "out_len", "lowered_bytes", "scratch_bytes")] + \
+                                               "out_len", "lowered_bytes", "scratch_bytes", "wb_len")] + \
                [("Oh", ctypes.c_int32), ("Ow", ctypes.c_int32)]
 
 
@@ -76,7 +76,7 @@ EXPORTS = (
     "im2col_conv", "select_layer_algo", "cpoconv_map_header_to_host", "cpoconv_geometry",
     "cpoconv_strerror", "cpoconv_last_hip_error", "cpoconv_kernel_timing", "cpoconv_kernel_timing_read",
     "cpoconv_scratch_init", "cpoconv_batch_sizes", "cpo_encode_batch", "cps_encode_batch", "cpo_conv_batch", "cps_conv_batch",
-    "im2col_conv_batch", "cpo_encode_conv", "cps_encode_conv", "cpo_encode_conv_batch", "cps_encode_conv_batch",
+    "im2col_conv_batch", "im2col_prepare_weights_bf16", "cpo_encode_conv", "cps_encode_conv", "cpo_encode_conv_batch", "cps_encode_conv_batch",
     "cpo_encode_relu", "cps_encode_relu", "im2col_conv_relu", "cpoconv_chain_sizes", "cpoconv_chain_forward",
     "cpo_encode_static_scratch",
 )
@@ -172,6 +172,14 @@ def _stream_handle(stream) -> ctypes.c_void_p:
     if stream is None:
         stream = torch.cuda.current_stream()
     return ctypes.c_void_p(stream.cuda_stream)
+
+
+def _weights_ptr(weights, precision: int) -> ctypes.c_void_p:
+    """im2col weights: fp32 K x C x kh x kw for precision 0 and 1, the int16-typed bf16 kernel matrix
+    of im2col_prepare_weights_bf16 for precision 2."""
+    import torch
+
+    return _dev_ptr(weights, torch.int16 if int(precision) == 2 else torch.float32)
 
 
 def _dev_ptr(t, dtype=None) -> ctypes.c_void_p:
@@ -293,9 +301,18 @@ def im2col_conv(act, shape, weights, lowered, out, precision: int = 0, stream=No
     import torch
 
     sh = make_shape(shape)
-    _check(lib().im2col_conv(_dev_ptr(act, torch.float32), ctypes.byref(sh), _dev_ptr(weights, torch.float32),
+    _check(lib().im2col_conv(_dev_ptr(act, torch.float32), ctypes.byref(sh), _weights_ptr(weights, precision),
                              _dev_ptr(lowered), _dev_ptr(out, torch.float32), int(precision),
                              _stream_handle(stream)))
+
+
+def im2col_prepare_weights_bf16(weights, shape, wb, stream=None) -> None:
+    """wb: int16 device tensor of cpoconv_sizes(shape).wb_len elements (bf16 bit patterns)."""
+    import torch
+
+    sh = make_shape(shape)
+    _check(lib().im2col_prepare_weights_bf16(_dev_ptr(weights, torch.float32), ctypes.byref(sh),
+                                             _dev_ptr(wb, torch.int16), _stream_handle(stream)))
 
 
 def cpoconv_map_header_to_host(m: EncodedMap, stream=None, image=0):
@@ -326,6 +343,7 @@ class LayerBuffers:
         self.scratch = torch.empty(sz.scratch_bytes, dtype=torch.uint8, device=device)
         cpoconv_scratch_init(self.scratch)
         self.wt = torch.empty(sz.wt_len, dtype=torch.float32, device=device)
+        self.wb = torch.empty(sz.wb_len, dtype=torch.int16, device=device)
         self.lowered = torch.empty(sz.lowered_bytes, dtype=torch.uint8, device=device)
         dims = (self.shape.K, sz.Oh, sz.Ow) if self.n_images == 1 else (self.n_images, self.shape.K, sz.Oh, sz.Ow)
         self.out = torch.empty(dims, dtype=torch.float32, device=device)
@@ -387,7 +405,7 @@ def im2col_conv_batch(act, shape, n_images: int, weights, lowered, out, precisio
 
     sh = make_shape(shape)
     _check(lib().im2col_conv_batch(_dev_ptr(act, torch.float32), ctypes.byref(sh), int(n_images),
-                                   _dev_ptr(weights, torch.float32), _dev_ptr(lowered), _dev_ptr(out, torch.float32),
+                                   _weights_ptr(weights, precision), _dev_ptr(lowered), _dev_ptr(out, torch.float32),
                                    int(precision), _stream_handle(stream)))
 
 
@@ -439,7 +457,7 @@ def im2col_conv_relu(pre, bias, shape, n_images: int, weights, lowered, out, pre
 
     sh = make_shape(shape)
     _check(lib().im2col_conv_relu(_dev_ptr(pre, torch.float32), _dev_ptr(bias, torch.float32), ctypes.byref(sh),
-                                  int(n_images), _dev_ptr(weights, torch.float32), _dev_ptr(lowered),
+                                  int(n_images), _weights_ptr(weights, precision), _dev_ptr(lowered),
                                   _dev_ptr(out, torch.float32), int(precision), _stream_handle(stream)))
 
 
@@ -473,7 +491,7 @@ class Chain:
         self.device = device
         n = len(self.shapes)
         self.table = (ChainLayer * n)()
-        self.outs, self.prepared = [], [None] * n
+        self.outs, self.prepared, self.prepared_bf16 = [], [None] * n, [None] * n
         for i, sh in enumerate(self.shapes):
             sz = cpoconv_batch_sizes(sh, self.n_images)
             self.outs.append(torch.empty((self.n_images, sh.K, sz.Oh, sz.Ow), dtype=torch.float32, device=device))
@@ -497,7 +515,13 @@ class Chain:
         self.methods = [int(m) for m in methods]
         for i, (m, sh) in enumerate(zip(self.methods, self.shapes)):
             self.table[i].method = m
-            if m == ALGO_IM2COL:
+            if m == ALGO_IM2COL and self.precision == 2:
+                if self.prepared_bf16[i] is None:
+                    wb = torch.empty(cpoconv_sizes(sh).wb_len, dtype=torch.int16, device=self.device)
+                    im2col_prepare_weights_bf16(self.weights[i], sh, wb)
+                    self.prepared_bf16[i] = wb
+                self.table[i].weights = self.prepared_bf16[i].data_ptr()
+            elif m == ALGO_IM2COL:
                 self.table[i].weights = _dev_ptr(self.weights[i], torch.float32).value
             else:
                 if self.prepared[i] is None:

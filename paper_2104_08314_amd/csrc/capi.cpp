@@ -203,6 +203,7 @@ int cpoconv_batch_sizes(const cpoconv_shape *shape, int n_images, cpoconv_sizes_
     sizes->out_len = static_cast<int64_t>(g.N) * g.K * g.Oh * g.Ow;
     sizes->lowered_bytes = im2col_scratch_bytes(g);
     sizes->scratch_bytes = scratch_bytes_for(g);
+    sizes->wb_len = im2col_weights_bf16_len(g);
     sizes->Oh = g.Oh;
     sizes->Ow = g.Ow;
     return CPOCONV_OK;
@@ -399,26 +400,37 @@ int cps_conv_batch(const cpoconv_map *maps, const cpoconv_shape *shape, int n_im
     return conv_common(maps, shape, n_images, wt, out, scratch, scratch_bytes, stream, CPOCONV_ALGO_CPS);
 }
 
-int im2col_conv(const float *act, const cpoconv_shape *shape, const float *weights, void *lowered,
+int im2col_conv(const float *act, const cpoconv_shape *shape, const void *weights, void *lowered,
                 float *out, int precision, void *stream)
 {
     return im2col_conv_batch(act, shape, 1, weights, lowered, out, precision, stream);
 }
 
-static int im2col_common(const float *act, const cpoconv_shape *shape, int n_images, const float *weights,
+int im2col_prepare_weights_bf16(const float *weights, const cpoconv_shape *shape, void *wb, void *stream)
+{
+    if (!weights || !shape || !wb) return CPOCONV_ERR_NULL;
+    Geometry g;
+    const int rc = batch_geometry(shape, 1, &g);
+    if (rc != CPOCONV_OK) return rc;
+    if (reinterpret_cast<uintptr_t>(wb) % 16 != 0) return CPOCONV_ERR_SHAPE;
+    return launch_prepare_weights_bf16(weights, g, static_cast<uint16_t *>(wb), static_cast<hipStream_t>(stream));
+}
+
+static int im2col_common(const float *act, const cpoconv_shape *shape, int n_images, const void *weights,
                          void *lowered, float *out, int precision, void *stream, const Producer &prod)
 {
     if (!act || !shape || !weights || !lowered || !out) return CPOCONV_ERR_NULL;
     Geometry g;
     const int rc = batch_geometry(shape, n_images, &g);
     if (rc != CPOCONV_OK) return rc;
-    if (precision != 0 && precision != 1) return CPOCONV_ERR_ALGO;
+    if (precision < 0 || precision > 2) return CPOCONV_ERR_ALGO;
     if (reinterpret_cast<uintptr_t>(lowered) % 16 != 0) return CPOCONV_ERR_SHAPE;   // vector accesses
+    if (precision == 2 && reinterpret_cast<uintptr_t>(weights) % 16 != 0) return CPOCONV_ERR_SHAPE;
     return launch_im2col_conv(act, prod, g, weights, lowered, out, precision,
                               static_cast<hipStream_t>(stream));
 }
 
-int im2col_conv_batch(const float *act, const cpoconv_shape *shape, int n_images, const float *weights,
+int im2col_conv_batch(const float *act, const cpoconv_shape *shape, int n_images, const void *weights,
                       void *lowered, float *out, int precision, void *stream)
 {
     return im2col_common(act, shape, n_images, weights, lowered, out, precision, stream, kAsStored);
@@ -438,7 +450,7 @@ int cps_encode_relu(const float *pre, const float *bias, const cpoconv_shape *sh
 }
 
 int im2col_conv_relu(const float *pre, const float *bias, const cpoconv_shape *shape, int n_images,
-                     const float *weights, void *lowered, float *out, int precision, void *stream)
+                     const void *weights, void *lowered, float *out, int precision, void *stream)
 {
     return im2col_common(pre, shape, n_images, weights, lowered, out, precision, stream, Producer{bias, 1});
 }
@@ -455,7 +467,7 @@ static int chain_check(const cpoconv_chain_layer *layers, int n_layers, int n_im
         if (rc != CPOCONV_OK) return rc;
         if (l.method != CPOCONV_ALGO_IM2COL && l.method != CPOCONV_ALGO_CPO && l.method != CPOCONV_ALGO_CPS)
             return CPOCONV_ERR_ALGO;
-        if (l.method == CPOCONV_ALGO_IM2COL && l.precision != 0 && l.precision != 1) return CPOCONV_ERR_ALGO;
+        if (l.method == CPOCONV_ALGO_IM2COL && (l.precision < 0 || l.precision > 2)) return CPOCONV_ERR_ALGO;
         if (l.relu_in != 0 && l.relu_in != 1) return CPOCONV_ERR_ALGO;
         if (!l.relu_in && l.bias_in) return CPOCONV_ERR_ALGO;      // a bias is only applied in front of the ReLU
         // a layer reads what the layer before it wrote
@@ -483,6 +495,7 @@ int cpoconv_chain_sizes(const cpoconv_chain_layer *layers, int n_layers, int n_i
         sizes->out_len = std::max(sizes->out_len, one.out_len);
         sizes->lowered_bytes = std::max(sizes->lowered_bytes, one.lowered_bytes);
         sizes->scratch_bytes = std::max(sizes->scratch_bytes, one.scratch_bytes);
+        sizes->wb_len = std::max(sizes->wb_len, one.wb_len);
         sizes->Oh = one.Oh;
         sizes->Ow = one.Ow;
     }

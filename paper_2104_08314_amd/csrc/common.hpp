@@ -177,7 +177,9 @@ __device__ inline float sum_slices(const float *src, int64_t slice_stride, int s
     return (s0 + s1) + (s2 + s3);
 }
 int64_t im2col_scratch_bytes(const Geometry &g);
-int launch_im2col_conv(const float *act, const Producer &prod, const Geometry &g, const float *w, void *lowered,
+int64_t im2col_weights_bf16_len(const Geometry &g);
+int launch_prepare_weights_bf16(const float *w, const Geometry &g, uint16_t *wb, hipStream_t stream);
+int launch_im2col_conv(const float *act, const Producer &prod, const Geometry &g, const void *w, void *lowered,
                        float *out, int precision, hipStream_t stream);
 
 }  // namespace cpoconv

@@ -62,6 +62,7 @@ def test_sizes(shape):
     assert sz.out_len == K * g.Oh * g.Ow
     assert sz.lowered_bytes >= 4 * C * kh * kw * g.Oh * g.Ow            # S_im2col elements at least
     assert sz.wt_len == C * kh * kw * ((K + 63) // 64 * 64)
+    assert sz.wb_len == (C * kh * kw + 7) // 8 * ((K + 63) // 64 * 64) * 8
     # the ptr capacity covers the oracle's ptr for a dense map (no skip flags)
     act = np.ones((C, H, W), np.float32)
     assert sz.ptr_cap >= oracle.cpo_encode(act, shape).ptr.size
@@ -96,6 +97,9 @@ def test_bad_arguments_are_rejected_on_the_host():
     assert lib.im2col_conv(one, ctypes.byref(good), one, one, one, 7, None) == api.ERR_ALGO
     assert lib.im2col_conv(one, ctypes.byref(good), one, ctypes.c_void_p(260), one, 0, None) == api.ERR_SHAPE
     assert lib.im2col_conv(one, ctypes.byref(good), one, None, one, 0, None) == api.ERR_NULL
+    assert lib.im2col_conv(one, ctypes.byref(good), ctypes.c_void_p(260), one, one, 2, None) == api.ERR_SHAPE
+    assert lib.im2col_prepare_weights_bf16(one, ctypes.byref(good), None, None) == api.ERR_NULL
+    assert lib.im2col_prepare_weights_bf16(one, ctypes.byref(good), ctypes.c_void_p(260), None) == api.ERR_SHAPE
     assert lib.cpoconv_prepare_weights(one, ctypes.byref(good), None, None) == api.ERR_NULL
     assert lib.cpoconv_map_header_to_host(None, None, None) == api.ERR_NULL
     assert api.cpoconv_strerror(api.ERR_SMALL) != api.cpoconv_strerror(api.ERR_SHAPE)
@@ -167,7 +171,7 @@ def test_chain_sizes_and_argument_checks():
     table = _chain_table([a, b, c], [api.ALGO_CPO, api.ALGO_IM2COL, api.ALGO_CPS], relu=[0, 1, 1])
     sz = api.cpoconv_chain_sizes(table, 2)
     each = [api.cpoconv_batch_sizes(s, 2) for s in (a, b, c)]
-    for field in ("ptr_cap", "da_cap", "in_cap", "chan_off_len", "wt_len", "out_len", "lowered_bytes", "scratch_bytes"):
+    for field in ("ptr_cap", "da_cap", "in_cap", "chan_off_len", "wt_len", "out_len", "lowered_bytes", "scratch_bytes", "wb_len"):
         assert getattr(sz, field) == max(getattr(e, field) for e in each), field
     assert (sz.Oh, sz.Ow) == (each[2].Oh, each[2].Ow)
     out = api.Sizes()

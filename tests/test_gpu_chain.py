@@ -241,6 +241,8 @@ def test_chain_workload_batched_bf16_comparator(api):
     act1, _, _ = workloads.make_chain(1)
     _say("[case] chain workload, 7 layers, bf16 im2col, 2 images")
     _check_chain(api, np.stack([act0, act1]), shapes, w_np[:7], b_np[:7], [api.ALGO_IM2COL] * 7, tol=BF16_TOL, precision=1)
+    _say("[case] the same with the bf16 kernel matrices prepared once")
+    _check_chain(api, np.stack([act0, act1]), shapes, w_np[:7], b_np[:7], [api.ALGO_IM2COL] * 7, tol=BF16_TOL, precision=2)
 
 
 def test_chain_workload_eight_images(api):

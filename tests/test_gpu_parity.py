@@ -98,6 +98,14 @@ def _check_layer(api, act_np, w_np, shape, convs=True, name=""):
         err = float(np.abs(got - ref).max())
         assert np.isfinite(got).all(), prec
         assert err <= tol * scale, (prec, err, scale)
+    # the bf16 kernel matrix prepared once: the same product, bit for bit
+    _say("[step] im2col_conv precision=2")
+    rounded = buf.out.clone()
+    api.im2col_prepare_weights_bf16(w, shape, buf.wb)
+    buf.out.fill_(float("nan"))
+    api.im2col_conv(act, shape, buf.wb, buf.lowered, buf.out, 2)
+    torch.cuda.synchronize()
+    assert torch.equal(buf.out, rounded)
 
 
 # --- the five workloads at full size ------------------------------------------------------
@@ -421,6 +429,13 @@ def test_batched_calls(api, case):
         got = buf.out.cpu().numpy().reshape(ref.shape)
         assert np.isfinite(got).all(), prec
         assert float(np.abs(got - ref).max()) <= tol * scale, prec
+    _say("[step] im2col_conv_batch precision=2")
+    rounded = buf.out.clone()
+    api.im2col_prepare_weights_bf16(w, shape, buf.wb)
+    buf.out.fill_(float("nan"))
+    api.im2col_conv_batch(act, shape, n_images, buf.wb, buf.lowered, buf.out, 2)
+    torch.cuda.synchronize()
+    assert torch.equal(buf.out, rounded)
 
 
 def test_batched_workload_layers(api):
