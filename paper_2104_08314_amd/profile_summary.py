@@ -18,9 +18,10 @@ from collections import defaultdict
 
 csv.field_size_limit(1 << 30)
 
-OURS = ("encode_kernel", "encode_small_kernel", "conv_prologue_kernel", "conv_prologue_wave_kernel", "zero_fill_kernel", "spmv_conv_tile_kernel", "spmv_conv_strip_kernel",
-        "spmv_conv_lds_kernel", "reduce_transpose_kernel", "im2col_lower_kernel", "im2col_lower_bf16_kernel",
-        "gemm_f32_kernel", "gemm_bf16_kernel", "splitk_reduce_kernel", "prepare_weights_kernel")
+OURS = ("encode_kernel", "encode_small_kernel", "encode_channel_kernel", "conv_prologue_kernel", "conv_prologue_wave_kernel",
+        "zero_fill_kernel", "spmv_conv_tile_kernel", "spmv_conv_strip_kernel", "spmv_conv_runs_kernel",
+        "spmv_conv_lds_kernel", "reduce_transpose_kernel", "im2col_lower_kernel", "im2col_lower_direct_kernel",
+        "gemm_f32_kernel", "gemm_bf16_kernel", "splitk_reduce_kernel", "prepare_weights_kernel", "prepare_weights_bf16_kernel")
 
 
 def _find(directory, suffix):
@@ -31,17 +32,22 @@ def _find(directory, suffix):
 
 
 def short_name(name):
-    """Kernel name as the library's timing aid reports it: no template arguments, parameters,
-    namespaces or _kernel suffix; the encoder's publish-only instantiation is encode_count, the
-    fp32 lowering is im2col_lower_f32."""
+    """Kernel name without template arguments, parameters, namespaces or _kernel suffix.  The three
+    encoders keep their names (encode: column bands; encode_channel: a workgroup per channel;
+    encode_small: a wavefront per channel - the library's timing aid calls all of them encode), a
+    publish-only instantiation gets _count appended; the lowering kernels are named for their
+    output type, the direct one (small launches) with _direct appended."""
     name = name.replace("(anonymous namespace)::", "")
     base = re.split(r"[<(]", name, 1)[0].replace("void ", "").split("::")[-1].strip()
-    if base == "encode_kernel":
-        m = re.search(r"encode_kernel<\(?(?:[\w:]+\))?\s*(\w+)", name)
-        return "encode_count" if (m and m.group(1) == "1") else "encode"
-    if base == "im2col_lower_kernel":
-        return "im2col_lower_f32"
-    return base[:-len("_kernel")] if base.endswith("_kernel") else base
+    short = base[:-len("_kernel")] if base.endswith("_kernel") else base
+    if short in ("encode", "encode_channel", "encode_small"):
+        m = re.search(r"_kernel<\(?(?:[\w:]+\))?\s*(\w+)", name)
+        return short + "_count" if (m and m.group(1) == "1") else short
+    if short in ("im2col_lower", "im2col_lower_direct"):
+        m = re.search(r"_kernel<\s*(\w+)", name)
+        kind = "bf16" if (m and m.group(1) in ("true", "1")) else "f32"
+        return "im2col_lower_" + kind + ("_direct" if short.endswith("direct") else "")
+    return short
 
 
 def kernel_stats(directory):
