@@ -12,14 +12,16 @@
 // a wavefront
 //   1. reads the bounds of the runs of the (TX-1)*S+KW padded columns behind its tile from the
 //      table of resolved ptr offsets (wavefront-uniform);
-//   2. loads every run with lane = position in the run (value and index, coalesced);
-//   3. finds the piece of the run whose rows reach the tile with two compares and two population
-//      counts (index < first row * kw, index < (last row + 1) * kw);
-//   4. walks that piece NZE by NZE: value and index are read from their lane into scalar registers,
-//      the row inside the tile's input window selects one of (TY-1)*S+KH code paths, each issuing
-//      the kh*(pType+1) multiply-adds of convSpMv that land in the tile with compile-time
-//      registers for sums and weights.
-// Empty cells cost nothing: the instruction count follows the number of NZEs, not the map size.
+//   2. loads every run with lane = position in the run (value and index, coalesced; lanes past the
+//      run repeat its last NZE);
+//   3. sends every NZE whose row lies inside the input window behind the tile to the lane of that
+//      row (index - first index of the window, divided by kw; one forward permute per column), so a
+//      window column is a dense vector in one register, and takes the ballot of its non-zero lanes;
+//   4. walks the set bits: the value is read from its (compile-time) lane into a scalar register
+//      and the kh*(pType+1) multiply-adds of convSpMv that land in the tile are issued with
+//      compile-time registers for sums and weights.
+// An empty cell costs one scalar bit test and an untaken branch; loads, permutes and multiply-adds
+// follow the number of NZEs and runs, not the map size.
 // Loads of the next channel (bounds, runs, weights) are issued before the current one is applied.
 // With several channel slices across workgroups the tile's sums go to partial[slice][y][x][k] and a
 // second kernel adds the slices in a fixed order; with one slice the output is written directly.
