@@ -147,10 +147,11 @@ int64_t max_ptr_len(const Geometry &g)
 
 // Scratch layout: the encoder's look-back words (epochs, per-band stream lengths) | the convolution's
 // table of resolved ptr offsets | one int16 per NZE for the indices cps_conv rebuilds | partial
-// sums of the register-tile convolution.
+// sums of the convolution | the column table of the column-run convolution.
 // (each region holds g.N images back to back, with the per-image strides below)
 int64_t indices_stride(const Geometry &g) { return static_cast<int64_t>(g.C) * g.H * g.W; }                 // entries
 int64_t mtab_stride(const Geometry &g) { return static_cast<int64_t>(g.C) * std::max(g.n_types, 1) * (g.Ow + 1); }   // ints
+int64_t columns_stride(const Geometry &g) { return static_cast<int64_t>(g.C) * g.Iw; }                       // entries
 
 // encoder look-back words: the fixed region every scratch buffer starts with (its place and size do
 // not depend on the call, so calls of any shape and batch size may share a buffer), then the words
@@ -159,12 +160,14 @@ int64_t scratch_counts_bytes(const Geometry &g) { return encode_fixed_bytes() + 
 int64_t scratch_indices_bytes(const Geometry &g) { return (2 * indices_stride(g) * g.N + 255) / 256 * 256; }   // int16 each
 int64_t scratch_mtab_bytes(const Geometry &g) { return (4 * mtab_stride(g) * g.N + 255) / 256 * 256; }
 
-int64_t scratch_bytes_for(const Geometry &g)
+int64_t scratch_columns_offset(const Geometry &g)
 {
     const int64_t partial = std::max(std::max(tile_kernel_partial_bytes(g), strip_kernel_partial_bytes(g)),
                                      runs_kernel_partial_bytes(g));
-    return scratch_counts_bytes(g) + scratch_mtab_bytes(g) + scratch_indices_bytes(g) + partial;
+    return scratch_counts_bytes(g) + scratch_mtab_bytes(g) + scratch_indices_bytes(g) + (partial + 255) / 256 * 256;
 }
+
+int64_t scratch_bytes_for(const Geometry &g) { return scratch_columns_offset(g) + runs_kernel_columns_bytes(g); }
 
 }  // namespace cpoconv
 
@@ -349,7 +352,7 @@ static int encode_conv_common(const float *act, const cpoconv_shape *shape, int 
     const bool indices = algo == CPOCONV_ALGO_CPS && g.top_slot >= 0;
     const int erc = launch_encode(act, prod, g, *map, algo, scratch, st, table, indices);
     if (erc != CPOCONV_OK) return erc;
-    return launch_sparse_conv(*map, g, algo, wt, out, scratch, st, table, indices);
+    return launch_sparse_conv(*map, g, algo, wt, out, scratch, st, table, indices, table && encode_writes_columns(g));
 }
 
 int cpo_encode_conv(const float *act, const cpoconv_shape *shape, const cpoconv_map *map, const float *wt,

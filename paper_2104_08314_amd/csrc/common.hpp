@@ -40,10 +40,19 @@ struct BatchStrides {
     int64_t ptr, da, in;   // streams and side band: the per-image capacities of the map
     int64_t indices;       // what the convolution reads as IN: the stream itself or the rebuilt CPS indices (entries)
     int64_t mtab, partial, out;
+    int64_t columns;       // entries of the column table per image (column-run kernel)
     int32_t map_in16;      // the map's IN stream holds int16 entries
     int32_t indices16;     // so does what the convolution reads as IN (the rebuilt CPS indices always do)
     const int32_t *hdr;    // the map's header (8 ints per image)
     int32_t algo;          // the algorithm the call expects the map to hold
+};
+
+// What the column-run kernel knows of one padded column of one channel: where the column's run of
+// NZEs starts in DA and which padded rows hold one (maps of at most 64 padded rows).
+struct ColumnEntry {
+    int32_t begin;             // absolute offset of the run in DA
+    int32_t count;             // its length (= set bits)
+    uint32_t rows_lo, rows_hi; // bit r: padded row r holds an NZE
 };
 
 // A map the convolution must not read: its encoder gave up (hdr[7] equals the header's stamp), or it holds the other
@@ -125,13 +134,14 @@ private:
 // launchers (defined next to their kernels)
 int launch_encode(const float *act, const Producer &prod, const Geometry &g, const cpoconv_map &map, int algo,
                   void *scratch, hipStream_t stream, bool write_table = false, bool write_indices = false);
+bool encode_writes_columns(const Geometry &g);      // with write_table: does the encoder also leave the column table?
 int64_t encode_fixed_bytes();                        // look-back words every scratch buffer starts with
 int64_t encode_call_flags_bytes(const Geometry &g);  // look-back words of a call that takes two launches
 int launch_prepare_weights(const float *w, const Geometry &g, float *wt, hipStream_t stream);
 int launch_zero_fill(void *buffer, int64_t bytes, hipStream_t stream);
 int launch_sparse_conv(const cpoconv_map &map, const Geometry &g, int algo, const float *wt,
                        float *out, void *scratch, hipStream_t stream, bool table_ready = false,
-                       bool indices_ready = false);
+                       bool indices_ready = false, bool columns_ready = false);
 bool sparse_conv_uses_prologue(const Geometry &g);
 // register-tile SpMV kernel (spmv_conv_tile.hip)
 bool tile_kernel_supports(const Geometry &g);
@@ -148,15 +158,20 @@ int launch_sparse_conv_strip(const cpoconv_map &map, const int32_t *indices, con
 bool runs_kernel_supports(const Geometry &g);
 bool runs_kernel_preferred(const Geometry &g);
 int64_t runs_kernel_partial_bytes(const Geometry &g);
-int launch_sparse_conv_runs(const cpoconv_map &map, const int32_t *indices, const int32_t *mtab, const Geometry &g,
-                            const float *wt, float *out, float *partial, BatchStrides bs, hipStream_t stream);
+int64_t runs_kernel_columns_bytes(const Geometry &g);
+int launch_column_table(const cpoconv_map &map, const int32_t *indices, const int32_t *mtab, ColumnEntry *columns,
+                        const Geometry &g, const BatchStrides &bs, hipStream_t stream);
+int launch_sparse_conv_runs(const cpoconv_map &map, const ColumnEntry *columns, const Geometry &g, const float *wt, float *out,
+                            float *partial, BatchStrides bs, hipStream_t stream);
 // byte offsets of the regions of the caller's scratch buffer
 int64_t scratch_counts_bytes(const Geometry &g);
 int64_t scratch_indices_bytes(const Geometry &g);
 int64_t scratch_mtab_bytes(const Geometry &g);
+int64_t scratch_columns_offset(const Geometry &g);   // the column table comes last
 // per-image strides inside those regions, in 4-byte elements
 int64_t indices_stride(const Geometry &g);
 int64_t mtab_stride(const Geometry &g);
+int64_t columns_stride(const Geometry &g);           // in entries
 // out[k][y][x] = sum over channel slices of partial[slice][y][x][k] (spmv_conv.hip)
 int launch_reduce_transpose(const Geometry &g, const float *partial, int slices, int Ypad, int Xpad, float *out,
                             const BatchStrides &bs, hipStream_t stream);   // per image: partial advances by slices*Ypad*Xpad*Kpad, out by K*Oh*Ow

@@ -570,7 +570,8 @@ __global__ __launch_bounds__(kThreads) void encode_channel_kernel(const Geometry
                                                          unsigned long long *__restrict__ flags_all, const int units_stride,
                                                          const cpoconv_map maps, int32_t *__restrict__ mtab_all,
                                                          const int64_t mtab_stride, int16_t *__restrict__ full_all,
-                                                         const int64_t full_stride)
+                                                         const int64_t full_stride, ColumnEntry *__restrict__ columns_all,
+                                                         const int64_t columns_stride)
 {
     // image blockIdx.y of the launch: its map is image 0's advanced by the per-image capacities
     const int image = blockIdx.y;
@@ -631,6 +632,7 @@ __global__ __launch_bounds__(kThreads) void encode_channel_kernel(const Geometry
     // order) and leaves its part of every column's row bitmap in LDS; one thread per column then
     // puts the eight parts together ------------------------------------------------------------
     const int rows_per_wave = kChunk / kWaves;   // 8
+    unsigned long long rows_first = 0;           // column tid: the bitmap of its first 64 padded rows
     for (int q = 0; q < nchunks; ++q) {
         if (q > 0) {
             __syncthreads();   // every thread is done with the previous chunk
@@ -656,6 +658,7 @@ __global__ __launch_bounds__(kThreads) void encode_channel_kernel(const Geometry
             cnt_q[q][tid] = static_cast<uint16_t>(__popcll(mask));
             ecnt_q[q][tid] = static_cast<uint16_t>((tid >= top_begin && tid < top_end) ? set4_entries(mask)
                                                                                       : __popcll(mask));
+            if (q == 0) rows_first = mask;
         }
     }
 
@@ -776,6 +779,22 @@ __global__ __launch_bounds__(kThreads) void encode_channel_kernel(const Geometry
                 for (int pp = col_p0[vi]; pp < p_end; ++pp) row[1 + pp] = upto;
             }
         }
+    }
+
+    // ---- and, for the column-run convolution (maps of at most 64 padded rows: one chunk): where every
+    // padded column's run starts in DA and which padded rows it holds; padding columns hold nothing
+    if (columns_all != nullptr) {
+        ColumnEntry *row = columns_all + image * columns_stride + static_cast<int64_t>(c) * g.Iw;
+        if (tid < g.n_cols) {
+            ColumnEntry e;
+            e.begin = da_off + col_excl[tid];
+            e.count = col_excl[tid + 1] - col_excl[tid];
+            e.rows_lo = static_cast<uint32_t>(rows_first);
+            e.rows_hi = static_cast<uint32_t>(rows_first >> 32);
+            row[g.col_j[tid]] = e;
+        }
+        for (int j = tid; j < g.Iw; j += kThreads)
+            if (j < g.pad_w || j >= g.pad_w + g.W) row[j] = ColumnEntry{0, 0, 0u, 0u};
     }
 
     // ---- ptr of this channel -------------------------------------------------------------
@@ -1297,6 +1316,20 @@ static int launch_encode_bands(const float *act, const Producer &prod, const Geo
     return CPOCONV_OK;
 }
 
+// A wavefront walks its channel's rows alone, which costs latency on the larger of the small maps:
+// those take the one-wavefront-per-channel kernel only once workgroups of the other kernel would
+// queue for a compute unit.
+static bool use_small(const Geometry &g)
+{
+    const size_t small_tile = static_cast<size_t>(g.H) * (g.W | 1) * sizeof(float);
+    const bool worth = g.Ih * g.Iw <= kSmallAlways || static_cast<int64_t>(g.N) * g.C >= kSmallFromChannels;
+    return g.Ih <= kLanes && g.Iw <= kLanes && small_tile <= kSmallTileBytes && worth;
+}
+
+// The workgroup-per-channel kernel is the one that leaves the column table (for layers the
+// column-run convolution takes); after the other two the convolution rebuilds it from the streams.
+bool encode_writes_columns(const Geometry &g) { return runs_kernel_preferred(g) && !use_bands(g) && !use_small(g); }
+
 int launch_encode(const float *act, const Producer &prod, const Geometry &g, const cpoconv_map &map, int algo,
                   void *scratch, hipStream_t stream, bool write_table, bool write_indices)
 {
@@ -1311,6 +1344,11 @@ int launch_encode(const float *act, const Producer &prod, const Geometry &g, con
     const int64_t mstride = mtab_stride(g);
     const int cps = algo == CPOCONV_ALGO_CPS ? 1 : 0;
     if (use_bands(g)) return launch_encode_bands(act, prod, g, map, cps, scratch, stream, mtab, mstride, full, fstride);
+    // the column table of the column-run convolution, where that kernel takes the layer
+    ColumnEntry *columns = (write_table && encode_writes_columns(g))
+                               ? reinterpret_cast<ColumnEntry *>(static_cast<char *>(scratch) + scratch_columns_offset(g))
+                               : nullptr;
+    const int64_t cstride = columns_stride(g);
 
     unsigned long long *ctrl = static_cast<unsigned long long *>(scratch);
     const bool single = channels_single_pass(g);
@@ -1322,10 +1360,7 @@ int launch_encode(const float *act, const Producer &prod, const Geometry &g, con
     const int chunk = kLanes;
     const size_t lds = chunk * row_bytes;
     const size_t small_tile = static_cast<size_t>(g.H) * (g.W | 1) * sizeof(float);
-    // A wavefront walks its channel's rows alone, which costs latency on the larger of the small maps:
-    // those take the path only once workgroups of the other kernel would queue for a compute unit.
-    const bool worth = g.Ih * g.Iw <= kSmallAlways || static_cast<int64_t>(g.N) * g.C >= kSmallFromChannels;
-    if (g.Ih <= kLanes && g.Iw <= kLanes && small_tile <= kSmallTileBytes && worth) {
+    if (use_small(g)) {
         // small maps: one wavefront per channel
         const size_t lds_small = kWaves * (small_tile + kLanes * sizeof(float));
         const dim3 grid((g.C + kWaves - 1) / kWaves, g.N);
@@ -1350,17 +1385,18 @@ int launch_encode(const float *act, const Producer &prod, const Geometry &g, con
     if (single) {
         KernelTimer timer("encode", stream);
         hipLaunchKernelGGL(encode_channel_kernel<kSinglePass>, dim3(g.C, g.N), dim3(kThreads), lds, stream, g, act, prod, cps, chunk,
-                           ctrl, flags, units_stride, map, mtab, mstride, full, fstride);
+                           ctrl, flags, units_stride, map, mtab, mstride, full, fstride, columns, cstride);
     } else {
         {
             KernelTimer timer("encode_count", stream);
             hipLaunchKernelGGL(encode_channel_kernel<kPublishOnly>, dim3(g.C, g.N), dim3(kThreads), lds, stream, g, act, prod, cps,
-                               chunk, ctrl, flags, units_stride, map, static_cast<int32_t *>(nullptr), mstride, static_cast<int16_t *>(nullptr), fstride);
+                               chunk, ctrl, flags, units_stride, map, static_cast<int32_t *>(nullptr), mstride, static_cast<int16_t *>(nullptr), fstride,
+                               static_cast<ColumnEntry *>(nullptr), cstride);
         }
         CPOCONV_HIP_TRY(hipGetLastError());
         KernelTimer timer("encode", stream);
         hipLaunchKernelGGL(encode_channel_kernel<kPublished>, dim3(g.C, g.N), dim3(kThreads), lds, stream, g, act, prod, cps, chunk,
-                           ctrl, flags, units_stride, map, mtab, mstride, full, fstride);
+                           ctrl, flags, units_stride, map, mtab, mstride, full, fstride, columns, cstride);
     }
     CPOCONV_HIP_TRY(hipGetLastError());
     return CPOCONV_OK;

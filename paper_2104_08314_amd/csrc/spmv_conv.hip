@@ -391,7 +391,7 @@ bool sparse_conv_uses_prologue(const Geometry &g)
 }
 
 int launch_sparse_conv(const cpoconv_map &map, const Geometry &g, int algo, const float *wt, float *out,
-                       void *scratch, hipStream_t stream, bool table_ready, bool indices_ready)
+                       void *scratch, hipStream_t stream, bool table_ready, bool indices_ready, bool columns_ready)
 {
     char *base = static_cast<char *>(scratch);
     int32_t *mtab = reinterpret_cast<int32_t *>(base + scratch_counts_bytes(g));
@@ -401,6 +401,7 @@ int launch_sparse_conv(const cpoconv_map &map, const Geometry &g, int algo, cons
     BatchStrides bs;
     bs.ptr = map.ptr_cap; bs.da = map.da_cap; bs.in = map.in_cap; bs.indices = map.in_cap;
     bs.mtab = mtab_stride(g); bs.partial = 0; bs.out = static_cast<int64_t>(g.K) * g.Oh * g.Ow;
+    bs.columns = columns_stride(g);
     bs.map_in16 = map.in_bits == 16 ? 1 : 0;
     bs.indices16 = bs.map_in16;
     bs.hdr = map.hdr;
@@ -418,10 +419,13 @@ int launch_sparse_conv(const cpoconv_map &map, const Geometry &g, int algo, cons
     // 1-4 us faster than a prologue launch; in the register-tile kernel, where many more workgroups
     // would repeat the work, it was slower).  Otherwise, and for the index reconstruction of CPS,
     // a prologue kernel runs first.
-    // (table_ready / indices_ready: the encoder of the same call left the table / the plain CPS
-    // indices in the scratch buffer)
+    // (table_ready / indices_ready / columns_ready: the encoder of the same call left the table / the
+    // plain CPS indices / the column table of the column-run kernel in the scratch buffer)
+    ColumnEntry *columns = reinterpret_cast<ColumnEntry *>(base + scratch_columns_offset(g));
+    if (runs && columns_ready) return launch_sparse_conv_runs(map, columns, g, wt, out, nullptr, bs, stream);
     const bool expand = in_full != nullptr && !indices_ready;
-    const bool in_kernel = strip && !expand && !table_ready && resolve_in_kernel_ok(g);
+    // ... as does the kernel that builds the column table in front of the column-run kernel
+    const bool in_kernel = (strip || runs) && !expand && !table_ready && resolve_in_kernel_ok(g);
     if (in_kernel) mtab = nullptr;
     if ((tile && !in_kernel && !table_ready) || expand) {
         KernelTimer timer("conv_prologue", stream);
@@ -434,7 +438,12 @@ int launch_sparse_conv(const cpoconv_map &map, const Geometry &g, int algo, cons
         CPOCONV_HIP_TRY(hipGetLastError());
     }
     float *partial = reinterpret_cast<float *>(base + after_mtab + scratch_indices_bytes(g));
-    if (runs) return launch_sparse_conv_runs(map, indices, mtab, g, wt, out, partial, bs, stream);
+    if (runs) {
+        // the column table from the resolved offsets and the plain indices, then the convolution
+        const int rc = launch_column_table(map, indices, mtab, columns, g, bs, stream);
+        if (rc != CPOCONV_OK) return rc;
+        return launch_sparse_conv_runs(map, columns, g, wt, out, partial, bs, stream);
+    }
     if (strip) return launch_sparse_conv_strip(map, indices, mtab, g, wt, out, partial, bs, stream);
     if (tile) return launch_sparse_conv_tile(map, indices, mtab, g, wt, out, partial, bs, stream);
     const dim3 grid((g.Ow + kTX - 1) / kTX, (g.Oh + kTY - 1) / kTY, (g.Kpad / kLanes) * g.N);

@@ -3,32 +3,37 @@
 // CPO streams are column-major: inside a channel and overlap type the NZEs follow the partitions
 // and, inside a partition's new column, the padded rows, ascending.  ptr therefore delimits the
 // run of NZEs of every padded column (with one new column per overlap type and partition, which
-// holds for every kernel shape taken here), and inside a run the NZEs that reach a band of output
-// rows are one contiguous piece, because the run is sorted by row.
+// holds for every kernel shape taken here), and a run is sorted by row.  What the kernel needs of
+// a column is then two things: where its run starts in DA, and which padded rows hold an NZE - a
+// 64-bit row bitmap (maps up to 64 padded rows).  Both sit in a table of one 16-byte entry per
+// (channel, padded column), written by the encoder when it runs in the same call (it has the
+// bitmaps in hand: they are how it counts) or rebuilt from ptr and IN by column_table_kernel.
+// With the table the indices of a run never have to be read: the k-th set bit of the bitmap is the
+// row of the run's k-th NZE.
 //
 // Work split: a workgroup owns one TY x TX tile of output positions for 64*KPL output kernels
 // (lanes are kernels, KPL per lane); its wavefronts split the input channels and add their sums
 // through LDS in a fixed order when the channels are done - no barrier before that.  Per channel
 // a wavefront
-//   1. reads the bounds of the runs of the (TX-1)*S+KW padded columns behind its tile from the
-//      table of resolved ptr offsets (wavefront-uniform);
-//   2. loads every run with lane = position in the run (value and index, coalesced; lanes past the
-//      run repeat its last NZE);
-//   3. sends every NZE whose row lies inside the input window behind the tile to the lane of that
-//      row (index - first index of the window, divided by kw; one forward permute per column), so a
-//      window column is a dense vector in one register, and takes the ballot of its non-zero lanes;
-//   4. walks the set bits: the value is read from its (compile-time) lane into a scalar register
-//      and the kh*(pType+1) multiply-adds of convSpMv that land in the tile are issued with
+//   1. reads the table entries of the (TX-1)*S+KW padded columns behind its tile (scalar loads) and
+//      cuts the rows of the input window behind the tile out of every bitmap: the window's bits, and
+//      the number of NZEs of the run above the window (a population count);
+//   2. loads the window's NZEs with ONE vector load, lane = 8 * window column + window row: the
+//      lane of a set bit reads DA[run start + NZEs above the window + set bits below its own];
+//   3. walks the window bits, which are scalar registers: a clear bit costs a scalar bit test and an
+//      untaken branch, a set bit reads the value from its (compile-time) lane into a scalar register
+//      and issues the kh*(pType+1) multiply-adds of convSpMv that land in the tile, with
 //      compile-time registers for sums and weights.
-// An empty cell costs one scalar bit test and an untaken branch; loads, permutes and multiply-adds
-// follow the number of NZEs and runs, not the map size.
-// Loads of the next channel (bounds, runs, weights) are issued before the current one is applied.
-// With several channel slices across workgroups the tile's sums go to partial[slice][y][x][k] and a
-// second kernel adds the slices in a fixed order; with one slice the output is written directly.
+// Loads and multiply-adds follow the number of NZEs, not the map size.  The entries of the channel
+// after next and the values and weights of the next channel are in flight while the current one is
+// applied.  With several channel slices across workgroups the tile's sums go to
+// partial[slice][y][x][k] and a second kernel adds the slices in a fixed order; with one slice the
+// output is written directly.
 
 #include <algorithm>
 
 #include "common.hpp"
+#include "resolve_ptr.hpp"
 
 namespace cpoconv {
 
@@ -36,7 +41,7 @@ namespace {
 
 constexpr int kMaxWaves = 16;              // wavefronts (channel slices) per workgroup
 constexpr int kRunsMaxSlices = 16;         // channel slices across workgroups
-constexpr int kEmptyIndex = 0x7fffffff;    // index of a lane past the end of its run
+constexpr int kRowsPerColumn = 8;          // lanes a window column takes in the value register
 
 __device__ __forceinline__ int lane_id() { return threadIdx.x & (kLanes - 1); }
 __device__ __forceinline__ int uni(int v) { return __builtin_amdgcn_readfirstlane(v); }
@@ -65,78 +70,42 @@ __device__ __forceinline__ void apply_nze(float (&acc)[TY][TX][KPL], const float
     }
 }
 
-// One window column.  Lane k of idx / val is the k-th NZE of the column's run (lanes past the run
-// hold kEmptyIndex).  The NZEs whose rows lie inside the window are sent to the lane of their window
-// row with one cross-lane move (a forward permute: it uses the LDS crossbar, no LDS memory; lanes
-// that receive nothing read zero), so the column segment sits in a register as a dense vector.  A
-// ballot of its non-zero lanes is the bitmap of occupied rows; the walk over the rows is unrolled: a
-// clear bit costs a scalar bit test and an untaken branch, a set bit broadcasts the value from its
-// (compile-time) lane and issues the multiply-adds of that row.
+// The walk over one window column, unrolled: bit R of `bits` says whether window row R holds an NZE;
+// its value sits in lane 8 * Q + R of `values`.
 template <int KH, int KW, int S, int TY, int TX, int KPL, int Q, int R>
-__device__ __forceinline__ void apply_rows(float (&acc)[TY][TX][KPL], const float (&w)[KH * KW][KPL], const int col,
-                                           const unsigned mask)
+__device__ __forceinline__ void apply_rows(float (&acc)[TY][TX][KPL], const float (&w)[KH * KW][KPL], const float values,
+                                           const unsigned bits)
 {
     constexpr int RH = (TY - 1) * S + KH;
     if constexpr (R < RH) {
-        if (__builtin_expect((mask >> R) & 1u, 1)) {
-            const float v = __int_as_float(__builtin_amdgcn_readlane(col, R));
+        if (__builtin_expect((bits >> R) & 1u, 1)) {
+            const float v = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(values), Q * kRowsPerColumn + R));
             apply_nze<KH, KW, S, TY, TX, KPL, Q, R>(acc, w, v);
         }
-        apply_rows<KH, KW, S, TY, TX, KPL, Q, R + 1>(acc, w, col, mask);
+        apply_rows<KH, KW, S, TY, TX, KPL, Q, R + 1>(acc, w, values, bits);
     }
 }
 
 template <int KH, int KW, int S, int TY, int TX, int KPL, int Q>
-__device__ __forceinline__ void walk_columns(float (&acc)[TY][TX][KPL], const float (&w)[KH * KW][KPL],
-                                             const int (&col)[(TX - 1) * S + KW], const unsigned (&mask)[(TX - 1) * S + KW])
+__device__ __forceinline__ void walk_columns(float (&acc)[TY][TX][KPL], const float (&w)[KH * KW][KPL], const float values,
+                                             const unsigned (&bits)[(TX - 1) * S + KW])
 {
     constexpr int RW = (TX - 1) * S + KW;
     if constexpr (Q < RW) {
-        apply_rows<KH, KW, S, TY, TX, KPL, Q, 0>(acc, w, col[Q], mask[Q]);
-        walk_columns<KH, KW, S, TY, TX, KPL, Q + 1>(acc, w, col, mask);
+        apply_rows<KH, KW, S, TY, TX, KPL, Q, 0>(acc, w, values, bits[Q]);
+        walk_columns<KH, KW, S, TY, TX, KPL, Q + 1>(acc, w, values, bits);
     }
 }
 
-// One channel's loads: per window column the run's indices and values, lane k = k-th NZE of the run
-// (lanes past the run repeat its last NZE: harmless, they land on the same lane with the same value),
-// the scalar bound that tells rows inside the window from the rest (0 for a column without a run:
-// then nothing is inside), and the channel's weights for this lane's KPL kernels.
+// One channel's window: the occupied rows of every window column (wavefront-uniform), the NZEs
+// themselves (lane 8 * column + row; other lanes hold zero) and the channel's weights for this
+// lane's KPL kernels.
 template <int TAPS, int KPL, int RW>
 struct ChannelSet {
-    int idx[RW];
-    float val[RW];
-    unsigned lim[RW];
+    unsigned bits[RW];
+    float values;
     float w[TAPS][KPL];
 };
-
-template <int KH, int KW, int S, int TY, int TX, int KPL>
-__device__ __forceinline__ void apply_columns(float (&acc)[TY][TX][KPL], ChannelSet<KH * KW, KPL, (TX - 1) * S + KW> &cs,
-                                              const int lo)
-{
-    constexpr int RH = (TY - 1) * S + KH;
-    constexpr int RW = (TX - 1) * S + KW;
-    static_assert(RH < kLanes - 1, "the window's rows must leave the last lane free");
-    static_assert(RH * KW < (1 << 12), "the multiply-shift below is exact for small operands only");
-    int col[RW];
-    unsigned mask[RW];
-    // The weights are the youngest loads of this channel's set and loads complete in order: one
-    // wait on the last weight register here covers every register the walk below reads, instead
-    // of a wait in front of each multiply-add.
-    asm volatile("" : "+v"(cs.w[KH * KW - 1][KPL - 1]));
-    // every column's cross-lane move is issued before the first one is used
-#pragma unroll
-    for (int q = 0; q < RW; ++q) {
-        // index = column in partition + padded row * kw: d / kw is the row inside the window
-        const unsigned d = static_cast<unsigned>(cs.idx[q] - lo);
-        const bool inside = d < cs.lim[q];
-        const unsigned row = KW == 1 ? d : __umul24(d, (1u << 16) / KW + 1u) >> 16;
-        const int dst = inside ? static_cast<int>(row) : kLanes - 1;   // the last lane collects the rest and is never read
-        col[q] = __builtin_amdgcn_ds_permute(dst << 2, __float_as_int(cs.val[q]));
-    }
-#pragma unroll
-    for (int q = 0; q < RW; ++q) mask[q] = static_cast<unsigned>(__ballot(col[q] != 0));
-    walk_columns<KH, KW, S, TY, TX, KPL, 0>(acc, cs.w, col, mask);
-}
 
 // KPL consecutive floats as one load
 template <int KPL> struct WeightVec;
@@ -145,18 +114,19 @@ template <> struct WeightVec<2> { typedef float2 type; };
 template <> struct WeightVec<3> { struct type { float x, y, z; }; };
 template <> struct WeightVec<4> { typedef float4 type; };
 
-typedef const __attribute__((address_space(4))) int32_t *TablePtr;   // read-only for the kernel: scalar loads
+typedef const __attribute__((address_space(4))) int32_t *EntryPtr;   // the column table, read-only for the kernel: scalar loads
+static_assert(sizeof(ColumnEntry) == 16, "an entry is read as four ints");
 
-template <int KH, int KW, int S, int TY, int TX, int KPL, int NW, bool IN16>
+template <int KH, int KW, int S, int TY, int TX, int KPL, int NW>
 __global__ __launch_bounds__(NW *kLanes) void spmv_conv_runs_kernel(
-    const Geometry g, const RunsArgs a, const float *__restrict__ da_all, const int32_t *__restrict__ in_all,
-    const int32_t *__restrict__ mtab_all, const float *__restrict__ wt, float *__restrict__ partial_all,
-    float *__restrict__ out_all)
+    const Geometry g, const RunsArgs a, const float *__restrict__ da_all, const ColumnEntry *__restrict__ columns_all,
+    const float *__restrict__ wt, float *__restrict__ partial_all, float *__restrict__ out_all)
 {
     constexpr int RH = (TY - 1) * S + KH;      // rows of the padded input behind the tile
     constexpr int RW = (TX - 1) * S + KW;      // columns of it
     constexpr int TAPS = KH * KW;
     constexpr int A = TY * TX * KPL;           // accumulators per lane
+    static_assert(RH <= kRowsPerColumn && RW * kRowsPerColumn <= kLanes, "the window must fit one register, 8 lanes per column");
     using Set = ChannelSet<TAPS, KPL, RW>;
 
     extern __shared__ float red[];             // [wavefront][accumulator][lane], used after the channel loop
@@ -169,29 +139,14 @@ __global__ __launch_bounds__(NW *kLanes) void spmv_conv_runs_kernel(
     if (map_unusable(a.bs, image)) return;
     const int x0 = blockIdx.x * TX, y0 = blockIdx.y * TY;
     const int kbase = kg * kLanes * KPL;       // this lane holds kernels kbase + lane * KPL .. + KPL - 1
-    const char *__restrict__ da = reinterpret_cast<const char *>(da_all + image * a.bs.da);
-    const char *__restrict__ in = reinterpret_cast<const char *>(index_advance(in_all, image * a.bs.indices, IN16 ? 1 : 0));
-    const TablePtr mtab = (TablePtr)(mtab_all + image * a.bs.mtab);
-
-    // where the bounds of every window column's run sit inside a channel's block of the table:
-    // row of its overlap type, entry of its first partition (Section 3.2); -1: no encoded column
-    int toff[RW];
-#pragma unroll
-    for (int q = 0; q < RW; ++q) {
-        const int j = x0 * S + q;
-        const int lo_num = j - KW + 1;
-        const int p_lo = lo_num <= 0 ? 0 : (lo_num + S - 1) / S;
-        const int p_hi = min(j / S, g.Ow - 1);
-        const int t = p_hi - p_lo;               // overlap type: partitions holding the column, minus one
-        int slot = -1;
-        for (int i = 0; i < g.n_types; ++i)
-            if (static_cast<int>(g.type_id[i]) == t) slot = i;
-        const bool real = j >= g.pad_w && j < g.pad_w + g.W;
-        toff[q] = (real && t >= 0 && slot >= 0) ? slot * (g.Ow + 1) + p_lo : -1;
-    }
-    const int lo = y0 * S * KW;                  // indices below it lie above the window
-    const int tab_block = g.n_types * (g.Ow + 1);
-    const unsigned lane4 = static_cast<unsigned>(lane) * 4u;
+    const float *__restrict__ da = da_all + image * a.bs.da;
+    // the window's first padded column and row; columns past the padded width (a tile that hangs over
+    // the map's edge) read the last entry of the row and count as empty
+    const int j0 = x0 * S, top = y0 * S;
+    const EntryPtr columns = (EntryPtr)(reinterpret_cast<const int32_t *>(columns_all + image * a.bs.columns));
+    const unsigned long long above = (1ull << top) - 1ull;        // top <= 63: the map has at most 64 padded rows
+    const int my_q = lane / kRowsPerColumn, my_r = lane % kRowsPerColumn;
+    const unsigned below_mine = (1u << my_r) - 1u;
     const unsigned lane_w = static_cast<unsigned>(lane) * (KPL * 4u);
 
     // channels of this wavefront: c_begin + wave, + nwaves, ..
@@ -206,28 +161,32 @@ __global__ __launch_bounds__(NW *kLanes) void spmv_conv_runs_kernel(
 #pragma unroll
             for (int kk = 0; kk < KPL; ++kk) acc[y][x][kk] = 0.0f;
 
-    // bounds of a channel's runs: scalar loads, (begin, end) pairs side by side in the table
-    auto load_bounds = [&](int c, int (&beg)[RW], int (&end)[RW]) {
-        const TablePtr blk = mtab + static_cast<int64_t>(min(c, c_end - 1)) * tab_block;
+    // a channel's table entries for the window columns: scalar loads, 16 bytes each, side by side
+    // (begin, count, rows_lo, rows_hi)
+    auto load_entries = [&](int c, int (&e)[RW][4]) {
+        const EntryPtr row = columns + static_cast<int64_t>(min(c, c_end - 1)) * g.Iw * 4;
 #pragma unroll
         for (int q = 0; q < RW; ++q) {
-            const int at = max(toff[q], 0);
-            beg[q] = blk[at];
-            end[q] = (toff[q] >= 0 && c < c_end) ? blk[at + 1] : beg[q];   // no column, no channel: an empty run
+            const EntryPtr at = row + min(j0 + q, g.Iw - 1) * 4;
+#pragma unroll
+            for (int k = 0; k < 4; ++k) e[q][k] = at[k];
         }
     };
-    auto load_set = [&](int c, const int (&beg)[RW], const int (&end)[RW], Set &cs) {
+    auto load_set = [&](int c, const int (&e)[RW][4], Set &cs) {
+        unsigned mine = 0;      // this lane's column: its window bits and where the window's NZEs start in DA
+        int first = 0;
 #pragma unroll
         for (int q = 0; q < RW; ++q) {
-            const int cnt = end[q] - beg[q];
-            cs.lim[q] = cnt > 0 ? static_cast<unsigned>(RH * KW) : 0u;
-            // lane k reads NZE min(k, cnt - 1) of the run (NZE 0 of the stream for an empty run: never used)
-            const unsigned last4 = static_cast<unsigned>(max(end[q], 1) - 1) * 4u;
-            const unsigned at = min(static_cast<unsigned>(beg[q]) * 4u + lane4, last4);
-            cs.idx[q] = IN16 ? static_cast<int>(*reinterpret_cast<const int16_t *>(in + at / 2))   // compact map: same values
-                             : *reinterpret_cast<const int32_t *>(in + at);
-            cs.val[q] = *reinterpret_cast<const float *>(da + at);
+            const unsigned long long rows = (static_cast<unsigned long long>(static_cast<unsigned>(e[q][3])) << 32) |
+                                            static_cast<unsigned>(e[q][2]);
+            const bool live = c < c_end && j0 + q < g.Iw;
+            cs.bits[q] = live ? static_cast<unsigned>(rows >> top) & ((1u << RH) - 1u) : 0u;
+            const int start = e[q][0] + __popcll(rows & above);
+            if (my_q == q) { mine = cs.bits[q]; first = start; }
         }
+        const bool has = (mine >> my_r) & 1u;     // lanes of rows past RH and columns past RW see no bit
+        const int at = first + __popc(mine & below_mine);
+        cs.values = has ? da[at] : 0.0f;
         const float *wc = wt + static_cast<int64_t>(min(c, g.C - 1)) * TAPS * g.Kpad + kbase;
 #pragma unroll
         for (int tp = 0; tp < TAPS; ++tp) {
@@ -238,24 +197,31 @@ __global__ __launch_bounds__(NW *kLanes) void spmv_conv_runs_kernel(
             for (int kk = 0; kk < KPL; ++kk) cs.w[tp][kk] = f[kk];
         }
     };
+    auto apply = [&](Set &cs) {
+        // The weights are the youngest loads of the set and loads complete in order: one wait on
+        // the last weight register covers every register the walk reads, instead of a wait in
+        // front of each multiply-add.
+        asm volatile("" : "+v"(cs.w[TAPS - 1][KPL - 1]));
+        walk_columns<KH, KW, S, TY, TX, KPL, 0>(acc, cs.w, cs.values, cs.bits);
+    };
 
     // two register sets in turn: the loads of one channel are in flight while the other is applied,
-    // and the bounds are fetched one channel further ahead
+    // and the table entries are fetched one channel further ahead
     {
         Set sa, sb;
-        int beg_a[RW], end_a[RW], beg_b[RW], end_b[RW];
+        int ea[RW][4], eb[RW][4];
         const int c0 = c_begin + wave;
-        load_bounds(c0, beg_a, end_a);
-        load_bounds(c0 + nwaves, beg_b, end_b);
-        load_set(c0, beg_a, end_a, sa);
+        load_entries(c0, ea);
+        load_entries(c0 + nwaves, eb);
+        load_set(c0, ea, sa);
 #pragma unroll 1
         for (int c = c0; c < c_end; c += 2 * nwaves) {
-            load_set(c + nwaves, beg_b, end_b, sb);
-            load_bounds(c + 2 * nwaves, beg_a, end_a);
-            apply_columns<KH, KW, S, TY, TX, KPL>(acc, sa, lo);
-            load_set(c + 2 * nwaves, beg_a, end_a, sa);
-            load_bounds(c + 3 * nwaves, beg_b, end_b);
-            apply_columns<KH, KW, S, TY, TX, KPL>(acc, sb, lo);
+            load_set(c + nwaves, eb, sb);
+            load_entries(c + 2 * nwaves, ea);
+            apply(sa);
+            load_set(c + 2 * nwaves, ea, sa);
+            load_entries(c + 3 * nwaves, eb);
+            apply(sb);
         }
     }
 
@@ -269,7 +235,7 @@ __global__ __launch_bounds__(NW *kLanes) void spmv_conv_runs_kernel(
     float *out = out_all + image * a.bs.out;
     for (int n = wave; n < A; n += nwaves) {
         float s = red[n * kLanes + lane];
-        for (int w2 = 1; w2 < nwaves; ++w2) s += red[(w2 * A + n) * kLanes + lane];
+        for (int w = 1; w < nwaves; ++w) s += red[(w * A + n) * kLanes + lane];
         const int y = y0 + n / (TX * KPL), x = x0 + (n / KPL) % TX, k = kbase + lane * KPL + n % KPL;
         if (a.slices > 1) {
             // partial sums of this channel slice, kernel index fastest (tiles past the map's edge included)
@@ -280,6 +246,74 @@ __global__ __launch_bounds__(NW *kLanes) void spmv_conv_runs_kernel(
     }
 }
 
+// The table of column entries rebuilt from the streams, for a convolution whose encoder ran in an
+// earlier call: one workgroup per (channel, image).  First the channel's ptr segments become
+// absolute DA offsets after every partition (Algorithm 2's forward fill, a running maximum: one
+// wavefront, one lane per partition - or they are copied from the table of resolved offsets when a
+// kernel before this one has left it).  Then one wavefront per stream column in turn: the column's
+// run is delimited by entries p0 and p0 + 1 of its type's row; every lane takes one NZE of the run,
+// its index / kw is the padded row, and the rows are or-ed into the bitmap through LDS.
+constexpr int kTableThreads = 256;
+
+__global__ __launch_bounds__(kTableThreads) void column_table_kernel(const Geometry g, const int32_t *__restrict__ ptr_all,
+                                                                    const int32_t *__restrict__ chan_off_all,
+                                                                    const int32_t *__restrict__ indices_all,
+                                                                    const int32_t *__restrict__ mtab_all,
+                                                                    ColumnEntry *__restrict__ columns_all, const BatchStrides bs)
+{
+    __shared__ unsigned long long rows[kMaxCols];
+    __shared__ int32_t offsets[kMaxTypes][kLanes + 1];   // Ow <= 62 for the maps taken here
+    const int c = blockIdx.x, image = blockIdx.y;
+    if (map_unusable(bs, image)) return;
+    const int lane = lane_id(), wave = threadIdx.x / kLanes;
+    const int32_t *indices = index_advance(indices_all, image * bs.indices, bs.indices16);
+    ColumnEntry *out = columns_all + image * bs.columns + static_cast<int64_t>(c) * g.Iw;
+    for (int j = threadIdx.x; j < g.Iw; j += kTableThreads) rows[j] = 0ull;
+    if (mtab_all != nullptr) {
+        const int32_t *table = mtab_all + image * bs.mtab + static_cast<int64_t>(c) * g.n_types * (g.Ow + 1);
+        for (int n = threadIdx.x; n < g.n_types * (g.Ow + 1); n += kTableThreads)
+            offsets[n / (g.Ow + 1)][n % (g.Ow + 1)] = table[n];
+    } else if (wave == 0) {
+        const int32_t *ptr = ptr_all + image * bs.ptr;
+        const int32_t *chan_off = chan_off_all + static_cast<int64_t>(image) * 3 * (g.C + 1);
+        int seg = chan_off[c], at = chan_off[(g.C + 1) + c];
+        const bool npc = ptr[seg] == CPOCONV_NPC;
+        for (int i = 0; i < g.n_types; ++i) {
+            int live = 0;   // 0: no NZE, 1: [pType, e_0 .. e_{Ow-1}], 2: the three-entry NOP segment
+            if (!npc) live = (g.nop3 && g.type_id[i] == 0) ? 2 : (ptr[seg] == CPOCONV_NPF ? 0 : 1);
+            int e = -1;
+            if (lane < g.Ow) {
+                if (live == 1) e = ptr[seg + 1 + lane];
+                else if (live == 2) e = lane < g.Ow - 1 ? ptr[seg + 1] : ptr[seg + 2];
+            }
+            const int m = max(wave_running_max(e), 0);
+            if (lane < g.Ow) offsets[i][1 + lane] = at + m;
+            if (lane == 0) offsets[i][0] = at;
+            at += __builtin_amdgcn_readlane(m, kLanes - 1);
+            seg += npc ? 0 : (live == 2 ? 3 : (live == 1 ? 1 + g.Ow : 1));
+        }
+    }
+    __syncthreads();
+    for (int i = 0; i < g.n_types; ++i) {
+        for (int vi = g.type_begin[i] + wave; vi < g.type_begin[i + 1]; vi += kTableThreads / kLanes) {
+            const int p0 = g.col_p0[vi], j = g.col_j[vi];
+            const int begin = offsets[i][p0], end = offsets[i][p0 + 1];
+            if (lane < end - begin) {
+                const int index = load_index(indices, begin + lane, bs.indices16);
+                atomicOr(&rows[j], 1ull << (index / g.kw));
+            }
+            if (lane == 0) { out[j].begin = begin; out[j].count = end - begin; }
+        }
+    }
+    __syncthreads();
+    for (int j = threadIdx.x; j < g.Iw; j += kTableThreads) {
+        const bool real = j >= g.pad_w && j < g.pad_w + g.W;
+        if (!real) { out[j].begin = 0; out[j].count = 0; }
+        out[j].rows_lo = static_cast<uint32_t>(rows[j]);
+        out[j].rows_hi = static_cast<uint32_t>(rows[j] >> 32);
+    }
+}
+
 struct RunsPlan {
     int ty, tx, kpl, waves, slices;
 };
@@ -287,8 +321,7 @@ struct RunsPlan {
 // Launch shape (measured on MI355X at one to three images per launch, where this kernel is used):
 // 4 x 4 tiles, two kernels per lane where the padded kernel count allows, sixteen wavefronts per
 // workgroup - fewer when that would leave a wavefront less than two channels - and channel slices
-// across workgroups only while the tiles alone leave compute units without a workgroup (config 2:
-// 196 workgroups, one slice, 31 against 35 us for the strip kernel and its slice sum).
+// across workgroups only while the tiles alone leave compute units without a workgroup.
 RunsPlan runs_plan(const Geometry &g)
 {
     RunsPlan p;
@@ -306,8 +339,8 @@ RunsPlan runs_plan(const Geometry &g)
 }
 
 template <int KH, int KW, int S, int TY, int TX, int KPL, int NW>
-int launch_runs(const cpoconv_map &map, const int32_t *indices, const int32_t *mtab, const Geometry &g, const float *wt,
-                float *out, float *partial, const RunsPlan &p, BatchStrides bs, hipStream_t stream)
+int launch_runs(const cpoconv_map &map, const ColumnEntry *columns, const Geometry &g, const float *wt, float *out,
+                float *partial, const RunsPlan &p, BatchStrides bs, hipStream_t stream)
 {
     const int ntx = (g.Ow + TX - 1) / TX, nty = (g.Oh + TY - 1) / TY;
     const int ngroups = g.Kpad / (kLanes * KPL);
@@ -320,12 +353,8 @@ int launch_runs(const cpoconv_map &map, const int32_t *indices, const int32_t *m
     {
         KernelTimer timer("spmv_conv_runs", stream);
         const dim3 grid(ntx, nty, ngroups * p.slices * g.N), block(p.waves * kLanes);
-        if (bs.indices16)
-            hipLaunchKernelGGL((spmv_conv_runs_kernel<KH, KW, S, TY, TX, KPL, NW, true>), grid, block, lds, stream, g, a, map.da,
-                               indices, mtab, wt, partial, out);
-        else
-            hipLaunchKernelGGL((spmv_conv_runs_kernel<KH, KW, S, TY, TX, KPL, NW, false>), grid, block, lds, stream, g, a, map.da,
-                               indices, mtab, wt, partial, out);
+        hipLaunchKernelGGL((spmv_conv_runs_kernel<KH, KW, S, TY, TX, KPL, NW>), grid, block, lds, stream, g, a, map.da, columns,
+                           wt, partial, out);
     }
     CPOCONV_HIP_TRY(hipGetLastError());
     if (p.slices > 1) return launch_reduce_transpose(g, partial, p.slices, a.Ypad, a.Xpad, out, bs, stream);
@@ -334,8 +363,8 @@ int launch_runs(const cpoconv_map &map, const int32_t *indices, const int32_t *m
 
 }  // namespace
 
-// Shapes the kernel is instantiated for, maps whose column runs fit a wavefront (one lane per
-// padded row), and geometries with one new column per overlap type and partition (a stride that
+// Shapes the kernel is instantiated for, maps of at most 64 padded rows (a column's rows are one
+// 64-bit bitmap), and geometries with one new column per overlap type and partition (a stride that
 // does not divide the padded width leaves a last column that shares its partition with another).
 bool runs_kernel_supports(const Geometry &g)
 {
@@ -349,10 +378,9 @@ bool runs_kernel_supports(const Geometry &g)
 
 // Measured over the workload layers at one to three images per launch: where the tiles alone give
 // every compute unit a workgroup (one channel slice: no partial sums, no second kernel) the kernel
-// is 3 us faster per layer than the strip kernel with its slice sum (config 2: 44 against 47 us for
-// the layer, 64 x 56 x 56: 32 against 35); on the smaller maps, which need channel slices across
-// workgroups either way, it ties with the register-tile kernel, which keeps them.  From four images
-// on the strip kernel's shared decode wins (config 2 at 32 images: 12.6 against 15.3 us per image).
+// beats the strip kernel with its slice sum; on the smaller maps, which need channel slices across
+// workgroups either way, the register-tile kernel keeps the layers.  From four images on the strip
+// kernel's shared decode wins.
 bool runs_kernel_preferred(const Geometry &g)
 {
     return runs_kernel_supports(g) && g.N < 4 && runs_plan(g).slices == 1;
@@ -367,16 +395,34 @@ int64_t runs_kernel_partial_bytes(const Geometry &g)
     return 4 * Ypad * Xpad * g.Kpad * p.slices * g.N;
 }
 
-int launch_sparse_conv_runs(const cpoconv_map &map, const int32_t *indices, const int32_t *mtab, const Geometry &g,
-                            const float *wt, float *out, float *partial, BatchStrides bs, hipStream_t stream)
+int64_t runs_kernel_columns_bytes(const Geometry &g)
+{
+    if (!runs_kernel_preferred(g)) return 0;
+    return (static_cast<int64_t>(sizeof(ColumnEntry)) * columns_stride(g) * g.N + 255) / 256 * 256;
+}
+
+// mtab: the table of resolved ptr offsets if a kernel before this one has left it, else nullptr
+// (then the kernel resolves ptr itself)
+int launch_column_table(const cpoconv_map &map, const int32_t *indices, const int32_t *mtab, ColumnEntry *columns,
+                        const Geometry &g, const BatchStrides &bs, hipStream_t stream)
+{
+    KernelTimer timer("column_table", stream);
+    hipLaunchKernelGGL(column_table_kernel, dim3(g.C, g.N), dim3(kTableThreads), 0, stream, g, map.ptr, map.chan_off, indices,
+                       mtab, columns, bs);
+    CPOCONV_HIP_TRY(hipGetLastError());
+    return CPOCONV_OK;
+}
+
+int launch_sparse_conv_runs(const cpoconv_map &map, const ColumnEntry *columns, const Geometry &g, const float *wt, float *out,
+                            float *partial, BatchStrides bs, hipStream_t stream)
 {
     const RunsPlan p = runs_plan(g);
     if (p.kpl == 2) {
-        if (p.waves > 8) return launch_runs<3, 3, 1, 4, 4, 2, 16>(map, indices, mtab, g, wt, out, partial, p, bs, stream);
-        return launch_runs<3, 3, 1, 4, 4, 2, 8>(map, indices, mtab, g, wt, out, partial, p, bs, stream);
+        if (p.waves > 8) return launch_runs<3, 3, 1, 4, 4, 2, 16>(map, columns, g, wt, out, partial, p, bs, stream);
+        return launch_runs<3, 3, 1, 4, 4, 2, 8>(map, columns, g, wt, out, partial, p, bs, stream);
     }
-    if (p.waves > 8) return launch_runs<3, 3, 1, 4, 4, 1, 16>(map, indices, mtab, g, wt, out, partial, p, bs, stream);
-    return launch_runs<3, 3, 1, 4, 4, 1, 8>(map, indices, mtab, g, wt, out, partial, p, bs, stream);
+    if (p.waves > 8) return launch_runs<3, 3, 1, 4, 4, 1, 16>(map, columns, g, wt, out, partial, p, bs, stream);
+    return launch_runs<3, 3, 1, 4, 4, 1, 8>(map, columns, g, wt, out, partial, p, bs, stream);
 }
 
 }  // namespace cpoconv
