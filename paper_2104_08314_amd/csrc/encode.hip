@@ -610,11 +610,23 @@ __global__ __launch_bounds__(kThreads) void encode_channel_kernel(const Geometry
     const float *chan = act + static_cast<int64_t>(c) * g.H * g.W;
     const float bias_c = (prod.relu && prod.bias != nullptr) ? prod.bias[c] : 0.0f;
 
+    // rows wave, wave + 8, .. of the chunk: all of a wavefront's row loads are in flight before the
+    // first value is stored (one memory round trip per 64 columns instead of one per row)
     auto load_tile = [&](int q) {
-        for (int r = wave; r < kChunk; r += kWaves) {
-            const int hr = q * kChunk + r - g.pad_h;
-            if (hr < 0 || hr >= g.H) continue;
-            for (int jr = lane; jr < g.W; jr += kLanes) tile[r * Wt + jr] = produced(chan[hr * g.W + jr], prod, bias_c);
+        constexpr int kRowsPerWave = kLanes / kWaves;   // the chunk has at most 64 rows
+        for (int j0 = 0; j0 < g.W; j0 += kLanes) {
+            const int jr = j0 + lane;
+            float v[kRowsPerWave];
+#pragma unroll
+            for (int i = 0; i < kRowsPerWave; ++i) {
+                const int r = wave + i * kWaves, hr = q * kChunk + r - g.pad_h;
+                v[i] = (r < kChunk && hr >= 0 && hr < g.H && jr < g.W) ? chan[hr * g.W + jr] : 0.0f;
+            }
+#pragma unroll
+            for (int i = 0; i < kRowsPerWave; ++i) {
+                const int r = wave + i * kWaves, hr = q * kChunk + r - g.pad_h;
+                if (r < kChunk && hr >= 0 && hr < g.H && jr < g.W) tile[r * Wt + jr] = produced(v[i], prod, bias_c);
+            }
         }
     };
 
@@ -930,9 +942,20 @@ __global__ __launch_bounds__(kThreads) void encode_small_kernel(const Geometry g
     if (live) {
         const float *chan = act + static_cast<int64_t>(c) * g.H * g.W;
         const float bias_c = (prod.relu && prod.bias != nullptr) ? prod.bias[c] : 0.0f;
-        for (int i = lane; i < g.H * g.W; i += kLanes) {
-            const int r = i / g.W;
-            tile[r * Wt + (i - r * g.W)] = produced(chan[i], prod, bias_c);
+        // eight loads of the wavefront in flight before the first value is stored
+        constexpr int kInFlight = 8;
+        for (int i0 = lane; i0 < g.H * g.W; i0 += kInFlight * kLanes) {
+            float v[kInFlight];
+#pragma unroll
+            for (int u = 0; u < kInFlight; ++u) {
+                const int i = i0 + u * kLanes;
+                v[u] = i < g.H * g.W ? chan[i] : 0.0f;
+            }
+#pragma unroll
+            for (int u = 0; u < kInFlight; ++u) {
+                const int i = i0 + u * kLanes, r = i / g.W;
+                if (i < g.H * g.W) tile[r * Wt + (i - r * g.W)] = produced(v[u], prod, bias_c);
+            }
         }
     }
     wave_lds_fence();
