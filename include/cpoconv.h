@@ -54,7 +54,18 @@ typedef struct {
     int32_t kh, kw;      /* kernel height and width                       */
     int32_t stride;      /* both directions                               */
     int32_t pad_h, pad_w; /* zero rows above and below, zero columns left and right */
+    int32_t layout;      /* of the input map `act` / `pre`: CPOCONV_LAYOUT_CHW (0) or _HWC (1)  */
 } cpoconv_shape;
+
+/*
+ * Layout of the dense input map of a call (the "N x H x W x C" input of Table 1's I_n beside the
+ * channel-first one): CHW = C x H x W (N x C x H x W for a batch), HWC = H x W x C (N x H x W x C).
+ * Only the readers of `act` / `pre` look at it - the encoders and the im2col lowering; the encoded
+ * streams, the weights and every output (K x Oh x Ow) are the same for both.  In a chain only the
+ * first layer may be HWC: the others read what a convolution wrote.
+ */
+#define CPOCONV_LAYOUT_CHW 0
+#define CPOCONV_LAYOUT_HWC 1
 
 /*
  * An encoded activation map: the three streams of Section 3.3 in caller-allocated device

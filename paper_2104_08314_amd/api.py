@@ -17,6 +17,7 @@ LIB_PATH = os.path.join(_HERE, "libcpoconv.so")
 ALGO_IM2COL, ALGO_CPO, ALGO_CPS = 0, 1, 2
 NPF, NPC = -2, -3
 ERR_NULL, ERR_SHAPE, ERR_SMALL, ERR_HIP, ERR_ALGO, ERR_MAP = -1, -2, -3, -4, -5, -6
+LAYOUT_CHW, LAYOUT_HWC = 0, 1
 MAX_I = 256
 
 
@@ -27,7 +28,7 @@ class CpoconvError(RuntimeError):
 
 
 class Shape(ctypes.Structure):
-    _fields_ = [(n, ctypes.c_int32) for n in ("C", "H", "W", "K", "kh", "kw", "stride", "pad_h", "pad_w")]
+    _fields_ = [(n, ctypes.c_int32) for n in ("C", "H", "W", "K", "kh", "kw", "stride", "pad_h", "pad_w", "layout")]
 
     def as_tuple(self) -> Tuple[int, ...]:
         return tuple(int(getattr(self, n)) for n, _ in self._fields_)
@@ -119,12 +120,15 @@ def make_shape(shape) -> Shape:
     if isinstance(shape, Shape):
         return shape
     # (C, H, W, K, kh, kw, stride, pad) pads rows and columns alike; a ninth entry gives the
-    # columns their own padding: (.., stride, pad_h, pad_w)
+    # columns their own padding: (.., stride, pad_h, pad_w); a tenth the layout of the dense input
+    # map: LAYOUT_CHW (default) or LAYOUT_HWC
     v = [int(x) for x in shape]
     if len(v) == 8:
         v.append(v[7])
-    if len(v) != 9:
-        raise ValueError("a shape has eight or nine entries: (C, H, W, K, kh, kw, stride, pad_h[, pad_w])")
+    if len(v) == 9:
+        v.append(LAYOUT_CHW)
+    if len(v) != 10:
+        raise ValueError("a shape has eight to ten entries: (C, H, W, K, kh, kw, stride, pad_h[, pad_w[, layout]])")
     return Shape(*v)
 
 

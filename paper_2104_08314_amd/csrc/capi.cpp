@@ -68,6 +68,7 @@ int check_shape(const cpoconv_shape *s)
     if (s->stride < 1 || s->pad_h < 0 || s->pad_h > CPOCONV_MAX_I || s->pad_w < 0 || s->pad_w > CPOCONV_MAX_I)
         return CPOCONV_ERR_SHAPE;
     if (s->H > CPOCONV_MAX_I || s->W > CPOCONV_MAX_I) return CPOCONV_ERR_SHAPE;
+    if (s->layout != CPOCONV_LAYOUT_CHW && s->layout != CPOCONV_LAYOUT_HWC) return CPOCONV_ERR_SHAPE;
     const int Ih = s->H + 2 * s->pad_h, Iw = s->W + 2 * s->pad_w;
     if (Ih > CPOCONV_MAX_I || Iw > CPOCONV_MAX_I) return CPOCONV_ERR_SHAPE;
     if (Ih < s->kh || Iw < s->kw) return CPOCONV_ERR_SHAPE;
@@ -86,6 +87,7 @@ int build_geometry(const cpoconv_shape *s, Geometry *g)
     if (rc != CPOCONV_OK) return rc;
     memset(g, 0, sizeof(*g));
     g->C = s->C; g->H = s->H; g->W = s->W; g->K = s->K;
+    g->channel_last = s->layout == CPOCONV_LAYOUT_HWC ? 1 : 0;
     g->kh = s->kh; g->kw = s->kw; g->stride = s->stride; g->pad_h = s->pad_h; g->pad_w = s->pad_w;
     g->Ih = s->H + 2 * s->pad_h;
     g->Iw = s->W + 2 * s->pad_w;
@@ -473,8 +475,8 @@ static int chain_check(const cpoconv_chain_layer *layers, int n_layers, int n_im
         if (l.method == CPOCONV_ALGO_IM2COL && (l.precision < 0 || l.precision > 2)) return CPOCONV_ERR_ALGO;
         if (l.relu_in != 0 && l.relu_in != 1) return CPOCONV_ERR_ALGO;
         if (!l.relu_in && l.bias_in) return CPOCONV_ERR_ALGO;      // a bias is only applied in front of the ReLU
-        // a layer reads what the layer before it wrote
-        if (i > 0 && (g.C != prev.K || g.H != prev.Oh || g.W != prev.Ow)) return CPOCONV_ERR_SHAPE;
+        // a layer reads what the layer before it wrote: K x Oh x Ow, channel-first
+        if (i > 0 && (g.C != prev.K || g.H != prev.Oh || g.W != prev.Ow || g.channel_last)) return CPOCONV_ERR_SHAPE;
         prev = g;
     }
     return CPOCONV_OK;

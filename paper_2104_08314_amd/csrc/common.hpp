@@ -28,12 +28,20 @@ struct Geometry {
     int32_t top_slot;                // its slot in type_id, -1 if none
     int32_t Kpad;                    // K rounded up to a multiple of 64
     int32_t N;                       // images in the launch (1 unless a batched entry point)
+    int32_t channel_last;            // the dense input map is H x W x C instead of C x H x W
     uint8_t type_id[kMaxTypes];      // present types, ascending
     uint16_t type_begin[kMaxTypes + 1];  // column range of each present type
     uint8_t col_j[kMaxCols];         // padded column
     uint8_t col_p0[kMaxCols];        // first partition holding it
     uint8_t col_what[kMaxCols];      // column inside that partition
 };
+
+// Where element (channel c, row hr, column jr) of one image's dense input map sits.
+__device__ __forceinline__ int64_t map_index(const Geometry &g, int c, int hr, int jr)
+{
+    return g.channel_last ? (static_cast<int64_t>(hr) * g.W + jr) * g.C + c
+                          : (static_cast<int64_t>(c) * g.H + hr) * g.W + jr;
+}
 
 // Element strides between consecutive images of a batched launch (image 0 is at the base pointers).
 struct BatchStrides {

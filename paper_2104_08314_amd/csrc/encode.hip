@@ -245,7 +245,7 @@ __global__ __launch_bounds__(kEncThreads) void encode_kernel(const Geometry g, c
     const int IhP = g.Ih | 1;                             // odd column stride: conflict-free rows
     float *tile = lds + wave * (tile_floats + kLanes);
     int32_t *tblw = reinterpret_cast<int32_t *>(tile + tile_floats);
-    const float *chan = act_all + (static_cast<int64_t>(image) * g.C + c) * g.H * g.W;
+    const float *map_in = act_all + static_cast<int64_t>(image) * g.C * g.H * g.W;
     const float bias_c = (prod.relu && prod.bias != nullptr) ? prod.bias[c] : 0.0f;
 
     unsigned long long m[kMaskWords];   // bit h % 64 of word h / 64: padded row h of this lane's column holds an NZE
@@ -261,7 +261,7 @@ __global__ __launch_bounds__(kEncThreads) void encode_kernel(const Geometry g, c
             for (int u = 0; u < kInFlight; ++u) {
                 const int h = h0 + u * RP + rp, hr = h - g.pad_h;
                 const bool ok = col_ok && h < h_end && hr >= 0 && hr < g.H;
-                v[u] = ok ? chan[hr * g.W + jr] : 0.0f;
+                v[u] = ok ? map_in[map_index(g, c, hr, jr)] : 0.0f;
             }
 #pragma unroll
             for (int u = 0; u < kInFlight; ++u) {
@@ -607,7 +607,6 @@ __global__ __launch_bounds__(kThreads) void encode_channel_kernel(const Geometry
     const int nchunks = (g.Ih + kChunk - 1) / kChunk;
     const int top_begin = (cps && g.top_slot >= 0) ? g.type_begin[g.top_slot] : kMaxCols + 1;
     const int top_end = (cps && g.top_slot >= 0) ? g.type_begin[g.top_slot + 1] : 0;
-    const float *chan = act + static_cast<int64_t>(c) * g.H * g.W;
     const float bias_c = (prod.relu && prod.bias != nullptr) ? prod.bias[c] : 0.0f;
 
     // rows wave, wave + 8, .. of the chunk: all of a wavefront's row loads are in flight before the
@@ -620,7 +619,7 @@ __global__ __launch_bounds__(kThreads) void encode_channel_kernel(const Geometry
 #pragma unroll
             for (int i = 0; i < kRowsPerWave; ++i) {
                 const int r = wave + i * kWaves, hr = q * kChunk + r - g.pad_h;
-                v[i] = (r < kChunk && hr >= 0 && hr < g.H && jr < g.W) ? chan[hr * g.W + jr] : 0.0f;
+                v[i] = (r < kChunk && hr >= 0 && hr < g.H && jr < g.W) ? act[map_index(g, c, hr, jr)] : 0.0f;
             }
 #pragma unroll
             for (int i = 0; i < kRowsPerWave; ++i) {
@@ -940,7 +939,6 @@ __global__ __launch_bounds__(kThreads) void encode_small_kernel(const Geometry g
 
     // ---- the channel into LDS (coalesced), then its column bitmaps: lane = column in stream order ----
     if (live) {
-        const float *chan = act + static_cast<int64_t>(c) * g.H * g.W;
         const float bias_c = (prod.relu && prod.bias != nullptr) ? prod.bias[c] : 0.0f;
         // eight loads of the wavefront in flight before the first value is stored
         constexpr int kInFlight = 8;
@@ -948,8 +946,8 @@ __global__ __launch_bounds__(kThreads) void encode_small_kernel(const Geometry g
             float v[kInFlight];
 #pragma unroll
             for (int u = 0; u < kInFlight; ++u) {
-                const int i = i0 + u * kLanes;
-                v[u] = i < g.H * g.W ? chan[i] : 0.0f;
+                const int i = i0 + u * kLanes, r = i / g.W;
+                v[u] = i < g.H * g.W ? act[map_index(g, c, r, i - r * g.W)] : 0.0f;
             }
 #pragma unroll
             for (int u = 0; u < kInFlight; ++u) {

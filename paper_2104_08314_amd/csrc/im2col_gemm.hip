@@ -56,7 +56,7 @@ __global__ __launch_bounds__(kLowThreads) void im2col_lower_kernel(const Geometr
     const int band = blockIdx.x / parts, part = blockIdx.x - band * parts;
     const int y0 = band * band_rows, rows_out = min(band_rows, g.Oh - y0);
     const int c0 = blockIdx.y * kLowChannels, nc = min(kLowChannels, g.C - c0);
-    const float *__restrict__ act = act_all + (static_cast<int64_t>(blockIdx.z) * g.C + c0) * g.H * g.W;
+    const float *__restrict__ act = act_all + static_cast<int64_t>(blockIdx.z) * g.C * g.H * g.W;
     const int rows_max = (band_rows - 1) * g.stride + g.kh, rows_in = (rows_out - 1) * g.stride + g.kh;
     const int wp = (g.Ow - 1) * g.stride + g.kw;
 
@@ -78,7 +78,7 @@ __global__ __launch_bounds__(kLowThreads) void im2col_lower_kernel(const Geometr
                 if (x < wp) {
                     at[q] = (c * rows_max + r) * wp + x;
                     if (hr >= 0 && hr < g.H && jr >= 0 && jr < g.W)
-                        v[q] = produced(act[(static_cast<int64_t>(c) * g.H + hr) * g.W + jr], prod,
+                        v[q] = produced(act[map_index(g, c0 + c, hr, jr)], prod,
                                         (prod.relu && prod.bias != nullptr) ? prod.bias[c0 + c] : 0.0f);
                 }
             }
@@ -159,7 +159,7 @@ __global__ __launch_bounds__(kLowThreads) void im2col_lower_direct_kernel(const 
             const int hr = hr0 + l, jr = jr0 + w;
             v[u] = 0.0f;
             if (row0 + u < Kd && hr >= 0 && hr < g.H && jr >= 0 && jr < g.W)
-                v[u] = produced(act[(static_cast<int64_t>(c) * g.H + hr) * g.W + jr], prod,
+                v[u] = produced(act[map_index(g, c, hr, jr)], prod,
                                 (prod.relu && prod.bias != nullptr) ? prod.bias[c] : 0.0f);
             if (++w == g.kw) {
                 w = 0;

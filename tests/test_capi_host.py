@@ -82,6 +82,12 @@ def test_bad_arguments_are_rejected_on_the_host():
                 (4, 8, 2, 4, 3, 5, 1, 2, 1)]:
         sh = api.make_shape(bad)
         assert lib.cpoconv_sizes(ctypes.byref(sh), ctypes.byref(sz)) == api.ERR_SHAPE, bad
+    # the layout of the dense input map: CHW or HWC, nothing else; sizes do not depend on it
+    hwc = api.make_shape((4, 8, 8, 4, 3, 3, 1, 1, 1, api.LAYOUT_HWC))
+    assert lib.cpoconv_sizes(ctypes.byref(hwc), ctypes.byref(sz)) == 0
+    assert sz.scratch_bytes == api.cpoconv_sizes((4, 8, 8, 4, 3, 3, 1, 1)).scratch_bytes
+    odd = api.make_shape((4, 8, 8, 4, 3, 3, 1, 1, 1, 2))
+    assert lib.cpoconv_sizes(ctypes.byref(odd), ctypes.byref(sz)) == api.ERR_SHAPE
     # encode / conv / im2col: NULL pointers, short buffers, unknown precision -> no launch
     m = api._Map()
     one = ctypes.c_void_p(256)   # never dereferenced: validation fails first
@@ -175,6 +181,11 @@ def test_chain_sizes_and_argument_checks():
         assert getattr(sz, field) == max(getattr(e, field) for e in each), field
     assert (sz.Oh, sz.Ow) == (each[2].Oh, each[2].Ow)
     out = api.Sizes()
+    # only the first layer of a chain may read a channel-last map
+    first_last = _chain_table([a + (1, api.LAYOUT_HWC), b, c], [api.ALGO_CPO, api.ALGO_IM2COL, api.ALGO_CPS], relu=[0, 1, 1])
+    assert lib.cpoconv_chain_sizes(first_last, 3, 2, ctypes.byref(out)) == 0
+    second_last = _chain_table([a, b + (1, api.LAYOUT_HWC), c], [api.ALGO_CPO, api.ALGO_IM2COL, api.ALGO_CPS], relu=[0, 1, 1])
+    assert lib.cpoconv_chain_sizes(second_last, 3, 2, ctypes.byref(out)) == api.ERR_SHAPE
     # layers that do not fit each other: channels, then height
     bad = _chain_table([a, (8, 10, 12, 5, 3, 3, 1, 1)], [api.ALGO_CPO] * 2)
     assert lib.cpoconv_chain_sizes(bad, 2, 1, ctypes.byref(out)) == api.ERR_SHAPE
