@@ -350,11 +350,13 @@ static int encode_conv_common(const float *act, const cpoconv_shape *shape, int 
     // the encoder also leaves the table of resolved ptr offsets: the convolution needs no prologue
     // of its own; for a CPS map it also leaves there the plain index of every NZE (16 bits each: what
     // Algorithm 4 rebuilds from the packed IN stream, which the map itself holds as after cps_encode)
+    // (not where the column-run convolution follows: the encoder's column table is all it reads)
     const bool table = sparse_conv_uses_prologue(g);
-    const bool indices = algo == CPOCONV_ALGO_CPS && g.top_slot >= 0;
+    const bool columns = table && encode_writes_columns(g);
+    const bool indices = algo == CPOCONV_ALGO_CPS && g.top_slot >= 0 && !columns;
     const int erc = launch_encode(act, prod, g, *map, algo, scratch, st, table, indices);
     if (erc != CPOCONV_OK) return erc;
-    return launch_sparse_conv(*map, g, algo, wt, out, scratch, st, table, indices, table && encode_writes_columns(g));
+    return launch_sparse_conv(*map, g, algo, wt, out, scratch, st, table, indices, columns);
 }
 
 int cpo_encode_conv(const float *act, const cpoconv_shape *shape, const cpoconv_map *map, const float *wt,

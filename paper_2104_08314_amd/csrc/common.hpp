@@ -142,6 +142,7 @@ private:
 // launchers (defined next to their kernels)
 int launch_encode(const float *act, const Producer &prod, const Geometry &g, const cpoconv_map &map, int algo,
                   void *scratch, hipStream_t stream, bool write_table = false, bool write_indices = false);
+bool encode_uses_channel_kernel(const Geometry &g); // the workgroup-per-channel encoder takes the layer
 bool encode_writes_columns(const Geometry &g);      // with write_table: does the encoder also leave the column table?
 int64_t encode_fixed_bytes();                        // look-back words every scratch buffer starts with
 int64_t encode_call_flags_bytes(const Geometry &g);  // look-back words of a call that takes two launches

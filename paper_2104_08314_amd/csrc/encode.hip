@@ -1349,7 +1349,8 @@ static bool use_small(const Geometry &g)
 
 // The workgroup-per-channel kernel is the one that leaves the column table (for layers the
 // column-run convolution takes); after the other two the convolution rebuilds it from the streams.
-bool encode_writes_columns(const Geometry &g) { return runs_kernel_preferred(g) && !use_bands(g) && !use_small(g); }
+bool encode_uses_channel_kernel(const Geometry &g) { return !use_bands(g) && !use_small(g); }
+bool encode_writes_columns(const Geometry &g) { return runs_kernel_preferred(g) && encode_uses_channel_kernel(g); }
 
 int launch_encode(const float *act, const Producer &prod, const Geometry &g, const cpoconv_map &map, int algo,
                   void *scratch, hipStream_t stream, bool write_table, bool write_indices)

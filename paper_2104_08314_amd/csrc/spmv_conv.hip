@@ -422,7 +422,8 @@ int launch_sparse_conv(const cpoconv_map &map, const Geometry &g, int algo, cons
     // (table_ready / indices_ready / columns_ready: the encoder of the same call left the table / the
     // plain CPS indices / the column table of the column-run kernel in the scratch buffer)
     ColumnEntry *columns = reinterpret_cast<ColumnEntry *>(base + scratch_columns_offset(g));
-    if (runs && columns_ready) return launch_sparse_conv_runs(map, columns, g, wt, out, nullptr, bs, stream);
+    float *partial = reinterpret_cast<float *>(base + after_mtab + scratch_indices_bytes(g));
+    if (runs && columns_ready) return launch_sparse_conv_runs(map, columns, g, wt, out, partial, bs, stream);
     const bool expand = in_full != nullptr && !indices_ready;
     // ... as does the kernel that builds the column table in front of the column-run kernel
     const bool in_kernel = (strip || runs) && !expand && !table_ready && resolve_in_kernel_ok(g);
@@ -437,7 +438,6 @@ int launch_sparse_conv(const cpoconv_map &map, const Geometry &g, int algo, cons
                                map.chan_off, mtab, expand ? in_full : static_cast<int32_t *>(nullptr), bs);
         CPOCONV_HIP_TRY(hipGetLastError());
     }
-    float *partial = reinterpret_cast<float *>(base + after_mtab + scratch_indices_bytes(g));
     if (runs) {
         // the column table from the resolved offsets and the plain indices, then the convolution
         const int rc = launch_column_table(map, indices, mtab, columns, g, bs, stream);
