@@ -882,6 +882,282 @@ __global__ __launch_bounds__(kThreads) void encode_channel_kernel(const Geometry
 }
 
 // ---------------------------------------------------------------------------------------------
+// The workgroup-per-channel encoder for maps of at most 64 padded rows and 64 padded columns (every
+// layer of the workloads but the stems): the eight wavefronts share the channel's loads, the column
+// bitmaps and the scatter, and in between EVERY wavefront does the channel's bookkeeping for itself,
+// lane = column in stream order - counts, prefix sums, type bases, offsets; only the look-back over
+// the channels before it is shared out (its words are read past the caches).  Almost nothing has to
+// be handed from wavefront to wavefront then, so the kernel has three workgroup barriers (tile
+// loaded, bitmaps built, look-back added up) where the general one has about fifteen, and a
+// workgroup lives two thirds as long.  The tables of a convolution that follows and the ptr segments
+// are written by the wavefront whose number the overlap type has (mod 8).
+// ---------------------------------------------------------------------------------------------
+template <int kMode>
+__global__ __launch_bounds__(kThreads) void encode_channel64_kernel(const Geometry g, const float *__restrict__ act_all,
+                                                                   const Producer prod, const int cps,
+                                                                   unsigned long long *__restrict__ ctrl,
+                                                                   unsigned long long *__restrict__ flags_all,
+                                                                   const int units_stride, const cpoconv_map maps,
+                                                                   int32_t *__restrict__ mtab_all, const int64_t mtab_stride,
+                                                                   int16_t *__restrict__ full_all, const int64_t full_stride,
+                                                                   ColumnEntry *__restrict__ columns_all,
+                                                                   const int64_t columns_stride)
+{
+    extern __shared__ float tile[];                              // Ih x Wt, Wt odd: conflict-free column reads
+    __shared__ unsigned long long parts[kLanes];                 // a column's row bitmap: byte w from wavefront w
+    __shared__ int32_t stage[kWaves][kLanes];                    // one ptr segment under construction, per wavefront
+    __shared__ int32_t chan_base[4];                             // ptr / DA / IN start of the channel, look-back failures
+
+    const int image = blockIdx.y, c = blockIdx.x;
+    const int lane = lane_id(), tid = threadIdx.x;
+    const int wave = __builtin_amdgcn_readfirstlane(wave_id());
+    const float *__restrict__ act = act_all + static_cast<int64_t>(image) * g.C * g.H * g.W;
+    const unsigned long long epoch = peek(ctrl + 8 + image);   // one launch: the tag of its words; always: the call's stamp
+    const int stamp = call_stamp(epoch);
+    const unsigned long long tag = kMode == kSinglePass ? epoch % 0xFFFFFFFEull + 1ull : kTagTwoLaunches;
+    unsigned long long *flags = flags_all + 2 * static_cast<int64_t>(image) * units_stride;
+    cpoconv_map map = maps;
+    map.ptr += image * maps.ptr_cap;
+    map.da += image * maps.da_cap;
+    const int in16 = maps.in_bits == 16 ? 1 : 0;
+    map.in = index_advance(maps.in, image * maps.in_cap, in16);
+    map.chan_off += static_cast<int64_t>(image) * 3 * (g.C + 1);
+    map.hdr += image * 8;
+    int16_t *__restrict__ full = full_all != nullptr ? full_all + image * full_stride : nullptr;
+
+    const int Wt = g.W | 1;
+    const int top_begin = (cps && g.top_slot >= 0) ? g.type_begin[g.top_slot] : kMaxCols + 1;
+    const int top_end = (cps && g.top_slot >= 0) ? g.type_begin[g.top_slot + 1] : 0;
+    const float bias_c = (prod.relu && prod.bias != nullptr) ? prod.bias[c] : 0.0f;
+    constexpr int kRowsPerWave = kLanes / kWaves;   // 8: padded rows wave * 8 .. + 7 belong to the wavefront
+
+    // ---- the channel into LDS: all of a wavefront's row loads in flight before the first store -----
+    {
+        float v[kRowsPerWave];
+#pragma unroll
+        for (int i = 0; i < kRowsPerWave; ++i) {
+            const int hr = wave * kRowsPerWave + i - g.pad_h;
+            v[i] = (hr >= 0 && hr < g.H && lane < g.W) ? act[map_index(g, c, hr, lane)] : 0.0f;
+        }
+#pragma unroll
+        for (int i = 0; i < kRowsPerWave; ++i) {
+            const int hr = wave * kRowsPerWave + i - g.pad_h;
+            if (hr >= 0 && hr < g.H && lane < g.W) tile[hr * Wt + lane] = produced(v[i], prod, bias_c);
+        }
+    }
+    const bool col_ok = lane < g.n_cols;
+    const int my_jr = col_ok ? static_cast<int>(g.col_j[lane]) - g.pad_w : 0;
+    const int my_p0 = col_ok ? static_cast<int>(g.col_p0[lane]) : 0;
+    const int next_p0 = lane + 1 < g.n_cols ? static_cast<int>(g.col_p0[lane + 1]) : -1;
+    if (tid < 4) chan_base[tid] = 0;
+    __syncthreads();
+
+    // ---- column bitmaps: the wavefront's eight rows of every column (lane = column), one byte each ---
+    {
+        unsigned bits = 0;
+        if (col_ok) {
+#pragma unroll
+            for (int i = 0; i < kRowsPerWave; ++i) {
+                const int hr = wave * kRowsPerWave + i - g.pad_h;
+                if (hr >= 0 && hr < g.H) bits |= static_cast<unsigned>(is_nze(tile[hr * Wt + my_jr])) << i;
+            }
+        }
+        reinterpret_cast<uint8_t *>(parts)[lane * kWaves + wave] = static_cast<uint8_t>(bits);
+    }
+    __syncthreads();
+
+    // ---- from here on every wavefront keeps the channel's books itself: lane = column ---------------
+    const unsigned long long colmask = col_ok ? parts[lane] : 0ull;      // bit = padded row
+    const int cnt = __popcll(colmask);
+    const int ecnt = (lane >= top_begin && lane < top_end) ? set4_entries(colmask) : cnt;
+    const int incl = wave_inclusive_sum(cnt), eincl = wave_inclusive_sum(ecnt);
+    const int excl = incl - cnt, eexcl = eincl - ecnt;
+    const int nnz_c = __builtin_amdgcn_readlane(incl, kLanes - 1), in_c = __builtin_amdgcn_readlane(eincl, kLanes - 1);
+    int type_base[kMaxTypes + 1];
+#pragma unroll
+    for (int i = 0; i <= kMaxTypes; ++i) {
+        type_base[i] = nnz_c;
+        if (i <= g.n_types) {
+            const int b = g.type_begin[i];
+            if (b < g.n_cols) type_base[i] = __builtin_amdgcn_readlane(excl, b);
+        }
+    }
+    int ptr_c = 1;  // NPC
+    if (nnz_c > 0) {
+        ptr_c = 0;
+#pragma unroll
+        for (int i = 0; i < kMaxTypes; ++i) {
+            if (i >= g.n_types) continue;
+            if (g.nop3 && g.type_id[i] == 0) ptr_c += 3;
+            else ptr_c += (type_base[i + 1] > type_base[i]) ? 1 + g.Ow : 1;
+        }
+    }
+
+    // ---- look-back: one wavefront publishes, every wavefront adds up the channels before this one ---
+    if (kMode != kPublished && tid == 0) {
+        poke(flags + 2 * c, (tag << 32) | static_cast<unsigned>(nnz_c));
+        poke(flags + 2 * c + 1, (tag << 32) | static_cast<unsigned>(in_c) | (static_cast<unsigned>(ptr_c) << 17));
+    }
+    if (kMode == kPublishOnly) return;
+    {
+        // the channels before this one are shared out over the 512 threads and added up through LDS
+        int a0 = 0, a1 = 0, a2 = 0, bad = 0;
+        for (int cc = tid; cc < c; cc += kThreads) {
+            unsigned long long w0, w1;
+            if (kMode == kPublished) {   // written by the launch before this one: ordinary loads
+                w0 = flags[2 * cc];
+                w1 = flags[2 * cc + 1];
+            } else {
+                w0 = peek(flags + 2 * cc);
+                w1 = peek(flags + 2 * cc + 1);
+                for (int spin = 0; ((w0 >> 32) != tag || (w1 >> 32) != tag) && spin < kSpinLimit; ++spin) {
+                    __builtin_amdgcn_s_sleep(8);
+                    w0 = peek(flags + 2 * cc);
+                    w1 = peek(flags + 2 * cc + 1);
+                }
+            }
+            if ((w0 >> 32) != tag || (w1 >> 32) != tag || !lengths_plausible(w0, w1)) { bad = 1; break; }
+            a1 += static_cast<int>(w0 & 0xFFFFFFFFull);
+            a2 += static_cast<int>(w1 & 0x1FFFFull);
+            a0 += static_cast<int>((w1 >> 17) & 0x7FFFull);
+        }
+        a0 = wave_sum(a0); a1 = wave_sum(a1); a2 = wave_sum(a2); bad = wave_sum(bad);
+        if (lane == 0 && (a0 | a1 | a2 | bad) != 0) {
+            atomicAdd(&chan_base[0], a0);
+            atomicAdd(&chan_base[1], a1);
+            atomicAdd(&chan_base[2], a2);
+            atomicAdd(&chan_base[3], bad);
+        }
+    }
+    __syncthreads();
+    const int ptr_off = chan_base[0], da_off = chan_base[1], in_off = chan_base[2], failed = chan_base[3];
+    // the last channel has seen every other channel's lengths, so all of them have read the epoch:
+    // it may move on (also after a failure, so that the words of this call are never taken for the next one's)
+    if (tid == 0 && c == g.C - 1) {
+        poke(ctrl + 8 + image, epoch + 1ull);
+        close_header(map.hdr, stamp, in16);
+    }
+    // a predecessor never showed up, or the offsets would leave the map's buffers: write nothing
+    if (failed != 0 || ptr_off + ptr_c > maps.ptr_cap || da_off + nnz_c > maps.da_cap || in_off + in_c > maps.in_cap) {
+        if (tid == 0) raise_failure(map.hdr, stamp);
+        return;
+    }
+
+    if (tid == 0) {
+        map.chan_off[c] = ptr_off;
+        map.chan_off[(g.C + 1) + c] = da_off;
+        map.chan_off[2 * (g.C + 1) + c] = in_off;
+        if (c == g.C - 1) {
+            map.chan_off[g.C] = ptr_off + ptr_c;
+            map.chan_off[(g.C + 1) + g.C] = da_off + nnz_c;
+            map.chan_off[2 * (g.C + 1) + g.C] = in_off + in_c;
+            map.hdr[0] = ptr_off + ptr_c;
+            map.hdr[1] = da_off + nnz_c;
+            map.hdr[2] = in_off + in_c;
+            map.hdr[3] = cps ? CPOCONV_ALGO_CPS : CPOCONV_ALGO_CPO;
+            map.hdr[4] = g.C;
+            map.hdr[5] = g.Ow;
+        }
+    }
+
+    // ---- for a convolution of the same call: the table of absolute DA offsets after every partition
+    // (overlap type i by wavefront i mod 8) and the column table of the column-run kernel -----------
+    if (mtab_all != nullptr) {
+#pragma unroll
+        for (int i = 0; i < kMaxTypes; ++i) {
+            if (i >= g.n_types || (i & (kWaves - 1)) != wave) continue;
+            int32_t *row = mtab_all + image * mtab_stride + (static_cast<int64_t>(c) * g.n_types + i) * (g.Ow + 1);
+            const int cb = g.type_begin[i], ce = g.type_begin[i + 1];
+            const int at = da_off + type_base[i];
+            const int p_first = cb < ce ? static_cast<int>(g.col_p0[cb]) : g.Ow;
+            for (int k = lane; k <= p_first; k += kLanes) row[k] = at;
+            if (lane >= cb && lane < ce) {
+                const int p_end = lane + 1 < ce ? next_p0 : g.Ow;
+                const int upto = da_off + incl;
+                for (int pp = my_p0; pp < p_end; ++pp) row[1 + pp] = upto;
+            }
+        }
+    }
+    if (columns_all != nullptr && wave == kWaves - 1) {
+        ColumnEntry *row = columns_all + image * columns_stride + static_cast<int64_t>(c) * g.Iw;
+        if (col_ok)
+            row[g.col_j[lane]] = ColumnEntry{da_off + excl, cnt, static_cast<uint32_t>(colmask), static_cast<uint32_t>(colmask >> 32)};
+        if (lane < g.Iw && (lane < g.pad_w || lane >= g.pad_w + g.W)) row[lane] = ColumnEntry{0, 0, 0u, 0u};
+    }
+
+    // ---- ptr: overlap type i by wavefront i mod 8 ----------------------------------------------------
+    if (nnz_c == 0) {
+        if (tid == 0) map.ptr[ptr_off] = CPOCONV_NPC;
+        return;  // nothing to write to DA / IN
+    }
+    {
+        int seg = ptr_off;
+#pragma unroll
+        for (int i = 0; i < kMaxTypes; ++i) {
+            if (i >= g.n_types) continue;
+            const int cb = g.type_begin[i], ce = g.type_begin[i + 1];
+            const int base = type_base[i];
+            const bool mine = (i & (kWaves - 1)) == wave;
+            if (g.nop3 && g.type_id[i] == 0) {
+                // [0, NZEs of the first column, NZEs of first + last column]
+                const int n1 = __builtin_amdgcn_readlane(incl, min(cb, kLanes - 1)) - base;
+                const int n2 = __builtin_amdgcn_readlane(incl, min(max(ce - 1, cb), kLanes - 1)) - base;
+                if (mine && lane == 0) { map.ptr[seg] = 0; map.ptr[seg + 1] = n1; map.ptr[seg + 2] = n2; }
+                seg += 3;
+                continue;
+            }
+            if (type_base[i + 1] == base) {
+                if (mine && lane == 0) map.ptr[seg] = CPOCONV_NPF;
+                seg += 1;
+                continue;
+            }
+            if (mine) {
+                int32_t *tblw = stage[wave];
+                tblw[lane] = -1;
+                wave_lds_fence();
+                // cumulative count after the last column first seen in each partition
+                if (lane >= cb && lane < ce && (lane + 1 == ce || next_p0 != my_p0)) tblw[my_p0] = incl - base;
+                wave_lds_fence();
+                if (lane == 0) map.ptr[seg] = g.type_id[i];
+                if (lane < g.Ow) map.ptr[seg + 1 + lane] = tblw[lane];
+                wave_lds_fence();
+            }
+            seg += 1 + g.Ow;
+        }
+    }
+
+    // ---- scatter DA and IN: columns wave, wave + 8, .. ; lane = padded row -----------------------------
+    const int hr = lane - g.pad_h;
+    const bool row_ok = hr >= 0 && hr < g.H;
+    const unsigned long long below = (1ull << lane) - 1ull;
+#pragma unroll 2
+    for (int vi = wave; vi < g.n_cols; vi += kWaves) {
+        const int jr = __builtin_amdgcn_readlane(my_jr, vi);
+        const int da_at = da_off + __builtin_amdgcn_readlane(excl, vi), in_at = in_off + __builtin_amdgcn_readlane(eexcl, vi);
+        const float v = row_ok ? tile[hr * Wt + jr] : 0.0f;
+        const bool nz = is_nze(v);
+        const unsigned long long mask = __ballot(nz);
+        const int rank = __popcll(mask & below);
+        const int index = static_cast<int>(g.col_what[vi]) + lane * g.kw;
+        if (nz) map.da[da_at + rank] = v;
+        if (nz && full != nullptr) full[da_at + rank] = static_cast<int16_t>(index);
+        if (vi >= top_begin && vi < top_end) {
+            // set4 of Algorithm 3: the four padded rows 4*(h/4) .. +3
+            const int pattern = static_cast<int>((mask >> (lane & ~3)) & 0xFull);
+            const int r = __popc(pattern & ((1 << (lane & 3)) - 1));   // rank inside the set
+            const bool emit = nz && r < 2;
+            const int erank = __popcll(__ballot(emit) & below);
+            // first NZE of the set: its index (negated unless a pattern follows);
+            // second NZE: the pattern, or its own negated index
+            const int entry = __popc(pattern) >= 3 ? (r == 0 ? index : pattern) : -index;
+            if (emit) store_index(map.in, in_at + erank, entry, in16);
+        } else {
+            if (nz) store_index(map.in, in_at + rank, index, in16);
+        }
+    }
+}
+
+// ---------------------------------------------------------------------------------------------
 // The same encoder for small maps (padded height and width up to 64, the unpadded map within 4 KiB):
 // one WAVEFRONT per channel, eight channels per workgroup.  A 14 x 14 or 7 x 7 map keeps a
 // 512-thread workgroup idle almost everywhere; here every step of a channel is a wavefront-wide
@@ -1400,6 +1676,28 @@ int launch_encode(const float *act, const Producer &prod, const Geometry &g, con
             KernelTimer timer("encode", stream);
             hipLaunchKernelGGL(encode_small_kernel<kPublished>, grid, dim3(kThreads), lds_small, stream, g, act, prod, cps, ctrl,
                                flags, units_stride, map, mtab, mstride, full, fstride);
+        }
+        CPOCONV_HIP_TRY(hipGetLastError());
+        return CPOCONV_OK;
+    }
+    if (g.Ih <= kLanes && g.Iw <= kLanes) {
+        // maps of at most 64 x 64 padded cells: the variant whose wavefronts keep their own books
+        const size_t lds64 = static_cast<size_t>(g.H) * (g.W | 1) * sizeof(float);
+        if (single) {
+            KernelTimer timer("encode", stream);
+            hipLaunchKernelGGL(encode_channel64_kernel<kSinglePass>, dim3(g.C, g.N), dim3(kThreads), lds64, stream, g, act, prod,
+                               cps, ctrl, flags, units_stride, map, mtab, mstride, full, fstride, columns, cstride);
+        } else {
+            {
+                KernelTimer timer("encode_count", stream);
+                hipLaunchKernelGGL(encode_channel64_kernel<kPublishOnly>, dim3(g.C, g.N), dim3(kThreads), lds64, stream, g, act,
+                                   prod, cps, ctrl, flags, units_stride, map, static_cast<int32_t *>(nullptr), mstride,
+                                   static_cast<int16_t *>(nullptr), fstride, static_cast<ColumnEntry *>(nullptr), cstride);
+            }
+            CPOCONV_HIP_TRY(hipGetLastError());
+            KernelTimer timer("encode", stream);
+            hipLaunchKernelGGL(encode_channel64_kernel<kPublished>, dim3(g.C, g.N), dim3(kThreads), lds64, stream, g, act, prod,
+                               cps, ctrl, flags, units_stride, map, mtab, mstride, full, fstride, columns, cstride);
         }
         CPOCONV_HIP_TRY(hipGetLastError());
         return CPOCONV_OK;

@@ -18,7 +18,7 @@ from collections import defaultdict
 
 csv.field_size_limit(1 << 30)
 
-OURS = ("encode_kernel", "encode_small_kernel", "encode_channel_kernel", "conv_prologue_kernel", "conv_prologue_wave_kernel",
+OURS = ("encode_kernel", "encode_small_kernel", "encode_channel_kernel", "encode_channel64_kernel", "column_table_kernel", "conv_prologue_kernel", "conv_prologue_wave_kernel",
         "zero_fill_kernel", "spmv_conv_tile_kernel", "spmv_conv_strip_kernel", "spmv_conv_runs_kernel",
         "spmv_conv_lds_kernel", "reduce_transpose_kernel", "im2col_lower_kernel", "im2col_lower_direct_kernel",
         "gemm_f32_kernel", "gemm_bf16_kernel", "splitk_reduce_kernel", "prepare_weights_kernel", "prepare_weights_bf16_kernel")
@@ -33,14 +33,15 @@ def _find(directory, suffix):
 
 def short_name(name):
     """Kernel name without template arguments, parameters, namespaces or _kernel suffix.  The three
-    encoders keep their names (encode: column bands; encode_channel: a workgroup per channel;
-    encode_small: a wavefront per channel - the library's timing aid calls all of them encode), a
+    encoders keep their names (encode: column bands; encode_channel / encode_channel64: a workgroup
+    per channel, the latter for maps up to 64 x 64 padded cells; encode_small: a wavefront per
+    channel - the library's timing aid calls all of them encode), a
     publish-only instantiation gets _count appended; the lowering kernels are named for their
     output type, the direct one (small launches) with _direct appended."""
     name = name.replace("(anonymous namespace)::", "")
     base = re.split(r"[<(]", name, 1)[0].replace("void ", "").split("::")[-1].strip()
     short = base[:-len("_kernel")] if base.endswith("_kernel") else base
-    if short in ("encode", "encode_channel", "encode_small"):
+    if short in ("encode", "encode_channel", "encode_channel64", "encode_small"):
         m = re.search(r"_kernel<\(?(?:[\w:]+\))?\s*(\w+)", name)
         return short + "_count" if (m and m.group(1) == "1") else short
     if short in ("im2col_lower", "im2col_lower_direct"):
