@@ -912,9 +912,6 @@ __global__ __launch_bounds__(kThreads) void encode_channel64_kernel(const Geomet
     const int lane = lane_id(), tid = threadIdx.x;
     const int wave = __builtin_amdgcn_readfirstlane(wave_id());
     const float *__restrict__ act = act_all + static_cast<int64_t>(image) * g.C * g.H * g.W;
-    const unsigned long long epoch = peek(ctrl + 8 + image);   // one launch: the tag of its words; always: the call's stamp
-    const int stamp = call_stamp(epoch);
-    const unsigned long long tag = kMode == kSinglePass ? epoch % 0xFFFFFFFEull + 1ull : kTagTwoLaunches;
     unsigned long long *flags = flags_all + 2 * static_cast<int64_t>(image) * units_stride;
     cpoconv_map map = maps;
     map.ptr += image * maps.ptr_cap;
@@ -945,6 +942,10 @@ __global__ __launch_bounds__(kThreads) void encode_channel64_kernel(const Geomet
             if (hr >= 0 && hr < g.H && lane < g.W) tile[hr * Wt + lane] = produced(v[i], prod, bias_c);
         }
     }
+    // (read behind the tile's loads: loads complete in order, and this one goes past the caches)
+    const unsigned long long epoch = peek(ctrl + 8 + image);   // one launch: the tag of its words; always: the call's stamp
+    const int stamp = call_stamp(epoch);
+    const unsigned long long tag = kMode == kSinglePass ? epoch % 0xFFFFFFFEull + 1ull : kTagTwoLaunches;
     const bool col_ok = lane < g.n_cols;
     const int my_jr = col_ok ? static_cast<int>(g.col_j[lane]) - g.pad_w : 0;
     const int my_p0 = col_ok ? static_cast<int>(g.col_p0[lane]) : 0;
@@ -999,28 +1000,78 @@ __global__ __launch_bounds__(kThreads) void encode_channel64_kernel(const Geomet
         poke(flags + 2 * c + 1, (tag << 32) | static_cast<unsigned>(in_c) | (static_cast<unsigned>(ptr_c) << 17));
     }
     if (kMode == kPublishOnly) return;
-    {
-        // the channels before this one are shared out over the 512 threads and added up through LDS
-        int a0 = 0, a1 = 0, a2 = 0, bad = 0;
-        for (int cc = tid; cc < c; cc += kThreads) {
-            unsigned long long w0, w1;
-            if (kMode == kPublished) {   // written by the launch before this one: ordinary loads
-                w0 = flags[2 * cc];
-                w1 = flags[2 * cc + 1];
+    // the channels before this one are shared out over the 512 threads (at most 512 channels take this
+    // path in one launch, so a thread has at most one); the first reads go out now ...
+    // (a launch that follows a publish-only launch may have more channels: it reads them as ordinary data below)
+    const bool polls = kMode == kSinglePass && tid < c;
+    unsigned long long w0 = 0, w1 = 0;
+    if (polls) {
+        w0 = peek(flags + 2 * tid);
+        w1 = peek(flags + 2 * tid + 1);
+    }
+
+    // ... and while they travel, the scatter's items are prepared: columns wave, wave + 8, .. of the
+    // wavefront, lane = padded row; value, rank among the column's NZEs, and the IN entry with its rank
+    constexpr int kColsPerWave = kLanes / kWaves;   // n_cols <= 64
+    const int hr = lane - g.pad_h;
+    const bool row_ok = hr >= 0 && hr < g.H;
+    const unsigned long long below = (1ull << lane) - 1ull;
+    float item_v[kColsPerWave];
+    int item_rank[kColsPerWave], item_erank[kColsPerWave], item_entry[kColsPerWave];   // erank < 0: no IN entry from this lane
+#pragma unroll
+    for (int n = 0; n < kColsPerWave; ++n) {
+        const int vi = wave + n * kWaves;
+        item_v[n] = 0.0f;
+        item_rank[n] = 0; item_erank[n] = -1; item_entry[n] = 0;
+        if (vi < g.n_cols) {
+            const int jr = __builtin_amdgcn_readlane(my_jr, vi);
+            const float v = row_ok ? tile[hr * Wt + jr] : 0.0f;
+            const bool nz = is_nze(v);
+            const unsigned long long mask = __ballot(nz);
+            const int rank = __popcll(mask & below);
+            const int index = static_cast<int>(g.col_what[vi]) + lane * g.kw;
+            item_v[n] = v;
+            item_rank[n] = rank;
+            if (vi >= top_begin && vi < top_end) {
+                // set4 of Algorithm 3: the four padded rows 4*(h/4) .. +3
+                const int pattern = static_cast<int>((mask >> (lane & ~3)) & 0xFull);
+                const int r = __popc(pattern & ((1 << (lane & 3)) - 1));   // rank inside the set
+                const bool emit = nz && r < 2;
+                const int erank = __popcll(__ballot(emit) & below);
+                // first NZE of the set: its index (negated unless a pattern follows);
+                // second NZE: the pattern, or its own negated index
+                item_entry[n] = __popc(pattern) >= 3 ? (r == 0 ? index : pattern) : -index;
+                if (emit) item_erank[n] = erank;
             } else {
-                w0 = peek(flags + 2 * cc);
-                w1 = peek(flags + 2 * cc + 1);
-                for (int spin = 0; ((w0 >> 32) != tag || (w1 >> 32) != tag) && spin < kSpinLimit; ++spin) {
-                    __builtin_amdgcn_s_sleep(8);
-                    w0 = peek(flags + 2 * cc);
-                    w1 = peek(flags + 2 * cc + 1);
-                }
+                item_entry[n] = index;
+                if (nz) item_erank[n] = rank;
             }
-            if ((w0 >> 32) != tag || (w1 >> 32) != tag || !lengths_plausible(w0, w1)) { bad = 1; break; }
-            a1 += static_cast<int>(w0 & 0xFFFFFFFFull);
-            a2 += static_cast<int>(w1 & 0x1FFFFull);
-            a0 += static_cast<int>((w1 >> 17) & 0x7FFFull);
         }
+    }
+
+    {
+        int a0 = 0, a1 = 0, a2 = 0, bad = 0;
+        if (polls) {
+            for (int spin = 0; ((w0 >> 32) != tag || (w1 >> 32) != tag) && spin < kSpinLimit; ++spin) {
+                __builtin_amdgcn_s_sleep(8);
+                w0 = peek(flags + 2 * tid);
+                w1 = peek(flags + 2 * tid + 1);
+            }
+            if ((w0 >> 32) != tag || (w1 >> 32) != tag || !lengths_plausible(w0, w1)) bad = 1;
+            else {
+                a1 = static_cast<int>(w0 & 0xFFFFFFFFull);
+                a2 = static_cast<int>(w1 & 0x1FFFFull);
+                a0 = static_cast<int>((w1 >> 17) & 0x7FFFull);
+            }
+        }
+        if (kMode == kPublished)
+            for (int cc = tid; cc < c; cc += kThreads) {
+                const unsigned long long p0 = flags[2 * cc], p1 = flags[2 * cc + 1];
+                if ((p0 >> 32) != tag || (p1 >> 32) != tag || !lengths_plausible(p0, p1)) { bad = 1; break; }
+                a1 += static_cast<int>(p0 & 0xFFFFFFFFull);
+                a2 += static_cast<int>(p1 & 0x1FFFFull);
+                a0 += static_cast<int>((p1 >> 17) & 0x7FFFull);
+            }
         a0 = wave_sum(a0); a1 = wave_sum(a1); a2 = wave_sum(a2); bad = wave_sum(bad);
         if (lane == 0 && (a0 | a1 | a2 | bad) != 0) {
             atomicAdd(&chan_base[0], a0);
@@ -1126,33 +1177,17 @@ __global__ __launch_bounds__(kThreads) void encode_channel64_kernel(const Geomet
         }
     }
 
-    // ---- scatter DA and IN: columns wave, wave + 8, .. ; lane = padded row -----------------------------
-    const int hr = lane - g.pad_h;
-    const bool row_ok = hr >= 0 && hr < g.H;
-    const unsigned long long below = (1ull << lane) - 1ull;
-#pragma unroll 2
-    for (int vi = wave; vi < g.n_cols; vi += kWaves) {
-        const int jr = __builtin_amdgcn_readlane(my_jr, vi);
-        const int da_at = da_off + __builtin_amdgcn_readlane(excl, vi), in_at = in_off + __builtin_amdgcn_readlane(eexcl, vi);
-        const float v = row_ok ? tile[hr * Wt + jr] : 0.0f;
-        const bool nz = is_nze(v);
-        const unsigned long long mask = __ballot(nz);
-        const int rank = __popcll(mask & below);
-        const int index = static_cast<int>(g.col_what[vi]) + lane * g.kw;
-        if (nz) map.da[da_at + rank] = v;
-        if (nz && full != nullptr) full[da_at + rank] = static_cast<int16_t>(index);
-        if (vi >= top_begin && vi < top_end) {
-            // set4 of Algorithm 3: the four padded rows 4*(h/4) .. +3
-            const int pattern = static_cast<int>((mask >> (lane & ~3)) & 0xFull);
-            const int r = __popc(pattern & ((1 << (lane & 3)) - 1));   // rank inside the set
-            const bool emit = nz && r < 2;
-            const int erank = __popcll(__ballot(emit) & below);
-            // first NZE of the set: its index (negated unless a pattern follows);
-            // second NZE: the pattern, or its own negated index
-            const int entry = __popc(pattern) >= 3 ? (r == 0 ? index : pattern) : -index;
-            if (emit) store_index(map.in, in_at + erank, entry, in16);
-        } else {
-            if (nz) store_index(map.in, in_at + rank, index, in16);
+    // ---- scatter DA and IN from the prepared items ------------------------------------------------------
+#pragma unroll
+    for (int n = 0; n < kColsPerWave; ++n) {
+        const int vi = wave + n * kWaves;
+        if (vi < g.n_cols) {
+            const int da_at = da_off + __builtin_amdgcn_readlane(excl, vi), in_at = in_off + __builtin_amdgcn_readlane(eexcl, vi);
+            const bool nz = is_nze(item_v[n]);
+            if (nz) map.da[da_at + item_rank[n]] = item_v[n];
+            if (nz && full != nullptr)
+                full[da_at + item_rank[n]] = static_cast<int16_t>(static_cast<int>(g.col_what[vi]) + lane * g.kw);
+            if (item_erank[n] >= 0) store_index(map.in, in_at + item_erank[n], item_entry[n], in16);
         }
     }
 }
@@ -1647,6 +1682,7 @@ int launch_encode(const float *act, const Producer &prod, const Geometry &g, con
                                ? reinterpret_cast<ColumnEntry *>(static_cast<char *>(scratch) + scratch_columns_offset(g))
                                : nullptr;
     const int64_t cstride = columns_stride(g);
+    if (columns != nullptr) mtab = nullptr;   // the column-run convolution reads the column table only
 
     unsigned long long *ctrl = static_cast<unsigned long long *>(scratch);
     const bool single = channels_single_pass(g);
