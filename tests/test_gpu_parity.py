@@ -160,6 +160,9 @@ EDGE_SHAPES = [
     (40, 30, 29, 70, 3, 3, 1, 1),     # several channel slices, ragged tiles
     (33, 21, 37, 4, 3, 3, 1, 0),      # VALID padding in the register-tile kernel
     (520, 5, 6, 3, 3, 3, 1, 1),       # more channels than the encoder's single-launch look-back takes
+    (520, 40, 38, 3, 3, 3, 1, 1),     # the same on a map the workgroup-per-channel encoder takes: its two-launch form
+    (24, 62, 60, 130, 3, 3, 1, 1),    # 64 padded rows: the column-run kernel's bitmaps full to the last bit
+    (130, 28, 28, 128, 3, 3, 1, 1),   # column-run kernel with channel slices and the slice sum
     (5, 15, 17, 70, 3, 3, 2, 1),      # strip kernel, stride 2, two kernels per lane, ragged
     (3, 17, 17, 70, 7, 1, 1, 0),      # 7 x 1 kernel: the K_w = 1 special case of the SI
     (6, 8, 8, 5, 3, 1, 1, 0),         # 3 x 1
@@ -322,6 +325,8 @@ BATCH_CASES = [
     # launch and (more than 512 channels) in two
     (3, (400, 20, 22, 3, 3, 3, 1, 1)),
     (2, (600, 19, 37, 2, 3, 3, 1, 0)),
+    (130, (3, 40, 38, 4, 3, 3, 1, 1)),            # more images than one launch's look-back slots: two launches
+    (3, (24, 30, 30, 70, 3, 3, 1, 1)),            # three images through the column-run kernel
     # several images of small 3 x 3 maps: strips of two or four tiles per workgroup, stride 1 and 2,
     # one and two kernels per lane
     (4, (40, 14, 14, 128, 3, 3, 1, 1)),
