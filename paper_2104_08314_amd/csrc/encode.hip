@@ -893,7 +893,7 @@ __global__ __launch_bounds__(kThreads) void encode_channel_kernel(const Geometry
 // are written by the wavefront whose number the overlap type has (mod 8).
 // ---------------------------------------------------------------------------------------------
 template <int kMode>
-__global__ __launch_bounds__(kThreads) void encode_channel64_kernel(const Geometry g, const float *__restrict__ act_all,
+__global__ __launch_bounds__(kThreads, 8) void encode_channel64_kernel(const Geometry g, const float *__restrict__ act_all,
                                                                    const Producer prod, const int cps,
                                                                    unsigned long long *__restrict__ ctrl,
                                                                    unsigned long long *__restrict__ flags_all,
