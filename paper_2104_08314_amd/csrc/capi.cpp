@@ -165,7 +165,7 @@ int64_t scratch_mtab_bytes(const Geometry &g) { return (4 * mtab_stride(g) * g.N
 int64_t scratch_columns_offset(const Geometry &g)
 {
     const int64_t partial = std::max(std::max(tile_kernel_partial_bytes(g), strip_kernel_partial_bytes(g)),
-                                     runs_kernel_partial_bytes(g));
+                                     std::max(runs_kernel_partial_bytes(g), lds_kernel_partial_bytes(g)));
     return scratch_counts_bytes(g) + scratch_mtab_bytes(g) + scratch_indices_bytes(g) + (partial + 255) / 256 * 256;
 }
 

@@ -152,6 +152,7 @@ int launch_sparse_conv(const cpoconv_map &map, const Geometry &g, int algo, cons
                        float *out, void *scratch, hipStream_t stream, bool table_ready = false,
                        bool indices_ready = false, bool columns_ready = false);
 bool sparse_conv_uses_prologue(const Geometry &g);
+int64_t lds_kernel_partial_bytes(const Geometry &g);   // general kernel (spmv_conv.hip)
 // register-tile SpMV kernel (spmv_conv_tile.hip)
 bool tile_kernel_supports(const Geometry &g);
 int64_t tile_kernel_partial_bytes(const Geometry &g);

@@ -159,7 +159,9 @@ __global__ __launch_bounds__(kExpThreads) void conv_prologue_kernel(const Geomet
 // ---------------------------------------------------------------------------------------
 // General SpMV convolution (any kh, kw, stride): accumulators of a TY x TX output tile for 64
 // kernels live in LDS, [row][col][k] with k fastest (conflict-free).  Wavefront w of the
-// workgroup owns the tile rows w*RW .. w*RW+RW-1.
+// workgroup owns the tile rows w*RW .. w*RW+RW-1.  Where the tiles alone leave compute units
+// idle the input channels are cut into slices across workgroups; the slices' sums go to
+// partial[slice][y][x][k] and reduce_transpose_kernel adds them in a fixed order.
 // ---------------------------------------------------------------------------------------
 constexpr int kConvThreads = 256;
 constexpr int kConvWaves = kConvThreads / kLanes;
@@ -172,11 +174,16 @@ __global__ __launch_bounds__(kConvThreads) void spmv_conv_lds_kernel(const Geome
                                                                     const int32_t *__restrict__ in_all,
                                                                     const int32_t *__restrict__ chan_off_all,
                                                                     const float *__restrict__ wt,
-                                                                    float *__restrict__ out_all, const BatchStrides bs)
+                                                                    float *__restrict__ out_all,
+                                                                    float *__restrict__ partial_all, const int slices,
+                                                                    const BatchStrides bs)
 {
     const int ngroups = g.Kpad / kLanes;
-    const int image = blockIdx.z / ngroups;
+    const int slice = (blockIdx.z / ngroups) % slices;
+    const int image = blockIdx.z / (ngroups * slices);
     if (map_unusable(bs, image)) return;
+    const int per_slice = (g.C + slices - 1) / slices;
+    const int c_begin = slice * per_slice, c_end = min(g.C, c_begin + per_slice);
     const int32_t *__restrict__ ptr = ptr_all + image * bs.ptr;
     const float *__restrict__ da = da_all + image * bs.da;
     const int32_t *__restrict__ in = index_advance(in_all, image * bs.indices, bs.indices16);
@@ -198,7 +205,7 @@ __global__ __launch_bounds__(kConvThreads) void spmv_conv_lds_kernel(const Geome
     for (int i = tid; i < kTY * kTX * kLanes; i += kConvThreads) acc[i] = 0.0f;
     __syncthreads();
 
-    for (int c = 0; c < g.C; ++c) {
+    for (int c = c_begin; c < c_end; ++c) {
         const int pbase = chan_off[c];
         if (ptr[pbase] == CPOCONV_NPC) continue;       // skip channel (uniform)
         __syncthreads();                                 // previous channel done with wl / Mtab
@@ -284,11 +291,32 @@ __global__ __launch_bounds__(kConvThreads) void spmv_conv_lds_kernel(const Geome
     }
     // each wavefront stores its own rows
     const int k = k0 + lane;
-    if (k < g.K)
+    if (slices > 1) {
+        // partial sums of this channel slice, kernel index fastest; rows and columns past the map's edge hold zeros
+        const int Ypad = gridDim.y * kTY, Xpad = gridDim.x * kTX;
+        float *partial = partial_all + image * bs.partial;
+        for (int y = ylo; y < min(ylo + kRW, y0 + kTY); ++y)
+            for (int x = 0; x < kTX; ++x)
+                partial[((static_cast<int64_t>(slice) * Ypad + y) * Xpad + x0 + x) * g.Kpad + k] =
+                    acc[((y - y0) * kTX + x) * kLanes + lane];
+    } else if (k < g.K) {
         for (int y = ylo; y < yhi; ++y)
             for (int x = 0; x < kTX && x0 + x < g.Ow; ++x)
                 out[(static_cast<int64_t>(k) * g.Oh + y) * g.Ow + x0 + x] = acc[((y - y0) * kTX + x) * kLanes + lane];
+    }
 }
+
+// Channel slices of the general kernel: about 512 workgroups per launch, at least four channels a slice.
+static int lds_kernel_slices(const Geometry &g)
+{
+    const int64_t tiles = static_cast<int64_t>((g.Ow + kTX - 1) / kTX) * ((g.Oh + kTY - 1) / kTY) * (g.Kpad / kLanes) * g.N;
+    int s = static_cast<int>(std::min<int64_t>(16, 512 / std::max<int64_t>(tiles, 1)));
+    s = std::min(s, g.C / 4);
+    s = std::max(s, 1);
+    const int per_slice = (g.C + s - 1) / s;
+    return (g.C + per_slice - 1) / per_slice;
+}
+
 
 // The table of conv_prologue_kernel for layers whose ptr segments of one channel fit a wavefront's
 // stage (resolve_in_kernel_ok): one wavefront per channel, the channel's ptr entries loaded at
@@ -370,6 +398,14 @@ __global__ __launch_bounds__(256) void reduce_transpose_kernel(const Geometry g,
 
 }  // namespace
 
+int64_t lds_kernel_partial_bytes(const Geometry &g)
+{
+    const int s = lds_kernel_slices(g);
+    if (s == 1) return 0;
+    const int64_t Ypad = (g.Oh + kTY - 1) / kTY * kTY, Xpad = (g.Ow + kTX - 1) / kTX * kTX;
+    return 4 * Ypad * Xpad * g.Kpad * s * g.N;
+}
+
 int launch_reduce_transpose(const Geometry &g, const float *partial, int slices, int Ypad, int Xpad, float *out,
                             const BatchStrides &bs, hipStream_t stream)
 {
@@ -446,14 +482,18 @@ int launch_sparse_conv(const cpoconv_map &map, const Geometry &g, int algo, cons
     }
     if (strip) return launch_sparse_conv_strip(map, indices, mtab, g, wt, out, partial, bs, stream);
     if (tile) return launch_sparse_conv_tile(map, indices, mtab, g, wt, out, partial, bs, stream);
-    const dim3 grid((g.Ow + kTX - 1) / kTX, (g.Oh + kTY - 1) / kTY, (g.Kpad / kLanes) * g.N);
+    const int slices = lds_kernel_slices(g);
+    const dim3 grid((g.Ow + kTX - 1) / kTX, (g.Oh + kTY - 1) / kTY, (g.Kpad / kLanes) * slices * g.N);
     const size_t lds = (static_cast<size_t>(kTY) * kTX + static_cast<size_t>(g.kh) * g.kw) * kLanes * sizeof(float);
+    const int Ypad = grid.y * kTY, Xpad = grid.x * kTX;
+    bs.partial = static_cast<int64_t>(slices) * Ypad * Xpad * g.Kpad;
     {
         KernelTimer timer("spmv_conv_lds", stream);
         hipLaunchKernelGGL(spmv_conv_lds_kernel, grid, dim3(kConvThreads), lds, stream, g, map.ptr, map.da, indices,
-                           map.chan_off, wt, out, bs);
+                           map.chan_off, wt, out, partial, slices, bs);
     }
     CPOCONV_HIP_TRY(hipGetLastError());
+    if (slices > 1) return launch_reduce_transpose(g, partial, slices, Ypad, Xpad, out, bs, stream);
     return CPOCONV_OK;
 }
 

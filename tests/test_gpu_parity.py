@@ -163,6 +163,10 @@ EDGE_SHAPES = [
     (520, 40, 38, 3, 3, 3, 1, 1),     # the same on a map the workgroup-per-channel encoder takes: its two-launch form
     (24, 62, 60, 130, 3, 3, 1, 1),    # 64 padded rows: the column-run kernel's bitmaps full to the last bit
     (130, 28, 28, 128, 3, 3, 1, 1),   # column-run kernel with channel slices and the slice sum
+    # shapes without an instantiation of the fast kernels: the general kernel, with channel slices
+    (40, 20, 20, 70, 4, 4, 1, 1),
+    (33, 19, 19, 5, 5, 5, 2, 2),
+    (24, 15, 15, 66, 7, 7, 1, 3),
     (5, 15, 17, 70, 3, 3, 2, 1),      # strip kernel, stride 2, two kernels per lane, ragged
     (3, 17, 17, 70, 7, 1, 1, 0),      # 7 x 1 kernel: the K_w = 1 special case of the SI
     (6, 8, 8, 5, 3, 1, 1, 0),         # 3 x 1
@@ -327,6 +331,7 @@ BATCH_CASES = [
     (2, (600, 19, 37, 2, 3, 3, 1, 0)),
     (130, (3, 40, 38, 4, 3, 3, 1, 1)),            # more images than one launch's look-back slots: two launches
     (3, (24, 30, 30, 70, 3, 3, 1, 1)),            # three images through the column-run kernel
+    (3, (20, 12, 13, 70, 4, 4, 1, 1)),            # the general kernel with channel slices, three images
     # several images of small 3 x 3 maps: strips of two or four tiles per workgroup, stride 1 and 2,
     # one and two kernels per lane
     (4, (40, 14, 14, 128, 3, 3, 1, 1)),
