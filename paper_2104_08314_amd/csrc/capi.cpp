@@ -350,10 +350,11 @@ static int encode_conv_common(const float *act, const cpoconv_shape *shape, int 
     // the encoder also leaves the table of resolved ptr offsets: the convolution needs no prologue
     // of its own; for a CPS map it also leaves there the plain index of every NZE (16 bits each: what
     // Algorithm 4 rebuilds from the packed IN stream, which the map itself holds as after cps_encode)
-    // (not where the column-run convolution follows: the encoder's column table is all it reads)
+    // (not where the column-run convolution follows: the column table is all it reads, and where the
+    // encoder does not leave it, it is rebuilt from the packed stream itself)
     const bool table = sparse_conv_uses_prologue(g);
     const bool columns = table && encode_writes_columns(g);
-    const bool indices = algo == CPOCONV_ALGO_CPS && g.top_slot >= 0 && !columns;
+    const bool indices = algo == CPOCONV_ALGO_CPS && g.top_slot >= 0 && !runs_kernel_preferred(g);
     const int erc = launch_encode(act, prod, g, *map, algo, scratch, st, table, indices);
     if (erc != CPOCONV_OK) return erc;
     return launch_sparse_conv(*map, g, algo, wt, out, scratch, st, table, indices, columns);

@@ -169,8 +169,8 @@ bool runs_kernel_supports(const Geometry &g);
 bool runs_kernel_preferred(const Geometry &g);
 int64_t runs_kernel_partial_bytes(const Geometry &g);
 int64_t runs_kernel_columns_bytes(const Geometry &g);
-int launch_column_table(const cpoconv_map &map, const int32_t *indices, const int32_t *mtab, ColumnEntry *columns,
-                        const Geometry &g, const BatchStrides &bs, hipStream_t stream);
+int launch_column_table(const cpoconv_map &map, const int32_t *mtab, ColumnEntry *columns, const Geometry &g, BatchStrides bs,
+                        bool cps, hipStream_t stream);
 int launch_sparse_conv_runs(const cpoconv_map &map, const ColumnEntry *columns, const Geometry &g, const float *wt, float *out,
                             float *partial, BatchStrides bs, hipStream_t stream);
 // byte offsets of the regions of the caller's scratch buffer

@@ -460,9 +460,16 @@ int launch_sparse_conv(const cpoconv_map &map, const Geometry &g, int algo, cons
     ColumnEntry *columns = reinterpret_cast<ColumnEntry *>(base + scratch_columns_offset(g));
     float *partial = reinterpret_cast<float *>(base + after_mtab + scratch_indices_bytes(g));
     if (runs && columns_ready) return launch_sparse_conv_runs(map, columns, g, wt, out, partial, bs, stream);
+    if (runs) {
+        // the column table from ptr and IN (a CPS map's packed stream is decoded there), then the
+        // convolution: nothing is written per NZE
+        const int rc = launch_column_table(map, table_ready ? mtab : static_cast<const int32_t *>(nullptr), columns, g, bs,
+                                           in_full != nullptr, stream);
+        if (rc != CPOCONV_OK) return rc;
+        return launch_sparse_conv_runs(map, columns, g, wt, out, partial, bs, stream);
+    }
     const bool expand = in_full != nullptr && !indices_ready;
-    // ... as does the kernel that builds the column table in front of the column-run kernel
-    const bool in_kernel = (strip || runs) && !expand && !table_ready && resolve_in_kernel_ok(g);
+    const bool in_kernel = strip && !expand && !table_ready && resolve_in_kernel_ok(g);
     if (in_kernel) mtab = nullptr;
     if ((tile && !in_kernel && !table_ready) || expand) {
         KernelTimer timer("conv_prologue", stream);
@@ -473,12 +480,6 @@ int launch_sparse_conv(const cpoconv_map &map, const Geometry &g, int algo, cons
             hipLaunchKernelGGL(conv_prologue_kernel, dim3(g.C, g.N), dim3(kExpThreads), 0, stream, g, map.ptr, map.in,
                                map.chan_off, mtab, expand ? in_full : static_cast<int32_t *>(nullptr), bs);
         CPOCONV_HIP_TRY(hipGetLastError());
-    }
-    if (runs) {
-        // the column table from the resolved offsets and the plain indices, then the convolution
-        const int rc = launch_column_table(map, indices, mtab, columns, g, bs, stream);
-        if (rc != CPOCONV_OK) return rc;
-        return launch_sparse_conv_runs(map, columns, g, wt, out, partial, bs, stream);
     }
     if (strip) return launch_sparse_conv_strip(map, indices, mtab, g, wt, out, partial, bs, stream);
     if (tile) return launch_sparse_conv_tile(map, indices, mtab, g, wt, out, partial, bs, stream);

@@ -246,6 +246,18 @@ __global__ __launch_bounds__(NW *kLanes) void spmv_conv_runs_kernel(
     }
 }
 
+// inclusive running sum over the 64 lanes (same moves as wave_running_max)
+__device__ __forceinline__ int wave_running_sum(int v)
+{
+    v += __builtin_amdgcn_update_dpp(0, v, 0x111, 0xf, 0xf, false);   // row_shr:1
+    v += __builtin_amdgcn_update_dpp(0, v, 0x112, 0xf, 0xf, false);   // row_shr:2
+    v += __builtin_amdgcn_update_dpp(0, v, 0x114, 0xf, 0xf, false);   // row_shr:4
+    v += __builtin_amdgcn_update_dpp(0, v, 0x118, 0xf, 0xf, false);   // row_shr:8
+    v += __builtin_amdgcn_update_dpp(0, v, 0x142, 0xa, 0xf, false);   // row_bcast:15 -> rows 1, 3
+    v += __builtin_amdgcn_update_dpp(0, v, 0x143, 0xc, 0xf, false);   // row_bcast:31 -> rows 2, 3
+    return v;
+}
+
 // The table of column entries rebuilt from the streams, for a convolution whose encoder ran in an
 // earlier call: one workgroup per (channel, image).  First the channel's ptr segments become
 // absolute DA offsets after every partition (Algorithm 2's forward fill, a running maximum: one
@@ -253,29 +265,51 @@ __global__ __launch_bounds__(NW *kLanes) void spmv_conv_runs_kernel(
 // kernel before this one has left it).  Then one wavefront per stream column in turn: the column's
 // run is delimited by entries p0 and p0 + 1 of its type's row; every lane takes one NZE of the run,
 // its index / kw is the padded row, and the rows are or-ed into the bitmap through LDS.
-constexpr int kTableThreads = 256;
+//
+// A CPS map (cps_top = slot of the overlap-kw type, else -1) is decoded here, straight from the
+// packed stream: below the top type IN_cps holds one plain index per NZE, at the channel's IN
+// offset plus the NZE's rank in the channel; the top type's entries are parsed as Algorithm 4 reads
+// them, in parallel: an entry < 0 is a single NZE with the index negated; a run of entries >= 0
+// alternates {index of the set's first NZE, pattern}, so an entry's role is the parity of its
+// distance to the last negative entry before it (a running maximum), and the NZE an entry starts
+// at is the running sum of the NZEs of the entries before it.  The pattern's bits from its first
+// set bit up are the rows of the set's NZEs from the first one's row up; the column is the
+// partition whose DA range holds the entry's first NZE (a search over the resolved offsets).
+// Nothing is written per NZE.
+constexpr int kTableThreads = 1024;                       // at most; the launch sizes the workgroup to the map
+constexpr int kTableWaves = kTableThreads / kLanes;
 
 __global__ __launch_bounds__(kTableThreads) void column_table_kernel(const Geometry g, const int32_t *__restrict__ ptr_all,
                                                                     const int32_t *__restrict__ chan_off_all,
                                                                     const int32_t *__restrict__ indices_all,
                                                                     const int32_t *__restrict__ mtab_all,
-                                                                    ColumnEntry *__restrict__ columns_all, const BatchStrides bs)
+                                                                    ColumnEntry *__restrict__ columns_all, const BatchStrides bs,
+                                                                    const int cps_top)
 {
     __shared__ unsigned long long rows[kMaxCols];
     __shared__ int32_t offsets[kMaxTypes][kLanes + 1];   // Ow <= 62 for the maps taken here
+    __shared__ int32_t run_begin[kMaxCols];              // start of every padded column's run in DA (count = set bits)
+    __shared__ int32_t top_col[kLanes];                  // CPS: padded column of every partition of the top type
+    __shared__ int32_t wave_neg[kTableWaves], wave_out[kTableWaves];
     const int c = blockIdx.x, image = blockIdx.y;
     if (map_unusable(bs, image)) return;
     const int lane = lane_id(), wave = threadIdx.x / kLanes;
+    const int nthreads = blockDim.x, nwaves = nthreads / kLanes;
     const int32_t *indices = index_advance(indices_all, image * bs.indices, bs.indices16);
+    const int32_t *chan_off = chan_off_all + static_cast<int64_t>(image) * 3 * (g.C + 1);
     ColumnEntry *out = columns_all + image * bs.columns + static_cast<int64_t>(c) * g.Iw;
-    for (int j = threadIdx.x; j < g.Iw; j += kTableThreads) rows[j] = 0ull;
+    // CPS: IN entry of a lower-type NZE = the channel's IN offset + the NZE's rank in the channel
+    const int da0 = chan_off[(g.C + 1) + c];
+    const int in_shift = cps_top >= 0 ? chan_off[2 * (g.C + 1) + c] - da0 : 0;
+    const int in_end = cps_top >= 0 ? chan_off[2 * (g.C + 1) + c + 1] : 0;
+    for (int j = threadIdx.x; j < g.Iw; j += nthreads) { rows[j] = 0ull; run_begin[j] = 0; }
+    if (threadIdx.x < kLanes) top_col[threadIdx.x] = 0;
     if (mtab_all != nullptr) {
         const int32_t *table = mtab_all + image * bs.mtab + static_cast<int64_t>(c) * g.n_types * (g.Ow + 1);
-        for (int n = threadIdx.x; n < g.n_types * (g.Ow + 1); n += kTableThreads)
+        for (int n = threadIdx.x; n < g.n_types * (g.Ow + 1); n += nthreads)
             offsets[n / (g.Ow + 1)][n % (g.Ow + 1)] = table[n];
     } else if (wave == 0) {
         const int32_t *ptr = ptr_all + image * bs.ptr;
-        const int32_t *chan_off = chan_off_all + static_cast<int64_t>(image) * 3 * (g.C + 1);
         int seg = chan_off[c], at = chan_off[(g.C + 1) + c];
         const bool npc = ptr[seg] == CPOCONV_NPC;
         for (int i = 0; i < g.n_types; ++i) {
@@ -295,22 +329,79 @@ __global__ __launch_bounds__(kTableThreads) void column_table_kernel(const Geome
     }
     __syncthreads();
     for (int i = 0; i < g.n_types; ++i) {
-        for (int vi = g.type_begin[i] + wave; vi < g.type_begin[i + 1]; vi += kTableThreads / kLanes) {
+        for (int vi = g.type_begin[i] + wave; vi < g.type_begin[i + 1]; vi += nwaves) {
             const int p0 = g.col_p0[vi], j = g.col_j[vi];
             const int begin = offsets[i][p0], end = offsets[i][p0 + 1];
-            if (lane < end - begin) {
-                const int index = load_index(indices, begin + lane, bs.indices16);
+            if (lane == 0) run_begin[j] = begin;
+            if (i == cps_top) {
+                if (lane == 0) top_col[p0] = j;
+            } else if (lane < end - begin) {
+                const int index = load_index(indices, begin + lane + in_shift, bs.indices16);
                 atomicOr(&rows[j], 1ull << (index / g.kw));
             }
-            if (lane == 0) { out[j].begin = begin; out[j].count = end - begin; }
+        }
+    }
+    if (cps_top >= 0) {
+        __syncthreads();   // top_col complete
+        const int32_t *bound = offsets[cps_top];
+        const int top_base = bound[0];
+        const int e0 = top_base + in_shift;                           // first IN entry of the top type
+        const int n_entries = in_end - e0;                            // the top type closes the channel
+        int carry_neg = -1;   // position (from e0) of the last negative entry so far
+        int carry_out = 0;    // NZEs of the entries so far
+        // a lane's entry and the one behind it (the pattern, if the lane's entry leads a pair); the
+        // next round's are in flight while this round's are parsed
+        auto fetch = [&](int e, int &entry, int &after) {
+            entry = e < n_entries ? load_index(indices, e0 + e, bs.indices16) : -1;
+            after = e + 1 < n_entries ? load_index(indices, e0 + e + 1, bs.indices16) : 0;
+        };
+        int entry_next, after_next;
+        fetch(threadIdx.x, entry_next, after_next);
+        for (int first = 0; first < n_entries; first += nthreads) {
+            const int e = first + threadIdx.x;
+            const bool valid = e < n_entries;
+            const int entry = entry_next, after = after_next;
+            if (first + nthreads < n_entries) fetch(e + nthreads, entry_next, after_next);
+            const int m = wave_running_max(entry < 0 ? e : -1);
+            if (lane == kLanes - 1) wave_neg[wave] = m;
+            __syncthreads();
+            int before_neg = carry_neg;
+            for (int w = 0; w < wave; ++w) before_neg = max(before_neg, wave_neg[w]);
+            const int last_neg = max(m, before_neg);
+            const bool leads = valid && entry >= 0 && ((e - last_neg - 1) & 1) == 0;   // the index of a {index, pattern} pair
+            const int pattern = leads ? after : 0;
+            const int emits = !valid ? 0 : (entry < 0 ? 1 : (leads ? __popc(pattern) : 0));
+            const int s = wave_running_sum(emits);
+            if (lane == kLanes - 1) wave_out[wave] = s;
+            __syncthreads();
+            int before_out = carry_out;
+            for (int w = 0; w < wave; ++w) before_out += wave_out[w];
+            if (emits > 0) {
+                const int at = top_base + before_out + s - emits;   // DA position of the entry's first NZE
+                int lo = 0, hi = g.Ow - 1;                          // smallest partition whose range ends past it
+                while (lo < hi) {
+                    const int mid = (lo + hi) >> 1;
+                    if (bound[mid + 1] > at) hi = mid; else lo = mid + 1;
+                }
+                const int index = entry < 0 ? -entry : entry;
+                const unsigned long long set = entry < 0 ? 1ull : static_cast<unsigned long long>(pattern >> (__ffs(pattern) - 1));
+                atomicOr(&rows[top_col[lo]], set << (index / g.kw));
+            }
+            int all_neg = carry_neg, all_out = carry_out;
+            for (int w = 0; w < nwaves; ++w) { all_neg = max(all_neg, wave_neg[w]); all_out += wave_out[w]; }
+            carry_neg = all_neg;
+            carry_out = all_out;
+            __syncthreads();   // wave_neg / wave_out free for the next round
         }
     }
     __syncthreads();
-    for (int j = threadIdx.x; j < g.Iw; j += kTableThreads) {
-        const bool real = j >= g.pad_w && j < g.pad_w + g.W;
-        if (!real) { out[j].begin = 0; out[j].count = 0; }
-        out[j].rows_lo = static_cast<uint32_t>(rows[j]);
-        out[j].rows_hi = static_cast<uint32_t>(rows[j] >> 32);
+    for (int j = threadIdx.x; j < g.Iw; j += nthreads) {   // padding columns: no run, no rows
+        ColumnEntry entry;
+        entry.begin = run_begin[j];
+        entry.count = __popcll(rows[j]);
+        entry.rows_lo = static_cast<uint32_t>(rows[j]);
+        entry.rows_hi = static_cast<uint32_t>(rows[j] >> 32);
+        out[j] = entry;
     }
 }
 
@@ -364,11 +455,11 @@ int launch_runs(const cpoconv_map &map, const ColumnEntry *columns, const Geomet
 }  // namespace
 
 // Shapes the kernel is instantiated for, maps of at most 64 padded rows (a column's rows are one
-// 64-bit bitmap), and geometries with one new column per overlap type and partition (a stride that
+// 64-bit bitmap) and 64 partitions (one lane per partition where the table is rebuilt), and geometries with one new column per overlap type and partition (a stride that
 // does not divide the padded width leaves a last column that shares its partition with another).
 bool runs_kernel_supports(const Geometry &g)
 {
-    if (g.n_types < 1 || g.Ih > kLanes) return false;
+    if (g.n_types < 1 || g.Ih > kLanes || g.Ow > kLanes) return false;
     if (!(g.kh == 3 && g.kw == 3 && g.stride == 1)) return false;
     for (int i = 0; i < g.n_types; ++i)
         for (int n = g.type_begin[i] + 1; n < g.type_begin[i + 1]; ++n)
@@ -406,12 +497,17 @@ int64_t runs_kernel_columns_bytes(const Geometry &g)
 
 // mtab: the table of resolved ptr offsets if a kernel before this one has left it, else nullptr
 // (then the kernel resolves ptr itself)
-int launch_column_table(const cpoconv_map &map, const int32_t *indices, const int32_t *mtab, ColumnEntry *columns,
-                        const Geometry &g, const BatchStrides &bs, hipStream_t stream)
+// cps: the map's IN stream is the packed one of Algorithm 3 (decoded in the kernel)
+int launch_column_table(const cpoconv_map &map, const int32_t *mtab, ColumnEntry *columns, const Geometry &g, BatchStrides bs,
+                        bool cps, hipStream_t stream)
 {
+    bs.indices = map.in_cap;
+    bs.indices16 = bs.map_in16;
+    // a lane per packed entry / a wavefront per column: enough wavefronts for one or two rounds
+    const int threads = std::min(kTableThreads, std::max(256, (g.H * g.W / 2 + kLanes - 1) / kLanes * kLanes));
     KernelTimer timer("column_table", stream);
-    hipLaunchKernelGGL(column_table_kernel, dim3(g.C, g.N), dim3(kTableThreads), 0, stream, g, map.ptr, map.chan_off, indices,
-                       mtab, columns, bs);
+    hipLaunchKernelGGL(column_table_kernel, dim3(g.C, g.N), dim3(threads), 0, stream, g, map.ptr, map.chan_off, map.in,
+                       mtab, columns, bs, cps ? g.top_slot : -1);
     CPOCONV_HIP_TRY(hipGetLastError());
     return CPOCONV_OK;
 }
