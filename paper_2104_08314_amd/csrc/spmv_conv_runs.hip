@@ -172,7 +172,18 @@ __global__ __launch_bounds__(NW *kLanes) void spmv_conv_runs_kernel(
             for (int k = 0; k < 4; ++k) e[q][k] = at[k];
         }
     };
-    auto load_set = [&](int c, const int (&e)[RW][4], Set &cs) {
+    auto load_weights = [&](int c, Set &cs) {
+        const float *wc = wt + static_cast<int64_t>(min(c, g.C - 1)) * TAPS * g.Kpad + kbase;
+#pragma unroll
+        for (int tp = 0; tp < TAPS; ++tp) {
+            typedef typename WeightVec<KPL>::type Vec;
+            const Vec v = *reinterpret_cast<const Vec *>(reinterpret_cast<const char *>(wc + tp * g.Kpad) + lane_w);
+            const float *f = reinterpret_cast<const float *>(&v);
+#pragma unroll
+            for (int kk = 0; kk < KPL; ++kk) cs.w[tp][kk] = f[kk];
+        }
+    };
+    auto load_values = [&](int c, const int (&e)[RW][4], Set &cs) {
         unsigned mine = 0;      // this lane's column: its window bits and where the window's NZEs start in DA
         int first = 0;
 #pragma unroll
@@ -187,15 +198,11 @@ __global__ __launch_bounds__(NW *kLanes) void spmv_conv_runs_kernel(
         const bool has = (mine >> my_r) & 1u;     // lanes of rows past RH and columns past RW see no bit
         const int at = first + __popc(mine & below_mine);
         cs.values = has ? da[at] : 0.0f;
-        const float *wc = wt + static_cast<int64_t>(min(c, g.C - 1)) * TAPS * g.Kpad + kbase;
-#pragma unroll
-        for (int tp = 0; tp < TAPS; ++tp) {
-            typedef typename WeightVec<KPL>::type Vec;
-            const Vec v = *reinterpret_cast<const Vec *>(reinterpret_cast<const char *>(wc + tp * g.Kpad) + lane_w);
-            const float *f = reinterpret_cast<const float *>(&v);
-#pragma unroll
-            for (int kk = 0; kk < KPL; ++kk) cs.w[tp][kk] = f[kk];
-        }
+    };
+    // values first: the weights are then the youngest loads of the set (see apply)
+    auto load_set = [&](int c, const int (&e)[RW][4], Set &cs) {
+        load_values(c, e, cs);
+        if (c < c_end) load_weights(c, cs);   // (wavefront-uniform) past the last channel the walk finds no bit set
     };
     auto apply = [&](Set &cs) {
         // The weights are the youngest loads of the set and loads complete in order: one wait on
@@ -208,12 +215,13 @@ __global__ __launch_bounds__(NW *kLanes) void spmv_conv_runs_kernel(
     // two register sets in turn: the loads of one channel are in flight while the other is applied,
     // and the table entries are fetched one channel further ahead
     {
-        Set sa, sb;
+        Set sa = {}, sb = {};
         int ea[RW][4], eb[RW][4];
         const int c0 = c_begin + wave;
         load_entries(c0, ea);
         load_entries(c0 + nwaves, eb);
-        load_set(c0, ea, sa);
+        load_weights(c0, sa);    // on their way before the first entries are back
+        load_values(c0, ea, sa);
 #pragma unroll 1
         for (int c = c0; c < c_end; c += 2 * nwaves) {
             load_set(c + nwaves, eb, sb);
@@ -262,9 +270,12 @@ __device__ __forceinline__ int wave_running_sum(int v)
 // earlier call: one workgroup per (channel, image).  First the channel's ptr segments become
 // absolute DA offsets after every partition (Algorithm 2's forward fill, a running maximum: one
 // wavefront, one lane per partition - or they are copied from the table of resolved offsets when a
-// kernel before this one has left it).  Then one wavefront per stream column in turn: the column's
-// run is delimited by entries p0 and p0 + 1 of its type's row; every lane takes one NZE of the run,
-// its index / kw is the padded row, and the rows are or-ed into the bitmap through LDS.
+// kernel before this one has left it).  Then one wavefront per stream column in turn: entries p0 and
+// p0 + 1 of its type's row delimit the NZEs of the column's partition, which holds its columns one
+// after the other (mostly just one; two at the map's edge when the stride is 2); every lane takes
+// one NZE, index / kw is its padded row and index mod kw its column inside the partition: the NZEs
+// of earlier columns give the start of this column's run, the rows of its own are or-ed into the
+// bitmap through LDS.
 //
 // A CPS map (cps_top = slot of the overlap-kw type, else -1) is decoded here, straight from the
 // packed stream: below the top type IN_cps holds one plain index per NZE, at the channel's IN
@@ -330,15 +341,20 @@ __global__ __launch_bounds__(kTableThreads) void column_table_kernel(const Geome
     __syncthreads();
     for (int i = 0; i < g.n_types; ++i) {
         for (int vi = g.type_begin[i] + wave; vi < g.type_begin[i + 1]; vi += nwaves) {
-            const int p0 = g.col_p0[vi], j = g.col_j[vi];
-            const int begin = offsets[i][p0], end = offsets[i][p0 + 1];
-            if (lane == 0) run_begin[j] = begin;
-            if (i == cps_top) {
-                if (lane == 0) top_col[p0] = j;
-            } else if (lane < end - begin) {
-                const int index = load_index(indices, begin + lane + in_shift, bs.indices16);
-                atomicOr(&rows[j], 1ull << (index / g.kw));
+            const int p0 = g.col_p0[vi], j = g.col_j[vi], what = g.col_what[vi];
+            const int begin = offsets[i][p0], end = offsets[i][p0 + 1];   // the partition's NZEs: its columns in turn
+            if (i == cps_top) {   // (one column per partition in this type)
+                if (lane == 0) { run_begin[j] = begin; top_col[p0] = j; }
+                continue;
             }
+            int before = 0;       // NZEs of the partition's columns before this one
+            for (int n0 = begin; n0 < end; n0 += kLanes) {
+                const int index = n0 + lane < end ? load_index(indices, n0 + lane + in_shift, bs.indices16) : -1;
+                const int row = index / g.kw, column = index - row * g.kw;
+                before += __popcll(__ballot(index >= 0 && column < what));
+                if (index >= 0 && column == what) atomicOr(&rows[j], 1ull << row);
+            }
+            if (lane == 0) run_begin[j] = begin + before;
         }
     }
     if (cps_top >= 0) {
@@ -416,7 +432,7 @@ struct RunsPlan {
 RunsPlan runs_plan(const Geometry &g)
 {
     RunsPlan p;
-    p.ty = 4; p.tx = 4;
+    p.ty = p.tx = g.stride == 1 ? 4 : 3;   // the window behind the tile: 6 x 6 / 7 x 7 padded cells
     p.kpl = g.Kpad % 128 == 0 ? 2 : 1;
     const int tiles = ((g.Ow + p.tx - 1) / p.tx) * ((g.Oh + p.ty - 1) / p.ty) * (g.Kpad / (kLanes * p.kpl)) * g.N;
     p.waves = kMaxWaves;
@@ -455,15 +471,14 @@ int launch_runs(const cpoconv_map &map, const ColumnEntry *columns, const Geomet
 }  // namespace
 
 // Shapes the kernel is instantiated for, maps of at most 64 padded rows (a column's rows are one
-// 64-bit bitmap) and 64 partitions (one lane per partition where the table is rebuilt), and geometries with one new column per overlap type and partition (a stride that
-// does not divide the padded width leaves a last column that shares its partition with another).
+// 64-bit bitmap) and 64 partitions (one lane per partition where the table is rebuilt).
 bool runs_kernel_supports(const Geometry &g)
 {
     if (g.n_types < 1 || g.Ih > kLanes || g.Ow > kLanes) return false;
-    if (!(g.kh == 3 && g.kw == 3 && g.stride == 1)) return false;
-    for (int i = 0; i < g.n_types; ++i)
-        for (int n = g.type_begin[i] + 1; n < g.type_begin[i + 1]; ++n)
-            if (g.col_p0[n] == g.col_p0[n - 1]) return false;
+    if (!(g.kh == 3 && g.kw == 3 && (g.stride == 1 || g.stride == 2))) return false;
+    // every column of the map itself lies under some kernel position: then all columns outside the
+    // streams are padding, and the table holds an empty entry for each of them
+    if ((g.Ow - 1) * g.stride + g.kw < g.pad_w + g.W) return false;
     return true;
 }
 
@@ -516,6 +531,14 @@ int launch_sparse_conv_runs(const cpoconv_map &map, const ColumnEntry *columns, 
                             float *partial, BatchStrides bs, hipStream_t stream)
 {
     const RunsPlan p = runs_plan(g);
+    if (g.stride == 2) {
+        if (p.kpl == 2) {
+            if (p.waves > 8) return launch_runs<3, 3, 2, 3, 3, 2, 16>(map, columns, g, wt, out, partial, p, bs, stream);
+            return launch_runs<3, 3, 2, 3, 3, 2, 8>(map, columns, g, wt, out, partial, p, bs, stream);
+        }
+        if (p.waves > 8) return launch_runs<3, 3, 2, 3, 3, 1, 16>(map, columns, g, wt, out, partial, p, bs, stream);
+        return launch_runs<3, 3, 2, 3, 3, 1, 8>(map, columns, g, wt, out, partial, p, bs, stream);
+    }
     if (p.kpl == 2) {
         if (p.waves > 8) return launch_runs<3, 3, 1, 4, 4, 2, 16>(map, columns, g, wt, out, partial, p, bs, stream);
         return launch_runs<3, 3, 1, 4, 4, 2, 8>(map, columns, g, wt, out, partial, p, bs, stream);

@@ -189,6 +189,11 @@ EDGE_SHAPES = [
     (33, 17, 19, 70, 1, 7, 1, 0, 0),  # 1 x 7 without padding: three-entry NOP segment, six overlap types
     (33, 19, 17, 70, 7, 1, 1, 0, 0),
     (33, 17, 19, 5, 1, 7, 1, 1, 2),   # padding narrower than the kernel's reach, rows padded too
+    (20, 15, 17, 70, 3, 3, 2, 1),     # column-run kernel at stride 2: odd map, ragged 3 x 3 tiles
+    (130, 30, 30, 128, 3, 3, 2, 1),   # the same, channel slices, two kernels per lane, last padded column unused
+    (8, 61, 61, 130, 3, 3, 2, 1),     # 63 padded rows
+    (24, 16, 16, 64, 3, 3, 2, 0),     # stride 2 without padding: a column of the map under no kernel position
+    (24, 17, 15, 64, 3, 3, 2, 0),
 ]
 
 
@@ -377,6 +382,8 @@ BATCH_CASES = [
     (4, (33, 17, 17, 192, 3, 3, 1, 1)),
     (8, (36, 8, 8, 384, 3, 3, 1, 1)),
     (4, (33, 17, 17, 160, 3, 3, 2, 1)),
+    (3, (33, 17, 17, 160, 3, 3, 2, 1)),           # column-run kernel at stride 2, three images
+    (2, (130, 29, 30, 128, 3, 3, 2, 1)),
     (4, (33, 30, 31, 190, 3, 3, 1, 1)),
     # 5 x 5 with two and three kernels per lane
     (4, (20, 27, 27, 192, 5, 5, 1, 2)),
