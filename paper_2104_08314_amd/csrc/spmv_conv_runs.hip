@@ -432,8 +432,8 @@ struct RunsPlan {
 RunsPlan runs_plan(const Geometry &g)
 {
     RunsPlan p;
-    p.ty = p.tx = g.stride == 1 ? 4 : 3;   // the window behind the tile: 6 x 6 / 7 x 7 padded cells
-    p.kpl = g.Kpad % 128 == 0 ? 2 : 1;
+    p.ty = p.tx = g.stride == 1 ? 4 : 3;   // the window behind the tile: 6 x 6 (3 x 3), 8 x 8 (5 x 5) / 7 x 7 (stride 2) padded cells
+    p.kpl = (g.Kpad % 128 == 0 && g.kh * g.kw <= 9) ? 2 : 1;   // 25 weights per kernel: one kernel's worth of registers
     const int tiles = ((g.Ow + p.tx - 1) / p.tx) * ((g.Oh + p.ty - 1) / p.ty) * (g.Kpad / (kLanes * p.kpl)) * g.N;
     p.waves = kMaxWaves;
     while (p.waves > 1 && g.C < 2 * p.waves) p.waves /= 2;
@@ -475,7 +475,9 @@ int launch_runs(const cpoconv_map &map, const ColumnEntry *columns, const Geomet
 bool runs_kernel_supports(const Geometry &g)
 {
     if (g.n_types < 1 || g.Ih > kLanes || g.Ow > kLanes) return false;
-    if (!(g.kh == 3 && g.kw == 3 && (g.stride == 1 || g.stride == 2))) return false;
+    const bool k3 = g.kh == 3 && g.kw == 3 && (g.stride == 1 || g.stride == 2);
+    const bool k5 = g.kh == 5 && g.kw == 5 && g.stride == 1;
+    if (!k3 && !k5) return false;
     // every column of the map itself lies under some kernel position: then all columns outside the
     // streams are padding, and the table holds an empty entry for each of them
     if ((g.Ow - 1) * g.stride + g.kw < g.pad_w + g.W) return false;
@@ -531,6 +533,10 @@ int launch_sparse_conv_runs(const cpoconv_map &map, const ColumnEntry *columns, 
                             float *partial, BatchStrides bs, hipStream_t stream)
 {
     const RunsPlan p = runs_plan(g);
+    if (g.kh == 5) {
+        if (p.waves > 8) return launch_runs<5, 5, 1, 4, 4, 1, 16>(map, columns, g, wt, out, partial, p, bs, stream);
+        return launch_runs<5, 5, 1, 4, 4, 1, 8>(map, columns, g, wt, out, partial, p, bs, stream);
+    }
     if (g.stride == 2) {
         if (p.kpl == 2) {
             if (p.waves > 8) return launch_runs<3, 3, 2, 3, 3, 2, 16>(map, columns, g, wt, out, partial, p, bs, stream);

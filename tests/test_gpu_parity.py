@@ -194,6 +194,10 @@ EDGE_SHAPES = [
     (8, 61, 61, 130, 3, 3, 2, 1),     # 63 padded rows
     (24, 16, 16, 64, 3, 3, 2, 0),     # stride 2 without padding: a column of the map under no kernel position
     (24, 17, 15, 64, 3, 3, 2, 0),
+    (20, 13, 17, 70, 5, 5, 1, 2),     # column-run kernel, 5 x 5: an 8 x 8 window fills the wavefront
+    (70, 27, 27, 192, 5, 5, 1, 2),
+    (24, 30, 29, 64, 5, 5, 1, 0),     # without padding
+    (9, 60, 60, 130, 5, 5, 1, 2),     # 64 padded rows and columns
 ]
 
 
@@ -384,6 +388,7 @@ BATCH_CASES = [
     (4, (33, 17, 17, 160, 3, 3, 2, 1)),
     (3, (33, 17, 17, 160, 3, 3, 2, 1)),           # column-run kernel at stride 2, three images
     (2, (130, 29, 30, 128, 3, 3, 2, 1)),
+    (3, (20, 13, 17, 70, 5, 5, 1, 2)),            # column-run kernel, 5 x 5
     (4, (33, 30, 31, 190, 3, 3, 1, 1)),
     # 5 x 5 with two and three kernels per lane
     (4, (20, 27, 27, 192, 5, 5, 1, 2)),
