@@ -70,39 +70,39 @@ __device__ __forceinline__ void apply_nze(float (&acc)[TY][TX][KPL], const float
     }
 }
 
-// The walk over one window column, unrolled: bit R of `bits` says whether window row R holds an NZE;
-// its value sits in lane 8 * Q + R of `values`.
+// The walk over the window, unrolled: bit 8 * Q + R of `cells` says whether row R of window column Q
+// holds an NZE; its value sits in the lane of that number.
 template <int KH, int KW, int S, int TY, int TX, int KPL, int Q, int R>
 __device__ __forceinline__ void apply_rows(float (&acc)[TY][TX][KPL], const float (&w)[KH * KW][KPL], const float values,
-                                           const unsigned bits)
+                                           const unsigned long long cells)
 {
     constexpr int RH = (TY - 1) * S + KH;
     if constexpr (R < RH) {
-        if (__builtin_expect((bits >> R) & 1u, 1)) {
+        if (__builtin_expect((cells >> (Q * kRowsPerColumn + R)) & 1ull, 1)) {
             const float v = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(values), Q * kRowsPerColumn + R));
             apply_nze<KH, KW, S, TY, TX, KPL, Q, R>(acc, w, v);
         }
-        apply_rows<KH, KW, S, TY, TX, KPL, Q, R + 1>(acc, w, values, bits);
+        apply_rows<KH, KW, S, TY, TX, KPL, Q, R + 1>(acc, w, values, cells);
     }
 }
 
 template <int KH, int KW, int S, int TY, int TX, int KPL, int Q>
 __device__ __forceinline__ void walk_columns(float (&acc)[TY][TX][KPL], const float (&w)[KH * KW][KPL], const float values,
-                                             const unsigned (&bits)[(TX - 1) * S + KW])
+                                             const unsigned long long cells)
 {
     constexpr int RW = (TX - 1) * S + KW;
     if constexpr (Q < RW) {
-        apply_rows<KH, KW, S, TY, TX, KPL, Q, 0>(acc, w, values, bits[Q]);
-        walk_columns<KH, KW, S, TY, TX, KPL, Q + 1>(acc, w, values, bits);
+        apply_rows<KH, KW, S, TY, TX, KPL, Q, 0>(acc, w, values, cells);
+        walk_columns<KH, KW, S, TY, TX, KPL, Q + 1>(acc, w, values, cells);
     }
 }
 
-// One channel's window: the occupied rows of every window column (wavefront-uniform), the NZEs
-// themselves (lane 8 * column + row; other lanes hold zero) and the channel's weights for this
-// lane's KPL kernels.
-template <int TAPS, int KPL, int RW>
+// One channel's window: which of its cells hold an NZE (bit 8 * column + row, wavefront-uniform),
+// the NZEs themselves (in the lane of that number; other lanes hold zero) and the channel's weights
+// for this lane's KPL kernels.
+template <int TAPS, int KPL>
 struct ChannelSet {
-    unsigned bits[RW];
+    unsigned long long cells;
     float values;
     float w[TAPS][KPL];
 };
@@ -114,7 +114,6 @@ template <> struct WeightVec<2> { typedef float2 type; };
 template <> struct WeightVec<3> { struct type { float x, y, z; }; };
 template <> struct WeightVec<4> { typedef float4 type; };
 
-typedef const __attribute__((address_space(4))) int32_t *EntryPtr;   // the column table, read-only for the kernel: scalar loads
 static_assert(sizeof(ColumnEntry) == 16, "an entry is read as four ints");
 
 template <int KH, int KW, int S, int TY, int TX, int KPL, int NW>
@@ -127,7 +126,7 @@ __global__ __launch_bounds__(NW *kLanes) void spmv_conv_runs_kernel(
     constexpr int TAPS = KH * KW;
     constexpr int A = TY * TX * KPL;           // accumulators per lane
     static_assert(RH <= kRowsPerColumn && RW * kRowsPerColumn <= kLanes, "the window must fit one register, 8 lanes per column");
-    using Set = ChannelSet<TAPS, KPL, RW>;
+    using Set = ChannelSet<TAPS, KPL>;
 
     extern __shared__ float red[];             // [wavefront][accumulator][lane], used after the channel loop
 
@@ -140,12 +139,16 @@ __global__ __launch_bounds__(NW *kLanes) void spmv_conv_runs_kernel(
     const int x0 = blockIdx.x * TX, y0 = blockIdx.y * TY;
     const int kbase = kg * kLanes * KPL;       // this lane holds kernels kbase + lane * KPL .. + KPL - 1
     const float *__restrict__ da = da_all + image * a.bs.da;
-    // the window's first padded column and row; columns past the padded width (a tile that hangs over
-    // the map's edge) read the last entry of the row and count as empty
+    // the window's first padded column and row; lane 8 * q + r stands for row r of window column q; a
+    // column past the padded width (a tile that hangs over the map's edge) reads the row's last entry
+    // and counts as empty
     const int j0 = x0 * S, top = y0 * S;
-    const EntryPtr columns = (EntryPtr)(reinterpret_cast<const int32_t *>(columns_all + image * a.bs.columns));
-    const unsigned long long above = (1ull << top) - 1ull;        // top <= 63: the map has at most 64 padded rows
     const int my_q = lane / kRowsPerColumn, my_r = lane % kRowsPerColumn;
+    const bool my_cell = my_q < RW && my_r < RH && j0 + my_q < g.Iw;
+    const int4 *__restrict__ my_entries =
+        reinterpret_cast<const int4 *>(columns_all + image * a.bs.columns) + min(j0 + my_q, g.Iw - 1);
+    const unsigned long long above = (1ull << top) - 1ull;        // top <= 63: the map has at most 64 padded rows
+    const unsigned above_lo = static_cast<unsigned>(above), above_hi = static_cast<unsigned>(above >> 32);
     const unsigned below_mine = (1u << my_r) - 1u;
     const unsigned lane_w = static_cast<unsigned>(lane) * (KPL * 4u);
 
@@ -161,17 +164,9 @@ __global__ __launch_bounds__(NW *kLanes) void spmv_conv_runs_kernel(
 #pragma unroll
             for (int kk = 0; kk < KPL; ++kk) acc[y][x][kk] = 0.0f;
 
-    // a channel's table entries for the window columns: scalar loads, 16 bytes each, side by side
-    // (begin, count, rows_lo, rows_hi)
-    auto load_entries = [&](int c, int (&e)[RW][4]) {
-        const EntryPtr row = columns + static_cast<int64_t>(min(c, c_end - 1)) * g.Iw * 4;
-#pragma unroll
-        for (int q = 0; q < RW; ++q) {
-            const EntryPtr at = row + min(j0 + q, g.Iw - 1) * 4;
-#pragma unroll
-            for (int k = 0; k < 4; ++k) e[q][k] = at[k];
-        }
-    };
+    // every lane reads the table entry of its own window column (begin, count, rows_lo, rows_hi): one
+    // 16-byte load, the eight lanes of a column the same address
+    auto load_entries = [&](int c, int4 &e) { e = my_entries[static_cast<int64_t>(min(c, c_end - 1)) * g.Iw]; };
     auto load_weights = [&](int c, Set &cs) {
         const float *wc = wt + static_cast<int64_t>(min(c, g.C - 1)) * TAPS * g.Kpad + kbase;
 #pragma unroll
@@ -183,24 +178,18 @@ __global__ __launch_bounds__(NW *kLanes) void spmv_conv_runs_kernel(
             for (int kk = 0; kk < KPL; ++kk) cs.w[tp][kk] = f[kk];
         }
     };
-    auto load_values = [&](int c, const int (&e)[RW][4], Set &cs) {
-        unsigned mine = 0;      // this lane's column: its window bits and where the window's NZEs start in DA
-        int first = 0;
-#pragma unroll
-        for (int q = 0; q < RW; ++q) {
-            const unsigned long long rows = (static_cast<unsigned long long>(static_cast<unsigned>(e[q][3])) << 32) |
-                                            static_cast<unsigned>(e[q][2]);
-            const bool live = c < c_end && j0 + q < g.Iw;
-            cs.bits[q] = live ? static_cast<unsigned>(rows >> top) & ((1u << RH) - 1u) : 0u;
-            const int start = e[q][0] + __popcll(rows & above);
-            if (my_q == q) { mine = cs.bits[q]; first = start; }
-        }
-        const bool has = (mine >> my_r) & 1u;     // lanes of rows past RH and columns past RW see no bit
-        const int at = first + __popc(mine & below_mine);
+    // the lane's cell: its bit of the column's rows; the NZE's place in DA is the run's start + the
+    // NZEs of the run above the window + those of the window above the lane's row
+    auto load_values = [&](int c, const int4 &e, Set &cs) {
+        const unsigned rows_lo = static_cast<unsigned>(e.z), rows_hi = static_cast<unsigned>(e.w);
+        const unsigned window = static_cast<unsigned>(((static_cast<unsigned long long>(rows_hi) << 32) | rows_lo) >> top);
+        const bool has = my_cell && c < c_end && ((window >> my_r) & 1u);
+        const int at = e.x + __popc(rows_lo & above_lo) + __popc(rows_hi & above_hi) + __popc(window & below_mine);
+        cs.cells = __ballot(has);
         cs.values = has ? da[at] : 0.0f;
     };
     // values first: the weights are then the youngest loads of the set (see apply)
-    auto load_set = [&](int c, const int (&e)[RW][4], Set &cs) {
+    auto load_set = [&](int c, const int4 &e, Set &cs) {
         load_values(c, e, cs);
         if (c < c_end) load_weights(c, cs);   // (wavefront-uniform) past the last channel the walk finds no bit set
     };
@@ -209,14 +198,14 @@ __global__ __launch_bounds__(NW *kLanes) void spmv_conv_runs_kernel(
         // the last weight register covers every register the walk reads, instead of a wait in
         // front of each multiply-add.
         asm volatile("" : "+v"(cs.w[TAPS - 1][KPL - 1]));
-        walk_columns<KH, KW, S, TY, TX, KPL, 0>(acc, cs.w, cs.values, cs.bits);
+        if (cs.cells != 0ull) walk_columns<KH, KW, S, TY, TX, KPL, 0>(acc, cs.w, cs.values, cs.cells);
     };
 
     // two register sets in turn: the loads of one channel are in flight while the other is applied,
     // and the table entries are fetched one channel further ahead
     {
         Set sa = {}, sb = {};
-        int ea[RW][4], eb[RW][4];
+        int4 ea, eb;
         const int c0 = c_begin + wave;
         load_entries(c0, ea);
         load_entries(c0 + nwaves, eb);
