@@ -414,15 +414,40 @@ struct RunsPlan {
     int ty, tx, kpl, waves, slices;
 };
 
+// The instantiations: kernel shape, stride, output tile.  The window of padded cells behind a tile,
+// ((ty - 1) s + kh) x ((tx - 1) s + kw), takes a lane per cell, eight lanes per window column.
+struct RunsShape {
+    int kh, kw, stride, ty, tx, max_kpl;
+};
+constexpr RunsShape kRunsShapes[] = {
+    {3, 3, 1, 4, 4, 2},   // 6 x 6 window
+    {3, 3, 2, 3, 3, 2},   // 7 x 7
+    {5, 5, 1, 4, 4, 1},   // 8 x 8; 25 weights per kernel: one kernel's worth of registers
+    {1, 7, 1, 8, 2, 2},   // 8 x 8
+    {7, 1, 1, 2, 8, 2},
+    {1, 3, 1, 4, 4, 2},   // 4 x 6
+    {3, 1, 1, 4, 4, 2},
+};
+
+const RunsShape *runs_shape(const Geometry &g)
+{
+    for (const RunsShape &r : kRunsShapes)
+        if (r.kh == g.kh && r.kw == g.kw && r.stride == g.stride) return &r;
+    return nullptr;
+}
+
 // Launch shape (measured on MI355X at one to three images per launch, where this kernel is used):
-// 4 x 4 tiles, two kernels per lane where the padded kernel count allows, sixteen wavefronts per
+// the tile of the kernel shape (4 x 4 for 3 x 3 stride 1; larger and smaller tiles were slower), two
+// kernels per lane where the padded kernel count allows, sixteen wavefronts per
 // workgroup - fewer when that would leave a wavefront less than two channels - and channel slices
 // across workgroups only while the tiles alone leave compute units without a workgroup.
 RunsPlan runs_plan(const Geometry &g)
 {
     RunsPlan p;
-    p.ty = p.tx = g.stride == 1 ? 4 : 3;   // the window behind the tile: 6 x 6 (3 x 3), 8 x 8 (5 x 5) / 7 x 7 (stride 2) padded cells
-    p.kpl = (g.Kpad % 128 == 0 && g.kh * g.kw <= 9) ? 2 : 1;   // 25 weights per kernel: one kernel's worth of registers
+    const RunsShape *shape = runs_shape(g);
+    p.ty = shape ? shape->ty : 4;
+    p.tx = shape ? shape->tx : 4;
+    p.kpl = (shape && g.Kpad % 128 == 0) ? shape->max_kpl : 1;
     const int tiles = ((g.Ow + p.tx - 1) / p.tx) * ((g.Oh + p.ty - 1) / p.ty) * (g.Kpad / (kLanes * p.kpl)) * g.N;
     p.waves = kMaxWaves;
     while (p.waves > 1 && g.C < 2 * p.waves) p.waves /= 2;
@@ -445,7 +470,7 @@ int launch_runs(const cpoconv_map &map, const ColumnEntry *columns, const Geomet
     bs.partial = static_cast<int64_t>(p.slices) * a.Ypad * a.Xpad * g.Kpad;
     a.bs = bs;
     const size_t lds = static_cast<size_t>(p.waves) * TY * TX * KPL * kLanes * sizeof(float);
-    if (lds > 160 * 1024 || p.waves > NW) return CPOCONV_ERR_SHAPE;
+    if (lds > 160 * 1024 || p.waves > NW || p.ty != TY || p.tx != TX || p.kpl != KPL) return CPOCONV_ERR_SHAPE;
     {
         KernelTimer timer("spmv_conv_runs", stream);
         const dim3 grid(ntx, nty, ngroups * p.slices * g.N), block(p.waves * kLanes);
@@ -464,9 +489,9 @@ int launch_runs(const cpoconv_map &map, const ColumnEntry *columns, const Geomet
 bool runs_kernel_supports(const Geometry &g)
 {
     if (g.n_types < 1 || g.Ih > kLanes || g.Ow > kLanes) return false;
-    const bool k3 = g.kh == 3 && g.kw == 3 && (g.stride == 1 || g.stride == 2);
-    const bool k5 = g.kh == 5 && g.kw == 5 && g.stride == 1;
-    if (!k3 && !k5) return false;
+    if (runs_shape(g) == nullptr) return false;
+    const RunsPlan p = runs_plan(g);
+    if (static_cast<size_t>(p.waves) * p.ty * p.tx * p.kpl * kLanes * sizeof(float) > 160 * 1024) return false;   // the sums' LDS
     // every column of the map itself lies under some kernel position: then all columns outside the
     // streams are padding, and the table holds an empty entry for each of them
     if ((g.Ow - 1) * g.stride + g.kw < g.pad_w + g.W) return false;
@@ -522,24 +547,21 @@ int launch_sparse_conv_runs(const cpoconv_map &map, const ColumnEntry *columns, 
                             float *partial, BatchStrides bs, hipStream_t stream)
 {
     const RunsPlan p = runs_plan(g);
-    if (g.kh == 5) {
-        if (p.waves > 8) return launch_runs<5, 5, 1, 4, 4, 1, 16>(map, columns, g, wt, out, partial, p, bs, stream);
-        return launch_runs<5, 5, 1, 4, 4, 1, 8>(map, columns, g, wt, out, partial, p, bs, stream);
-    }
-    if (g.stride == 2) {
-        if (p.kpl == 2) {
-            if (p.waves > 8) return launch_runs<3, 3, 2, 3, 3, 2, 16>(map, columns, g, wt, out, partial, p, bs, stream);
-            return launch_runs<3, 3, 2, 3, 3, 2, 8>(map, columns, g, wt, out, partial, p, bs, stream);
-        }
-        if (p.waves > 8) return launch_runs<3, 3, 2, 3, 3, 1, 16>(map, columns, g, wt, out, partial, p, bs, stream);
-        return launch_runs<3, 3, 2, 3, 3, 1, 8>(map, columns, g, wt, out, partial, p, bs, stream);
-    }
-    if (p.kpl == 2) {
-        if (p.waves > 8) return launch_runs<3, 3, 1, 4, 4, 2, 16>(map, columns, g, wt, out, partial, p, bs, stream);
-        return launch_runs<3, 3, 1, 4, 4, 2, 8>(map, columns, g, wt, out, partial, p, bs, stream);
-    }
-    if (p.waves > 8) return launch_runs<3, 3, 1, 4, 4, 1, 16>(map, columns, g, wt, out, partial, p, bs, stream);
-    return launch_runs<3, 3, 1, 4, 4, 1, 8>(map, columns, g, wt, out, partial, p, bs, stream);
+    const RunsShape *shape = runs_shape(g);
+    if (shape == nullptr) return CPOCONV_ERR_SHAPE;
+#define CPOCONV_RUNS(KH, KW, S, TY, TX)                                                                                  \
+    if (g.kh == KH && g.kw == KW && g.stride == S)                                                                      \
+        return p.kpl == 2 ? launch_runs<KH, KW, S, TY, TX, 2, kMaxWaves>(map, columns, g, wt, out, partial, p, bs, stream) \
+                          : launch_runs<KH, KW, S, TY, TX, 1, kMaxWaves>(map, columns, g, wt, out, partial, p, bs, stream);
+    CPOCONV_RUNS(3, 3, 1, 4, 4)
+    CPOCONV_RUNS(3, 3, 2, 3, 3)
+    CPOCONV_RUNS(1, 7, 1, 8, 2)
+    CPOCONV_RUNS(7, 1, 1, 2, 8)
+    CPOCONV_RUNS(1, 3, 1, 4, 4)
+    CPOCONV_RUNS(3, 1, 1, 4, 4)
+#undef CPOCONV_RUNS
+    if (g.kh == 5) return launch_runs<5, 5, 1, 4, 4, 1, kMaxWaves>(map, columns, g, wt, out, partial, p, bs, stream);
+    return CPOCONV_ERR_SHAPE;
 }
 
 }  // namespace cpoconv
