@@ -42,6 +42,7 @@ namespace {
 constexpr int kMaxWaves = 16;              // wavefronts (channel slices) per workgroup
 constexpr int kRunsMaxSlices = 16;         // channel slices across workgroups
 constexpr int kRowsPerColumn = 8;          // lanes a window column takes in the value register
+constexpr int kXcds = 8;                   // accelerator dies, each with an L2 of its own
 
 __device__ __forceinline__ int lane_id() { return threadIdx.x & (kLanes - 1); }
 __device__ __forceinline__ int uni(int v) { return __builtin_amdgcn_readfirstlane(v); }
@@ -136,7 +137,14 @@ __global__ __launch_bounds__(NW *kLanes) void spmv_conv_runs_kernel(
     const int kg = blockIdx.z % ngroups, slice = (blockIdx.z / ngroups) % a.slices;
     const int image = blockIdx.z / (ngroups * a.slices);
     if (map_unusable(a.bs, image)) return;
-    const int x0 = blockIdx.x * TX, y0 = blockIdx.y * TY;
+    // Tile of this workgroup.  Workgroups go to the eight XCDs in turn by their linear number, and an
+    // XCD's L2 fetches what its workgroups read: the tiles are numbered down the tile columns and the
+    // numbers dealt so that an XCD holds a stretch of neighbouring tile columns - its L2 then fetches
+    // the runs of those columns only, not the whole of DA and the table.
+    const int n_tiles = gridDim.x * gridDim.y, issued = blockIdx.x + gridDim.x * blockIdx.y;
+    const int xcd = issued % kXcds, nth = issued / kXcds;
+    const int tile = xcd * (n_tiles / kXcds) + min(xcd, n_tiles % kXcds) + nth;
+    const int x0 = (tile / static_cast<int>(gridDim.y)) * TX, y0 = (tile % static_cast<int>(gridDim.y)) * TY;
     const int kbase = kg * kLanes * KPL;       // this lane holds kernels kbase + lane * KPL .. + KPL - 1
     const float *__restrict__ da = da_all + image * a.bs.da;
     // the window's first padded column and row; lane 8 * q + r stands for row r of window column q; a
