@@ -558,6 +558,7 @@ __global__ __launch_bounds__(kEncThreads) void encode_kernel(const Geometry g, c
 // ---------------------------------------------------------------------------------------------
 constexpr int kThreads = 512;
 constexpr int kWaves = kThreads / kLanes;
+constexpr int64_t kNarrowFrom = 2048;   // channel-images from which the 64 x 64 encoder runs four wavefronts per workgroup
 // Padded rows handled per pass (lane = row inside the chunk): 64, a multiple of 4, so a set4 never
 // straddles chunks.
 constexpr int kMaxChunks = (CPOCONV_MAX_I + kLanes - 1) / kLanes;
@@ -892,8 +893,8 @@ __global__ __launch_bounds__(kThreads) void encode_channel_kernel(const Geometry
 // workgroup lives two thirds as long.  The tables of a convolution that follows and the ptr segments
 // are written by the wavefront whose number the overlap type has (mod 8).
 // ---------------------------------------------------------------------------------------------
-template <int kMode>
-__global__ __launch_bounds__(kThreads, 8) void encode_channel64_kernel(const Geometry g, const float *__restrict__ act_all,
+template <int kMode, int NW>
+__global__ __launch_bounds__(NW *kLanes, 8) void encode_channel64_kernel(const Geometry g, const float *__restrict__ act_all,
                                                                    const Producer prod, const int cps,
                                                                    unsigned long long *__restrict__ ctrl,
                                                                    unsigned long long *__restrict__ flags_all,
@@ -904,8 +905,9 @@ __global__ __launch_bounds__(kThreads, 8) void encode_channel64_kernel(const Geo
                                                                    const int64_t columns_stride)
 {
     extern __shared__ float tile[];                              // Ih x Wt, Wt odd: conflict-free column reads
-    __shared__ unsigned long long parts[kLanes];                 // a column's row bitmap: byte w from wavefront w
-    __shared__ int32_t stage[kWaves][kLanes];                    // one ptr segment under construction, per wavefront
+    __shared__ unsigned long long parts[kLanes];                 // a column's row bitmap: piece w (64 / NW bits) from wavefront w
+    constexpr int kT = NW * kLanes;                              // threads of the workgroup
+    __shared__ int32_t stage[NW][kLanes];                        // one ptr segment under construction, per wavefront
     __shared__ int32_t chan_base[4];                             // ptr / DA / IN start of the channel, look-back failures
 
     const int image = blockIdx.y, c = blockIdx.x;
@@ -926,7 +928,7 @@ __global__ __launch_bounds__(kThreads, 8) void encode_channel64_kernel(const Geo
     const int top_begin = (cps && g.top_slot >= 0) ? g.type_begin[g.top_slot] : kMaxCols + 1;
     const int top_end = (cps && g.top_slot >= 0) ? g.type_begin[g.top_slot + 1] : 0;
     const float bias_c = (prod.relu && prod.bias != nullptr) ? prod.bias[c] : 0.0f;
-    constexpr int kRowsPerWave = kLanes / kWaves;   // 8: padded rows wave * 8 .. + 7 belong to the wavefront
+    constexpr int kRowsPerWave = kLanes / NW;   // 8 or 16: padded rows wave * kRowsPerWave .. belong to the wavefront
 
     // ---- the channel into LDS: all of a wavefront's row loads in flight before the first store -----
     {
@@ -963,7 +965,8 @@ __global__ __launch_bounds__(kThreads, 8) void encode_channel64_kernel(const Geo
                 if (hr >= 0 && hr < g.H) bits |= static_cast<unsigned>(is_nze(tile[hr * Wt + my_jr])) << i;
             }
         }
-        reinterpret_cast<uint8_t *>(parts)[lane * kWaves + wave] = static_cast<uint8_t>(bits);
+        if constexpr (NW == 8) reinterpret_cast<uint8_t *>(parts)[lane * NW + wave] = static_cast<uint8_t>(bits);
+        else reinterpret_cast<uint16_t *>(parts)[lane * NW + wave] = static_cast<uint16_t>(bits);
     }
     __syncthreads();
 
@@ -1000,30 +1003,33 @@ __global__ __launch_bounds__(kThreads, 8) void encode_channel64_kernel(const Geo
         poke(flags + 2 * c + 1, (tag << 32) | static_cast<unsigned>(in_c) | (static_cast<unsigned>(ptr_c) << 17));
     }
     if (kMode == kPublishOnly) return;
-    // the channels before this one are shared out over the 512 threads (at most 512 channels take this
-    // path in one launch, so a thread has at most one); the first reads go out now ...
+    // the channels before this one are shared out over the threads (at most 512 channels take this
+    // path in one launch, so a thread has at most kPolls of them); the first reads go out now ...
     // (a launch that follows a publish-only launch may have more channels: it reads them as ordinary data below)
-    const bool polls = kMode == kSinglePass && tid < c;
-    unsigned long long w0 = 0, w1 = 0;
-    if (polls) {
+    constexpr int kPolls = kUnitsPerImage / kT;
+    unsigned long long w0 = 0, w1 = 0;   // (the first of them)
+    if (kMode == kSinglePass && tid < c) {
         w0 = peek(flags + 2 * tid);
         w1 = peek(flags + 2 * tid + 1);
     }
 
     // ... and while they travel, the scatter's items are prepared: columns wave, wave + 8, .. of the
     // wavefront, lane = padded row; value, rank among the column's NZEs, and the IN entry with its rank
-    constexpr int kColsPerWave = kLanes / kWaves;   // n_cols <= 64
+    constexpr int kColsPerWave = kLanes / NW;   // n_cols <= 64
     const int hr = lane - g.pad_h;
     const bool row_ok = hr >= 0 && hr < g.H;
     const unsigned long long below = (1ull << lane) - 1ull;
+    // (an item's integers share a register: rank in bits 0-6, rank of the IN entry + 1 in bits 7-13 -
+    // 0: no IN entry from this lane -, the entry itself, which fits 16 bits, above)
     float item_v[kColsPerWave];
-    int item_rank[kColsPerWave], item_erank[kColsPerWave], item_entry[kColsPerWave];   // erank < 0: no IN entry from this lane
+    int item_n[kColsPerWave];
 #pragma unroll
     for (int n = 0; n < kColsPerWave; ++n) {
-        const int vi = wave + n * kWaves;
+        const int vi = wave + n * NW;
         item_v[n] = 0.0f;
-        item_rank[n] = 0; item_erank[n] = -1; item_entry[n] = 0;
+        item_n[n] = 0;
         if (vi < g.n_cols) {
+            int entry, erank = -1;
             const int jr = __builtin_amdgcn_readlane(my_jr, vi);
             const float v = row_ok ? tile[hr * Wt + jr] : 0.0f;
             const bool nz = is_nze(v);
@@ -1031,41 +1037,48 @@ __global__ __launch_bounds__(kThreads, 8) void encode_channel64_kernel(const Geo
             const int rank = __popcll(mask & below);
             const int index = static_cast<int>(g.col_what[vi]) + lane * g.kw;
             item_v[n] = v;
-            item_rank[n] = rank;
             if (vi >= top_begin && vi < top_end) {
                 // set4 of Algorithm 3: the four padded rows 4*(h/4) .. +3
                 const int pattern = static_cast<int>((mask >> (lane & ~3)) & 0xFull);
                 const int r = __popc(pattern & ((1 << (lane & 3)) - 1));   // rank inside the set
                 const bool emit = nz && r < 2;
-                const int erank = __popcll(__ballot(emit) & below);
+                const int among = __popcll(__ballot(emit) & below);
                 // first NZE of the set: its index (negated unless a pattern follows);
                 // second NZE: the pattern, or its own negated index
-                item_entry[n] = __popc(pattern) >= 3 ? (r == 0 ? index : pattern) : -index;
-                if (emit) item_erank[n] = erank;
+                entry = __popc(pattern) >= 3 ? (r == 0 ? index : pattern) : -index;
+                if (emit) erank = among;
             } else {
-                item_entry[n] = index;
-                if (nz) item_erank[n] = rank;
+                entry = index;
+                if (nz) erank = rank;
             }
+            item_n[n] = rank | ((erank + 1) << 7) | (entry << 16);
         }
     }
 
     {
         int a0 = 0, a1 = 0, a2 = 0, bad = 0;
-        if (polls) {
-            for (int spin = 0; ((w0 >> 32) != tag || (w1 >> 32) != tag) && spin < kSpinLimit; ++spin) {
-                __builtin_amdgcn_s_sleep(8);
-                w0 = peek(flags + 2 * tid);
-                w1 = peek(flags + 2 * tid + 1);
+#pragma unroll
+        for (int p = 0; p < kPolls; ++p) {
+            if (!(kMode == kSinglePass && tid + p * kT < c)) continue;
+            unsigned long long v0 = w0, v1 = w1;
+            if (p > 0) {
+                v0 = peek(flags + 2 * (tid + p * kT));
+                v1 = peek(flags + 2 * (tid + p * kT) + 1);
             }
-            if ((w0 >> 32) != tag || (w1 >> 32) != tag || !lengths_plausible(w0, w1)) bad = 1;
+            for (int spin = 0; ((v0 >> 32) != tag || (v1 >> 32) != tag) && spin < kSpinLimit; ++spin) {
+                __builtin_amdgcn_s_sleep(8);
+                v0 = peek(flags + 2 * (tid + p * kT));
+                v1 = peek(flags + 2 * (tid + p * kT) + 1);
+            }
+            if ((v0 >> 32) != tag || (v1 >> 32) != tag || !lengths_plausible(v0, v1)) bad = 1;
             else {
-                a1 = static_cast<int>(w0 & 0xFFFFFFFFull);
-                a2 = static_cast<int>(w1 & 0x1FFFFull);
-                a0 = static_cast<int>((w1 >> 17) & 0x7FFFull);
+                a1 += static_cast<int>(v0 & 0xFFFFFFFFull);
+                a2 += static_cast<int>(v1 & 0x1FFFFull);
+                a0 += static_cast<int>((v1 >> 17) & 0x7FFFull);
             }
         }
         if (kMode == kPublished)
-            for (int cc = tid; cc < c; cc += kThreads) {
+            for (int cc = tid; cc < c; cc += kT) {
                 const unsigned long long p0 = flags[2 * cc], p1 = flags[2 * cc + 1];
                 if ((p0 >> 32) != tag || (p1 >> 32) != tag || !lengths_plausible(p0, p1)) { bad = 1; break; }
                 a1 += static_cast<int>(p0 & 0xFFFFFFFFull);
@@ -1116,7 +1129,7 @@ __global__ __launch_bounds__(kThreads, 8) void encode_channel64_kernel(const Geo
     if (mtab_all != nullptr) {
 #pragma unroll
         for (int i = 0; i < kMaxTypes; ++i) {
-            if (i >= g.n_types || (i & (kWaves - 1)) != wave) continue;
+            if (i >= g.n_types || (i & (NW - 1)) != wave) continue;
             int32_t *row = mtab_all + image * mtab_stride + (static_cast<int64_t>(c) * g.n_types + i) * (g.Ow + 1);
             const int cb = g.type_begin[i], ce = g.type_begin[i + 1];
             const int at = da_off + type_base[i];
@@ -1129,7 +1142,7 @@ __global__ __launch_bounds__(kThreads, 8) void encode_channel64_kernel(const Geo
             }
         }
     }
-    if (columns_all != nullptr && wave == kWaves - 1) {
+    if (columns_all != nullptr && wave == NW - 1) {
         ColumnEntry *row = columns_all + image * columns_stride + static_cast<int64_t>(c) * g.Iw;
         if (col_ok)
             row[g.col_j[lane]] = ColumnEntry{da_off + excl, cnt, static_cast<uint32_t>(colmask), static_cast<uint32_t>(colmask >> 32)};
@@ -1148,7 +1161,7 @@ __global__ __launch_bounds__(kThreads, 8) void encode_channel64_kernel(const Geo
             if (i >= g.n_types) continue;
             const int cb = g.type_begin[i], ce = g.type_begin[i + 1];
             const int base = type_base[i];
-            const bool mine = (i & (kWaves - 1)) == wave;
+            const bool mine = (i & (NW - 1)) == wave;
             if (g.nop3 && g.type_id[i] == 0) {
                 // [0, NZEs of the first column, NZEs of first + last column]
                 const int n1 = __builtin_amdgcn_readlane(incl, min(cb, kLanes - 1)) - base;
@@ -1180,14 +1193,15 @@ __global__ __launch_bounds__(kThreads, 8) void encode_channel64_kernel(const Geo
     // ---- scatter DA and IN from the prepared items ------------------------------------------------------
 #pragma unroll
     for (int n = 0; n < kColsPerWave; ++n) {
-        const int vi = wave + n * kWaves;
+        const int vi = wave + n * NW;
         if (vi < g.n_cols) {
             const int da_at = da_off + __builtin_amdgcn_readlane(excl, vi), in_at = in_off + __builtin_amdgcn_readlane(eexcl, vi);
             const bool nz = is_nze(item_v[n]);
-            if (nz) map.da[da_at + item_rank[n]] = item_v[n];
+            const int rank = item_n[n] & 127, erank = ((item_n[n] >> 7) & 127) - 1, entry = item_n[n] >> 16;
+            if (nz) map.da[da_at + rank] = item_v[n];
             if (nz && full != nullptr)
-                full[da_at + item_rank[n]] = static_cast<int16_t>(static_cast<int>(g.col_what[vi]) + lane * g.kw);
-            if (item_erank[n] >= 0) store_index(map.in, in_at + item_erank[n], item_entry[n], in16);
+                full[da_at + rank] = static_cast<int16_t>(static_cast<int>(g.col_what[vi]) + lane * g.kw);
+            if (erank >= 0) store_index(map.in, in_at + erank, entry, in16);
         }
     }
 }
@@ -1724,22 +1738,33 @@ int launch_encode(const float *act, const Producer &prod, const Geometry &g, con
     if (g.Ih <= kLanes && g.Iw <= kLanes) {
         // maps of at most 64 x 64 padded cells: the variant whose wavefronts keep their own books
         const size_t lds64 = static_cast<size_t>(g.H) * (g.W | 1) * sizeof(float);
+        // Launches with many channel-images run four wavefronts per workgroup: twice the workgroups in
+        // flight on a compute unit, half the copies of the per-wavefront bookkeeping (few channel-images:
+        // eight wavefronts, the shorter life of a single workgroup counts).
+        const bool narrow = static_cast<int64_t>(g.C) * g.N >= kNarrowFrom;
+#define CPOCONV_ENCODE64(MODE, NW, ...) \
+    hipLaunchKernelGGL((encode_channel64_kernel<MODE, NW>), dim3(g.C, g.N), dim3(NW * kLanes), lds64, stream, g, act, prod, cps, ctrl, \
+                       flags, units_stride, map, __VA_ARGS__)
         if (single) {
             KernelTimer timer("encode", stream);
-            hipLaunchKernelGGL(encode_channel64_kernel<kSinglePass>, dim3(g.C, g.N), dim3(kThreads), lds64, stream, g, act, prod,
-                               cps, ctrl, flags, units_stride, map, mtab, mstride, full, fstride, columns, cstride);
+            if (narrow) CPOCONV_ENCODE64(kSinglePass, 4, mtab, mstride, full, fstride, columns, cstride);
+            else CPOCONV_ENCODE64(kSinglePass, 8, mtab, mstride, full, fstride, columns, cstride);
         } else {
             {
                 KernelTimer timer("encode_count", stream);
-                hipLaunchKernelGGL(encode_channel64_kernel<kPublishOnly>, dim3(g.C, g.N), dim3(kThreads), lds64, stream, g, act,
-                                   prod, cps, ctrl, flags, units_stride, map, static_cast<int32_t *>(nullptr), mstride,
-                                   static_cast<int16_t *>(nullptr), fstride, static_cast<ColumnEntry *>(nullptr), cstride);
+                if (narrow)
+                    CPOCONV_ENCODE64(kPublishOnly, 4, static_cast<int32_t *>(nullptr), mstride, static_cast<int16_t *>(nullptr), fstride,
+                                     static_cast<ColumnEntry *>(nullptr), cstride);
+                else
+                    CPOCONV_ENCODE64(kPublishOnly, 8, static_cast<int32_t *>(nullptr), mstride, static_cast<int16_t *>(nullptr), fstride,
+                                     static_cast<ColumnEntry *>(nullptr), cstride);
             }
             CPOCONV_HIP_TRY(hipGetLastError());
             KernelTimer timer("encode", stream);
-            hipLaunchKernelGGL(encode_channel64_kernel<kPublished>, dim3(g.C, g.N), dim3(kThreads), lds64, stream, g, act, prod,
-                               cps, ctrl, flags, units_stride, map, mtab, mstride, full, fstride, columns, cstride);
+            if (narrow) CPOCONV_ENCODE64(kPublished, 4, mtab, mstride, full, fstride, columns, cstride);
+            else CPOCONV_ENCODE64(kPublished, 8, mtab, mstride, full, fstride, columns, cstride);
         }
+#undef CPOCONV_ENCODE64
         CPOCONV_HIP_TRY(hipGetLastError());
         return CPOCONV_OK;
     }

@@ -110,7 +110,8 @@ def test_compact_workload_layers(api, name):
 
 
 @pytest.mark.parametrize("case", [(3, (5, 12, 13, 70, 3, 3, 1, 1)), (8, (36, 13, 9, 70, 3, 3, 2, 1)),
-                                  (4, (40, 14, 14, 128, 3, 3, 1, 1)), (9, (33, 7, 7, 64, 3, 3, 1, 1))],
+                                  (4, (40, 14, 14, 128, 3, 3, 1, 1)), (9, (33, 7, 7, 64, 3, 3, 1, 1)),
+                                  (40, (52, 36, 35, 6, 3, 3, 1, 1))],   # four-wavefront encoder workgroups
                          ids=lambda c: f"n{c[0]}-" + "x".join(map(str, c[1])))
 def test_compact_batched(api, case):
     n_images, shape = case

@@ -389,6 +389,11 @@ BATCH_CASES = [
     (3, (33, 17, 17, 160, 3, 3, 2, 1)),           # column-run kernel at stride 2, three images
     (2, (130, 29, 30, 128, 3, 3, 2, 1)),
     (3, (20, 13, 17, 70, 5, 5, 1, 2)),            # column-run kernel, 5 x 5
+    (40, (52, 36, 35, 6, 3, 3, 1, 1)),            # 2080 channel-images on a map beyond 4 KiB: four-wavefront encoder workgroups
+    (36, (60, 40, 38, 4, 5, 5, 1, 2)),            # the same: five overlap types, 44 padded rows
+    (34, (64, 33, 34, 4, 3, 3, 2, 0)),            # stride 2 without padding
+    (4, (520, 40, 38, 3, 3, 3, 1, 1)),            # and in two launches (more than 512 channels)
+    (33, (64, 62, 60, 2, 3, 3, 1, 1)),            # 64 padded rows: sixteen rows per wavefront, all of them used
     (4, (33, 30, 31, 190, 3, 3, 1, 1)),
     # 5 x 5 with two and three kernels per lane
     (4, (20, 27, 27, 192, 5, 5, 1, 2)),
