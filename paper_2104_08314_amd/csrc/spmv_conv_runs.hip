@@ -460,7 +460,8 @@ RunsPlan runs_plan(const Geometry &g)
     p.waves = kMaxWaves;
     while (p.waves > 1 && g.C < 2 * p.waves) p.waves /= 2;
     int s = 256 / std::max(tiles, 1);
-    s = std::min(std::min(s, std::max(1, g.C / (2 * p.waves))), kRunsMaxSlices);
+    // (a slice leaves every wavefront at least one channel; layers of few channels: two, measured on 16 -> 16 at 28 x 28)
+    s = std::min(std::min(s, std::max(1, g.C / ((g.C < 64 ? 2 : 1) * p.waves))), kRunsMaxSlices);
     s = std::max(s, 1);
     const int per_slice = (g.C + s - 1) / s;
     p.slices = (g.C + per_slice - 1) / per_slice;
