@@ -238,6 +238,24 @@ __global__ __launch_bounds__(NW *kLanes) void spmv_conv_runs_kernel(
     __syncthreads();
     float *partial = partial_all + image * a.bs.partial;
     float *out = out_all + image * a.bs.out;
+    if (TX == 4 && a.slices == 1 && g.Ow % 4 == 0 && (reinterpret_cast<uintptr_t>(out) & 15u) == 0) {
+        // direct output, four columns wide: a wavefront adds the four sums of a tile row for one of the
+        // lane's kernels (same order of additions as below) and stores them as one 16-byte piece
+        for (int pair = wave; pair < TY * KPL; pair += nwaves) {
+            const int ty = pair / KPL, kk = pair % KPL;
+            float s[4];
+#pragma unroll
+            for (int x = 0; x < 4; ++x) {
+                const int n = (ty * TX + x) * KPL + kk;
+                s[x] = red[n * kLanes + lane];
+                for (int w = 1; w < nwaves; ++w) s[x] += red[(w * A + n) * kLanes + lane];
+            }
+            const int y = y0 + ty, k = kbase + lane * KPL + kk;
+            if (y < g.Oh && x0 < g.Ow && k < g.K)   // Ow is a multiple of four: the whole piece lies inside the map
+                *reinterpret_cast<float4 *>(out + (static_cast<int64_t>(k) * g.Oh + y) * g.Ow + x0) = make_float4(s[0], s[1], s[2], s[3]);
+        }
+        return;
+    }
     for (int n = wave; n < A; n += nwaves) {
         float s = red[n * kLanes + lane];
         for (int w = 1; w < nwaves; ++w) s += red[(w * A + n) * kLanes + lane];
