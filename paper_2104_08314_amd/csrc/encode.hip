@@ -1667,7 +1667,7 @@ static int launch_encode_bands(const float *act, const Producer &prod, const Geo
 // queue for a compute unit.
 static bool use_small(const Geometry &g)
 {
-    // Where the column-run convolution can follow (fewer than four images, 3 x 3 stride 1) the
+    // Where the column-run convolution can follow (fewer than four images, a shape it is instantiated for) the
     // workgroup-per-channel encoder takes the small maps too: it leaves the column table, and the
     // layer gains more from that kernel than the encoder loses (256 x 14 x 14: 28.8 -> 24.5 us for
     // the one-call layer, 512 x 7 x 7: 28.4 -> 26.6, the encoder alone 9.7 -> 12.0).

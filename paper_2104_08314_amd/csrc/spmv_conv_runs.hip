@@ -527,12 +527,12 @@ bool runs_kernel_supports(const Geometry &g)
 
 // Measured over the workload layers at one to three images per launch: where the tiles alone give
 // every compute unit a workgroup (one channel slice: no partial sums, no second kernel) the kernel
-// beats the strip kernel with its slice sum (config 2: 21.5 against 25 + 5.5 us); with channel
-// slices and the slice sum it still beats the register-tile kernel where the encoder of a one-call
-// layer leaves the column table (28 x 28 maps: 27.8 against 30.8 us for the layer); on the maps the
-// one-wavefront-per-channel encoder takes (14 x 14, 7 x 7), where the table costs a launch of its
-// own, the register-tile kernel keeps the layers (28.8 against 31.8 us).  From four images on the
-// strip kernel's shared decode wins.
+// beats the strip kernel with its slice sum (config 2: 19 against 25 + 5.5 us); with channel slices
+// and the slice sum it still beats the register-tile and strip kernels where the encoder of a
+// one-call layer leaves the column table - the workgroup-per-channel encoder, which at these batch
+// sizes takes every layer this kernel supports (one-call layers: 128 @ 28 30.5 -> 23.5 us,
+// 256 @ 14 28.7 -> 23.4, 3 x 3 stride 2 128 @ 56 39.7 -> 27.5, 5 x 5 38.3 -> 27.3).  From four images
+// on the strip kernel's shared decode wins.
 bool runs_kernel_preferred(const Geometry &g)
 {
     return runs_kernel_supports(g) && g.N < 4 && (runs_plan(g).slices == 1 || encode_uses_channel_kernel(g));
