@@ -488,6 +488,24 @@ def cpu_baseline(spec, workloads, w_np, config, inputs=5, repeats=10):
                       "double accumulation, gcc -O2, one thread" % (inputs, repeats)}
 
 
+def trace_avg_from_profiles(kernel, summary="bench_cfg2_128at56_all_kernels.txt"):
+    """Average duration (us) of `kernel` in the committed rocprofv3 kernel trace of this workload: the
+    row of the summary's kernel-trace table (kernel, calls, avg_us, ...).  The tracer lengthens every
+    kernel by 1.5-3 us, so it reads above the event-timed figure."""
+    path = os.path.join(ROOT, "profiles", summary)
+    if not os.path.exists(path):
+        return None
+    with open(path) as f:
+        for line in f:
+            parts = line.split()
+            if len(parts) >= 6 and parts[0] == kernel:
+                try:
+                    return float(parts[2])
+                except ValueError:
+                    return None
+    return None
+
+
 def traffic_from_profiles(kernel_key):
     """HBM bytes per launch measured with rocprofv3 --pmc (FETCH_SIZE / WRITE_SIZE runs), if a
     summary under profiles/ records them as a line `traffic_bytes_per_launch[<key>]: <n>`."""
@@ -669,6 +687,8 @@ def main():
         if k in dom:
             roof[k] = dom[k]
     roof["traffic"] = traffic_from_profiles(dom["kernel"])
+    if args.config == 2:
+        roof["rocprofv3_trace_avg_us"] = trace_avg_from_profiles(dom["kernel"])
 
     result = {
         "metric": "per-layer CPO/CPS conv time (us) + HBM GB/s, speedup and CR vs im2col",
