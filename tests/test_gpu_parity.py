@@ -198,6 +198,8 @@ EDGE_SHAPES = [
     (70, 27, 27, 192, 5, 5, 1, 2),
     (24, 30, 29, 64, 5, 5, 1, 0),     # without padding
     (9, 60, 60, 130, 5, 5, 1, 2),     # 64 padded rows and columns
+    (3, 64, 64, 64, 3, 3, 1, 0),      # band encoder in front of the column-run kernel: the column table rebuilt from its offsets
+    (2, 64, 64, 130, 3, 3, 2, 0),
 ]
 
 
